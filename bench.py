@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the DDD draft round on one MI355X.
+
+A "step" is one whole draft round (Algorithm 1 of the paper end to end: reset, up to D draft
+calls each = stand-in draft body + LM-head weight stream + merge/beam/stop kernel, final tree,
+stand-in target, accept walk) launched as one captured HIP graph.  Inputs are seeded and
+synthetic (7B-shaped by default) and resident in HBM before the timed region starts.
+
+Prints ONE JSON line: draft rounds/s plus us per executed depth step, the HBM roofline of the
+dominant kernel (the LM-head weight stream) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(wl, W_bits, plant_dir, threshold, budget_s):
+    """The CPU oracle, as it stands, on a bounded sample of the same rounds."""
+    from oracle import synth_round as SR
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    rounds = steps = 0
+    while True:
+        res, _, _ = SR.oracle_round(wl, W_bits, plant_dir, 0, rounds, threshold=threshold)
+        rounds += 1
+        steps += res.steps
+        el = time.perf_counter() - t0
+        if el > budget_s or rounds >= 64:
+            break
+    return {"value": rounds / el, "unit": "rounds/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{rounds} rounds ({steps} depth steps) of sequence 0, rounds 0..{rounds - 1}, {el:.1f} s",
+            "us_per_depth_step": 1e6 * el / steps}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000, help="timed draft rounds")
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="7b_b1", help="synthetic workload name (see synth/inputs.py)")
+    ap.add_argument("--threshold", type=float, default=None, help="stop threshold t (default: the workload's)")
+    ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
+    ap.add_argument("--profile-iters", type=int, default=200)
+    ap.add_argument("--traffic", default=None,
+                    help="JSON file {\"fetch_bytes\":..,\"write_bytes\":..} from rocprofv3 --pmc runs (optional)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    import paper_2409_00142_amd as D
+    import synth
+    from synth import device as SD
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a gfx950 GPU (the HIP path has no CPU fallback)")
+    D.load_library()
+    wl = synth.WORKLOADS[args.workload]
+    thr = wl.threshold if args.threshold is None else args.threshold
+    log(f"[bench] workload {wl.name}: B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} m={wl.m} t={thr} gain={wl.gain}")
+    t0 = time.perf_counter()
+    g = SD.GpuWorkload(wl, threshold=thr, debug=False)
+    log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s; "
+        f"stream slices={D.ddd_num_slices(g.ctx)}")
+
+    side = torch.cuda.Stream()
+    g.capture(side)
+    torch.cuda.synchronize()
+    g.set_round(0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(args.warmup):
+            g.launch(side.cuda_stream)
+        side.synchronize()
+        g.depth_hist.zero_()
+        g.accept_hist.zero_()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        e0.record(side)
+        for _ in range(args.steps):
+            g.launch(side.cuda_stream)
+        e1.record(side)
+        side.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - w0
+    ev_ms = e0.elapsed_time(e1)
+    depth_hist = g.depth_hist.cpu().numpy()
+    accept_hist = g.accept_hist.cpu().numpy()
+    exec_steps = int(sum(d * int(c) for d, c in enumerate(depth_hist)))
+    n_round_seq = int(depth_hist.sum())
+    assert n_round_seq == args.steps * wl.B, (n_round_seq, args.steps, wl.B)
+    rounds_per_s = args.steps * wl.B / wall
+    ms_per_round = 1e3 * wall / args.steps
+    # an executed depth step of the batch = one LM-head pass; count passes, not sequences
+    # (for B=1 the two are the same)
+    log(f"[bench] {args.steps} rounds in {wall * 1e3:.2f} ms wall ({ev_ms:.2f} ms by events): "
+        f"{rounds_per_s:.1f} rounds/s, {ms_per_round * 1e3:.1f} us/round")
+    log(f"[bench] depth histogram (steps -> sequences): "
+        f"{ {d: int(c) for d, c in enumerate(depth_hist) if c} }")
+    log(f"[bench] accept-length histogram: { {d: int(c) for d, c in enumerate(accept_hist) if c} }")
+
+    # ---- dominant kernel: the LM-head weight stream, alone, per-launch HIP events -------------
+    n_rows = min(wl.B * wl.k, 16)
+    mean_ms, min_ms = D.ddd_profile_lmhead_stream(g.ctx, g.W, g.hid, n_rows, args.profile_iters,
+                                                  stream=side.cuda_stream)
+    w_bytes = wl.V * wl.H * 2
+    alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * D.ddd_num_slices(g.ctx) * (wl.k * 8 + 4)
+    achieved = alg_bytes / (mean_ms * 1e-3) / 1e9
+    log(f"[bench] lmhead stream kernel: mean {mean_ms * 1e3:.2f} us, min {min_ms * 1e3:.2f} us per launch, "
+        f"{alg_bytes / 1e6:.2f} MB algorithmic -> {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
+
+    # ---- plain read stream over the same bytes: the practical ceiling --------------------------
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with torch.cuda.stream(side):
+        best = None
+        for blocks in (2048, 4096, 8192):
+            for _ in range(3):
+                D.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
+            r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            r0.record(side)
+            for _ in range(20):
+                D.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
+            r1.record(side)
+            side.synchronize()
+            gbs = 20 * w_bytes / (r0.elapsed_time(r1) * 1e-3) / 1e9
+            best = gbs if best is None else max(best, gbs)
+    log(f"[bench] plain read-stream kernel over W: {best:.0f} GB/s ({100 * best / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
+
+    traffic = None
+    if args.traffic and os.path.exists(args.traffic):
+        with open(args.traffic) as f:
+            traffic = json.load(f)
+
+    us_per_depth_step = 1e6 * wall / max(1, exec_steps) if wl.B == 1 else None
+    out = {
+        "metric": "DDD draft rounds/sec (7B-shaped synthetic draft round, whole hot path per round)",
+        "value": rounds_per_s,
+        "unit": "rounds/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_round,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
+                   "threshold": thr, "hidden_gain": wl.gain, "launch": "one hipGraph per round",
+                   "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},
+                   "accept_len_hist": {str(d): int(c) for d, c in enumerate(accept_hist) if c},
+                   "executed_depth_steps": exec_steps,
+                   "us_per_depth_step": us_per_depth_step,
+                   "mean_depth": exec_steps / max(1, n_round_seq)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "lmhead_stream_kernel", "us_per_launch": mean_ms * 1e3, "us_per_launch_min": min_ms * 1e3,
+                     "algorithmic_bytes_per_launch": alg_bytes, "launches_timed": args.profile_iters,
+                     "read_stream_ceiling_GBs": best},
+    }
+    if args.cpu_budget > 0:
+        log(f"[bench] timing the CPU oracle for about {args.cpu_budget:.0f} s ...")
+        out["cpu_baseline"] = cpu_baseline(wl, g.W_bits, g.plant_dir_np if wl.n_plant else None, thr, args.cpu_budget)
+        log(f"[bench] oracle: {out['cpu_baseline']}")
+    g.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

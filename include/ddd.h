@@ -1,0 +1,200 @@
+/*
+ * ddd.h - C ABI of the MI355X (gfx950) Dynamic Depth Decoding draft-round library.
+ *
+ * The library implements the hot path of DDD (arXiv 2409.00142): the EAGLE-2 style
+ * beam-search draft round of Section 1 made variable-depth by the confidence test of
+ * Section 2 (Eq. 1, Algorithm 1), the final draft tree with its attention mask
+ * (Section 1, EAGLE paragraph) and the temperature-0 accept walk (Section 1,
+ * speculative-decoding paragraph; Section 3.1).
+ *
+ * Conventions for every entry point
+ *  - All buffers named "device" are caller-owned HIP device memory on the current
+ *    device; the library never frees or reallocates them.  The context owns only
+ *    its own scratch (per-slice partial results) and an optional captured graph.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every
+ *    call only enqueues work; none synchronises with the host.
+ *  - Return value: 0 (DDD_OK) or a negative ddd_status.  Arguments are validated
+ *    before anything is enqueued, so a failing call has no effect.  No C++
+ *    exception crosses this boundary.
+ *  - Notation follows the paper: beam width w is `k`, the maximum number of
+ *    draft-model calls n is `max_depth` (D), the check set S is `check_mask`,
+ *    the threshold x is given in the probability domain, t = exp(x).
+ *  - NaN logits are outside the contract (ordering undefined).
+ */
+#ifndef DDD_H_
+#define DDD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DDD_KMAX 16          /* largest beam width k                         */
+#define DDD_MMAX 128         /* largest final tree size m                    */
+#define DDD_DMAX 31          /* largest max_depth (check_mask has 32 bits)   */
+#define DDD_POOL_MAX 4096    /* largest node pool per sequence               */
+#define DDD_STREAM_ROWS 16   /* rows handled by one pass of the weight stream */
+
+typedef enum ddd_status {
+  DDD_OK = 0,
+  DDD_ERR_INVALID_ARG = -1,   /* null pointer, size out of range, unsupported shape */
+  DDD_ERR_NO_DEVICE = -2,     /* no HIP device visible                               */
+  DDD_ERR_WRONG_ARCH = -3,    /* the current device is not gfx950                    */
+  DDD_ERR_HIP = -4,           /* a HIP runtime call failed (see ddd_last_hip_error)  */
+  DDD_ERR_UNIMPLEMENTED = -5,
+  DDD_ERR_STATE = -6          /* e.g. ddd_round_launch before ddd_round_capture      */
+} ddd_status;
+
+/* Parameters of Algorithm 1 ("Require" line) plus the problem shape. */
+typedef struct ddd_config {
+  int32_t B;           /* independent sequences, each with its own beam and stop decision */
+  int32_t H;           /* hidden size: H = 128*G*nw with G in {1,2,4} and 1 <= nw <= 10 (so H <= 5120)    */
+  int32_t V;           /* vocabulary size, k <= V < 2^24                                  */
+  int32_t k;           /* beam width w, 1..DDD_KMAX                                       */
+  int32_t max_depth;   /* n: maximum number of draft-model calls per round, 1..DDD_DMAX   */
+  int32_t m;           /* final tree size in draft nodes (root not counted), 1..DDD_MMAX  */
+  float threshold;     /* t: continue iff sum_i exp(logprobsum[i]) >= t  (Eq. 1, t = exp(x)) */
+  uint32_t check_mask; /* bit s set <=> s in S: test after the s-th draft call (s >= 1)   */
+  uint32_t flags;      /* reserved, must be 0                                             */
+} ddd_config;
+
+/* Per-round beam and node-pool state.  All members are device pointers (caller-owned).
+ * Nmax = ddd_pool_capacity(cfg) = 1 + k + (max_depth-1)*k*k.  Node 0 is the root; the prompt
+ * call creates nodes 1..k; the s-th later call (s >= 1) creates nodes
+ * 1 + k + (s-1)*k*k + i*k + j for beam slot i and rank j. */
+typedef struct ddd_state {
+  float* logprobsum;         /* [B,k]    summed logprob of each beam sequence (Algorithm 1)   */
+  int32_t* beam_node;        /* [B,k]    pool id of each beam entry                           */
+  int32_t* beam_token;       /* [B,k]    its token                                            */
+  int32_t* beam_parent_slot; /* [B,k]    slot of its parent in the previous beam              */
+  int32_t* pool_token;       /* [B,Nmax] token of every generated node                        */
+  int32_t* pool_parent;      /* [B,Nmax] pool id of its parent, -1 for the root               */
+  int32_t* pool_depth;       /* [B,Nmax] depth, root 0                                        */
+  float* pool_score;         /* [B,Nmax] summed logprob along the path, root 0                */
+  int32_t* n_nodes;          /* [B]      nodes in the pool, root included                     */
+  int32_t* steps;            /* [B]      draft calls made in this round                       */
+  uint8_t* active;           /* [B]      1 while the sequence keeps drafting                  */
+  uint8_t* row_active;       /* [B*k]    active[b] repeated for the k beam rows of b          */
+  double* conf;              /* [B]      P = sum_i exp(logprobsum[i]) after the latest call   */
+} ddd_state;
+
+/* Final draft tree.  Tree index 0 is the root, indices 1..n_sel the selected nodes in
+ * ascending pool id (parents precede children).  Entries past n_sel are padded
+ * (-1 for ids and tokens, 0 for pos and mask). */
+typedef struct ddd_tree {
+  int32_t* sel_node;    /* [B,m]         pool ids of the selected nodes              */
+  int32_t* n_sel;       /* [B]           min(m, n_nodes-1)                            */
+  int32_t* tree_token;  /* [B,m+1]                                                    */
+  int32_t* pos;         /* [B,m+1]       depth of each tree node (position offset)    */
+  int32_t* parent_idx;  /* [B,m+1]       tree index of the parent, -1 for the root    */
+  uint8_t* mask;        /* [B,m+1,m+1]   mask[i][j]=1 iff j is i or an ancestor of i  */
+} ddd_tree;
+
+typedef struct ddd_ctx ddd_ctx;
+
+/* Host-only helpers (no device needed). */
+const char* ddd_strerror(int code);
+const char* ddd_last_hip_error(void);                 /* text of the last failing HIP call on this thread */
+int ddd_config_validate(const ddd_config* cfg);       /* DDD_OK or DDD_ERR_INVALID_ARG                    */
+size_t ddd_pool_capacity(const ddd_config* cfg);      /* 1 + k + (max_depth-1)*k*k ; 0 if cfg is invalid  */
+size_t ddd_scratch_bytes(const ddd_config* cfg);      /* device scratch a context allocates               */
+
+/* Create / destroy a context on the current device.  DDD_ERR_NO_DEVICE without a GPU,
+ * DDD_ERR_WRONG_ARCH if it is not gfx950. */
+int ddd_create(const ddd_config* cfg, ddd_ctx** out);
+int ddd_destroy(ddd_ctx* ctx);
+
+/* Start of a round (Algorithm 1, before line 1): pool := {root}, steps := 0, active := 1.
+ * root_token: device int32[B] or NULL (root token recorded as -1). */
+int ddd_round_reset(ddd_ctx* ctx, ddd_state* st, const int32_t* root_token, void* stream);
+
+/* LM-head projection + logsoftmax + per-row top-k of one draft call (Section 2: the draft
+ * output goes through a logsoftmax; Section 1: top-k continuations per sequence).
+ *   W_bf16   device bf16[V,H] row-major (H contiguous): the target's LM head, reused by the draft model
+ *   hid_bf16 device bf16[n_rows,H] row-major: the draft body's output rows, 1 <= n_rows <= B*k
+ *   row_active device u8[n_rows] or NULL (all active); outputs of inactive rows are left untouched
+ *   topk_token   device int32[n_rows,k]: ids of the k largest logits, (logit desc, id asc)
+ *   topk_logprob device fp32[n_rows,k]:  logit - lse of those tokens
+ *   lse          device fp32[n_rows]:    log sum_v exp(logit[r,v])
+ *   logits_dbg   device fp32[n_rows,V] or NULL: full fp32 logits (bf16 inputs, fp32 accumulate) */
+int ddd_lmhead_topk(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, int32_t n_rows,
+                    const uint8_t* row_active, int32_t* topk_token, float* topk_logprob, float* lse,
+                    float* logits_dbg, void* stream);
+
+/* Beam update after draft call number step+1 (Algorithm 1 lines 2-3 for step 0, lines 11-12
+ * otherwise): adds logprobsum of the parents, appends all candidates to the pool, keeps the
+ * k best by (score desc, token asc, flat index asc) as the new beam; steps[b] += 1.
+ *   topk_token / topk_logprob: as written by ddd_lmhead_topk; rows [B] for step 0 (row b),
+ *   rows [B*k] for step >= 1 (row b*k+i is beam slot i of sequence b).
+ * Sequences with active[b] == 0 are left untouched. */
+int ddd_beam_select(ddd_ctx* ctx, int32_t step, const int32_t* topk_token, const float* topk_logprob,
+                    ddd_state* st, void* stream);
+
+/* DDD stop test (Eq. 1, Algorithm 1 lines 5-9) taken after `steps_done` draft calls:
+ * conf[b] = sum_i exp(logprobsum[b,i]) (fp64); active[b] stays 1 iff steps_done < max_depth and
+ * (bit steps_done of check_mask is clear or conf[b] >= threshold).  Written on the device; the
+ * host never needs to read it inside a round. */
+int ddd_depth_continue(ddd_ctx* ctx, int32_t steps_done, ddd_state* st, void* stream);
+
+/* One whole draft call for every active sequence: ddd_lmhead_topk + ddd_beam_select +
+ * ddd_depth_continue with the per-row results kept on chip (two kernel launches).
+ * hid_bf16: [B,H] for step 0, [B*k,H] for step >= 1.  logits_dbg as above or NULL;
+ * lse_dbg: device fp32[n_rows] or NULL, the lse of every row of this call. */
+int ddd_draft_step(ddd_ctx* ctx, int32_t step, const void* W_bf16, const void* hid_bf16, ddd_state* st,
+                   float* logits_dbg, float* lse_dbg, void* stream);
+
+/* Final top-m rerank of all pool nodes by (score desc, node id asc), tree order, mask,
+ * positions (Section 1: the tree is fed to the target model under a tree attention mask). */
+int ddd_tree_finalize(ddd_ctx* ctx, const ddd_state* st, ddd_tree* out, void* stream);
+
+/* Greedy accept walk (Section 1: tokens are verified until one is incorrect, then the token
+ * that should follow is emitted; Section 3.1: temperature 0).
+ *   target_argmax device int32[B,m+1]: the target model's argmax after each tree node
+ *   accept_len    device int32[B]:     accepted draft tokens
+ *   accept_path   device int32[B,max_depth+1]: tree indices root..last accepted, -1 padded
+ *   bonus_token   device int32[B]:     target_argmax at the last accepted node */
+int ddd_verify_accept(ddd_ctx* ctx, const ddd_tree* tree, const int32_t* target_argmax, int32_t* accept_len,
+                      int32_t* accept_path, int32_t* bonus_token, void* stream);
+
+/* Draft-model body supplied by the caller: must enqueue on `stream` the work that writes the
+ * hidden rows for draft call number step+1 into hid_out_bf16 ([B,H] for step 0, [B*k,H] after)
+ * from the current beam in *st; rows of inactive sequences may be left untouched.  It must not
+ * synchronise.  Returns 0 or a negative status. */
+typedef int (*ddd_draft_body_fn)(void* user, int32_t step, const ddd_state* st, void* hid_out_bf16, void* stream);
+/* Optional work enqueued after the tree is final (e.g. target model + ddd_verify_accept). */
+typedef int (*ddd_post_fn)(void* user, const ddd_state* st, const ddd_tree* tree, void* stream);
+
+/* Algorithm 1 end to end: reset, then max_depth draft calls (later calls are skipped on the
+ * device for sequences whose stop test failed), then ddd_tree_finalize and `post`.
+ * Only enqueues; usable inside or outside graph capture.
+ *   hid_buf    device bf16[B*k,H] scratch the draft body writes into
+ *   logits_dbg device fp32[max_depth, B*k, V] or NULL
+ *   lse_dbg    device fp32[max_depth, B*k] or NULL */
+int ddd_round_enqueue(ddd_ctx* ctx, const void* W_bf16, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
+                      void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,
+                      float* logits_dbg, float* lse_dbg, void* stream);
+
+/* Capture ddd_round_enqueue into a HIP graph owned by the context (replacing any earlier
+ * one), and launch it.  `stream` for capture must be a non-default stream. */
+int ddd_round_capture(ddd_ctx* ctx, const void* W_bf16, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
+                      void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,
+                      float* logits_dbg, float* lse_dbg, void* stream);
+int ddd_round_launch(ddd_ctx* ctx, void* stream);
+
+/* Introspection used by the benchmark: number of weight-stream workgroups (slices). */
+int ddd_num_slices(const ddd_ctx* ctx);
+
+/* Measurement helper (the one call that synchronises): launches the LM-head weight-stream
+ * kernel alone `iters` times on `stream` for n_rows <= DDD_STREAM_ROWS rows of hid_bf16, each
+ * launch bracketed by its own pair of HIP events recorded on that stream, waits for the last
+ * one and returns the mean and the minimum elapsed time per launch in milliseconds (host
+ * pointers).  Partial results go to the context scratch and are not consumed. */
+int ddd_profile_lmhead_stream(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, int32_t n_rows, int32_t iters,
+                              float* mean_ms, float* min_ms, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDD_H_ */

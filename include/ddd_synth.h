@@ -1,0 +1,58 @@
+/*
+ * ddd_synth.h - synthetic stand-ins for the two models the draft round talks to.
+ *
+ * These are workload generators for tests and the benchmark, not part of the method:
+ * the paper's draft body is EAGLE's trained layer and its target is a Vicuna / LLaMA2
+ * model (Section 3.1); neither is available, so a counter-based pseudo-Gaussian hidden
+ * state and a hashed target argmax take their place on the device.  The recipe is the
+ * one documented with the seeded input generators: SplitMix64 finaliser keys per
+ * (seed, sequence, round) and per (parent node, token); each element sums the four
+ * 16-bit fields of one mixed word, is centred, converted to fp32, multiplied by
+ * gain*(1+0.3*depth)/(65536/sqrt(3)), optionally shifted by a planted direction and
+ * rounded to bf16 (RNE).
+ */
+#ifndef DDD_SYNTH_H_
+#define DDD_SYNTH_H_
+
+#include "ddd.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ddd_synth_params {
+  ddd_config cfg;
+  uint64_t seed;
+  const int64_t* round_ctr;   /* device int64[1]: current round id (read on the device)          */
+  int32_t root_token;
+  int32_t n_plant;            /* rows of plant_dir, 0 = no planting                              */
+  float scale_depth[32];      /* fp32 scale for depth d, computed by the caller                  */
+  const float* plant_dir;     /* device fp32[n_plant,H] or NULL                                  */
+  uint32_t plant_round_p24;   /* a round is planted if its 24-bit hash is below this             */
+  uint32_t plant_row_p24;     /* a row is planted if its 24-bit hash is below this               */
+} ddd_synth_params;
+
+/* ddd_draft_body_fn: user = const ddd_synth_params* (host memory that outlives the call). */
+int ddd_synth_draft_body(void* user, int32_t step, const ddd_state* st, void* hid_out_bf16, void* stream);
+
+/* Hashed target argmax for every tree node: device int32[B,m+1] (padding = -1). */
+int ddd_synth_target_argmax(const ddd_synth_params* p, const ddd_state* st, const ddd_tree* tree,
+                            int32_t* target_argmax, void* stream);
+
+/* Adds 1 to *round_ctr on the device (enqueued; lets a captured round advance its own id). */
+int ddd_synth_next_round(int64_t* round_ctr, void* stream);
+
+/* End-of-round statistics kept on the device (no host synchronisation): for every sequence
+ * depth_hist[steps[b]] += 1 and accept_hist[accept_len[b]] += 1 (device int64[32] each, either
+ * may be NULL), then *round_ctr += 1. */
+int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_t* accept_len, int32_t B,
+                          int64_t* depth_hist, int64_t* accept_hist, void* stream);
+
+/* Plain coalesced read of n_bytes (multiple of 16) into a 4-byte checksum: the practical
+ * HBM read ceiling the weight stream is compared with. */
+int ddd_synth_read_stream(const void* src, size_t n_bytes, uint32_t* sink, int32_t n_blocks, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDD_SYNTH_H_ */

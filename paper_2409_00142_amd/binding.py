@@ -1,0 +1,309 @@
+"""ctypes binding of libddd.so.  Same names as the C ABI; argument marshalling only.
+
+torch is used for device memory and streams.  There is no CPU fallback: if the library has
+not been built, or no gfx950 device is present, the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Tuple
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libddd.so")
+
+DDD_OK = 0
+DDD_ERR_INVALID_ARG = -1
+DDD_ERR_NO_DEVICE = -2
+DDD_ERR_WRONG_ARCH = -3
+DDD_ERR_HIP = -4
+DDD_ERR_UNIMPLEMENTED = -5
+DDD_ERR_STATE = -6
+
+DDD_KMAX = 16
+DDD_MMAX = 128
+DDD_DMAX = 31
+DDD_POOL_MAX = 4096
+
+
+class DDDError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        lib = load_library()
+        msg = lib.ddd_strerror(code).decode()
+        hip = lib.ddd_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} ({code})" + (f" [{hip}]" if code == DDD_ERR_HIP and hip else ""))
+        self.code = code
+
+
+class ddd_config(C.Structure):
+    _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("V", C.c_int32), ("k", C.c_int32),
+                ("max_depth", C.c_int32), ("m", C.c_int32), ("threshold", C.c_float),
+                ("check_mask", C.c_uint32), ("flags", C.c_uint32)]
+
+
+_STATE_FIELDS = ["logprobsum", "beam_node", "beam_token", "beam_parent_slot", "pool_token", "pool_parent",
+                 "pool_depth", "pool_score", "n_nodes", "steps", "active", "row_active", "conf"]
+_TREE_FIELDS = ["sel_node", "n_sel", "tree_token", "pos", "parent_idx", "mask"]
+
+
+class ddd_state(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _STATE_FIELDS]
+
+
+class ddd_tree(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _TREE_FIELDS]
+
+
+class ddd_synth_params(C.Structure):
+    _fields_ = [("cfg", ddd_config), ("seed", C.c_uint64), ("round_ctr", C.c_void_p),
+                ("root_token", C.c_int32), ("n_plant", C.c_int32), ("scale_depth", C.c_float * 32),
+                ("plant_dir", C.c_void_p), ("plant_round_p24", C.c_uint32), ("plant_row_p24", C.c_uint32)]
+
+
+DRAFT_BODY_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int32, C.POINTER(ddd_state), C.c_void_p, C.c_void_p)
+POST_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(ddd_state), C.POINTER(ddd_tree), C.c_void_p)
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """dlopen libddd.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    cfgp, stp, trp = C.POINTER(ddd_config), C.POINTER(ddd_state), C.POINTER(ddd_tree)
+    sig = {
+        "ddd_strerror": (C.c_char_p, [C.c_int]),
+        "ddd_last_hip_error": (C.c_char_p, []),
+        "ddd_config_validate": (C.c_int, [cfgp]),
+        "ddd_pool_capacity": (sz, [cfgp]),
+        "ddd_scratch_bytes": (sz, [cfgp]),
+        "ddd_create": (C.c_int, [cfgp, C.POINTER(vp)]),
+        "ddd_destroy": (C.c_int, [vp]),
+        "ddd_num_slices": (C.c_int, [vp]),
+        "ddd_round_reset": (C.c_int, [vp, stp, vp, vp]),
+        "ddd_lmhead_topk": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]),
+        "ddd_beam_select": (C.c_int, [vp, i32, vp, vp, stp, vp]),
+        "ddd_depth_continue": (C.c_int, [vp, i32, stp, vp]),
+        "ddd_draft_step": (C.c_int, [vp, i32, vp, vp, stp, vp, vp, vp]),
+        "ddd_tree_finalize": (C.c_int, [vp, stp, trp, vp]),
+        "ddd_verify_accept": (C.c_int, [vp, trp, vp, vp, vp, vp, vp]),
+        "ddd_round_enqueue": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "ddd_round_capture": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "ddd_round_launch": (C.c_int, [vp, vp]),
+        "ddd_synth_draft_body": (C.c_int, [vp, i32, stp, vp, vp]),
+        "ddd_synth_target_argmax": (C.c_int, [C.POINTER(ddd_synth_params), stp, trp, vp, vp]),
+        "ddd_synth_next_round": (C.c_int, [vp, vp]),
+        "ddd_synth_read_stream": (C.c_int, [vp, sz, vp, i32, vp]),
+        "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp]),
+        "ddd_profile_lmhead_stream": (C.c_int, [vp, vp, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) pointer of a torch tensor / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _check(code: int, where: str) -> None:
+    if code != DDD_OK:
+        raise DDDError(code, where)
+
+
+def current_stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_config(B, H, V, k, max_depth, m, threshold, check_mask=0xFFFFFFFF) -> ddd_config:
+    return ddd_config(B, H, V, k, max_depth, m, float(threshold), check_mask & 0xFFFFFFFF, 0)
+
+
+def ddd_config_validate(cfg: ddd_config) -> int:
+    return load_library().ddd_config_validate(C.byref(cfg))
+
+
+def ddd_pool_capacity(cfg: ddd_config) -> int:
+    return load_library().ddd_pool_capacity(C.byref(cfg))
+
+
+def ddd_scratch_bytes(cfg: ddd_config) -> int:
+    return load_library().ddd_scratch_bytes(C.byref(cfg))
+
+
+def ddd_strerror(code: int) -> str:
+    return load_library().ddd_strerror(code).decode()
+
+
+def ddd_create(cfg: ddd_config) -> int:
+    out = C.c_void_p()
+    _check(load_library().ddd_create(C.byref(cfg), C.byref(out)), "ddd_create")
+    return out.value
+
+
+def ddd_destroy(ctx: int) -> None:
+    _check(load_library().ddd_destroy(ctx), "ddd_destroy")
+
+
+def ddd_num_slices(ctx: int) -> int:
+    return load_library().ddd_num_slices(ctx)
+
+
+def alloc_state(cfg: ddd_config, device="cuda") -> Tuple[ddd_state, Dict[str, "object"]]:
+    """Caller-owned device buffers of a ddd_state, as torch tensors, plus the struct of their pointers."""
+    import torch
+    B, k, nmax = cfg.B, cfg.k, ddd_pool_capacity(cfg)
+    i32, f32 = torch.int32, torch.float32
+    t = {
+        "logprobsum": torch.zeros(B, k, dtype=f32, device=device),
+        "beam_node": torch.zeros(B, k, dtype=i32, device=device),
+        "beam_token": torch.zeros(B, k, dtype=i32, device=device),
+        "beam_parent_slot": torch.zeros(B, k, dtype=i32, device=device),
+        "pool_token": torch.full((B, nmax), -1, dtype=i32, device=device),
+        "pool_parent": torch.full((B, nmax), -1, dtype=i32, device=device),
+        "pool_depth": torch.zeros(B, nmax, dtype=i32, device=device),
+        "pool_score": torch.zeros(B, nmax, dtype=f32, device=device),
+        "n_nodes": torch.ones(B, dtype=i32, device=device),
+        "steps": torch.zeros(B, dtype=i32, device=device),
+        "active": torch.ones(B, dtype=torch.uint8, device=device),
+        "row_active": torch.ones(B * k, dtype=torch.uint8, device=device),
+        "conf": torch.ones(B, dtype=torch.float64, device=device),
+    }
+    return ddd_state(*[t[n].data_ptr() for n in _STATE_FIELDS]), t
+
+
+def alloc_tree(cfg: ddd_config, device="cuda") -> Tuple[ddd_tree, Dict[str, "object"]]:
+    import torch
+    B, m = cfg.B, cfg.m
+    i32 = torch.int32
+    t = {
+        "sel_node": torch.full((B, m), -1, dtype=i32, device=device),
+        "n_sel": torch.zeros(B, dtype=i32, device=device),
+        "tree_token": torch.full((B, m + 1), -1, dtype=i32, device=device),
+        "pos": torch.zeros(B, m + 1, dtype=i32, device=device),
+        "parent_idx": torch.full((B, m + 1), -1, dtype=i32, device=device),
+        "mask": torch.zeros(B, m + 1, m + 1, dtype=torch.uint8, device=device),
+    }
+    return ddd_tree(*[t[n].data_ptr() for n in _TREE_FIELDS]), t
+
+
+def ddd_round_reset(ctx, st: ddd_state, root_token=None, stream=None) -> None:
+    _check(load_library().ddd_round_reset(ctx, C.byref(st), _ptr(root_token),
+                                          current_stream() if stream is None else stream), "ddd_round_reset")
+
+
+def ddd_lmhead_topk(ctx, W, hid, n_rows, row_active, topk_token, topk_logprob, lse, logits_dbg=None, stream=None):
+    _check(load_library().ddd_lmhead_topk(ctx, _ptr(W), _ptr(hid), n_rows, _ptr(row_active), _ptr(topk_token),
+                                          _ptr(topk_logprob), _ptr(lse), _ptr(logits_dbg),
+                                          current_stream() if stream is None else stream), "ddd_lmhead_topk")
+
+
+def ddd_beam_select(ctx, step, topk_token, topk_logprob, st: ddd_state, stream=None):
+    _check(load_library().ddd_beam_select(ctx, step, _ptr(topk_token), _ptr(topk_logprob), C.byref(st),
+                                          current_stream() if stream is None else stream), "ddd_beam_select")
+
+
+def ddd_depth_continue(ctx, steps_done, st: ddd_state, stream=None):
+    _check(load_library().ddd_depth_continue(ctx, steps_done, C.byref(st),
+                                             current_stream() if stream is None else stream), "ddd_depth_continue")
+
+
+def ddd_draft_step(ctx, step, W, hid, st: ddd_state, logits_dbg=None, lse_dbg=None, stream=None):
+    _check(load_library().ddd_draft_step(ctx, step, _ptr(W), _ptr(hid), C.byref(st), _ptr(logits_dbg), _ptr(lse_dbg),
+                                         current_stream() if stream is None else stream), "ddd_draft_step")
+
+
+def ddd_tree_finalize(ctx, st: ddd_state, tree: ddd_tree, stream=None):
+    _check(load_library().ddd_tree_finalize(ctx, C.byref(st), C.byref(tree),
+                                            current_stream() if stream is None else stream), "ddd_tree_finalize")
+
+
+def ddd_verify_accept(ctx, tree: ddd_tree, target_argmax, accept_len, accept_path, bonus_token, stream=None):
+    _check(load_library().ddd_verify_accept(ctx, C.byref(tree), _ptr(target_argmax), _ptr(accept_len),
+                                            _ptr(accept_path), _ptr(bonus_token),
+                                            current_stream() if stream is None else stream), "ddd_verify_accept")
+
+
+def _fn_ptr(fn) -> Optional[int]:
+    if fn is None:
+        return None
+    if isinstance(fn, int):
+        return fn
+    return C.cast(fn, C.c_void_p).value
+
+
+def ddd_round_enqueue(ctx, W, st, tree, root_token, hid_buf, body, body_user, post=None, post_user=None,
+                      logits_dbg=None, lse_dbg=None, stream=None):
+    _check(load_library().ddd_round_enqueue(ctx, _ptr(W), C.byref(st), C.byref(tree), _ptr(root_token), _ptr(hid_buf),
+                                            _fn_ptr(body), body_user, _fn_ptr(post), post_user, _ptr(logits_dbg),
+                                            _ptr(lse_dbg), current_stream() if stream is None else stream),
+           "ddd_round_enqueue")
+
+
+def ddd_round_capture(ctx, W, st, tree, root_token, hid_buf, body, body_user, post=None, post_user=None,
+                      logits_dbg=None, lse_dbg=None, stream=None):
+    _check(load_library().ddd_round_capture(ctx, _ptr(W), C.byref(st), C.byref(tree), _ptr(root_token), _ptr(hid_buf),
+                                            _fn_ptr(body), body_user, _fn_ptr(post), post_user, _ptr(logits_dbg),
+                                            _ptr(lse_dbg), current_stream() if stream is None else stream),
+           "ddd_round_capture")
+
+
+def ddd_round_launch(ctx, stream=None):
+    _check(load_library().ddd_round_launch(ctx, current_stream() if stream is None else stream), "ddd_round_launch")
+
+
+# ---- synthetic workload stand-ins (tests / benchmark) ----------------------------------------
+def synth_draft_body_ptr() -> int:
+    """Address of ddd_synth_draft_body, usable as the `body` argument of the round calls."""
+    return C.cast(load_library().ddd_synth_draft_body, C.c_void_p).value
+
+
+def ddd_synth_draft_body(params: ddd_synth_params, step, st: ddd_state, hid_out, stream=None):
+    _check(load_library().ddd_synth_draft_body(C.addressof(params), step, C.byref(st), _ptr(hid_out),
+                                               current_stream() if stream is None else stream), "ddd_synth_draft_body")
+
+
+def ddd_synth_target_argmax(params: ddd_synth_params, st: ddd_state, tree: ddd_tree, target_argmax, stream=None):
+    _check(load_library().ddd_synth_target_argmax(C.byref(params), C.byref(st), C.byref(tree), _ptr(target_argmax),
+                                                  current_stream() if stream is None else stream),
+           "ddd_synth_target_argmax")
+
+
+def ddd_synth_next_round(round_ctr, stream=None):
+    _check(load_library().ddd_synth_next_round(_ptr(round_ctr), current_stream() if stream is None else stream),
+           "ddd_synth_next_round")
+
+
+def ddd_synth_round_stats(round_ctr, steps, accept_len, B, depth_hist, accept_hist, stream=None):
+    _check(load_library().ddd_synth_round_stats(_ptr(round_ctr), _ptr(steps), _ptr(accept_len), B, _ptr(depth_hist),
+                                                _ptr(accept_hist), current_stream() if stream is None else stream),
+           "ddd_synth_round_stats")
+
+
+def ddd_profile_lmhead_stream(ctx, W, hid, n_rows, iters, stream=None):
+    """(mean_ms, min_ms) per launch of the weight-stream kernel alone; synchronises."""
+    mean, mn = C.c_float(), C.c_float()
+    _check(load_library().ddd_profile_lmhead_stream(ctx, _ptr(W), _ptr(hid), n_rows, iters, C.byref(mean), C.byref(mn),
+                                                    current_stream() if stream is None else stream),
+           "ddd_profile_lmhead_stream")
+    return mean.value, mn.value
+
+
+def ddd_synth_read_stream(src, n_bytes, sink, n_blocks, stream=None):
+    _check(load_library().ddd_synth_read_stream(_ptr(src), n_bytes, _ptr(sink), n_blocks,
+                                                current_stream() if stream is None else stream),
+           "ddd_synth_read_stream")

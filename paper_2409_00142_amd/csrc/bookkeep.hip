@@ -1,0 +1,288 @@
+// Per-row merge of the weight-stream partials, beam update and DDD stop test.
+//
+// merge_row      one wave per hidden row: combines the per-slice (max, sum of exponentials)
+//                into lse, and picks the row's top-k tokens: the k slices with the best
+//                heads contain every global top-k element, so only their k*k keys are ranked.
+// beam_update    one wave per sequence: score = logprobsum[parent] + logprob (one fp32 add),
+//                all k*k candidates go to the node pool, the k best by (score desc, token asc,
+//                flat index asc) become the new beam (Algorithm 1, "postprocess ... to
+//                produce the new beam", "calculate logprobsum").
+// stop_test      Eq. 1 in the probability domain: P = sum_i exp(logprobsum[i]) in fp64, index
+//                order; continue iff another call is allowed and (step not in S or P >= t).
+#include "ddd_device.hpp"
+#include "ddd_kernels.hpp"
+
+namespace ddd {
+
+constexpr int kKM = DDD_KMAX;
+
+// All 64 lanes of the calling wave must be active.  On return lane j < k holds the rank-j key.
+template <int HPL>
+__device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, const float* __restrict__ ps, int nslice,
+                                          int k, int lane, int* wl, uint64_t& my_key, float& lse) {
+  uint64_t head[HPL];
+  float psum[HPL];
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) {
+    const int s = lane + 64 * i;
+    head[i] = (s < nslice) ? pk[(size_t)s * k] : 0ull;
+    psum[i] = (s < nslice) ? ps[s] : 0.f;
+  }
+  uint64_t loc = 0;
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) loc = umax64(loc, head[i]);
+  const float M = key_value(wave_max_u64(loc));
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < HPL; ++i)
+    if (head[i] != 0ull) acc += psum[i] * __expf(key_value(head[i]) - M);
+  lse = M + __logf(wave_sum_f32(acc));
+
+  // the k slices with the largest heads
+  for (int round = 0; round < k; ++round) {
+    loc = 0;
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) loc = umax64(loc, head[i]);
+    const uint64_t best = wave_max_u64(loc);
+    if (best == 0ull) {
+      if (lane == 0) wl[round] = -1;
+    } else {
+#pragma unroll
+      for (int i = 0; i < HPL; ++i)
+        if (head[i] == best) {
+          wl[round] = lane + 64 * i;
+          head[i] = 0ull;
+        }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+
+  // rank their k*k keys
+  uint64_t cand[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int cidx = lane + 64 * i;
+    cand[i] = 0ull;
+    if (cidx < k * k) {
+      const int s = wl[cidx / k];
+      if (s >= 0) cand[i] = pk[(size_t)s * k + (cidx % k)];
+    }
+  }
+  my_key = 0ull;
+  for (int round = 0; round < k; ++round) {
+    loc = umax64(umax64(cand[0], cand[1]), umax64(cand[2], cand[3]));
+    const uint64_t best = wave_max_u64(loc);
+    if (lane == round) my_key = best;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (cand[i] == best) cand[i] = 0ull;
+  }
+}
+
+__device__ __forceinline__ void merge_row_dispatch(const uint64_t* pk, const float* ps, int nslice, int k, int lane,
+                                                   int* wl, uint64_t& my_key, float& lse) {
+  if (nslice <= 64)
+    merge_row<1>(pk, ps, nslice, k, lane, wl, my_key, lse);
+  else if (nslice <= 128)
+    merge_row<2>(pk, ps, nslice, k, lane, wl, my_key, lse);
+  else if (nslice <= 256)
+    merge_row<4>(pk, ps, nslice, k, lane, wl, my_key, lse);
+  else
+    merge_row<8>(pk, ps, nslice, k, lane, wl, my_key, lse);
+}
+
+// ---- standalone merge: one wave per row ------------------------------------------------------
+__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+  __shared__ int wl[4][kKM];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= a.n_rows) return;                                 // wave-uniform
+  if (a.row_active != nullptr && !a.row_active[row]) return;   // wave-uniform
+  uint64_t key;
+  float lse;
+  merge_row_dispatch(a.part_key + (size_t)row * a.nslice * a.k, a.part_sum + (size_t)row * a.nslice, a.nslice, a.k,
+                     lane, wl[wave], key, lse);
+  if (lane < a.k) {
+    a.topk_token[(size_t)row * a.k + lane] = key_token(key);
+    a.topk_logprob[(size_t)row * a.k + lane] = key_value(key) - lse;
+  }
+  if (lane == 0) a.lse[row] = lse;
+}
+
+hipError_t launch_merge(const MergeArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(merge_kernel, dim3((a.n_rows + 3) / 4), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ---- beam update by one wave (all 64 lanes active) -------------------------------------------
+// tok/lp: rows of k entries with the given row stride (LDS or global).
+// Returns the new logprobsum of beam slot `lane` (lanes >= k: 0).
+__device__ __forceinline__ float beam_update(const BeamArgs& a, int b, int lane, const int32_t* tok, const float* lp,
+                                             int stride) {
+  const int k = a.k, step = a.step;
+  float* lps = a.st.logprobsum + (size_t)b * k;
+  int32_t* bnode = a.st.beam_node + (size_t)b * k;
+  int32_t* btok = a.st.beam_token + (size_t)b * k;
+  int32_t* bslot = a.st.beam_parent_slot + (size_t)b * k;
+  int32_t* ptok = a.st.pool_token + (size_t)b * a.nmax;
+  int32_t* ppar = a.st.pool_parent + (size_t)b * a.nmax;
+  int32_t* pdep = a.st.pool_depth + (size_t)b * a.nmax;
+  float* psc = a.st.pool_score + (size_t)b * a.nmax;
+
+  float new_lps = 0.f;
+  if (step == 0) {
+    if (lane < k) {
+      const int nid = 1 + lane;
+      const int t = tok[lane];
+      const float s = lp[lane];
+      ptok[nid] = t;
+      ppar[nid] = 0;
+      pdep[nid] = 1;
+      psc[nid] = s;
+      bnode[lane] = nid;
+      btok[lane] = t;
+      bslot[lane] = 0;
+      lps[lane] = s;
+      new_lps = s;
+    }
+    if (lane == 0) a.st.n_nodes[b] = 1 + k;
+  } else {
+    const int base = 1 + k + (step - 1) * k * k;
+    uint64_t cand[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int f = lane + 64 * i;
+      cand[i] = 0ull;
+      if (f < k * k) {
+        const int slot = f / k, j = f - slot * k;
+        const int t = tok[slot * stride + j];
+        const float sc = __fadd_rn(lps[slot], lp[slot * stride + j]);
+        ptok[base + f] = t;
+        ppar[base + f] = bnode[slot];
+        pdep[base + f] = step + 1;
+        psc[base + f] = sc;
+        cand[i] = beam_key(sc, t, f);
+      }
+    }
+    uint64_t mine = 0ull;
+    for (int round = 0; round < k; ++round) {
+      const uint64_t loc = umax64(umax64(cand[0], cand[1]), umax64(cand[2], cand[3]));
+      const uint64_t best = wave_max_u64(loc);
+      if (lane == round) mine = best;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (cand[i] == best) cand[i] = 0ull;
+    }
+    if (lane < k) {
+      const int f = beam_key_flat(mine);
+      const int t = (int)(0xFFFFFFu - (((uint32_t)mine >> 8) & 0xFFFFFFu));
+      new_lps = key_value(mine);
+      bnode[lane] = base + f;
+      btok[lane] = t;
+      bslot[lane] = f / k;
+      lps[lane] = new_lps;
+    }
+    if (lane == 0) a.st.n_nodes[b] = base + k * k;
+  }
+  if (lane == 0) a.st.steps[b] = step + 1;
+  return new_lps;
+}
+
+// Stop test by one wave; lane i < k passes its logprobsum.  steps_done = draft calls made so far.
+__device__ __forceinline__ void stop_test(const BeamArgs& a, int b, int lane, float my_lps, int steps_done) {
+  const double e = (lane < a.k) ? exp((double)my_lps) : 0.0;
+  double P = 0.0;
+  for (int i = 0; i < a.k; ++i) {
+    const int lo = __shfl((int)(uint32_t)__double_as_longlong(e), i, 64);
+    const int hi = __shfl((int)(uint32_t)((unsigned long long)__double_as_longlong(e) >> 32), i, 64);
+    P += __longlong_as_double((long long)(((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo));
+  }
+  bool cont = steps_done < a.D;
+  if (cont && ((a.check_mask >> steps_done) & 1u) && P < (double)a.threshold) cont = false;
+  if (lane == 0) {
+    a.st.conf[b] = P;
+    a.st.active[b] = cont ? 1 : 0;
+  }
+  if (lane < a.k) a.st.row_active[(size_t)b * a.k + lane] = cont ? 1 : 0;
+}
+
+__global__ __launch_bounds__(64) void beam_select_kernel(BeamArgs a) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  if (!a.st.active[b]) return;
+  const size_t row0 = (a.step == 0) ? (size_t)b : (size_t)b * a.k;
+  beam_update(a, b, lane, a.topk_token + row0 * a.k, a.topk_logprob + row0 * a.k, a.k);
+}
+
+__global__ __launch_bounds__(64) void depth_continue_kernel(BeamArgs a, int steps_done) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  if (!a.st.active[b]) return;
+  const float v = (lane < a.k) ? a.st.logprobsum[(size_t)b * a.k + lane] : 0.f;
+  stop_test(a, b, lane, v, steps_done);
+}
+
+hipError_t launch_beam_select(const BeamArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(beam_select_kernel, dim3(a.B), dim3(64), 0, stream, a);
+  return hipGetLastError();
+}
+hipError_t launch_depth_continue(const BeamArgs& a, int steps_done, hipStream_t stream) {
+  hipLaunchKernelGGL(depth_continue_kernel, dim3(a.B), dim3(64), 0, stream, a, steps_done);
+  return hipGetLastError();
+}
+
+// ---- one launch per draft call: merge of the sequence's rows, beam update, stop test ----------
+__global__ __launch_bounds__(1024) void step_bookkeep_kernel(StepArgs a) {
+  __shared__ int wl[kKM][kKM];
+  __shared__ int s_tok[kKM][kKM];
+  __shared__ float s_lp[kKM][kKM];
+  const BeamArgs& g = a.beam;
+  const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (!g.st.active[b]) return;                    // uniform over the workgroup
+  const int rows = (g.step == 0) ? 1 : g.k;
+  const size_t row0 = (g.step == 0) ? (size_t)b : (size_t)b * g.k;
+  if (wave < rows) {
+    uint64_t key;
+    float lse;
+    const size_t row = row0 + wave;
+    merge_row_dispatch(a.part_key + row * a.nslice * g.k, a.part_sum + row * a.nslice, a.nslice, g.k, lane, wl[wave],
+                       key, lse);
+    if (lane < g.k) {
+      s_tok[wave][lane] = key_token(key);
+      s_lp[wave][lane] = key_value(key) - lse;
+    }
+    if (a.lse_dbg != nullptr && lane == 0) a.lse_dbg[row] = lse;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const float v = beam_update(g, b, lane, &s_tok[0][0], &s_lp[0][0], kKM);
+    stop_test(g, b, lane, v, g.step + 1);
+  }
+}
+
+hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(step_bookkeep_kernel, dim3(a.beam.B), dim3(64 * a.beam.k), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ---- start of a round ------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void round_reset_kernel(ResetArgs a) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  if (lane == 0) {
+    a.st.pool_token[(size_t)b * a.nmax] = a.root_token ? a.root_token[b] : -1;
+    a.st.pool_parent[(size_t)b * a.nmax] = -1;
+    a.st.pool_depth[(size_t)b * a.nmax] = 0;
+    a.st.pool_score[(size_t)b * a.nmax] = 0.f;
+    a.st.n_nodes[b] = 1;
+    a.st.steps[b] = 0;
+    a.st.active[b] = 1;
+    a.st.conf[b] = 1.0;
+  }
+  if (lane < a.k) a.st.row_active[(size_t)b * a.k + lane] = 1;
+}
+
+hipError_t launch_round_reset(const ResetArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(round_reset_kernel, dim3(a.B), dim3(64), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace ddd

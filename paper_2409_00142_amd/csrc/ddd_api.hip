@@ -1,0 +1,398 @@
+// C ABI of the DDD draft-round library: validation, context, dispatch, round orchestration.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ddd_kernels.hpp"
+
+using namespace ddd;
+
+struct ddd_ctx {
+  ddd_config cfg;
+  int device;
+  int n_cu;
+  int G, nw;            // K split of the weight stream: H == 128 * G * nw
+  int ntiles, nslice;   // 16-row tiles of W, workgroups of the weight stream
+  int nmax;
+  uint64_t* part_key;   // [B*k][nslice][k]
+  float* part_sum;      // [B*k][nslice]
+  hipGraph_t graph;
+  hipGraphExec_t graph_exec;
+};
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+int hip_fail(hipError_t e, const char* what) {
+  std::snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
+  return DDD_ERR_HIP;
+}
+#define DDD_HIP(call)                                 \
+  do {                                                \
+    hipError_t e_ = (call);                           \
+    if (e_ != hipSuccess) return hip_fail(e_, #call); \
+  } while (0)
+
+// K split: the smallest G in {1,2,4} with H == 128*G*nw and nw <= 10 streaming waves
+// (10 waves keep the dynamic LDS of the weight stream under 64 KB).
+bool pick_split(int H, int* G, int* nw) {
+  for (int g = 1; g <= 4; g <<= 1) {
+    if (H % (128 * g) != 0) continue;
+    const int w = H / (128 * g);
+    if (w >= 1 && w <= 10) {
+      *G = g;
+      *nw = w;
+      return true;
+    }
+  }
+  return false;
+}
+
+bool state_ok(const ddd_state* s) {
+  return s && s->logprobsum && s->beam_node && s->beam_token && s->beam_parent_slot && s->pool_token &&
+         s->pool_parent && s->pool_depth && s->pool_score && s->n_nodes && s->steps && s->active && s->row_active &&
+         s->conf;
+}
+bool tree_ok(const ddd_tree* t) {
+  return t && t->sel_node && t->n_sel && t->tree_token && t->pos && t->parent_idx && t->mask;
+}
+
+BeamArgs beam_args(const ddd_ctx* c, const ddd_state* st, int step) {
+  BeamArgs a;
+  a.st = *st;
+  a.topk_token = nullptr;
+  a.topk_logprob = nullptr;
+  a.B = c->cfg.B;
+  a.k = c->cfg.k;
+  a.D = c->cfg.max_depth;
+  a.nmax = c->nmax;
+  a.step = step;
+  a.threshold = c->cfg.threshold;
+  a.check_mask = c->cfg.check_mask;
+  return a;
+}
+
+// Weight stream over n_rows rows in passes of DDD_STREAM_ROWS, partials into the context scratch.
+int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const uint8_t* row_active, float* logits_dbg,
+                   hipStream_t s) {
+  for (int r0 = 0; r0 < n_rows; r0 += DDD_STREAM_ROWS) {
+    StreamArgs a;
+    a.W = static_cast<const uint16_t*>(W);
+    a.hid = static_cast<const uint16_t*>(hid) + (size_t)r0 * c->cfg.H;
+    a.row_active = row_active ? row_active + r0 : nullptr;
+    a.part_key = c->part_key + (size_t)r0 * c->nslice * c->cfg.k;
+    a.part_sum = c->part_sum + (size_t)r0 * c->nslice;
+    a.logits_dbg = logits_dbg ? logits_dbg + (size_t)r0 * c->cfg.V : nullptr;
+    a.H = c->cfg.H;
+    a.V = c->cfg.V;
+    a.R = (n_rows - r0 < DDD_STREAM_ROWS) ? (n_rows - r0) : DDD_STREAM_ROWS;
+    a.k = c->cfg.k;
+    a.ntiles = c->ntiles;
+    a.nw = c->nw;
+    DDD_HIP(launch_lmhead_stream(a, c->G, c->nslice, s));
+  }
+  return DDD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ddd_strerror(int code) {
+  switch (code) {
+    case DDD_OK: return "ok";
+    case DDD_ERR_INVALID_ARG: return "invalid argument";
+    case DDD_ERR_NO_DEVICE: return "no HIP device";
+    case DDD_ERR_WRONG_ARCH: return "device is not gfx950";
+    case DDD_ERR_HIP: return "HIP runtime error";
+    case DDD_ERR_UNIMPLEMENTED: return "not implemented";
+    case DDD_ERR_STATE: return "call not valid in the current state";
+    default: return "unknown status";
+  }
+}
+
+const char* ddd_last_hip_error(void) { return g_hip_err; }
+
+int ddd_config_validate(const ddd_config* cfg) {
+  if (cfg == nullptr) return DDD_ERR_INVALID_ARG;
+  if (cfg->B < 1 || cfg->B > 4096) return DDD_ERR_INVALID_ARG;
+  if (cfg->k < 1 || cfg->k > DDD_KMAX) return DDD_ERR_INVALID_ARG;
+  if (cfg->V < cfg->k || cfg->V >= (1 << 24)) return DDD_ERR_INVALID_ARG;
+  if (cfg->max_depth < 1 || cfg->max_depth > DDD_DMAX) return DDD_ERR_INVALID_ARG;
+  if (cfg->m < 1 || cfg->m > DDD_MMAX) return DDD_ERR_INVALID_ARG;
+  if (!(cfg->threshold >= 0.0f)) return DDD_ERR_INVALID_ARG;   // also rejects NaN
+  if (cfg->flags != 0) return DDD_ERR_INVALID_ARG;
+  int G, nw;
+  if (cfg->H < 128 || !pick_split(cfg->H, &G, &nw)) return DDD_ERR_INVALID_ARG;
+  const long long nmax = 1LL + cfg->k + (long long)(cfg->max_depth - 1) * cfg->k * cfg->k;
+  if (nmax > DDD_POOL_MAX) return DDD_ERR_INVALID_ARG;
+  return DDD_OK;
+}
+
+size_t ddd_pool_capacity(const ddd_config* cfg) {
+  if (ddd_config_validate(cfg) != DDD_OK) return 0;
+  return (size_t)1 + cfg->k + (size_t)(cfg->max_depth - 1) * cfg->k * cfg->k;
+}
+
+size_t ddd_scratch_bytes(const ddd_config* cfg) {
+  if (ddd_config_validate(cfg) != DDD_OK) return 0;
+  const size_t rows = (size_t)cfg->B * cfg->k, max_slices = 512;
+  return rows * max_slices * cfg->k * sizeof(uint64_t) + rows * max_slices * sizeof(float);
+}
+
+int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
+  if (out == nullptr) return DDD_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (ddd_config_validate(cfg) != DDD_OK) return DDD_ERR_INVALID_ARG;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+    (void)hipGetLastError();
+    return DDD_ERR_NO_DEVICE;
+  }
+  int dev = 0;
+  DDD_HIP(hipGetDevice(&dev));
+  hipDeviceProp_t prop;
+  DDD_HIP(hipGetDeviceProperties(&prop, dev));
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return DDD_ERR_WRONG_ARCH;
+
+  ddd_ctx* c = new (std::nothrow) ddd_ctx();
+  if (c == nullptr) return DDD_ERR_INVALID_ARG;
+  c->cfg = *cfg;
+  c->device = dev;
+  c->n_cu = prop.multiProcessorCount;
+  pick_split(cfg->H, &c->G, &c->nw);
+  c->ntiles = (cfg->V + 15) / 16;
+  c->nslice = c->n_cu < 512 ? c->n_cu : 512;
+  if (c->nslice > c->ntiles) c->nslice = c->ntiles;
+  c->nmax = (int)ddd_pool_capacity(cfg);
+  c->graph = nullptr;
+  c->graph_exec = nullptr;
+  const size_t rows = (size_t)cfg->B * cfg->k;
+  hipError_t e = hipMalloc(&c->part_key, rows * c->nslice * cfg->k * sizeof(uint64_t));
+  if (e == hipSuccess) e = hipMalloc(&c->part_sum, rows * c->nslice * sizeof(float));
+  if (e != hipSuccess) {
+    if (c->part_key) (void)hipFree(c->part_key);
+    delete c;
+    return hip_fail(e, "hipMalloc(scratch)");
+  }
+  *out = c;
+  return DDD_OK;
+}
+
+int ddd_destroy(ddd_ctx* c) {
+  if (c == nullptr) return DDD_ERR_INVALID_ARG;
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+  if (c->graph) (void)hipGraphDestroy(c->graph);
+  (void)hipFree(c->part_key);
+  (void)hipFree(c->part_sum);
+  delete c;
+  return DDD_OK;
+}
+
+int ddd_num_slices(const ddd_ctx* c) { return c ? c->nslice : DDD_ERR_INVALID_ARG; }
+
+int ddd_profile_lmhead_stream(ddd_ctx* c, const void* W, const void* hid, int32_t n_rows, int32_t iters,
+                              float* mean_ms, float* min_ms, void* stream) {
+  if (c == nullptr || W == nullptr || hid == nullptr || mean_ms == nullptr || min_ms == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  if (n_rows < 1 || n_rows > DDD_STREAM_ROWS || n_rows > c->cfg.B * c->cfg.k || iters < 1 || iters > 4096)
+    return DDD_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::vector<hipEvent_t> ev(2 * (size_t)iters, nullptr);
+  int rc = DDD_OK;
+  for (size_t i = 0; i < ev.size() && rc == DDD_OK; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) rc = DDD_ERR_HIP;
+  for (int i = 0; i < iters && rc == DDD_OK; ++i) {
+    if (hipEventRecord(ev[2 * i], s) != hipSuccess) rc = DDD_ERR_HIP;
+    if (rc == DDD_OK) rc = enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, s);
+    if (rc == DDD_OK && hipEventRecord(ev[2 * i + 1], s) != hipSuccess) rc = DDD_ERR_HIP;
+  }
+  if (rc == DDD_OK && hipEventSynchronize(ev[2 * (size_t)iters - 1]) != hipSuccess) rc = DDD_ERR_HIP;
+  if (rc == DDD_OK) {
+    double sum = 0.0;
+    float mn = 1e30f;
+    for (int i = 0; i < iters; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]) != hipSuccess) {
+        rc = DDD_ERR_HIP;
+        break;
+      }
+      sum += ms;
+      mn = ms < mn ? ms : mn;
+    }
+    *mean_ms = (float)(sum / iters);
+    *min_ms = mn;
+  }
+  for (hipEvent_t e : ev)
+    if (e) (void)hipEventDestroy(e);
+  return rc;
+}
+
+int ddd_round_reset(ddd_ctx* c, ddd_state* st, const int32_t* root_token, void* stream) {
+  if (c == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
+  ResetArgs a;
+  a.st = *st;
+  a.root_token = root_token;
+  a.B = c->cfg.B;
+  a.k = c->cfg.k;
+  a.nmax = c->nmax;
+  DDD_HIP(launch_round_reset(a, static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
+int ddd_lmhead_topk(ddd_ctx* c, const void* W, const void* hid, int32_t n_rows, const uint8_t* row_active,
+                    int32_t* topk_token, float* topk_logprob, float* lse, float* logits_dbg, void* stream) {
+  if (c == nullptr || W == nullptr || hid == nullptr || topk_token == nullptr || topk_logprob == nullptr ||
+      lse == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  if (n_rows < 1 || n_rows > c->cfg.B * c->cfg.k) return DDD_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int rc = enqueue_stream(c, W, hid, n_rows, row_active, logits_dbg, s);
+  if (rc != DDD_OK) return rc;
+  MergeArgs m;
+  m.part_key = c->part_key;
+  m.part_sum = c->part_sum;
+  m.row_active = row_active;
+  m.topk_token = topk_token;
+  m.topk_logprob = topk_logprob;
+  m.lse = lse;
+  m.n_rows = n_rows;
+  m.nslice = c->nslice;
+  m.k = c->cfg.k;
+  DDD_HIP(launch_merge(m, s));
+  return DDD_OK;
+}
+
+int ddd_beam_select(ddd_ctx* c, int32_t step, const int32_t* topk_token, const float* topk_logprob, ddd_state* st,
+                    void* stream) {
+  if (c == nullptr || topk_token == nullptr || topk_logprob == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
+  if (step < 0 || step >= c->cfg.max_depth) return DDD_ERR_INVALID_ARG;
+  BeamArgs a = beam_args(c, st, step);
+  a.topk_token = topk_token;
+  a.topk_logprob = topk_logprob;
+  DDD_HIP(launch_beam_select(a, static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
+int ddd_depth_continue(ddd_ctx* c, int32_t steps_done, ddd_state* st, void* stream) {
+  if (c == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
+  if (steps_done < 1 || steps_done > c->cfg.max_depth) return DDD_ERR_INVALID_ARG;
+  BeamArgs a = beam_args(c, st, steps_done - 1);
+  DDD_HIP(launch_depth_continue(a, steps_done, static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
+int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_state* st, float* logits_dbg,
+                   float* lse_dbg, void* stream) {
+  if (c == nullptr || W == nullptr || hid == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
+  if (step < 0 || step >= c->cfg.max_depth) return DDD_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int n_rows = (step == 0) ? c->cfg.B : c->cfg.B * c->cfg.k;
+  // step 0 rows are one per sequence: active[] is the row flag; later rows use row_active[]
+  const uint8_t* flags = (step == 0) ? st->active : st->row_active;
+  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, s);
+  if (rc != DDD_OK) return rc;
+  StepArgs a;
+  a.beam = beam_args(c, st, step);
+  a.part_key = c->part_key;
+  a.part_sum = c->part_sum;
+  a.lse_dbg = lse_dbg;
+  a.nslice = c->nslice;
+  DDD_HIP(launch_step_bookkeep(a, s));
+  return DDD_OK;
+}
+
+int ddd_tree_finalize(ddd_ctx* c, const ddd_state* st, ddd_tree* out, void* stream) {
+  if (c == nullptr || !state_ok(st) || !tree_ok(out)) return DDD_ERR_INVALID_ARG;
+  FinalizeArgs a;
+  a.st = *st;
+  a.tree = *out;
+  a.B = c->cfg.B;
+  a.k = c->cfg.k;
+  a.m = c->cfg.m;
+  a.nmax = c->nmax;
+  DDD_HIP(launch_tree_finalize(a, static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
+int ddd_verify_accept(ddd_ctx* c, const ddd_tree* tree, const int32_t* target_argmax, int32_t* accept_len,
+                      int32_t* accept_path, int32_t* bonus_token, void* stream) {
+  if (c == nullptr || !tree_ok(tree) || target_argmax == nullptr || accept_len == nullptr || accept_path == nullptr ||
+      bonus_token == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  VerifyArgs a;
+  a.tree = *tree;
+  a.target_argmax = target_argmax;
+  a.accept_len = accept_len;
+  a.accept_path = accept_path;
+  a.bonus_token = bonus_token;
+  a.B = c->cfg.B;
+  a.m = c->cfg.m;
+  a.D = c->cfg.max_depth;
+  DDD_HIP(launch_verify_accept(a, static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
+int ddd_round_enqueue(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
+                      void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,
+                      float* logits_dbg, float* lse_dbg, void* stream) {
+  if (c == nullptr || W == nullptr || !state_ok(st) || !tree_ok(tree) || hid_buf == nullptr || body == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  int rc = ddd_round_reset(c, st, root_token, stream);
+  if (rc != DDD_OK) return rc;
+  const size_t dbg_stride = (size_t)c->cfg.B * c->cfg.k * c->cfg.V;
+  for (int step = 0; step < c->cfg.max_depth; ++step) {
+    rc = body(body_user, step, st, hid_buf, stream);
+    if (rc != DDD_OK) return rc;
+    rc = ddd_draft_step(c, step, W, hid_buf, st, logits_dbg ? logits_dbg + dbg_stride * step : nullptr,
+                        lse_dbg ? lse_dbg + (size_t)c->cfg.B * c->cfg.k * step : nullptr, stream);
+    if (rc != DDD_OK) return rc;
+  }
+  rc = ddd_tree_finalize(c, st, tree, stream);
+  if (rc != DDD_OK) return rc;
+  if (post != nullptr) rc = post(post_user, st, tree, stream);
+  return rc;
+}
+
+int ddd_round_capture(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
+                      void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,
+                      float* logits_dbg, float* lse_dbg, void* stream) {
+  if (c == nullptr || stream == nullptr) return DDD_ERR_INVALID_ARG;
+  if (W == nullptr || !state_ok(st) || !tree_ok(tree) || hid_buf == nullptr || body == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DDD_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+  int rc = ddd_round_enqueue(c, W, st, tree, root_token, hid_buf, body, body_user, post, post_user, logits_dbg,
+                             lse_dbg, stream);
+  hipGraph_t g = nullptr;
+  hipError_t e = hipStreamEndCapture(s, &g);
+  if (rc != DDD_OK) {
+    if (g) (void)hipGraphDestroy(g);
+    return rc;
+  }
+  if (e != hipSuccess) return hip_fail(e, "hipStreamEndCapture");
+  hipGraphExec_t ge = nullptr;
+  e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+  if (e != hipSuccess) {
+    (void)hipGraphDestroy(g);
+    return hip_fail(e, "hipGraphInstantiate");
+  }
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+  if (c->graph) (void)hipGraphDestroy(c->graph);
+  c->graph = g;
+  c->graph_exec = ge;
+  return DDD_OK;
+}
+
+int ddd_round_launch(ddd_ctx* c, void* stream) {
+  if (c == nullptr) return DDD_ERR_INVALID_ARG;
+  if (c->graph_exec == nullptr) return DDD_ERR_STATE;
+  DDD_HIP(hipGraphLaunch(c->graph_exec, static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Host-visible argument blocks and launchers of the DDD kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ddd.h"
+
+namespace ddd {
+
+// ---- LM-head weight stream (lmhead_stream.hip) ------------------------------------------------
+struct StreamArgs {
+  const uint16_t* W;          // bf16 [V,H]
+  const uint16_t* hid;        // bf16 [R,H], first row of this pass
+  const uint8_t* row_active;  // [R] or null
+  uint64_t* part_key;         // [R][nslice][k], first row of this pass
+  float* part_sum;            // [R][nslice]
+  float* logits_dbg;          // fp32 [R][V] or null
+  int H, V, R, k, ntiles, nw;
+};
+// G = 128-wide K groups per streaming wave (1, 2 or 4); H == 128 * G * nw.
+hipError_t launch_lmhead_stream(const StreamArgs& a, int G, int nslice, hipStream_t stream);
+
+// ---- per-row merge, beam select, stop test (bookkeep.hip) -------------------------------------
+struct MergeArgs {
+  const uint64_t* part_key;   // [n_rows][nslice][k]
+  const float* part_sum;      // [n_rows][nslice]
+  const uint8_t* row_active;  // [n_rows] or null
+  int32_t* topk_token;        // [n_rows,k]
+  float* topk_logprob;        // [n_rows,k]
+  float* lse;                 // [n_rows]
+  int n_rows, nslice, k;
+};
+hipError_t launch_merge(const MergeArgs& a, hipStream_t stream);
+
+struct BeamArgs {
+  ddd_state st;
+  const int32_t* topk_token;  // [B] or [B*k] rows of k
+  const float* topk_logprob;
+  int B, k, D, nmax, step;
+  float threshold;
+  uint32_t check_mask;
+};
+hipError_t launch_beam_select(const BeamArgs& a, hipStream_t stream);
+hipError_t launch_depth_continue(const BeamArgs& a, int steps_done, hipStream_t stream);
+
+struct StepArgs {             // merge + beam select + stop test in one launch
+  BeamArgs beam;              // topk_* unused
+  const uint64_t* part_key;   // [B*k][nslice][k]
+  const float* part_sum;
+  float* lse_dbg;             // [B*k] or null: lse of every merged row
+  int nslice;
+};
+hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream);
+
+struct ResetArgs {
+  ddd_state st;
+  const int32_t* root_token;  // [B] or null
+  int B, k, nmax;
+};
+hipError_t launch_round_reset(const ResetArgs& a, hipStream_t stream);
+
+// ---- final tree and accept walk (tree.hip) ----------------------------------------------------
+struct FinalizeArgs {
+  ddd_state st;
+  ddd_tree tree;
+  int B, k, m, nmax;
+};
+hipError_t launch_tree_finalize(const FinalizeArgs& a, hipStream_t stream);
+
+struct VerifyArgs {
+  ddd_tree tree;
+  const int32_t* target_argmax;  // [B,m+1]
+  int32_t* accept_len;           // [B]
+  int32_t* accept_path;          // [B,D+1]
+  int32_t* bonus_token;          // [B]
+  int B, m, D;
+};
+hipError_t launch_verify_accept(const VerifyArgs& a, hipStream_t stream);
+
+}  // namespace ddd

@@ -1,0 +1,220 @@
+// LM-head weight stream with fused online logsoftmax statistics and per-slice top-k.
+//
+// Computes, for R <= 16 hidden rows, logits[r,v] = sum_h hid[r,h] * W[v,h] (bf16 in, fp32
+// accumulate) for every vocabulary row v, reading W exactly once, and leaves per
+// (row, slice) partial results: the slice's k best (logit, token) keys in order and
+// sum_v exp(logit - slice max).  A slice is the contiguous range of 16-row tiles owned by
+// one workgroup.  The full logits are never written unless a debug buffer is given.
+//
+// Workgroup = NW streaming waves + 1 epilogue wave.
+//  * Streaming wave w owns the K-slice [w*KS, (w+1)*KS) of the hidden dimension, KS = 128*G.
+//    Its share of the hidden rows sits in registers as MFMA B operands for the whole
+//    kernel.  For each 16-row tile of W it issues fully coalesced 16-byte loads (one
+//    instruction = 4 rows x 256 contiguous bytes), keeps G*4 of them in flight (a register
+//    ring that always holds the next tile), transposes each 16x128 group through a private
+//    LDS stage into the MFMA A layout and accumulates v_mfma_f32_16x16x32_bf16 into one
+//    16x16 fp32 tile; the tile is published to LDS and the workgroup meets at a barrier.
+//  * The epilogue wave sums the NW partial tiles in a fixed order (so equal W rows give
+//    bit-equal logits) and lane r < 16 keeps row r's running max, running sum of
+//    exponentials and sorted top-k list in registers while the streaming waves are already
+//    loading the next tile.
+#include "ddd_device.hpp"
+#include "ddd_kernels.hpp"
+
+namespace ddd {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+constexpr int kStagePitch = 272;               // 256 B of a row group + 16 B pad: conflict-free b128 reads
+constexpr int kStageBytes = 16 * kStagePitch;  // one 16x128 bf16 group
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// One 16-row tile of one streaming wave: drain the register ring group by group through the
+// LDS stage into MFMA operands; with REFILL each drained group is reloaded for the next tile.
+template <int G, bool REFILL>
+__device__ __forceinline__ f32x4 stream_tile(u32x4 (&ring)[G][4], const bf16x8 (&bfrag)[G][4], unsigned char* mystage,
+                                             int wr_off, int rd_off, const uint16_t* wbase, int H, int next_row0,
+                                             int vlast) {
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(mystage + wr_off + i * 4 * kStagePitch) = ring[g][i];
+    if (REFILL) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = min(next_row0 + i * 4, vlast);
+        ring[g][i] = *reinterpret_cast<const u32x4*>(wbase + (size_t)row * H + g * 128);
+      }
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const u32x4 u = *reinterpret_cast<const u32x4*>(mystage + rd_off + j * 64);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, u), bfrag[g][j], acc, 0, 0, 0);
+    }
+    wave_lds_fence();
+  }
+  return acc;
+}
+
+template <int G, int KL>
+__global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int NW = a.nw;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+
+  if (a.row_active != nullptr) {  // nothing to do if every row of this pass is inactive (uniform)
+    int any = 0;
+    for (int r = 0; r < a.R; ++r) any |= a.row_active[r];
+    if (!any) return;
+  }
+
+  const int nslice = gridDim.x, slice = blockIdx.x;
+  const int t0 = (int)(((long long)slice * a.ntiles) / nslice);
+  const int t1 = (int)(((long long)(slice + 1) * a.ntiles) / nslice);
+  const int nt = t1 - t0;
+
+  float* red = reinterpret_cast<float*>(smem);      // [2][NW][256] fp32 partial tiles
+  unsigned char* stage = smem + 2 * NW * 1024;      // [NW][kStageBytes]
+
+  if (wave < NW) {
+    // ------------------------------ streaming wave ------------------------------
+    const int ks = wave * (128 * G);
+    const int n = lane & 15, q = lane >> 4;          // MFMA operand coordinates
+    bf16x8 bfrag[G][4];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        u32x4 u = {0u, 0u, 0u, 0u};
+        if (n < a.R) u = *reinterpret_cast<const u32x4*>(a.hid + (size_t)n * a.H + ks + g * 128 + j * 32 + q * 8);
+        bfrag[g][j] = __builtin_bit_cast(bf16x8, u);
+      }
+
+    const int lrow = lane >> 4, c = lane & 15;       // load coordinates: 4 rows x 16 chunks per instruction
+    unsigned char* mystage = stage + wave * kStageBytes;
+    const int wr_off = lrow * kStagePitch + c * 16;
+    const int rd_off = n * kStagePitch + q * 16;
+    const uint16_t* wbase = a.W + ks + c * 8;
+    const int vlast = a.V - 1;
+
+    u32x4 ring[G][4];
+    {
+      const int v0 = t0 * 16;   // in range also when this slice owns no tile: rows are clamped
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          int row = min(v0 + i * 4 + lrow, vlast);
+          ring[g][i] = *reinterpret_cast<const u32x4*>(wbase + (size_t)row * a.H + g * 128);
+        }
+    }
+    // every tile but the last refills the ring with the next tile while it is consumed
+    for (int t = 0; t + 1 < nt; ++t) {
+      const f32x4 acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, (t0 + t + 1) * 16 + lrow,
+                                             vlast);
+      *reinterpret_cast<f32x4*>(red + ((t & 1) * NW + wave) * 256 + lane * 4) = acc;
+      __syncthreads();
+    }
+    if (nt > 0) {
+      const int t = nt - 1;
+      const f32x4 acc = stream_tile<G, false>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, 0, vlast);
+      *reinterpret_cast<f32x4*>(red + ((t & 1) * NW + wave) * 256 + lane * 4) = acc;
+      __syncthreads();
+    }
+  } else {
+    // ------------------------------ epilogue wave ------------------------------
+    const int r = lane;
+    const bool row_ok = (lane < 16) && (r < a.R);
+    float m_run = -INFINITY, s_run = 0.f;
+    uint64_t list[KL];
+#pragma unroll
+    for (int j = 0; j < KL; ++j) list[j] = 0;
+
+    for (int t = 0; t < nt; ++t) {
+      __syncthreads();
+      if (row_ok) {
+        float x[16];
+#pragma unroll
+        for (int vb = 0; vb < 4; ++vb) {
+          f32x4 s = {0.f, 0.f, 0.f, 0.f};
+          for (int w = 0; w < NW; ++w)
+            s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + (vb * 16 + r) * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[vb * 4 + e] = s[e] + 0.0f;   // -0 -> +0
+        }
+        const int v0 = (t0 + t) * 16;
+        const int nv = min(16, a.V - v0);
+        if (a.logits_dbg != nullptr) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (e < nv) a.logits_dbg[(size_t)r * a.V + v0 + e] = x[e];
+        }
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (e < nv) tmax = fmaxf(tmax, x[e]);
+        const float m_new = fmaxf(m_run, tmax);
+        float s_new = s_run * __expf(m_run - m_new);
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (e < nv) s_new += __expf(x[e] - m_new);
+        m_run = m_new;
+        s_run = s_new;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          uint64_t cur = row_key(x[e], v0 + e);
+          if (e < nv && cur > list[KL - 1]) {
+#pragma unroll
+            for (int j = 0; j < KL; ++j) {
+              const bool gt = cur > list[j];
+              const uint64_t hi = gt ? cur : list[j];
+              cur = gt ? list[j] : cur;
+              list[j] = hi;
+            }
+          }
+        }
+      }
+    }
+    if (row_ok) {
+      a.part_sum[(size_t)r * nslice + slice] = s_run;
+      uint64_t* pk = a.part_key + ((size_t)r * nslice + slice) * a.k;
+#pragma unroll
+      for (int j = 0; j < KL; ++j)
+        if (j < a.k) pk[j] = list[j];
+    }
+  }
+}
+
+template <int G>
+static hipError_t launch_g(const StreamArgs& a, int nslice, hipStream_t stream) {
+  const dim3 grid(nslice), block((a.nw + 1) * 64);
+  const size_t lds = (size_t)2 * a.nw * 1024 + (size_t)a.nw * kStageBytes;
+  if (a.k <= 4)
+    hipLaunchKernelGGL((lmhead_stream_kernel<G, 4>), grid, block, lds, stream, a);
+  else if (a.k <= 8)
+    hipLaunchKernelGGL((lmhead_stream_kernel<G, 8>), grid, block, lds, stream, a);
+  else if (a.k <= 10)
+    hipLaunchKernelGGL((lmhead_stream_kernel<G, 10>), grid, block, lds, stream, a);
+  else
+    hipLaunchKernelGGL((lmhead_stream_kernel<G, 16>), grid, block, lds, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_lmhead_stream(const StreamArgs& a, int G, int nslice, hipStream_t stream) {
+  switch (G) {
+    case 1: return launch_g<1>(a, nslice, stream);
+    case 2: return launch_g<2>(a, nslice, stream);
+    case 4: return launch_g<4>(a, nslice, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace ddd

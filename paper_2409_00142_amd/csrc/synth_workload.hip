@@ -1,0 +1,212 @@
+// Synthetic stand-ins for the draft-model body and the target model (workload generators for
+// tests and the benchmark; not part of the method), plus a plain read-stream kernel used as
+// the practical HBM ceiling.  The hidden-state recipe is the documented counter-based one:
+// SplitMix64-finaliser keys, four 16-bit fields summed per element, one fp32 multiply, an
+// optional planted direction, RNE to bf16.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ddd_synth.h"
+
+namespace {
+
+constexpr uint64_t kGold = 0x9E3779B97F4A7C15ull;
+constexpr uint64_t kSeq = 0xD1B54A32D192ED03ull;
+constexpr uint64_t kRoundPlant = 0xA5A5A5A5A5A5A5A5ull;
+constexpr uint64_t kRowPlant = 0x5A5A5A5A5A5A5A5Aull;
+constexpr uint64_t kTarget = 0x7A67E7ull;
+constexpr uint32_t kRootParent = 0xFFFFFFFFu;
+constexpr uint32_t kU24_070 = 11744051u;   // floor(0.70 * 2^24)
+constexpr uint32_t kU24_085 = 14260633u;   // floor(0.85 * 2^24)
+
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+__device__ inline uint64_t stream_key(uint64_t seed, int b, int64_t rnd) {
+  const uint64_t a = mix64(seed * kGold + (uint64_t)rnd + 1ull);
+  return mix64(a ^ ((uint64_t)(b + 1) * kSeq));
+}
+__device__ inline uint64_t node_key(uint64_t skey, uint32_t parent, uint32_t token) {
+  return mix64(skey ^ mix64(((uint64_t)parent << 32) | (uint64_t)token));
+}
+__device__ inline uint16_t f32_to_bf16_rne(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+struct BodyArgs {
+  ddd_synth_params p;
+  ddd_state st;
+  uint16_t* hid;
+  int step;
+};
+
+// grid: (rows, ceil(H / 256)); block 256: one element per thread
+__global__ __launch_bounds__(256) void synth_body_kernel(BodyArgs a) {
+  const int k = a.p.cfg.k, H = a.p.cfg.H;
+  const int row = blockIdx.x;
+  const int b = (a.step == 0) ? row : row / k;
+  if (!a.st.active[b]) return;
+  const int e = blockIdx.y * 256 + threadIdx.x;
+  if (e >= H) return;
+  const uint64_t skey = stream_key(a.p.seed, b, *a.p.round_ctr);
+  uint32_t parent, token;
+  if (a.step == 0) {
+    parent = kRootParent;
+    token = (uint32_t)a.p.root_token;
+  } else {
+    const int i = row - b * k;
+    const int node = a.st.beam_node[(size_t)b * k + i];
+    const size_t nmax = 1 + (size_t)k + (size_t)(a.p.cfg.max_depth - 1) * k * k;
+    parent = (uint32_t)a.st.pool_parent[(size_t)b * nmax + node];
+    token = (uint32_t)a.st.beam_token[(size_t)b * k + i];
+  }
+  const uint64_t nk = node_key(skey, parent, token);
+  const uint64_t z = mix64(nk + (uint64_t)(e + 1) * kGold);
+  const int s = (int)((z & 0xFFFFu) + ((z >> 16) & 0xFFFFu) + ((z >> 32) & 0xFFFFu) + (z >> 48)) - 131070;
+  float val = __fmul_rn((float)s, a.p.scale_depth[a.step]);
+  if (a.p.n_plant > 0) {
+    int pi = -1;
+    const uint64_t ur = mix64(skey ^ kRoundPlant);
+    if ((uint32_t)(ur >> 40) < a.p.plant_round_p24) {
+      pi = (int)((ur & 0xFFFFu) % (uint32_t)a.p.n_plant);
+    } else {
+      const uint64_t un = mix64(nk ^ kRowPlant);
+      if ((uint32_t)(un >> 40) < a.p.plant_row_p24) pi = (int)((un & 0xFFFFu) % (uint32_t)a.p.n_plant);
+    }
+    if (pi >= 0) val = __fadd_rn(val, a.p.plant_dir[(size_t)pi * H + e]);
+  }
+  a.hid[(size_t)row * H + e] = f32_to_bf16_rne(val);
+}
+
+struct TargetArgs {
+  ddd_synth_params p;
+  ddd_state st;
+  ddd_tree tree;
+  int32_t* out;
+};
+
+// grid: B; block 256: thread i handles tree index i
+__global__ __launch_bounds__(256) void synth_target_kernel(TargetArgs a) {
+  const int b = blockIdx.x, i = threadIdx.x;
+  const int k = a.p.cfg.k, m = a.p.cfg.m, T = m + 1;
+  if (i >= T) return;
+  const int n_sel = a.tree.n_sel[b];
+  if (i > n_sel) {
+    a.out[(size_t)b * T + i] = -1;
+    return;
+  }
+  const size_t nmax = 1 + (size_t)k + (size_t)(a.p.cfg.max_depth - 1) * k * k;
+  const int32_t* ppar = a.st.pool_parent + (size_t)b * nmax;
+  const int32_t* ptok = a.st.pool_token + (size_t)b * nmax;
+  const int n_nodes = a.st.n_nodes[b];
+  const int node = (i == 0) ? 0 : a.tree.sel_node[(size_t)b * m + i - 1];
+  const uint64_t skey = stream_key(a.p.seed, b, *a.p.round_ctr);
+  const uint64_t tk = mix64(skey ^ mix64(kTarget + (uint64_t)node));
+  const uint32_t u = (uint32_t)(tk >> 40);
+  const int uni = (int)((tk & 0xFFFFFFFFull) % (uint64_t)a.p.cfg.V);
+  int kid0 = -1, kid1 = -1;   // the two lowest-id children = rank 0 and rank 1
+  for (int c = node + 1; c < n_nodes; ++c) {
+    if (ppar[c] == node) {
+      if (kid0 < 0) {
+        kid0 = c;
+      } else {
+        kid1 = c;
+        break;
+      }
+    }
+  }
+  int out = uni;
+  if (u < kU24_070 && kid0 >= 0)
+    out = ptok[kid0];
+  else if (u >= kU24_070 && u < kU24_085 && kid1 >= 0)
+    out = ptok[kid1];
+  a.out[(size_t)b * T + i] = out;
+}
+
+__global__ void next_round_kernel(int64_t* ctr) { *ctr += 1; }
+
+__global__ void round_stats_kernel(int64_t* ctr, const int32_t* steps, const int32_t* accept_len, int B,
+                                   int64_t* depth_hist, int64_t* accept_hist) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  for (int b = 0; b < B; ++b) {
+    if (depth_hist != nullptr && steps != nullptr) depth_hist[min(max(steps[b], 0), 31)] += 1;
+    if (accept_hist != nullptr && accept_len != nullptr) accept_hist[min(max(accept_len[b], 0), 31)] += 1;
+  }
+  *ctr += 1;
+}
+
+// Each thread reads 16-byte words with a grid stride and folds them into one word.
+__global__ __launch_bounds__(256) void read_stream_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* sink) {
+  uint32_t acc = 0;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 a = src[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  if (acc == 0x9E3779B9u) *sink = acc;   // practically never: keeps the loads alive without a store
+}
+
+}  // namespace
+
+extern "C" {
+
+int ddd_synth_draft_body(void* user, int32_t step, const ddd_state* st, void* hid_out_bf16, void* stream) {
+  const ddd_synth_params* p = static_cast<const ddd_synth_params*>(user);
+  if (p == nullptr || st == nullptr || hid_out_bf16 == nullptr || p->round_ctr == nullptr) return DDD_ERR_INVALID_ARG;
+  if (step < 0 || step >= p->cfg.max_depth || step >= 32) return DDD_ERR_INVALID_ARG;
+  if (p->n_plant > 0 && p->plant_dir == nullptr) return DDD_ERR_INVALID_ARG;
+  BodyArgs a;
+  a.p = *p;
+  a.st = *st;
+  a.hid = static_cast<uint16_t*>(hid_out_bf16);
+  a.step = step;
+  const int rows = (step == 0) ? p->cfg.B : p->cfg.B * p->cfg.k;
+  hipLaunchKernelGGL(synth_body_kernel, dim3(rows, (p->cfg.H + 255) / 256), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), a);
+  return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
+}
+
+int ddd_synth_target_argmax(const ddd_synth_params* p, const ddd_state* st, const ddd_tree* tree,
+                            int32_t* target_argmax, void* stream) {
+  if (p == nullptr || st == nullptr || tree == nullptr || target_argmax == nullptr || p->round_ctr == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  if (p->cfg.m + 1 > 256) return DDD_ERR_INVALID_ARG;
+  TargetArgs a;
+  a.p = *p;
+  a.st = *st;
+  a.tree = *tree;
+  a.out = target_argmax;
+  hipLaunchKernelGGL(synth_target_kernel, dim3(p->cfg.B), dim3(256), 0, static_cast<hipStream_t>(stream), a);
+  return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
+}
+
+int ddd_synth_next_round(int64_t* round_ctr, void* stream) {
+  if (round_ctr == nullptr) return DDD_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(next_round_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), round_ctr);
+  return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
+}
+
+int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_t* accept_len, int32_t B,
+                          int64_t* depth_hist, int64_t* accept_hist, void* stream) {
+  if (round_ctr == nullptr || B < 1) return DDD_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(round_stats_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), round_ctr, steps,
+                     accept_len, B, depth_hist, accept_hist);
+  return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
+}
+
+int ddd_synth_read_stream(const void* src, size_t n_bytes, uint32_t* sink, int32_t n_blocks, void* stream) {
+  if (src == nullptr || sink == nullptr || n_bytes % 16 != 0 || n_blocks < 1) return DDD_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(read_stream_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(src), n_bytes / 16, sink);
+  return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+"""Device-side set-up of the synthetic workloads for the GPU tests and the benchmark.
+
+Uploads the seeded inputs, fills the parameter block of the on-device stand-in draft body /
+target model, and drives whole rounds through the C ABI binding.  Contains no method
+arithmetic: every step of a round runs inside libddd.so.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Optional
+
+import numpy as np
+import torch
+
+import paper_2409_00142_amd as D
+from .inputs import Workload, make_lm_head, make_plant_table
+
+
+def upload_bits(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> torch.bfloat16 tensor on the GPU (bit-exact)."""
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+class GpuWorkload:
+    """One context + caller-owned buffers for a synthetic workload."""
+
+    def __init__(self, wl: Workload, W_bits: Optional[np.ndarray] = None, threshold: Optional[float] = None,
+                 debug: bool = False):
+        self.wl = wl
+        self.W_bits = make_lm_head(wl.V, wl.H, wl.sigma_w, wl.seed, wl.dup_pairs) if W_bits is None else W_bits
+        self.plant_tokens, self.plant_dir_np = make_plant_table(self.W_bits, wl)
+        t = wl.threshold if threshold is None else threshold
+        self.cfg = D.make_config(wl.B, wl.H, wl.V, wl.k, wl.D, wl.m, t, wl.check_mask)
+        self.ctx = D.ddd_create(self.cfg)
+        self.W = upload_bits(self.W_bits)
+        self.st, self.st_t = D.alloc_state(self.cfg)
+        self.tree, self.tree_t = D.alloc_tree(self.cfg)
+        B, k, H, V, Dm, m = wl.B, wl.k, wl.H, wl.V, wl.D, wl.m
+        self.hid = torch.zeros(B * k, H, dtype=torch.bfloat16, device="cuda")
+        self.root_token = torch.full((B,), wl.root_token, dtype=torch.int32, device="cuda")
+        self.round_ctr = torch.zeros(1, dtype=torch.int64, device="cuda")
+        self.plant_dir = torch.from_numpy(self.plant_dir_np).cuda() if wl.n_plant > 0 else None
+        self.target = torch.full((B, m + 1), -1, dtype=torch.int32, device="cuda")
+        self.accept_len = torch.zeros(B, dtype=torch.int32, device="cuda")
+        self.accept_path = torch.full((B, Dm + 1), -1, dtype=torch.int32, device="cuda")
+        self.bonus = torch.zeros(B, dtype=torch.int32, device="cuda")
+        self.depth_hist = torch.zeros(32, dtype=torch.int64, device="cuda")
+        self.accept_hist = torch.zeros(32, dtype=torch.int64, device="cuda")
+        self.logits_dbg = torch.zeros(Dm, B * k, V, dtype=torch.float32, device="cuda") if debug else None
+        self.lse_dbg = torch.zeros(Dm, B * k, dtype=torch.float32, device="cuda") if debug else None
+        p = D.ddd_synth_params()
+        p.cfg = self.cfg
+        p.seed = wl.seed
+        p.round_ctr = self.round_ctr.data_ptr()
+        p.root_token = wl.root_token
+        p.n_plant = wl.n_plant
+        for d in range(32):
+            p.scale_depth[d] = float(wl.scale(d))
+        p.plant_dir = self.plant_dir.data_ptr() if self.plant_dir is not None else None
+        p.plant_round_p24 = wl.plant_round_p24()
+        p.plant_row_p24 = wl.plant_row_p24()
+        self.params = p
+        # post hook: stand-in target model, accept walk, advance the round counter
+        self._post = D.POST_FN(self._post_cb)
+        self.captured = False
+
+    def _post_cb(self, user, st_p, tree_p, stream):
+        try:
+            D.ddd_synth_target_argmax(self.params, self.st, self.tree, self.target, stream=stream)
+            D.ddd_verify_accept(self.ctx, self.tree, self.target, self.accept_len, self.accept_path, self.bonus,
+                                stream=stream)
+            D.ddd_synth_round_stats(self.round_ctr, self.st_t["steps"], self.accept_len, self.wl.B, self.depth_hist,
+                                    self.accept_hist, stream=stream)
+            return 0
+        except D.DDDError as e:
+            return e.code
+
+    def set_round(self, rnd: int) -> None:
+        self.round_ctr.fill_(rnd)
+
+    def _round_args(self):
+        return (self.ctx, self.W, self.st, self.tree, self.root_token, self.hid, D.synth_draft_body_ptr(),
+                C.addressof(self.params), self._post, None, self.logits_dbg, self.lse_dbg)
+
+    def enqueue_round(self, stream: Optional[int] = None) -> None:
+        """The whole round (reset, draft calls, tree, stand-in target, accept walk) without a graph."""
+        D.ddd_round_enqueue(*self._round_args(), stream=stream)
+
+    def capture(self, stream: torch.cuda.Stream) -> None:
+        D.ddd_round_capture(*self._round_args(), stream=stream.cuda_stream)
+        self.captured = True
+
+    def launch(self, stream: Optional[int] = None) -> None:
+        D.ddd_round_launch(self.ctx, stream=stream)
+
+    def close(self) -> None:
+        if self.ctx is not None:
+            D.ddd_destroy(self.ctx)
+            self.ctx = None
+
+    def snapshot(self) -> dict:
+        """Host copies of state, tree and accept outputs (synchronises)."""
+        torch.cuda.synchronize()
+        out = {n: t.cpu().numpy() for n, t in self.st_t.items()}
+        out.update({n: t.cpu().numpy() for n, t in self.tree_t.items()})
+        out["target"] = self.target.cpu().numpy()
+        out["accept_len"] = self.accept_len.cpu().numpy()
+        out["accept_path"] = self.accept_path.cpu().numpy()
+        out["bonus"] = self.bonus.cpu().numpy()
+        return out

@@ -1,0 +1,103 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, validates
+configurations and reports errors as status codes.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def D():
+    import paper_2409_00142_amd as D
+    if not os.path.exists(D.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    D.load_library()
+    return D
+
+
+def _declared_symbols():
+    names = []
+    for hdr in ("ddd.h", "ddd_synth.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"^\s*(?:const\s+char\s*\*|int|size_t)\s+(ddd_\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported(D):
+    lib = D.load_library()
+    names = _declared_symbols()
+    assert len(names) >= 24
+    for n in ("ddd_lmhead_topk", "ddd_beam_select", "ddd_depth_continue", "ddd_tree_finalize", "ddd_verify_accept"):
+        assert n in names
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/ but not exported"
+
+
+def test_struct_layouts_match_the_header(D):
+    assert C.sizeof(D.ddd_config) == 36
+    assert C.sizeof(D.ddd_state) == 13 * 8
+    assert C.sizeof(D.ddd_tree) == 6 * 8
+    assert D.ddd_synth_params.seed.offset == 40 and D.ddd_synth_params.scale_depth.offset == 64
+    assert C.sizeof(D.ddd_synth_params) == 208
+
+
+def test_config_validation(D):
+    ok = D.make_config(1, 4096, 32000, 10, 10, 60, 0.3)
+    assert D.ddd_config_validate(ok) == D.DDD_OK
+    assert D.ddd_pool_capacity(ok) == 1 + 10 + 9 * 100
+    for name in ("tiny", "7b_b1", "13b_b1", "7b_b64", "large_vocab"):
+        import synth
+        wl = synth.WORKLOADS[name]
+        cfg = D.make_config(wl.B, wl.H, wl.V, wl.k, wl.D, wl.m, wl.threshold)
+        assert D.ddd_config_validate(cfg) == D.DDD_OK, name
+        assert D.ddd_pool_capacity(cfg) == wl.pool_capacity
+    bad = [
+        dict(B=0), dict(k=0), dict(k=17), dict(V=5), dict(V=1 << 24), dict(max_depth=0), dict(max_depth=32),
+        dict(m=0), dict(m=129), dict(H=100), dict(H=4096 + 64), dict(H=128 * 64), dict(H=5632), dict(threshold=-0.1),
+        dict(threshold=float("nan")), dict(k=16, max_depth=20),
+    ]
+    base = dict(B=1, H=4096, V=32000, k=10, max_depth=10, m=60, threshold=0.3)
+    for b in bad:
+        kw = dict(base, **b)
+        cfg = D.make_config(**kw)
+        assert D.ddd_config_validate(cfg) == D.DDD_ERR_INVALID_ARG, b
+        assert D.ddd_pool_capacity(cfg) == 0
+    flagged = D.make_config(**base)
+    flagged.flags = 1
+    assert D.ddd_config_validate(flagged) == D.DDD_ERR_INVALID_ARG
+    assert D.load_library().ddd_config_validate(None) == D.DDD_ERR_INVALID_ARG
+
+
+def test_error_strings_and_null_arguments(D):
+    lib = D.load_library()
+    for code in (0, -1, -2, -3, -4, -5, -6):
+        assert D.ddd_strerror(code) not in ("", "unknown status")
+    assert D.ddd_strerror(-99) == "unknown status"
+    assert lib.ddd_create(None, None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_destroy(None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_round_launch(None, None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_lmhead_topk(None, None, None, 1, None, None, None, None, None, None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_synth_next_round(None, None) == D.DDD_ERR_INVALID_ARG
+
+
+def test_create_without_a_device_fails_with_a_status():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a device is present")
+    import paper_2409_00142_amd as D
+    with pytest.raises(D.DDDError) as e:
+        D.ddd_create(D.make_config(1, 256, 1000, 4, 6, 16, 0.35))
+    assert e.value.code == D.DDD_ERR_NO_DEVICE
+
+
+def test_product_package_does_not_import_the_oracle():
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_2409_00142_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text, f"{f} mentions the oracle"

@@ -1,0 +1,385 @@
+"""GPU parity tests: the HIP path (through the C ABI binding) against the CPU oracle on the same
+seeded inputs.  Integer outputs are compared bit for bit; logits within 2e-2 and lse / logprobs
+within 1e-4 (bf16 inputs, fp32 accumulation on the GPU, fp64 in the oracle)."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import ddd_oracle as O
+from oracle import synth_round as SR
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 2e-2
+LOGPROB_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a HIP device (run them with gpurun)")
+    import paper_2409_00142_amd as D
+    from synth import device as SD
+    return torch, D, SD
+
+
+def _rand_hid_bits(rng, R, H, scale):
+    return synth.f32_to_bf16_bits((rng.standard_normal((R, H)) * scale).astype(np.float32))
+
+
+# ------------------------------------------------------------------------------------------------
+# L1: ddd_lmhead_topk, teacher-forced
+# ------------------------------------------------------------------------------------------------
+LM_CASES = [
+    # name,  B, k,  H,    V,    R, sigma_w, hid scale, duplicate rows
+    ("tiny_r1", 1, 4, 256, 1000, 1, 0.05, 5.0, ()),
+    ("tiny_r4", 1, 4, 256, 1000, 4, 0.05, 5.0, ()),
+    ("ragged_V_g1", 1, 10, 1024, 5003, 10, 0.03, 3.0, ()),
+    ("g2_k16", 1, 16, 2048, 3001, 16, 0.02, 3.0, ()),
+    ("g4_nw8", 1, 10, 4096, 4100, 10, 0.02, 3.5, ((17, 2900), (100, 101))),
+    ("g4_nw10", 1, 8, 5120, 2050, 7, 0.02, 3.5, ()),
+    ("small_V", 1, 4, 128, 20, 3, 0.2, 2.0, ()),
+    ("two_pass_rows", 3, 8, 512, 2000, 24, 0.04, 3.0, ((5, 1999),)),
+]
+
+
+@pytest.mark.parametrize("case", LM_CASES, ids=[c[0] for c in LM_CASES])
+def test_lmhead_topk_against_oracle(gpu, case):
+    torch, D, SD = gpu
+    name, B, k, H, V, R, sigma, hscale, dups = case
+    print(f"[case] lmhead_topk {name} B={B} k={k} H={H} V={V} R={R}", flush=True)
+    rng = np.random.default_rng(abs(hash(name)) % (1 << 31))
+    W_bits = synth.make_lm_head(V, H, sigma, seed=3, dup_pairs=dups)
+    hid_bits = _rand_hid_bits(rng, R, H, hscale)
+    cfg = D.make_config(B, H, V, k, 4, 8, 0.3)
+    ctx = D.ddd_create(cfg)
+    try:
+        W = SD.upload_bits(W_bits)
+        hid = SD.upload_bits(hid_bits)
+        tok = torch.full((R, k), -7, dtype=torch.int32, device="cuda")
+        lp = torch.zeros(R, k, dtype=torch.float32, device="cuda")
+        lse = torch.zeros(R, dtype=torch.float32, device="cuda")
+        dbg = torch.full((R, V), float("nan"), dtype=torch.float32, device="cuda")
+        D.ddd_lmhead_topk(ctx, W, hid, R, None, tok, lp, lse, dbg)
+        torch.cuda.synchronize()
+        g_logits, g_tok, g_lp, g_lse = dbg.cpu().numpy(), tok.cpu().numpy(), lp.cpu().numpy(), lse.cpu().numpy()
+        # without the debug buffer the results are the same bits
+        tok2 = torch.zeros_like(tok); lp2 = torch.zeros_like(lp); lse2 = torch.zeros_like(lse)
+        D.ddd_lmhead_topk(ctx, W, hid, R, None, tok2, lp2, lse2, None)
+        torch.cuda.synchronize()
+        assert torch.equal(tok, tok2) and torch.equal(lp, lp2) and torch.equal(lse, lse2)
+    finally:
+        D.ddd_destroy(ctx)
+    o_logits = O.lmhead_logits(W_bits, hid_bits)
+    assert not np.isnan(g_logits).any()
+    assert np.max(np.abs(g_logits.astype(np.float64) - o_logits.astype(np.float64))) <= LOGIT_TOL
+    for a, b in dups:                                   # equal W rows give bit-equal logits
+        assert np.array_equal(g_logits[:, a], g_logits[:, b])
+    for r in range(R):
+        want_tok = O.row_topk(g_logits[r], k)           # oracle top-k of the GPU's own logits
+        assert np.array_equal(g_tok[r], want_tok), (r, g_tok[r], want_tok)
+        assert abs(float(g_lse[r]) - O.logsumexp_row(g_logits[r])) <= LOGPROB_TOL
+        want_lp = (g_logits[r][g_tok[r]] - g_lse[r]).astype(np.float32)        # one fp32 subtraction
+        assert np.array_equal(g_lp[r], want_lp)
+        o_lp = O.logprobs_row(g_logits[r])[g_tok[r]]
+        assert np.max(np.abs(g_lp[r].astype(np.float64) - o_lp)) <= LOGPROB_TOL
+
+
+def test_lmhead_topk_row_active_and_errors(gpu):
+    torch, D, SD = gpu
+    B, k, H, V, R = 1, 4, 256, 1000, 4
+    rng = np.random.default_rng(5)
+    W_bits = synth.make_lm_head(V, H, 0.05, seed=1)
+    hid_bits = _rand_hid_bits(rng, R, H, 5.0)
+    cfg = D.make_config(B, H, V, k, 4, 8, 0.3)
+    ctx = D.ddd_create(cfg)
+    try:
+        W, hid = SD.upload_bits(W_bits), SD.upload_bits(hid_bits)
+        tok = torch.full((R, k), -7, dtype=torch.int32, device="cuda")
+        lp = torch.full((R, k), 9.0, dtype=torch.float32, device="cuda")
+        lse = torch.full((R,), 9.0, dtype=torch.float32, device="cuda")
+        act = torch.tensor([1, 0, 1, 0], dtype=torch.uint8, device="cuda")
+        D.ddd_lmhead_topk(ctx, W, hid, R, act, tok, lp, lse, None)
+        torch.cuda.synchronize()
+        t = tok.cpu().numpy()
+        assert (t[1] == -7).all() and (t[3] == -7).all()          # inactive rows untouched
+        logits = O.lmhead_logits(W_bits, hid_bits)
+        assert set(t[0]) == set(O.row_topk(logits[0], k)) and set(t[2]) == set(O.row_topk(logits[2], k))
+        act.zero_()
+        tok.fill_(-7)
+        D.ddd_lmhead_topk(ctx, W, hid, R, act, tok, lp, lse, None)
+        torch.cuda.synchronize()
+        assert (tok.cpu().numpy() == -7).all()
+        with pytest.raises(D.DDDError):
+            D.ddd_lmhead_topk(ctx, W, hid, 0, None, tok, lp, lse, None)
+        with pytest.raises(D.DDDError):
+            D.ddd_lmhead_topk(ctx, W, hid, B * k + 1, None, tok, lp, lse, None)
+        with pytest.raises(D.DDDError):
+            D.ddd_lmhead_topk(ctx, None, hid, R, None, tok, lp, lse, None)
+    finally:
+        D.ddd_destroy(ctx)
+
+
+# ------------------------------------------------------------------------------------------------
+# L1: beam select, stop test, finalize, verify - teacher-forced from an oracle round
+# ------------------------------------------------------------------------------------------------
+def _upload_i32(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def _upload_f32(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+@pytest.mark.parametrize("wname,rnd,thr", [("tiny", 0, 0.0), ("tiny", 3, 0.35), ("tiny", 7, 0.35)])
+def test_bookkeeping_calls_teacher_forced(gpu, wname, rnd, thr):
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS[wname]
+    print(f"[case] bookkeeping {wname} round={rnd} t={thr}", flush=True)
+    W_bits = synth.make_lm_head(wl.V, wl.H, wl.sigma_w, wl.seed)
+    res, tgt, (o_len, o_path, o_bonus) = SR.oracle_round(wl, W_bits, None, 0, rnd, threshold=thr)
+    k, Dm, m = wl.k, wl.D, wl.m
+    cfg = D.make_config(1, wl.H, wl.V, k, Dm, m, thr, wl.check_mask)
+    ctx = D.ddd_create(cfg)
+    try:
+        st, st_t = D.alloc_state(cfg)
+        tree, tree_t = D.alloc_tree(cfg)
+        root = torch.tensor([wl.root_token], dtype=torch.int32, device="cuda")
+        D.ddd_round_reset(ctx, st, root)
+        for s, rec in enumerate(res.records):
+            tok, lp = _upload_i32(torch, rec.tok), _upload_f32(torch, rec.lp)
+            D.ddd_beam_select(ctx, s, tok, lp, st)
+            D.ddd_depth_continue(ctx, s + 1, st)
+            torch.cuda.synchronize()
+            assert np.array_equal(st_t["beam_node"].cpu().numpy()[0], rec.beam.node)
+            assert np.array_equal(st_t["beam_token"].cpu().numpy()[0], rec.beam.token)
+            assert np.array_equal(st_t["beam_parent_slot"].cpu().numpy()[0], rec.beam.parent_slot)
+            assert np.array_equal(st_t["logprobsum"].cpu().numpy()[0], rec.beam.logprobsum)      # bit-exact
+            assert int(st_t["steps"].cpu()[0]) == s + 1
+            assert int(st_t["active"].cpu()[0]) == int(rec.cont)
+            assert (st_t["row_active"].cpu().numpy() == int(rec.cont)).all()
+            P = float(st_t["conf"].cpu()[0])
+            assert abs(P - rec.P) <= 1e-12 * max(1.0, abs(rec.P))
+        # once inactive, further calls leave the state untouched
+        if res.steps < Dm:
+            before = {n: t.clone() for n, t in st_t.items()}
+            D.ddd_beam_select(ctx, res.steps, tok, lp, st)
+            D.ddd_depth_continue(ctx, res.steps + 1, st)
+            torch.cuda.synchronize()
+            for n in st_t:
+                assert torch.equal(before[n], st_t[n]), n
+        n = res.pool.n_nodes
+        assert int(st_t["n_nodes"].cpu()[0]) == n
+        assert np.array_equal(st_t["pool_token"].cpu().numpy()[0, :n], res.pool.token[:n])
+        assert np.array_equal(st_t["pool_parent"].cpu().numpy()[0, :n], res.pool.parent[:n])
+        assert np.array_equal(st_t["pool_depth"].cpu().numpy()[0, :n], res.pool.depth[:n])
+        assert np.array_equal(st_t["pool_score"].cpu().numpy()[0, :n], res.pool.score[:n])
+        # finalize + verify
+        D.ddd_tree_finalize(ctx, st, tree)
+        tgt_d = _upload_i32(torch, tgt[None, :])
+        alen = torch.zeros(1, dtype=torch.int32, device="cuda")
+        apath = torch.zeros(1, Dm + 1, dtype=torch.int32, device="cuda")
+        bonus = torch.zeros(1, dtype=torch.int32, device="cuda")
+        D.ddd_verify_accept(ctx, tree, tgt_d, alen, apath, bonus)
+        torch.cuda.synchronize()
+        tr = res.tree
+        assert int(tree_t["n_sel"].cpu()[0]) == tr.n_sel
+        assert np.array_equal(tree_t["sel_node"].cpu().numpy()[0], tr.sel_node)
+        assert np.array_equal(tree_t["tree_token"].cpu().numpy()[0], tr.tree_token)
+        assert np.array_equal(tree_t["pos"].cpu().numpy()[0], tr.pos)
+        assert np.array_equal(tree_t["parent_idx"].cpu().numpy()[0], tr.parent_idx)
+        assert np.array_equal(tree_t["mask"].cpu().numpy()[0], tr.mask)
+        assert int(alen.cpu()[0]) == o_len and int(bonus.cpu()[0]) == o_bonus
+        assert np.array_equal(apath.cpu().numpy()[0], o_path)
+    finally:
+        D.ddd_destroy(ctx)
+
+
+# ------------------------------------------------------------------------------------------------
+# the on-device stand-in draft body reproduces the numpy generator bit for bit
+# ------------------------------------------------------------------------------------------------
+def test_synth_draft_body_matches_numpy_generator(gpu):
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS["13b_b1"].with_(H=512, V=3000, D=4, m=20, plant_round_p=0.5, plant_row_p=0.3, B=2)
+    g = SD.GpuWorkload(wl)
+    try:
+        planted = 0
+        for rnd in range(6):
+            g.set_round(rnd)
+            D.ddd_round_reset(g.ctx, g.st, g.root_token)
+            for step in range(wl.D):
+                D.ddd_synth_draft_body(g.params, step, g.st, g.hid)
+                torch.cuda.synchronize()
+                hid = g.hid.view(torch.int16).cpu().numpy().view(np.uint16)
+                st = {n: t.cpu().numpy() for n, t in g.st_t.items()}
+                for b in range(wl.B):
+                    if not st["active"][b]:
+                        continue
+                    skey = synth.stream_key(wl.seed, b, rnd)
+                    if step == 0:
+                        want = synth.root_hidden(wl, skey, g.plant_dir_np)
+                        got = hid[b:b + 1]
+                    else:
+                        parents = [st["pool_parent"][b, n] for n in st["beam_node"][b]]
+                        want = synth.hidden_rows(wl, skey, parents, st["beam_token"][b], step, g.plant_dir_np)
+                        got = hid[b * wl.k:(b + 1) * wl.k]
+                    assert np.array_equal(got, want), (rnd, step, b)
+                    planted += int(synth.inputs._plant_index(skey, synth.node_key(skey, synth.ROOT_PARENT, wl.root_token), wl) >= 0)
+                D.ddd_draft_step(g.ctx, step, g.W, g.hid, g.st)
+        assert planted > 0
+    finally:
+        g.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# L2: whole rounds, the oracle replaying the GPU's logits and lse
+# ------------------------------------------------------------------------------------------------
+def _compare_round(g, snap, wl, rnd, thr, logits_dbg, lse_dbg, check_own_logits_steps=0):
+    """Replay sequence by sequence; returns the list of oracle step counts."""
+    k = wl.k
+    steps_out = []
+    for b in range(wl.B):
+        def logits_fn(s, hid, b=b):
+            rows = slice(b, b + 1) if s == 0 else slice(b * k, (b + 1) * k)
+            return logits_dbg[s, rows], lse_dbg[s, rows].astype(np.float64)
+
+        res, tgt, (o_len, o_path, o_bonus) = SR.oracle_round(wl, g.W_bits, g.plant_dir_np, b, rnd, threshold=thr,
+                                                            logits_fn=logits_fn)
+        steps_out.append(res.steps)
+        ctx_msg = f"round {rnd} seq {b}"
+        assert int(snap["steps"][b]) == res.steps, ctx_msg
+        assert int(snap["active"][b]) == 0, ctx_msg
+        n = res.pool.n_nodes
+        assert int(snap["n_nodes"][b]) == n, ctx_msg
+        assert np.array_equal(snap["pool_token"][b, :n], res.pool.token[:n]), ctx_msg
+        assert np.array_equal(snap["pool_parent"][b, :n], res.pool.parent[:n]), ctx_msg
+        assert np.array_equal(snap["pool_depth"][b, :n], res.pool.depth[:n]), ctx_msg
+        assert np.array_equal(snap["pool_score"][b, :n], res.pool.score[:n]), ctx_msg
+        last = res.records[-1]
+        assert np.array_equal(snap["beam_node"][b], last.beam.node), ctx_msg
+        assert np.array_equal(snap["logprobsum"][b], last.beam.logprobsum), ctx_msg
+        assert abs(float(snap["conf"][b]) - last.P) <= 1e-12, ctx_msg
+        assert abs(last.P - float(np.float32(thr))) > 1e-9, "stop test too close to the threshold to compare"
+        tr = res.tree
+        assert int(snap["n_sel"][b]) == tr.n_sel, ctx_msg
+        assert np.array_equal(snap["sel_node"][b], tr.sel_node), ctx_msg
+        assert np.array_equal(snap["tree_token"][b], tr.tree_token), ctx_msg
+        assert np.array_equal(snap["pos"][b], tr.pos), ctx_msg
+        assert np.array_equal(snap["parent_idx"][b], tr.parent_idx), ctx_msg
+        assert np.array_equal(snap["mask"][b], tr.mask), ctx_msg
+        assert np.array_equal(snap["target"][b], tgt), ctx_msg
+        assert int(snap["accept_len"][b]) == o_len and int(snap["bonus"][b]) == o_bonus, ctx_msg
+        assert np.array_equal(snap["accept_path"][b], o_path), ctx_msg
+        for s in range(res.steps):                      # equal W rows give bit-equal logits
+            rows = slice(b, b + 1) if s == 0 else slice(b * k, (b + 1) * k)
+            for va, vb in wl.dup_pairs:
+                assert np.array_equal(logits_dbg[s, rows][:, va], logits_dbg[s, rows][:, vb]), ctx_msg
+        # the oracle's own projection of the same hidden rows agrees with the GPU's logits
+        for s in range(min(check_own_logits_steps, res.steps)):
+            rows = slice(b, b + 1) if s == 0 else slice(b * k, (b + 1) * k)
+            own = O.lmhead_logits(g.W_bits, res.records[s].hid_bits)
+            assert np.max(np.abs(own.astype(np.float64) - logits_dbg[s, rows])) <= LOGIT_TOL, ctx_msg
+            for i in range(own.shape[0]):
+                assert abs(O.logsumexp_row(logits_dbg[s, rows][i]) - float(lse_dbg[s, rows][i])) <= LOGPROB_TOL
+    return steps_out
+
+
+ROUND_CASES = [
+    ("tiny", synth.WORKLOADS["tiny"], None, 16, 6),
+    ("tiny_t0", synth.WORKLOADS["tiny"], 0.0, 2, 6),
+    ("tiny_t_gt1", synth.WORKLOADS["tiny"], 1.5, 2, 1),
+    ("tiny_paper_S", synth.WORKLOADS["tiny"].with_(check_mask=(1 << 3) | (1 << 5), threshold=0.9), None, 3, 0),
+    ("tiny_b3", synth.WORKLOADS["tiny"].with_(B=3), None, 4, 6),
+    ("tiny_b5_two_passes", synth.WORKLOADS["tiny"].with_(B=5), None, 3, 2),
+    ("planted_ties_k16", synth.WORKLOADS["large_vocab"].with_(B=1, V=6007, H=1024, D=4, m=40, plant_row_p=0.3,
+                                                               dup_pairs=((1000, 5000), (1997, 4009)), n_plant=2),
+     None, 4, 4),
+    ("13b_shape_small_V", synth.WORKLOADS["13b_b1"].with_(V=4000, D=5), None, 4, 2),
+]
+
+
+@pytest.mark.parametrize("case", ROUND_CASES, ids=[c[0] for c in ROUND_CASES])
+def test_round_injected_parity(gpu, case):
+    torch, D, SD = gpu
+    name, wl, thr, n_rounds, own_steps = case
+    thr = wl.threshold if thr is None else thr
+    print(f"[case] round {name} B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} t={thr}", flush=True)
+    g = SD.GpuWorkload(wl, threshold=thr, debug=True)
+    try:
+        depths = []
+        for rnd in range(n_rounds):
+            g.set_round(rnd)
+            g.enqueue_round()
+            snap = g.snapshot()
+            assert int(g.round_ctr.cpu()[0]) == rnd + 1
+            depths += _compare_round(g, snap, wl, rnd, thr, g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy(),
+                                     check_own_logits_steps=own_steps if rnd < 2 else 0)
+        print(f"[info] {name} depth histogram {np.bincount(depths, minlength=wl.D + 1).tolist()}", flush=True)
+        if name == "tiny":
+            assert len(set(depths)) >= 3
+        if name == "tiny_t0":
+            assert set(depths) == {wl.D}
+        if name == "tiny_t_gt1":
+            assert set(depths) == {1}
+    finally:
+        g.close()
+
+
+def test_round_graph_replays_match_eager_and_are_deterministic(gpu):
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS["tiny"].with_(B=2)
+    print("[case] graph replay tiny B=2", flush=True)
+    g = SD.GpuWorkload(wl, debug=False)
+    try:
+        eager = []
+        for rnd in range(5):
+            g.set_round(rnd)
+            g.enqueue_round()
+            eager.append(g.snapshot())
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        g.capture(side)
+        torch.cuda.synchronize()
+        g.set_round(0)
+        torch.cuda.synchronize()
+        for rnd in range(5):                       # the captured round advances its own round id
+            g.launch(side.cuda_stream)
+            side.synchronize()
+            snap = g.snapshot()
+            for name, want in eager[rnd].items():
+                assert np.array_equal(snap[name], want), (rnd, name)
+        # same round twice: identical bytes
+        g.set_round(2)
+        torch.cuda.synchronize()
+        g.launch(side.cuda_stream)
+        side.synchronize()
+        again = g.snapshot()
+        for name, want in eager[2].items():
+            assert np.array_equal(again[name], want), name
+    finally:
+        g.close()
+
+
+def test_7b_shape_round_parity(gpu):
+    """Full 7B-shaped sizes in the launch configuration the benchmark times (one captured graph)."""
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS["7b_b1"]
+    print("[case] 7B-shaped rounds, graph launch", flush=True)
+    g = SD.GpuWorkload(wl, debug=True)
+    try:
+        side = torch.cuda.Stream()
+        g.capture(side)
+        torch.cuda.synchronize()
+        depths = []
+        for rnd in range(3):
+            g.set_round(rnd)
+            torch.cuda.synchronize()
+            g.launch(side.cuda_stream)
+            side.synchronize()
+            snap = g.snapshot()
+            depths += _compare_round(g, snap, wl, rnd, wl.threshold, g.logits_dbg.cpu().numpy(),
+                                     g.lse_dbg.cpu().numpy(), check_own_logits_steps=2 if rnd == 0 else 0)
+        print(f"[info] 7b depths {depths}", flush=True)
+    finally:
+        g.close()
