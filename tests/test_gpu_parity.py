@@ -326,6 +326,17 @@ def test_round_injected_parity(gpu, case):
         g.close()
 
 
+def _same_round(a, b):
+    """Two snapshots describe the same round: pool entries past n_nodes are leftovers and not compared."""
+    for name, want in b.items():
+        got = a[name]
+        if name.startswith("pool_"):
+            for q, n in enumerate(b["n_nodes"]):
+                assert np.array_equal(got[q, :n], want[q, :n]), name
+        else:
+            assert np.array_equal(got, want), name
+
+
 def test_round_graph_replays_match_eager_and_are_deterministic(gpu):
     torch, D, SD = gpu
     wl = synth.WORKLOADS["tiny"].with_(B=2)
@@ -346,17 +357,13 @@ def test_round_graph_replays_match_eager_and_are_deterministic(gpu):
         for rnd in range(5):                       # the captured round advances its own round id
             g.launch(side.cuda_stream)
             side.synchronize()
-            snap = g.snapshot()
-            for name, want in eager[rnd].items():
-                assert np.array_equal(snap[name], want), (rnd, name)
+            _same_round(g.snapshot(), eager[rnd])
         # same round twice: identical bytes
         g.set_round(2)
         torch.cuda.synchronize()
         g.launch(side.cuda_stream)
         side.synchronize()
-        again = g.snapshot()
-        for name, want in eager[2].items():
-            assert np.array_equal(again[name], want), name
+        _same_round(g.snapshot(), eager[2])
     finally:
         g.close()
 
