@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--threshold", type=float, default=None, help="stop threshold t (default: the workload's)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--profile-iters", type=int, default=200)
+    ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
+                    help="one captured hipGraph per round (default) or plain stream launches")
     ap.add_argument("--traffic", default=None,
                     help="JSON file {\"fetch_bytes\":..,\"write_bytes\":..} from rocprofv3 --pmc runs (optional)")
     args = ap.parse_args()
@@ -81,13 +83,17 @@ def main():
         f"stream slices={D.ddd_num_slices(g.ctx)}")
 
     side = torch.cuda.Stream()
-    g.capture(side)
+    if args.launch == "graph":
+        g.capture(side)
+        launch = lambda: g.launch(side.cuda_stream)
+    else:
+        launch = lambda: g.enqueue_round(side.cuda_stream)
     torch.cuda.synchronize()
     g.set_round(0)
     torch.cuda.synchronize()
     with torch.cuda.stream(side):
         for _ in range(args.warmup):
-            g.launch(side.cuda_stream)
+            launch()
         side.synchronize()
         g.depth_hist.zero_()
         g.accept_hist.zero_()
@@ -96,7 +102,7 @@ def main():
         w0 = time.perf_counter()
         e0.record(side)
         for _ in range(args.steps):
-            g.launch(side.cuda_stream)
+            launch()
         e1.record(side)
         side.synchronize()
         torch.cuda.synchronize()
@@ -143,6 +149,14 @@ def main():
             gbs = 20 * w_bytes / (r0.elapsed_time(r1) * 1e-3) / 1e9
             best = gbs if best is None else max(best, gbs)
     log(f"[bench] plain read-stream kernel over W: {best:.0f} GB/s ({100 * best / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
+    # a plain device-to-device copy of W (known size: reads and writes V*H*2 bytes): the reference the
+    # rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by
+    with torch.cuda.stream(side):
+        wcopy = torch.empty_like(g.W)
+        for _ in range(3):
+            wcopy.copy_(g.W)
+        side.synchronize()
+        del wcopy
 
     traffic = None
     if args.traffic and os.path.exists(args.traffic):
@@ -164,7 +178,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
-                   "threshold": thr, "hidden_gain": wl.gain, "launch": "one hipGraph per round",
+                   "threshold": thr, "hidden_gain": wl.gain,
+                   "launch": "one hipGraph per round" if args.launch == "graph" else "stream launches",
                    "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},
                    "accept_len_hist": {str(d): int(c) for d, c in enumerate(accept_hist) if c},
                    "executed_depth_steps": exec_steps,

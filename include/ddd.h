@@ -140,10 +140,12 @@ int ddd_depth_continue(ddd_ctx* ctx, int32_t steps_done, ddd_state* st, void* st
 
 /* One whole draft call for every active sequence: ddd_lmhead_topk + ddd_beam_select +
  * ddd_depth_continue with the per-row results kept on chip (two kernel launches).
- * hid_bf16: [B,H] for step 0, [B*k,H] for step >= 1.  logits_dbg as above or NULL;
- * lse_dbg: device fp32[n_rows] or NULL, the lse of every row of this call. */
+ * hid_bf16: [B,H] for step 0, [B*k,H] for step >= 1.
+ * tree: NULL, or the output of ddd_tree_finalize: a sequence whose stop test fails in this call
+ * (or that has made max_depth calls) gets its final tree written by the same launch.
+ * logits_dbg as above or NULL; lse_dbg: device fp32[n_rows] or NULL, the lse of every row. */
 int ddd_draft_step(ddd_ctx* ctx, int32_t step, const void* W_bf16, const void* hid_bf16, ddd_state* st,
-                   float* logits_dbg, float* lse_dbg, void* stream);
+                   ddd_tree* tree, float* logits_dbg, float* lse_dbg, void* stream);
 
 /* Final top-m rerank of all pool nodes by (score desc, node id asc), tree order, mask,
  * positions (Section 1: the tree is fed to the target model under a tree attention mask). */
@@ -167,7 +169,8 @@ typedef int (*ddd_draft_body_fn)(void* user, int32_t step, const ddd_state* st, 
 typedef int (*ddd_post_fn)(void* user, const ddd_state* st, const ddd_tree* tree, void* stream);
 
 /* Algorithm 1 end to end: reset, then max_depth draft calls (later calls are skipped on the
- * device for sequences whose stop test failed), then ddd_tree_finalize and `post`.
+ * device for sequences whose stop test failed; the call in which a sequence stops also builds
+ * its final tree), then `post`.
  * Only enqueues; usable inside or outside graph capture.
  *   hid_buf    device bf16[B*k,H] scratch the draft body writes into
  *   logits_dbg device fp32[max_depth, B*k, V] or NULL

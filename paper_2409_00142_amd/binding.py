@@ -89,7 +89,7 @@ def load_library() -> C.CDLL:
         "ddd_lmhead_topk": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]),
         "ddd_beam_select": (C.c_int, [vp, i32, vp, vp, stp, vp]),
         "ddd_depth_continue": (C.c_int, [vp, i32, stp, vp]),
-        "ddd_draft_step": (C.c_int, [vp, i32, vp, vp, stp, vp, vp, vp]),
+        "ddd_draft_step": (C.c_int, [vp, i32, vp, vp, stp, trp, vp, vp, vp]),
         "ddd_tree_finalize": (C.c_int, [vp, stp, trp, vp]),
         "ddd_verify_accept": (C.c_int, [vp, trp, vp, vp, vp, vp, vp]),
         "ddd_round_enqueue": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
@@ -222,8 +222,10 @@ def ddd_depth_continue(ctx, steps_done, st: ddd_state, stream=None):
                                              current_stream() if stream is None else stream), "ddd_depth_continue")
 
 
-def ddd_draft_step(ctx, step, W, hid, st: ddd_state, logits_dbg=None, lse_dbg=None, stream=None):
-    _check(load_library().ddd_draft_step(ctx, step, _ptr(W), _ptr(hid), C.byref(st), _ptr(logits_dbg), _ptr(lse_dbg),
+def ddd_draft_step(ctx, step, W, hid, st: ddd_state, tree: Optional[ddd_tree] = None, logits_dbg=None, lse_dbg=None,
+                   stream=None):
+    _check(load_library().ddd_draft_step(ctx, step, _ptr(W), _ptr(hid), C.byref(st),
+                                         C.byref(tree) if tree is not None else None, _ptr(logits_dbg), _ptr(lse_dbg),
                                          current_stream() if stream is None else stream), "ddd_draft_step")
 
 

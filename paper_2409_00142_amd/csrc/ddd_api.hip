@@ -286,9 +286,10 @@ int ddd_depth_continue(ddd_ctx* c, int32_t steps_done, ddd_state* st, void* stre
   return DDD_OK;
 }
 
-int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_state* st, float* logits_dbg,
-                   float* lse_dbg, void* stream) {
+int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_state* st, ddd_tree* tree,
+                   float* logits_dbg, float* lse_dbg, void* stream) {
   if (c == nullptr || W == nullptr || hid == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
+  if (tree != nullptr && !tree_ok(tree)) return DDD_ERR_INVALID_ARG;
   if (step < 0 || step >= c->cfg.max_depth) return DDD_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int n_rows = (step == 0) ? c->cfg.B : c->cfg.B * c->cfg.k;
@@ -301,7 +302,12 @@ int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd
   a.part_key = c->part_key;
   a.part_sum = c->part_sum;
   a.lse_dbg = lse_dbg;
+  if (tree != nullptr)
+    a.tree = *tree;
+  else
+    std::memset(&a.tree, 0, sizeof(a.tree));
   a.nslice = c->nslice;
+  a.m = c->cfg.m;
   DDD_HIP(launch_step_bookkeep(a, s));
   return DDD_OK;
 }
@@ -348,12 +354,10 @@ int ddd_round_enqueue(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, 
   for (int step = 0; step < c->cfg.max_depth; ++step) {
     rc = body(body_user, step, st, hid_buf, stream);
     if (rc != DDD_OK) return rc;
-    rc = ddd_draft_step(c, step, W, hid_buf, st, logits_dbg ? logits_dbg + dbg_stride * step : nullptr,
+    rc = ddd_draft_step(c, step, W, hid_buf, st, tree, logits_dbg ? logits_dbg + dbg_stride * step : nullptr,
                         lse_dbg ? lse_dbg + (size_t)c->cfg.B * c->cfg.k * step : nullptr, stream);
     if (rc != DDD_OK) return rc;
   }
-  rc = ddd_tree_finalize(c, st, tree, stream);
-  if (rc != DDD_OK) return rc;
   if (post != nullptr) rc = post(post_user, st, tree, stream);
   return rc;
 }

@@ -32,36 +32,47 @@ __device__ __forceinline__ uint64_t beam_key(float score, int token, int flat) {
 __device__ __forceinline__ int beam_key_flat(uint64_t key) { return (int)(0xFFu - ((uint32_t)key & 0xFFu)); }
 
 // ---- wave-wide max of a 64-bit key ----------------------------------------------------------
-// Must be called with all 64 lanes of the wave active.  Returns the maximum in every lane.
+// All of these must be called with all 64 lanes of the wave active; the result is the same in
+// every lane.  The cross-lane steps are DPP moves (quad swaps, half-row and row mirrors), the
+// four rows are combined through readlane.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move_u32(uint32_t x) {
+  // every pattern used here has a valid source lane, so bound_ctrl never takes effect
+  return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, CTRL, 0xf, 0xf, true);
+}
 template <int CTRL>
 __device__ __forceinline__ uint64_t dpp_move_u64(uint64_t x) {
-  int lo = (int)(uint32_t)x, hi = (int)(uint32_t)(x >> 32);
-  lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
-  hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
-  return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;
+  return ((uint64_t)dpp_move_u32<CTRL>((uint32_t)(x >> 32)) << 32) | dpp_move_u32<CTRL>((uint32_t)x);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_move_f32(float x) {
+  return __uint_as_float(dpp_move_u32<CTRL>(__float_as_uint(x)));
 }
 __device__ __forceinline__ uint64_t umax64(uint64_t a, uint64_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t umax32(uint32_t a, uint32_t b) { return a > b ? a : b; }
 
-__device__ __forceinline__ uint64_t readlane_u64(uint64_t x, int lane) {
-  uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, lane);
-  uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), lane);
-  return ((uint64_t)hi << 32) | lo;
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+  x = umax32(x, dpp_move_u32<0xB1>(x));    // quad_perm [1,0,3,2]  : lane ^ 1
+  x = umax32(x, dpp_move_u32<0x4E>(x));    // quad_perm [2,3,0,1]  : lane ^ 2
+  x = umax32(x, dpp_move_u32<0x141>(x));   // row_half_mirror      : other quad of each 8
+  x = umax32(x, dpp_move_u32<0x140>(x));   // row_mirror           : other half of each 16
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0);
+  const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32);
+  const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+  return umax32(umax32(a, b), umax32(c, d));
 }
 
+// Max of 64-bit keys as two 32-bit reductions: the high words first, then the low words of the
+// lanes that hold the maximal high word.  Valid keys have a non-zero low word; 0 means "none".
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t x) {
-  x = umax64(x, dpp_move_u64<0xB1>(x));    // quad_perm [1,0,3,2]  : lane ^ 1
-  x = umax64(x, dpp_move_u64<0x4E>(x));    // quad_perm [2,3,0,1]  : lane ^ 2
-  x = umax64(x, dpp_move_u64<0x141>(x));   // row_half_mirror      : other quad of each 8
-  x = umax64(x, dpp_move_u64<0x140>(x));   // row_mirror           : other half of each 16
-  uint64_t a = readlane_u64(x, 0), b = readlane_u64(x, 16), c = readlane_u64(x, 32), d = readlane_u64(x, 48);
-  return umax64(umax64(a, b), umax64(c, d));
+  const uint32_t hi = (uint32_t)(x >> 32), lo = (uint32_t)x;
+  const uint32_t M = wave_max_u32(hi);
+  const uint32_t L = wave_max_u32(hi == M ? lo : 0u);
+  return ((uint64_t)M << 32) | L;
 }
 
-__device__ __forceinline__ float wave_max_f32(float x) {
-  // ord32 keeps float order, reuse the integer path on the high word
-  uint64_t k = (uint64_t)ord32(x) << 32;
-  return unord32((uint32_t)(wave_max_u64(k) >> 32));
-}
+__device__ __forceinline__ float wave_max_f32(float x) { return unord32(wave_max_u32(ord32(x))); }
 
 // Sum over the wave in a fixed butterfly order (deterministic).  All lanes active.
 __device__ __forceinline__ float wave_sum_f32(float x) {

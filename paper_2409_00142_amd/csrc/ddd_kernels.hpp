@@ -48,7 +48,8 @@ struct StepArgs {             // merge + beam select + stop test in one launch
   const uint64_t* part_key;   // [B*k][nslice][k]
   const float* part_sum;
   float* lse_dbg;             // [B*k] or null: lse of every merged row
-  int nslice;
+  ddd_tree tree;              // tree.mask == null: do not build the final tree here
+  int nslice, m;
 };
 hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream);
 

@@ -15,9 +15,10 @@
 //    LDS stage into the MFMA A layout and accumulates v_mfma_f32_16x16x32_bf16 into one
 //    16x16 fp32 tile; the tile is published to LDS and the workgroup meets at a barrier.
 //  * The epilogue wave sums the NW partial tiles in a fixed order (so equal W rows give
-//    bit-equal logits) and lane r < 16 keeps row r's running max, running sum of
-//    exponentials and sorted top-k list in registers while the streaming waves are already
-//    loading the next tile.
+//    bit-equal logits).  Lane (vb, r) owns 4 of the 16 logits of hidden row r per tile and
+//    keeps their running max, running sum of exponentials and sorted top-k list in registers
+//    while the streaming waves are already loading the next tile; after the last tile the
+//    four lanes of a row merge their lists through LDS.
 #include "ddd_device.hpp"
 #include "ddd_kernels.hpp"
 
@@ -131,8 +132,9 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
     }
   } else {
     // ------------------------------ epilogue wave ------------------------------
-    const int r = lane;
-    const bool row_ok = (lane < 16) && (r < a.R);
+    // lane = (vb, r): rows 4*vb .. 4*vb+3 of the tile for hidden row r, exactly the MFMA C layout
+    const int r = lane & 15, vb = lane >> 4;
+    const bool row_ok = r < a.R;
     float m_run = -INFINITY, s_run = 0.f;
     uint64_t list[KL];
 #pragma unroll
@@ -140,36 +142,33 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
 
     for (int t = 0; t < nt; ++t) {
       __syncthreads();
-      if (row_ok) {
-        float x[16];
+      f32x4 s = {0.f, 0.f, 0.f, 0.f};
+      for (int w = 0; w < NW; ++w)   // fixed order: equal W rows give bit-equal logits
+        s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + lane * 4);
+      const int v0 = (t0 + t) * 16 + vb * 4;
+      const int nv = min(4, a.V - v0);
+      if (row_ok && nv > 0) {
+        float x[4];
 #pragma unroll
-        for (int vb = 0; vb < 4; ++vb) {
-          f32x4 s = {0.f, 0.f, 0.f, 0.f};
-          for (int w = 0; w < NW; ++w)
-            s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + (vb * 16 + r) * 4);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) x[vb * 4 + e] = s[e] + 0.0f;   // -0 -> +0
-        }
-        const int v0 = (t0 + t) * 16;
-        const int nv = min(16, a.V - v0);
+        for (int e = 0; e < 4; ++e) x[e] = s[e] + 0.0f;   // -0 -> +0
         if (a.logits_dbg != nullptr) {
 #pragma unroll
-          for (int e = 0; e < 16; ++e)
+          for (int e = 0; e < 4; ++e)
             if (e < nv) a.logits_dbg[(size_t)r * a.V + v0 + e] = x[e];
         }
-        float tmax = -INFINITY;
+        float tmax = x[0];
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
+        for (int e = 1; e < 4; ++e)
           if (e < nv) tmax = fmaxf(tmax, x[e]);
         const float m_new = fmaxf(m_run, tmax);
         float s_new = s_run * __expf(m_run - m_new);
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
+        for (int e = 0; e < 4; ++e)
           if (e < nv) s_new += __expf(x[e] - m_new);
         m_run = m_new;
         s_run = s_new;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int e = 0; e < 4; ++e) {
           uint64_t cur = row_key(x[e], v0 + e);
           if (e < nv && cur > list[KL - 1]) {
 #pragma unroll
@@ -183,20 +182,44 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
         }
       }
     }
-    if (row_ok) {
-      a.part_sum[(size_t)r * nslice + slice] = s_run;
-      uint64_t* pk = a.part_key + ((size_t)r * nslice + slice) * a.k;
+
+    // The four lanes of a hidden row merge their lists: through LDS into quads (lane' = 4*r + vb).
+    // Every streaming wave has passed its last barrier, so the stage area is free.
+    uint64_t* elist = reinterpret_cast<uint64_t*>(stage);            // [64][KL]
+    float* estat = reinterpret_cast<float*>(stage + 64 * KL * 8);    // [64][2]
+    const int slot = r * 4 + vb;
 #pragma unroll
-      for (int j = 0; j < KL; ++j)
-        if (j < a.k) pk[j] = list[j];
+    for (int j = 0; j < KL; ++j) elist[slot * KL + j] = list[j];
+    estat[slot * 2] = m_run;
+    estat[slot * 2 + 1] = s_run;
+    wave_lds_fence();
+    const int r2 = lane >> 2;
+    const bool ok2 = r2 < a.R;
+    const float m_l = estat[lane * 2], s_l = estat[lane * 2 + 1];
+    float m_q = fmaxf(m_l, dpp_move_f32<0xB1>(m_l));
+    m_q = fmaxf(m_q, dpp_move_f32<0x4E>(m_q));
+    float s_q = (s_l == 0.f) ? 0.f : s_l * __expf(m_l - m_q);
+    s_q += dpp_move_f32<0xB1>(s_q);
+    s_q += dpp_move_f32<0x4E>(s_q);
+    uint64_t* pk = a.part_key + ((size_t)(ok2 ? r2 : 0) * nslice + slice) * a.k;
+    int cur = 0;
+    for (int round = 0; round < a.k; ++round) {
+      const uint64_t head = (cur < KL) ? elist[lane * KL + cur] : 0ull;
+      uint64_t q = umax64(head, dpp_move_u64<0xB1>(head));
+      q = umax64(q, dpp_move_u64<0x4E>(q));
+      if (head == q && q != 0ull) ++cur;
+      if (ok2 && (lane & 3) == 0) pk[round] = q;
     }
+    if (ok2 && (lane & 3) == 0) a.part_sum[(size_t)r2 * nslice + slice] = s_q;
   }
 }
 
 template <int G>
 static hipError_t launch_g(const StreamArgs& a, int nslice, hipStream_t stream) {
   const dim3 grid(nslice), block((a.nw + 1) * 64);
-  const size_t lds = (size_t)2 * a.nw * 1024 + (size_t)a.nw * kStageBytes;
+  // partial tiles + per-wave stages; the stage area is reused by the epilogue's final merge (<= 8.5 KB)
+  const size_t stage_bytes = (size_t)a.nw * kStageBytes > 8704 ? (size_t)a.nw * kStageBytes : 8704;
+  const size_t lds = (size_t)2 * a.nw * 1024 + stage_bytes;
   if (a.k <= 4)
     hipLaunchKernelGGL((lmhead_stream_kernel<G, 4>), grid, block, lds, stream, a);
   else if (a.k <= 8)

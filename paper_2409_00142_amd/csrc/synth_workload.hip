@@ -88,41 +88,44 @@ struct TargetArgs {
   int32_t* out;
 };
 
-// grid: B; block 256: thread i handles tree index i
+// grid: B; block 256.  The rank-0 / rank-1 children of every pool node (its two lowest-id
+// children) are first scattered into LDS tables, then thread i handles tree index i.
 __global__ __launch_bounds__(256) void synth_target_kernel(TargetArgs a) {
-  const int b = blockIdx.x, i = threadIdx.x;
+  __shared__ int kid0[DDD_POOL_MAX], kid1[DDD_POOL_MAX];
+  const int b = blockIdx.x, tid = threadIdx.x;
   const int k = a.p.cfg.k, m = a.p.cfg.m, T = m + 1;
-  if (i >= T) return;
+  const size_t nmax = 1 + (size_t)k + (size_t)(a.p.cfg.max_depth - 1) * k * k;
+  const int32_t* ppar = a.st.pool_parent + (size_t)b * nmax;
+  const int32_t* ptok = a.st.pool_token + (size_t)b * nmax;
+  const int n_nodes = min(a.st.n_nodes[b], DDD_POOL_MAX);
   const int n_sel = a.tree.n_sel[b];
+  for (int c = tid; c < n_nodes; c += 256) {
+    kid0[c] = -1;
+    kid1[c] = -1;
+  }
+  __syncthreads();
+  for (int c = 1 + tid; c < n_nodes; c += 256) {
+    const int j = (c <= k) ? (c - 1) : ((c - 1 - k) % k);   // rank of node c among its siblings
+    if (j == 0) kid0[ppar[c]] = c;
+    if (j == 1) kid1[ppar[c]] = c;
+  }
+  __syncthreads();
+  const int i = tid;
+  if (i >= T) return;
   if (i > n_sel) {
     a.out[(size_t)b * T + i] = -1;
     return;
   }
-  const size_t nmax = 1 + (size_t)k + (size_t)(a.p.cfg.max_depth - 1) * k * k;
-  const int32_t* ppar = a.st.pool_parent + (size_t)b * nmax;
-  const int32_t* ptok = a.st.pool_token + (size_t)b * nmax;
-  const int n_nodes = a.st.n_nodes[b];
   const int node = (i == 0) ? 0 : a.tree.sel_node[(size_t)b * m + i - 1];
   const uint64_t skey = stream_key(a.p.seed, b, *a.p.round_ctr);
   const uint64_t tk = mix64(skey ^ mix64(kTarget + (uint64_t)node));
   const uint32_t u = (uint32_t)(tk >> 40);
   const int uni = (int)((tk & 0xFFFFFFFFull) % (uint64_t)a.p.cfg.V);
-  int kid0 = -1, kid1 = -1;   // the two lowest-id children = rank 0 and rank 1
-  for (int c = node + 1; c < n_nodes; ++c) {
-    if (ppar[c] == node) {
-      if (kid0 < 0) {
-        kid0 = c;
-      } else {
-        kid1 = c;
-        break;
-      }
-    }
-  }
   int out = uni;
-  if (u < kU24_070 && kid0 >= 0)
-    out = ptok[kid0];
-  else if (u >= kU24_070 && u < kU24_085 && kid1 >= 0)
-    out = ptok[kid1];
+  if (u < kU24_070 && kid0[node] >= 0)
+    out = ptok[kid0[node]];
+  else if (u >= kU24_070 && u < kU24_085 && kid1[node] >= 0)
+    out = ptok[kid1[node]];
   a.out[(size_t)b * T + i] = out;
 }
 
