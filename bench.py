@@ -60,7 +60,8 @@ def main():
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="one captured hipGraph per round (default) or plain stream launches")
     ap.add_argument("--traffic", default=None,
-                    help="JSON file {\"fetch_bytes\":..,\"write_bytes\":..} from rocprofv3 --pmc runs (optional)")
+                    help="JSON file with the HBM bytes per launch from rocprofv3 --pmc runs "
+                         "(default: profiles/traffic_<workload>.json)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -158,10 +159,12 @@ def main():
         side.synchronize()
         del wcopy
 
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload (null if none)
     traffic = None
-    if args.traffic and os.path.exists(args.traffic):
-        with open(args.traffic) as f:
-            traffic = json.load(f)
+    tpath = args.traffic or os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("bytes")
 
     us_per_depth_step = 1e6 * wall / max(1, exec_steps) if wl.B == 1 else None
     out = {
