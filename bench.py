@@ -19,7 +19,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 MFMA peak
 
 
 def log(*a):
@@ -124,15 +125,27 @@ def main():
         f"{ {d: int(c) for d, c in enumerate(depth_hist) if c} }")
     log(f"[bench] accept-length histogram: { {d: int(c) for d, c in enumerate(accept_hist) if c} }")
 
-    # ---- dominant kernel: the LM-head weight stream, alone, per-launch HIP events -------------
-    n_rows = min(wl.B * wl.k, 16)
-    mean_ms, min_ms = D.ddd_profile_lmhead_stream(g.ctx, g.W, g.hid, n_rows, args.profile_iters,
-                                                  stream=side.cuda_stream)
+    # ---- dominant kernel: the LM head, alone, per-launch HIP events --------------------------------
+    # <= 16 rows: the weight stream (HBM-bound); more rows: the MFMA GEMM (all B*k rows active)
+    n_rows = wl.B * wl.k
+    mean_ms, min_ms = D.ddd_profile_lmhead(g.ctx, g.W, g.hid, n_rows, args.profile_iters, stream=side.cuda_stream)
     w_bytes = wl.V * wl.H * 2
-    alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * D.ddd_num_slices(g.ctx) * (wl.k * 8 + 4)
+    if n_rows <= 16:
+        kernel_name = "lmhead_stream_kernel"
+        alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * D.ddd_num_slices(g.ctx) * (wl.k * 8 + 4)
+    else:
+        kernel_name = "lmhead_gemm_kernel"
+        n_slices = -(-((wl.V + 127) // 128) // (-(-((wl.V + 127) // 128) // 256)))
+        alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * n_slices * (wl.k * 8 + 4)
+    alg_flops = 2.0 * wl.V * wl.H * n_rows
     achieved = alg_bytes / (mean_ms * 1e-3) / 1e9
-    log(f"[bench] lmhead stream kernel: mean {mean_ms * 1e3:.2f} us, min {min_ms * 1e3:.2f} us per launch, "
-        f"{alg_bytes / 1e6:.2f} MB algorithmic -> {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
+    achieved_tflops = alg_flops / (mean_ms * 1e-3) / 1e12
+    log(f"[bench] {kernel_name} ({n_rows} rows): mean {mean_ms * 1e3:.2f} us, min {min_ms * 1e3:.2f} us per launch; "
+        f"{alg_bytes / 1e6:.2f} MB algorithmic -> {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of 8 TB/s); "
+        f"{alg_flops / 1e9:.1f} GFLOP -> {achieved_tflops:.0f} TFLOP/s ({100 * achieved_tflops / MFMA_PEAK_TFLOPS:.1f}% of "
+        f"{MFMA_PEAK_TFLOPS:.0f} TFLOP/s bf16)")
+    # which roofline binds: time at peak for the bytes vs for the flops
+    mfma_bound = alg_flops / (MFMA_PEAK_TFLOPS * 1e12) > alg_bytes / (HBM_PEAK_GBS * 1e9)
 
     # ---- plain read stream over the same bytes: the practical ceiling --------------------------
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -188,12 +201,16 @@ def main():
                    "executed_depth_steps": exec_steps,
                    "us_per_depth_step": us_per_depth_step,
                    "mean_depth": exec_steps / max(1, n_round_seq)},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "lmhead_stream_kernel", "us_per_launch": mean_ms * 1e3, "us_per_launch_min": min_ms * 1e3,
-                     "algorithmic_bytes_per_launch": alg_bytes, "launches_timed": args.profile_iters,
-                     "read_stream_ceiling_GBs": best},
+        "roofline": ({"bound": "mfma", "achieved": achieved_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": achieved_tflops / MFMA_PEAK_TFLOPS, "hbm_GBs": achieved,
+                      "hbm_frac": achieved / HBM_PEAK_GBS} if mfma_bound else
+                     {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": achieved / HBM_PEAK_GBS}),
     }
+    out["roofline"].update({"traffic": traffic, "kernel": kernel_name, "rows": n_rows,
+                            "us_per_launch": mean_ms * 1e3, "us_per_launch_min": min_ms * 1e3,
+                            "algorithmic_bytes_per_launch": alg_bytes, "algorithmic_flops_per_launch": alg_flops,
+                            "launches_timed": args.profile_iters, "read_stream_ceiling_GBs": best})
     if args.cpu_budget > 0:
         log(f"[bench] timing the CPU oracle for about {args.cpu_budget:.0f} s ...")
         out["cpu_baseline"] = cpu_baseline(wl, g.W_bits, g.plant_dir_np if wl.n_plant else None, thr, args.cpu_budget)

@@ -189,13 +189,14 @@ int ddd_round_launch(ddd_ctx* ctx, void* stream);
 /* Introspection used by the benchmark: number of weight-stream workgroups (slices). */
 int ddd_num_slices(const ddd_ctx* ctx);
 
-/* Measurement helper (the one call that synchronises): launches the LM-head weight-stream
- * kernel alone `iters` times on `stream` for n_rows <= DDD_STREAM_ROWS rows of hid_bf16, each
- * launch bracketed by its own pair of HIP events recorded on that stream, waits for the last
- * one and returns the mean and the minimum elapsed time per launch in milliseconds (host
- * pointers).  Partial results go to the context scratch and are not consumed. */
-int ddd_profile_lmhead_stream(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, int32_t n_rows, int32_t iters,
-                              float* mean_ms, float* min_ms, void* stream);
+/* Measurement helper (the one call that synchronises): launches the LM-head kernel alone
+ * `iters` times on `stream` for n_rows (<= B*k, all taken as active) rows of hid_bf16 - the weight
+ * stream for n_rows <= DDD_STREAM_ROWS, the MFMA GEMM otherwise - each launch bracketed by its own
+ * pair of HIP events recorded on that stream, waits for the last one and returns the mean and the
+ * minimum elapsed time per launch in milliseconds (host pointers).  Partial results go to the
+ * context scratch and are not consumed. */
+int ddd_profile_lmhead(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, int32_t n_rows, int32_t iters,
+                       float* mean_ms, float* min_ms, void* stream);
 
 #ifdef __cplusplus
 }

@@ -100,7 +100,7 @@ def load_library() -> C.CDLL:
         "ddd_synth_next_round": (C.c_int, [vp, vp]),
         "ddd_synth_read_stream": (C.c_int, [vp, sz, vp, i32, vp]),
         "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp]),
-        "ddd_profile_lmhead_stream": (C.c_int, [vp, vp, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
+        "ddd_profile_lmhead": (C.c_int, [vp, vp, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -296,12 +296,12 @@ def ddd_synth_round_stats(round_ctr, steps, accept_len, B, depth_hist, accept_hi
            "ddd_synth_round_stats")
 
 
-def ddd_profile_lmhead_stream(ctx, W, hid, n_rows, iters, stream=None):
-    """(mean_ms, min_ms) per launch of the weight-stream kernel alone; synchronises."""
+def ddd_profile_lmhead(ctx, W, hid, n_rows, iters, stream=None):
+    """(mean_ms, min_ms) per launch of the LM-head kernel alone; synchronises."""
     mean, mn = C.c_float(), C.c_float()
-    _check(load_library().ddd_profile_lmhead_stream(ctx, _ptr(W), _ptr(hid), n_rows, iters, C.byref(mean), C.byref(mn),
+    _check(load_library().ddd_profile_lmhead(ctx, _ptr(W), _ptr(hid), n_rows, iters, C.byref(mean), C.byref(mn),
                                                     current_stream() if stream is None else stream),
-           "ddd_profile_lmhead_stream")
+           "ddd_profile_lmhead")
     return mean.value, mn.value
 
 

@@ -15,10 +15,13 @@ struct ddd_ctx {
   int device;
   int n_cu;
   int G, nw;            // K split of the weight stream: H == 128 * G * nw
-  int ntiles, nslice;   // 16-row tiles of W, workgroups of the weight stream
+  int ntiles, nslice;   // 16-row tiles of W, workgroups of the weight stream (<= 16 rows)
+  int g_nmt, g_tps, g_nslice, g_grid;   // GEMM path (> 16 rows): 128-row tiles, tiles per slice, slices, grid
   int nmax;
-  uint64_t* part_key;   // [B*k][nslice][k]
-  float* part_sum;      // [B*k][nslice]
+  uint64_t* part_key;   // [B*k][max(nslice, g_nslice)][k] (indexed with the producing path's slice count)
+  float* part_sum;      // [B*k][max(nslice, g_nslice)]
+  int32_t* row_list;    // [B*k] active rows of the current call (GEMM path)
+  int32_t* n_act;       // [1]
   hipGraph_t graph;
   hipGraphExec_t graph_exec;
 };
@@ -76,9 +79,37 @@ BeamArgs beam_args(const ddd_ctx* c, const ddd_state* st, int step) {
   return a;
 }
 
-// Weight stream over n_rows rows in passes of DDD_STREAM_ROWS, partials into the context scratch.
+// MFMA GEMM over the rows listed in the context's row list.
+int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, float* logits_dbg, hipStream_t s) {
+  GemmArgs g;
+  g.W = static_cast<const uint16_t*>(W);
+  g.hid = static_cast<const uint16_t*>(hid);
+  g.row_list = c->row_list;
+  g.n_act_ptr = c->n_act;
+  g.part_key = c->part_key;
+  g.part_sum = c->part_sum;
+  g.logits_dbg = logits_dbg;
+  g.H = c->cfg.H;
+  g.V = c->cfg.V;
+  g.k = c->cfg.k;
+  g.nmt = c->g_nmt;
+  g.tps = c->g_tps;
+  g.nslice = c->g_nslice;
+  DDD_HIP(launch_lmhead_gemm(g, c->g_grid, s));
+  return DDD_OK;
+}
+
+// Slices of the path that handles n_rows rows.
+int slices_for(const ddd_ctx* c, int n_rows) { return n_rows <= DDD_STREAM_ROWS ? c->nslice : c->g_nslice; }
+
+// LM head over n_rows rows, partials into the context scratch: the weight stream for up to
+// DDD_STREAM_ROWS rows, the MFMA GEMM over the compacted active rows otherwise.
 int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const uint8_t* row_active, float* logits_dbg,
                    hipStream_t s) {
+  if (n_rows > DDD_STREAM_ROWS) {
+    DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
+    return enqueue_gemm(c, W, hid, logits_dbg, s);
+  }
   for (int r0 = 0; r0 < n_rows; r0 += DDD_STREAM_ROWS) {
     StreamArgs a;
     a.W = static_cast<const uint16_t*>(W);
@@ -171,13 +202,25 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->nmax = (int)ddd_pool_capacity(cfg);
   c->graph = nullptr;
   c->graph_exec = nullptr;
+  // GEMM path: slices of g_tps 128-row tiles, at most 256 of them; two workgroups per CU
+  c->g_nmt = (cfg->V + 127) / 128;
+  c->g_tps = (c->g_nmt + 255) / 256;
+  c->g_nslice = (c->g_nmt + c->g_tps - 1) / c->g_tps;
+  c->g_grid = 2 * ((c->n_cu + 7) / 8) * 8;
   const size_t rows = (size_t)cfg->B * cfg->k;
-  hipError_t e = hipMalloc(&c->part_key, rows * c->nslice * cfg->k * sizeof(uint64_t));
-  if (e == hipSuccess) e = hipMalloc(&c->part_sum, rows * c->nslice * sizeof(float));
+  const size_t ns = (size_t)(c->nslice > c->g_nslice ? c->nslice : c->g_nslice);
+  hipError_t e = hipMalloc(&c->part_key, rows * ns * cfg->k * sizeof(uint64_t));
+  if (e == hipSuccess) e = hipMalloc(&c->part_sum, rows * ns * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(&c->row_list, rows * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc(&c->n_act, sizeof(int32_t));
+  if (e == hipSuccess && rows > DDD_STREAM_ROWS) e = prepare_lmhead_gemm(cfg->k);
   if (e != hipSuccess) {
     if (c->part_key) (void)hipFree(c->part_key);
+    if (c->part_sum) (void)hipFree(c->part_sum);
+    if (c->row_list) (void)hipFree(c->row_list);
+    if (c->n_act) (void)hipFree(c->n_act);
     delete c;
-    return hip_fail(e, "hipMalloc(scratch)");
+    return hip_fail(e, "context scratch");
   }
   *out = c;
   return DDD_OK;
@@ -189,26 +232,29 @@ int ddd_destroy(ddd_ctx* c) {
   if (c->graph) (void)hipGraphDestroy(c->graph);
   (void)hipFree(c->part_key);
   (void)hipFree(c->part_sum);
+  (void)hipFree(c->row_list);
+  (void)hipFree(c->n_act);
   delete c;
   return DDD_OK;
 }
 
 int ddd_num_slices(const ddd_ctx* c) { return c ? c->nslice : DDD_ERR_INVALID_ARG; }
 
-int ddd_profile_lmhead_stream(ddd_ctx* c, const void* W, const void* hid, int32_t n_rows, int32_t iters,
-                              float* mean_ms, float* min_ms, void* stream) {
+int ddd_profile_lmhead(ddd_ctx* c, const void* W, const void* hid, int32_t n_rows, int32_t iters, float* mean_ms,
+                       float* min_ms, void* stream) {
   if (c == nullptr || W == nullptr || hid == nullptr || mean_ms == nullptr || min_ms == nullptr)
     return DDD_ERR_INVALID_ARG;
-  if (n_rows < 1 || n_rows > DDD_STREAM_ROWS || n_rows > c->cfg.B * c->cfg.k || iters < 1 || iters > 4096)
-    return DDD_ERR_INVALID_ARG;
+  if (n_rows < 1 || n_rows > c->cfg.B * c->cfg.k || iters < 1 || iters > 4096) return DDD_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool gemm = n_rows > DDD_STREAM_ROWS;
+  if (gemm) DDD_HIP(launch_build_row_list(nullptr, n_rows, c->row_list, c->n_act, s));
   std::vector<hipEvent_t> ev(2 * (size_t)iters, nullptr);
   int rc = DDD_OK;
   for (size_t i = 0; i < ev.size() && rc == DDD_OK; ++i)
     if (hipEventCreate(&ev[i]) != hipSuccess) rc = DDD_ERR_HIP;
   for (int i = 0; i < iters && rc == DDD_OK; ++i) {
     if (hipEventRecord(ev[2 * i], s) != hipSuccess) rc = DDD_ERR_HIP;
-    if (rc == DDD_OK) rc = enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, s);
+    if (rc == DDD_OK) rc = gemm ? enqueue_gemm(c, W, hid, nullptr, s) : enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, s);
     if (rc == DDD_OK && hipEventRecord(ev[2 * i + 1], s) != hipSuccess) rc = DDD_ERR_HIP;
   }
   if (rc == DDD_OK && hipEventSynchronize(ev[2 * (size_t)iters - 1]) != hipSuccess) rc = DDD_ERR_HIP;
@@ -261,7 +307,7 @@ int ddd_lmhead_topk(ddd_ctx* c, const void* W, const void* hid, int32_t n_rows, 
   m.topk_logprob = topk_logprob;
   m.lse = lse;
   m.n_rows = n_rows;
-  m.nslice = c->nslice;
+  m.nslice = slices_for(c, n_rows);
   m.k = c->cfg.k;
   DDD_HIP(launch_merge(m, s));
   return DDD_OK;
@@ -306,7 +352,7 @@ int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd
     a.tree = *tree;
   else
     std::memset(&a.tree, 0, sizeof(a.tree));
-  a.nslice = c->nslice;
+  a.nslice = slices_for(c, n_rows);
   a.m = c->cfg.m;
   DDD_HIP(launch_step_bookkeep(a, s));
   return DDD_OK;

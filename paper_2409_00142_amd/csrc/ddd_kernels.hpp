@@ -20,6 +20,23 @@ struct StreamArgs {
 // G = 128-wide K groups per streaming wave (1, 2 or 4); H == 128 * G * nw.
 hipError_t launch_lmhead_stream(const StreamArgs& a, int G, int nslice, hipStream_t stream);
 
+// ---- LM-head MFMA GEMM for more than 16 rows (lmhead_gemm.hip) --------------------------------
+struct GemmArgs {
+  const uint16_t* W;          // bf16 [V,H]
+  const uint16_t* hid;        // bf16 [rows,H]
+  const int32_t* row_list;    // [n_act] ids of the active rows, ascending
+  const int32_t* n_act_ptr;   // device scalar
+  uint64_t* part_key;         // [rows][nslice][k]
+  float* part_sum;            // [rows][nslice]
+  float* logits_dbg;          // fp32 [rows][V] or null
+  int H, V, k;
+  int nmt, tps, nslice;       // 128-row tiles of W, tiles per slice, slices
+};
+hipError_t prepare_lmhead_gemm(int k);   // once per process and k: enables the kernel's LDS size
+hipError_t launch_lmhead_gemm(const GemmArgs& a, int grid, hipStream_t stream);
+hipError_t launch_build_row_list(const uint8_t* row_active, int n_rows, int32_t* row_list, int32_t* n_act,
+                                 hipStream_t stream);
+
 // ---- per-row merge, beam select, stop test (bookkeep.hip) -------------------------------------
 struct MergeArgs {
   const uint64_t* part_key;   // [n_rows][nslice][k]

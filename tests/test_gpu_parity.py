@@ -40,7 +40,10 @@ LM_CASES = [
     ("g4_nw8", 1, 10, 4096, 4100, 10, 0.02, 3.5, ((17, 2900), (100, 101))),
     ("g4_nw10", 1, 8, 5120, 2050, 7, 0.02, 3.5, ()),
     ("small_V", 1, 4, 128, 20, 3, 0.2, 2.0, ()),
-    ("two_pass_rows", 3, 8, 512, 2000, 24, 0.04, 3.0, ((5, 1999),)),
+    ("gemm_rows24", 3, 8, 512, 2000, 24, 0.04, 3.0, ((5, 1999),)),
+    ("gemm_ragged_V_rows40", 4, 10, 1024, 5003, 40, 0.03, 3.0, ((7, 5002),)),
+    ("gemm_rows130_k16", 9, 16, 256, 3000, 130, 0.06, 3.0, ()),
+    ("gemm_two_tiles_per_slice", 5, 4, 128, 128 * 300 - 5, 20, 0.2, 2.0, ((100, 38000),)),
 ]
 
 
@@ -84,6 +87,44 @@ def test_lmhead_topk_against_oracle(gpu, case):
         assert np.array_equal(g_lp[r], want_lp)
         o_lp = O.logprobs_row(g_logits[r])[g_tok[r]]
         assert np.max(np.abs(g_lp[r].astype(np.float64) - o_lp)) <= LOGPROB_TOL
+
+
+def test_lmhead_topk_gemm_path_row_active(gpu):
+    """More than 16 rows: only the active rows are multiplied, the others are left untouched."""
+    torch, D, SD = gpu
+    B, k, H, V, R = 6, 8, 256, 1500, 48
+    print(f"[case] lmhead_topk gemm row_active B={B} k={k} H={H} V={V} R={R}", flush=True)
+    rng = np.random.default_rng(11)
+    W_bits = synth.make_lm_head(V, H, 0.05, seed=2)
+    hid_bits = _rand_hid_bits(rng, R, H, 4.0)
+    act_np = (rng.random(R) < 0.6).astype(np.uint8)
+    act_np[:3] = [1, 0, 1]
+    cfg = D.make_config(B, H, V, k, 4, 8, 0.3)
+    ctx = D.ddd_create(cfg)
+    try:
+        W, hid = SD.upload_bits(W_bits), SD.upload_bits(hid_bits)
+        tok = torch.full((R, k), -7, dtype=torch.int32, device="cuda")
+        lp = torch.full((R, k), 9.0, dtype=torch.float32, device="cuda")
+        lse = torch.full((R,), 9.0, dtype=torch.float32, device="cuda")
+        dbg = torch.full((R, V), float("nan"), dtype=torch.float32, device="cuda")
+        act = torch.from_numpy(act_np).cuda()
+        D.ddd_lmhead_topk(ctx, W, hid, R, act, tok, lp, lse, dbg)
+        torch.cuda.synchronize()
+        t, lg = tok.cpu().numpy(), dbg.cpu().numpy()
+        logits = O.lmhead_logits(W_bits, hid_bits)
+        for r in range(R):
+            if act_np[r]:
+                assert np.max(np.abs(lg[r] - logits[r])) <= LOGIT_TOL
+                assert np.array_equal(t[r], O.row_topk(lg[r], k)), r
+            else:
+                assert (t[r] == -7).all() and np.isnan(lg[r]).all(), r
+        act.zero_()
+        tok.fill_(-7)
+        D.ddd_lmhead_topk(ctx, W, hid, R, act, tok, lp, lse, None)
+        torch.cuda.synchronize()
+        assert (tok.cpu().numpy() == -7).all()
+    finally:
+        D.ddd_destroy(ctx)
 
 
 def test_lmhead_topk_row_active_and_errors(gpu):
@@ -291,7 +332,11 @@ ROUND_CASES = [
     ("tiny_t_gt1", synth.WORKLOADS["tiny"], 1.5, 2, 1),
     ("tiny_paper_S", synth.WORKLOADS["tiny"].with_(check_mask=(1 << 3) | (1 << 5), threshold=0.9), None, 3, 0),
     ("tiny_b3", synth.WORKLOADS["tiny"].with_(B=3), None, 4, 6),
-    ("tiny_b5_two_passes", synth.WORKLOADS["tiny"].with_(B=5), None, 3, 2),
+    ("tiny_b5_gemm_rows", synth.WORKLOADS["tiny"].with_(B=5), None, 3, 2),
+    ("b64_shape_small_V", synth.WORKLOADS["7b_b64"].with_(V=4096, H=1024, D=6, m=40), None, 2, 1),
+    ("large_vocab_shape_small", synth.WORKLOADS["large_vocab"].with_(V=128 * 300, H=512, B=8, D=4, m=40,
+                                                                     dup_pairs=((1000, 30000), (1997, 4009)),
+                                                                     n_plant=2, plant_row_p=0.2), None, 2, 1),
     ("planted_ties_k16", synth.WORKLOADS["large_vocab"].with_(B=1, V=6007, H=1024, D=4, m=40, plant_row_p=0.3,
                                                                dup_pairs=((1000, 5000), (1997, 4009)), n_plant=2),
      None, 4, 4),
