@@ -122,11 +122,16 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   if (a.row_active != nullptr && !a.row_active[row]) return;   // wave-uniform
   uint64_t key;
   float lse;
-  uint64_t head[kHPL], second[kHPL];
-  float psum[kHPL];
-  const uint64_t* pk = a.part_key + (size_t)row * a.nslice * a.k;
-  merge_load_heads(pk, a.part_sum + (size_t)row * a.nslice, a.nslice, a.k, lane, head, second, psum);
-  merge_row_dispatch(pk, head, second, psum, a.nslice, a.k, lane, wl[wave], key, lse);
+  if (a.nslice == 0) {   // dense format: the keys are final
+    key = a.part_key[(size_t)row * a.k + min(lane, a.k - 1)];
+    lse = a.part_sum[row];
+  } else {
+    uint64_t head[kHPL], second[kHPL];
+    float psum[kHPL];
+    const uint64_t* pk = a.part_key + (size_t)row * a.nslice * a.k;
+    merge_load_heads(pk, a.part_sum + (size_t)row * a.nslice, a.nslice, a.k, lane, head, second, psum);
+    merge_row_dispatch(pk, head, second, psum, a.nslice, a.k, lane, wl[wave], key, lse);
+  }
   if (lane < a.k) {
     a.topk_token[(size_t)row * a.k + lane] = key_token(key);
     a.topk_logprob[(size_t)row * a.k + lane] = key_value(key) - lse;
@@ -136,6 +141,156 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(merge_kernel, dim3((a.n_rows + 3) / 4), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ---- row reduction of materialised logits (GEMM path) ------------------------------------------
+// One workgroup per row.  The GEMM left, for every group of 64 consecutive vocabulary rows, the
+// group's max and sum of exponentials.  lse follows from those alone.  The k-th largest group max
+// T is a lower bound of the row's k-th largest logit (k distinct elements are >= T), so one
+// compare-only pass over the row collects the few candidates >= T, and the exact top-k by
+// (logit desc, token asc) is taken among them.  If more candidates than fit turn up (massive
+// ties, e.g. constant logits), an exact but slow path takes over: k passes over the row, each
+// finding the largest key below the previous winner.
+constexpr int kCandMax = 1024;
+
+__global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
+  __shared__ uint64_t s_cand[kCandMax];
+  __shared__ float s_red[8];
+  __shared__ float s_T;
+  __shared__ int s_cnt;
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (a.row_active != nullptr && !a.row_active[row]) return;   // uniform
+  const int ngrp_valid = (a.V + 63) >> 6;
+  const float* gmax = a.grp_max + (size_t)row * a.ngrp;
+  const float* gsum = a.grp_sum + (size_t)row * a.ngrp;
+
+  // ---- row max, lse ---------------------------------------------------------------------------
+  float m = -INFINITY;
+  for (int g = tid; g < ngrp_valid; g += 256) m = fmaxf(m, gmax[g]);
+  m = wave_max_f32(m);
+  if (lane == 0) s_red[wave] = m;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  float acc = 0.f;
+  for (int g = tid; g < ngrp_valid; g += 256) acc += gsum[g] * __expf(gmax[g] - M);
+  acc = wave_sum_f32(acc);
+  if (lane == 0) s_red[4 + wave] = acc;
+  // ---- T = k-th largest group max (or -inf if there are fewer than k groups): wave 0 -------------
+  if (tid == 0) s_cnt = 0;
+  if (wave == 0) {
+    // up to 2048 groups (V <= 131072): 32 per lane, kept as ordered keys, k rounds of wave max
+    uint32_t loc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const int g = lane + 64 * i;
+      loc[i] = (g < ngrp_valid) ? ord32(gmax[g]) : 0u;
+    }
+    uint32_t T = 0u;
+    for (int round = 0; round < a.k; ++round) {
+      uint32_t lm = 0u;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) lm = umax32(lm, loc[i]);
+      T = wave_max_u32(lm);
+      if (T == 0u) break;                                    // uniform: fewer than k groups
+      // remove one holder of the maximum (the lowest lane, its lowest slot)
+      const unsigned long long holders = __ballot(lm == T);
+      if (lane == __ffsll((long long)holders) - 1) {
+        bool done = false;
+#pragma unroll
+        for (int i = 0; i < 32; ++i)
+          if (!done && loc[i] == T) {
+            loc[i] = 0u;
+            done = true;
+          }
+      }
+    }
+    if (lane == 0) s_T = (T == 0u) ? -INFINITY : unord32(T);
+  }
+  __syncthreads();
+  const float lse = M + __logf(s_red[4] + s_red[5] + s_red[6] + s_red[7]);
+
+  // ---- collect candidates >= T ------------------------------------------------------------------
+  const float* x = a.logits + (size_t)row * a.V;
+  const float T = s_T;
+  if ((a.V & 3) == 0) {
+    const int nchunk = a.V >> 2;
+    for (int c0 = tid; c0 < nchunk; c0 += 8 * 256) {
+      float4 q[8];   // eight independent 16-byte loads in flight before any is consumed
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int c = c0 + u * 256;
+        q[u] = (c < nchunk) ? *reinterpret_cast<const float4*>(x + 4 * c)
+                            : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int c = c0 + u * 256;
+        const float xv[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+        if (c < nchunk && fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])) >= T) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (xv[e] >= T) {
+              const int p = atomicAdd(&s_cnt, 1);
+              if (p < kCandMax) s_cand[p] = row_key(xv[e], 4 * c + e);
+            }
+        }
+      }
+    }
+  } else {
+    for (int v = tid; v < a.V; v += 256) {
+      const float xv = x[v];
+      if (xv >= T) {
+        const int p = atomicAdd(&s_cnt, 1);
+        if (p < kCandMax) s_cand[p] = row_key(xv, v);
+      }
+    }
+  }
+  __syncthreads();
+  const int cnt = s_cnt;
+
+  if (cnt <= kCandMax) {                                       // uniform
+    // ---- exact top-k among the candidates: wave 0, k rounds of wave max over its strided share ---
+    if (wave == 0) {
+      uint64_t mine = 0ull;
+      for (int round = 0; round < a.k; ++round) {
+        uint64_t loc = 0ull;
+        for (int i = lane; i < cnt; i += 64) loc = umax64(loc, s_cand[i]);
+        const uint64_t best = wave_max_u64(loc);
+        if (lane == round) mine = best;
+        for (int i = lane; i < cnt; i += 64)
+          if (s_cand[i] == best) s_cand[i] = 0ull;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+      if (lane < a.k) a.part_key[(size_t)row * a.k + lane] = mine;
+      if (lane == 0) a.part_sum[row] = lse;
+    }
+  } else {
+    // ---- more than kCandMax elements tie at or above T (e.g. constant logits): exact but slow ------
+    // k rounds; each finds the largest key below the previous winner by a pass over the whole row.
+    uint64_t* s_best = s_cand;   // [4] per-wave maxima
+    uint64_t prev = ~0ull, mine = 0ull;
+    for (int round = 0; round < a.k; ++round) {
+      uint64_t loc = 0ull;
+      for (int v = tid; v < a.V; v += 256) {
+        const uint64_t key = row_key(x[v], v);
+        if (key < prev) loc = umax64(loc, key);
+      }
+      loc = wave_max_u64(loc);
+      __syncthreads();
+      if (lane == 0) s_best[wave] = loc;
+      __syncthreads();
+      prev = umax64(umax64(s_best[0], s_best[1]), umax64(s_best[2], s_best[3]));
+      if (tid == round) mine = prev;
+    }
+    if (tid < a.k) a.part_key[(size_t)row * a.k + tid] = mine;
+    if (tid == 0) a.part_sum[row] = lse;
+  }
+}
+
+hipError_t launch_row_topk(const RowTopkArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(row_topk_kernel, dim3(a.n_rows), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -278,19 +433,27 @@ __global__ __launch_bounds__(1024) void step_bookkeep_kernel(StepArgs a) {
   // Issue every independent load first: the flag, this wave's slice heads, the current beam.
   const uint8_t active = g.st.active[b];
   const size_t row = row0 + min(wave, rows - 1);
-  const uint64_t* pk = a.part_key + row * a.nslice * g.k;
+  const bool dense = (a.nslice == 0);             // keys already final (rows came through the GEMM path)
+  const uint64_t* pk = a.part_key + row * (dense ? 1 : a.nslice) * g.k;
   uint64_t head[kHPL], second[kHPL];
   float psum[kHPL];
-  merge_load_heads(pk, a.part_sum + row * a.nslice, a.nslice, g.k, lane, head, second, psum);
+  uint64_t dkey = 0ull;
+  float dlse = 0.f;
+  if (dense) {
+    dkey = pk[min(lane, g.k - 1)];
+    dlse = a.part_sum[row];
+  } else {
+    merge_load_heads(pk, a.part_sum + row * a.nslice, a.nslice, g.k, lane, head, second, psum);
+  }
   const int li = min(lane, g.k - 1);
   const float old_lps = g.st.logprobsum[(size_t)b * g.k + li];
   const int old_node = g.st.beam_node[(size_t)b * g.k + li];
   if (!active) return;                            // uniform over the workgroup
   if (threadIdx.x == 0) s_stopped = 0;
   if (wave < rows) {
-    uint64_t key;
-    float lse;
-    merge_row_dispatch(pk, head, second, psum, a.nslice, g.k, lane, wl[wave], key, lse);
+    uint64_t key = dkey;
+    float lse = dlse;
+    if (!dense) merge_row_dispatch(pk, head, second, psum, a.nslice, g.k, lane, wl[wave], key, lse);
     if (lane < g.k) {
       s_tok[wave][lane] = key_token(key);
       s_lp[wave][lane] = key_value(key) - lse;

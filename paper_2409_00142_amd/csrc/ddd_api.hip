@@ -16,12 +16,16 @@ struct ddd_ctx {
   int n_cu;
   int G, nw;            // K split of the weight stream: H == 128 * G * nw
   int ntiles, nslice;   // 16-row tiles of W, workgroups of the weight stream (<= 16 rows)
-  int g_nmt, g_tps, g_nslice, g_grid;   // GEMM path (> 16 rows): 128-row tiles, tiles per slice, slices, grid
+  int g_grid;           // GEMM path (> 16 rows): one workgroup per CU
   int nmax;
-  uint64_t* part_key;   // [B*k][max(nslice, g_nslice)][k] (indexed with the producing path's slice count)
-  float* part_sum;      // [B*k][max(nslice, g_nslice)]
+  uint64_t* part_key;   // [B*k][nslice][k] (weight stream) or [B*k][k] (GEMM path, dense)
+  float* part_sum;      // [B*k][nslice] or [B*k]
   int32_t* row_list;    // [B*k] active rows of the current call (GEMM path)
   int32_t* n_act;       // [1]
+  float* logits;        // [B*k][V] fp32 logits of the GEMM path (null if B*k <= 16)
+  float* grp_max;       // [B*k][ngrp] per-group max / sum-exp of the GEMM path
+  float* grp_sum;
+  int ngrp;
   hipGraph_t graph;
   hipGraphExec_t graph_exec;
 };
@@ -79,36 +83,48 @@ BeamArgs beam_args(const ddd_ctx* c, const ddd_state* st, int step) {
   return a;
 }
 
-// MFMA GEMM over the rows listed in the context's row list.
-int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, float* logits_dbg, hipStream_t s) {
+// MFMA GEMM over the rows listed in the context's row list, logits into `out`.
+int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, int max_rows, float* out, hipStream_t s) {
   GemmArgs g;
   g.W = static_cast<const uint16_t*>(W);
   g.hid = static_cast<const uint16_t*>(hid);
   g.row_list = c->row_list;
   g.n_act_ptr = c->n_act;
-  g.part_key = c->part_key;
-  g.part_sum = c->part_sum;
-  g.logits_dbg = logits_dbg;
+  g.logits = out;
+  g.grp_max = c->grp_max;
+  g.grp_sum = c->grp_sum;
   g.H = c->cfg.H;
   g.V = c->cfg.V;
-  g.k = c->cfg.k;
-  g.nmt = c->g_nmt;
-  g.tps = c->g_tps;
-  g.nslice = c->g_nslice;
-  DDD_HIP(launch_lmhead_gemm(g, c->g_grid, s));
+  g.ngrp = c->ngrp;
+  DDD_HIP(launch_lmhead_gemm(g, max_rows, c->g_grid, s));
   return DDD_OK;
 }
 
-// Slices of the path that handles n_rows rows.
-int slices_for(const ddd_ctx* c, int n_rows) { return n_rows <= DDD_STREAM_ROWS ? c->nslice : c->g_nslice; }
+// Slices of the path that handles n_rows rows (0 = dense results of the GEMM path).
+int slices_for(const ddd_ctx* c, int n_rows) { return n_rows <= DDD_STREAM_ROWS ? c->nslice : 0; }
 
 // LM head over n_rows rows, partials into the context scratch: the weight stream for up to
 // DDD_STREAM_ROWS rows, the MFMA GEMM over the compacted active rows otherwise.
 int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const uint8_t* row_active, float* logits_dbg,
                    hipStream_t s) {
   if (n_rows > DDD_STREAM_ROWS) {
+    float* out = logits_dbg ? logits_dbg : c->logits;
     DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
-    return enqueue_gemm(c, W, hid, logits_dbg, s);
+    int rc = enqueue_gemm(c, W, hid, n_rows, out, s);
+    if (rc != DDD_OK) return rc;
+    RowTopkArgs t;
+    t.logits = out;
+    t.grp_max = c->grp_max;
+    t.grp_sum = c->grp_sum;
+    t.ngrp = c->ngrp;
+    t.row_active = row_active;
+    t.part_key = c->part_key;
+    t.part_sum = c->part_sum;
+    t.n_rows = n_rows;
+    t.V = c->cfg.V;
+    t.k = c->cfg.k;
+    DDD_HIP(launch_row_topk(t, s));
+    return DDD_OK;
   }
   for (int r0 = 0; r0 < n_rows; r0 += DDD_STREAM_ROWS) {
     StreamArgs a;
@@ -172,7 +188,10 @@ size_t ddd_pool_capacity(const ddd_config* cfg) {
 size_t ddd_scratch_bytes(const ddd_config* cfg) {
   if (ddd_config_validate(cfg) != DDD_OK) return 0;
   const size_t rows = (size_t)cfg->B * cfg->k, max_slices = 512;
-  return rows * max_slices * cfg->k * sizeof(uint64_t) + rows * max_slices * sizeof(float);
+  size_t n = rows * max_slices * cfg->k * sizeof(uint64_t) + rows * max_slices * sizeof(float) + rows * 4 + 4;
+  if (rows > DDD_STREAM_ROWS)   // logits and per-group statistics of the GEMM path
+    n += rows * (size_t)cfg->V * sizeof(float) + 2 * rows * (size_t)(((cfg->V + 63) / 64 + 3) & ~3) * sizeof(float);
+  return n;
 }
 
 int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
@@ -202,19 +221,27 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->nmax = (int)ddd_pool_capacity(cfg);
   c->graph = nullptr;
   c->graph_exec = nullptr;
-  // GEMM path: slices of g_tps 128-row tiles, at most 256 of them; two workgroups per CU
-  c->g_nmt = (cfg->V + 127) / 128;
-  c->g_tps = (c->g_nmt + 255) / 256;
-  c->g_nslice = (c->g_nmt + c->g_tps - 1) / c->g_tps;
-  c->g_grid = 2 * ((c->n_cu + 7) / 8) * 8;
+  c->g_grid = ((c->n_cu + 7) / 8) * 8;
+  c->logits = nullptr;
+  c->grp_max = nullptr;
+  c->grp_sum = nullptr;
+  c->ngrp = ((cfg->V + 63) / 64 + 3) & ~3;
   const size_t rows = (size_t)cfg->B * cfg->k;
-  const size_t ns = (size_t)(c->nslice > c->g_nslice ? c->nslice : c->g_nslice);
+  const size_t ns = (size_t)c->nslice;
   hipError_t e = hipMalloc(&c->part_key, rows * ns * cfg->k * sizeof(uint64_t));
   if (e == hipSuccess) e = hipMalloc(&c->part_sum, rows * ns * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(&c->row_list, rows * sizeof(int32_t));
   if (e == hipSuccess) e = hipMalloc(&c->n_act, sizeof(int32_t));
-  if (e == hipSuccess && rows > DDD_STREAM_ROWS) e = prepare_lmhead_gemm(cfg->k);
+  if (e == hipSuccess && rows > DDD_STREAM_ROWS) {
+    e = hipMalloc(&c->logits, rows * (size_t)cfg->V * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(&c->grp_max, rows * (size_t)c->ngrp * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(&c->grp_sum, rows * (size_t)c->ngrp * sizeof(float));
+    if (e == hipSuccess) e = prepare_lmhead_gemm();
+  }
   if (e != hipSuccess) {
+    if (c->logits) (void)hipFree(c->logits);
+    if (c->grp_max) (void)hipFree(c->grp_max);
+    if (c->grp_sum) (void)hipFree(c->grp_sum);
     if (c->part_key) (void)hipFree(c->part_key);
     if (c->part_sum) (void)hipFree(c->part_sum);
     if (c->row_list) (void)hipFree(c->row_list);
@@ -234,6 +261,9 @@ int ddd_destroy(ddd_ctx* c) {
   (void)hipFree(c->part_sum);
   (void)hipFree(c->row_list);
   (void)hipFree(c->n_act);
+  if (c->logits) (void)hipFree(c->logits);
+  if (c->grp_max) (void)hipFree(c->grp_max);
+  if (c->grp_sum) (void)hipFree(c->grp_sum);
   delete c;
   return DDD_OK;
 }
@@ -254,7 +284,8 @@ int ddd_profile_lmhead(ddd_ctx* c, const void* W, const void* hid, int32_t n_row
     if (hipEventCreate(&ev[i]) != hipSuccess) rc = DDD_ERR_HIP;
   for (int i = 0; i < iters && rc == DDD_OK; ++i) {
     if (hipEventRecord(ev[2 * i], s) != hipSuccess) rc = DDD_ERR_HIP;
-    if (rc == DDD_OK) rc = gemm ? enqueue_gemm(c, W, hid, nullptr, s) : enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, s);
+    if (rc == DDD_OK)
+      rc = gemm ? enqueue_gemm(c, W, hid, n_rows, c->logits, s) : enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, s);
     if (rc == DDD_OK && hipEventRecord(ev[2 * i + 1], s) != hipSuccess) rc = DDD_ERR_HIP;
   }
   if (rc == DDD_OK && hipEventSynchronize(ev[2 * (size_t)iters - 1]) != hipSuccess) rc = DDD_ERR_HIP;

@@ -26,18 +26,32 @@ struct GemmArgs {
   const uint16_t* hid;        // bf16 [rows,H]
   const int32_t* row_list;    // [n_act] ids of the active rows, ascending
   const int32_t* n_act_ptr;   // device scalar
-  uint64_t* part_key;         // [rows][nslice][k]
-  float* part_sum;            // [rows][nslice]
-  float* logits_dbg;          // fp32 [rows][V] or null
-  int H, V, k;
-  int nmt, tps, nslice;       // 128-row tiles of W, tiles per slice, slices
+  float* logits;              // fp32 [rows][V]: written for the active rows
+  float* grp_max;             // fp32 [rows][ngrp]: max of each group of 64 consecutive vocabulary rows ...
+  float* grp_sum;             // fp32 [rows][ngrp]: ... and sum of exp(logit - that max); ngrp = ceil(V/64) rounded up to 4
+  int H, V, ngrp;
 };
-hipError_t prepare_lmhead_gemm(int k);   // once per process and k: enables the kernel's LDS size
-hipError_t launch_lmhead_gemm(const GemmArgs& a, int grid, hipStream_t stream);
+hipError_t prepare_lmhead_gemm();   // once per process: enables the kernels' LDS sizes
+// max_rows: the largest number of rows this call can have (picks the tile shape)
+hipError_t launch_lmhead_gemm(const GemmArgs& a, int max_rows, int grid, hipStream_t stream);
 hipError_t launch_build_row_list(const uint8_t* row_active, int n_rows, int32_t* row_list, int32_t* n_act,
                                  hipStream_t stream);
 
+// Row reduction of materialised logits: lse and top-k keys of every active row, in the "dense"
+// partial format part_key[row][k] (final keys in order), part_sum[row] = lse.
+struct RowTopkArgs {
+  const float* logits;        // fp32 [n_rows][V]
+  const float* grp_max;       // fp32 [n_rows][ngrp] per-group statistics written by the GEMM
+  const float* grp_sum;
+  const uint8_t* row_active;  // [n_rows] or null
+  uint64_t* part_key;         // [n_rows][k]
+  float* part_sum;            // [n_rows]
+  int n_rows, V, k, ngrp;
+};
+hipError_t launch_row_topk(const RowTopkArgs& a, hipStream_t stream);
+
 // ---- per-row merge, beam select, stop test (bookkeep.hip) -------------------------------------
+// nslice == 0 selects the dense format above (nothing to merge).
 struct MergeArgs {
   const uint64_t* part_key;   // [n_rows][nslice][k]
   const float* part_sum;      // [n_rows][nslice]

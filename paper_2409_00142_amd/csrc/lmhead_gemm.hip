@@ -1,22 +1,23 @@
-// LM-head projection for more than 16 hidden rows (batched rounds): an MFMA GEMM with the same
-// fused epilogue and the same partial-result format as the weight stream.
+// LM-head projection for more than 16 hidden rows (batched rounds): an MFMA GEMM.
 //
-//   logits^T[V, R] = W[V, H] * hid^T[H, R]      (bf16 in, fp32 accumulate)
+//   logits[r, v] = sum_h hid[r, h] * W[v, h]        (bf16 in, fp32 accumulate, fp32 out)
 //
-// Workgroup tile 128 (vocabulary rows) x 128 (hidden rows), K tile 64, 256 threads = 2 x 2 waves
-// with 64 x 64 wave tiles of v_mfma_f32_32x32x16_bf16.  W is the A operand, so a lane of the
-// accumulator owns one hidden row and 32 vocabulary rows per tile: the online logsoftmax
-// statistics and the sorted top-k list of that (lane, row) live in registers.  Both operands
-// are staged through double-buffered, padded (144-byte pitch) LDS tiles; the next K tile is
-// loaded from global memory into registers while the current one is multiplied.  Two workgroups
-// fit on a CU (about 74 KB of LDS, at most 256 VGPRs), so one workgroup's epilogue (vector ALU)
-// overlaps the other's matrix work.
+// With hundreds of rows the projection is bound by the matrix cores, not by HBM, and on this chip
+// by the LDS bandwidth that feeds them: a 64 x 64 wave tile needs one 1 KB fragment read per
+// MFMA, which measured LDS-bound at about a quarter of the MFMA peak.  The kernel therefore uses
+// large wave tiles - AB x BB blocks of v_mfma_f32_32x32x16_bf16 per wave, 2 x 2 waves per
+// workgroup, up to 256 (vocabulary rows) x 320 (hidden rows) per workgroup - which leaves no
+// registers for per-row top-k lists; the fp32 logits of the active rows are written out (HBM has
+// slack in this regime) and a second kernel reduces each row (row_topk_kernel).
 //
-// A slice is a group of `tps` consecutive 128-row tiles of W; a unit of work is (slice, column
-// tile).  Units are handed out so that workgroups of one XCD work on neighbouring units: the
-// column tiles of one slice read the same W rows and share them through that XCD's L2, so W
-// comes from HBM once.  Only active rows are multiplied: the columns are gathered through a
-// compacted row list built on the device.
+// W is the A operand, so an accumulator lane owns one hidden row and four consecutive vocabulary
+// rows per register quad: the output is stored as float4 along V.  Both operands go through
+// double-buffered LDS tiles of 32 k (80-byte pitch, conflict-free 16-byte reads); the K loop is
+// unrolled by two with two static register sets so that the loads of tile kt+2 are in flight
+// while tile kt is multiplied.  Only active rows are multiplied: the B rows are gathered through
+// the compacted row list and column blocks past the last active row are skipped per wave.
+// Work units are (row tile of W, column tile), handed out so that the column tiles of one row
+// tile run on the same XCD and share the W rows through its L2.
 #include "ddd_device.hpp"
 #include "ddd_kernels.hpp"
 
@@ -24,222 +25,188 @@ namespace ddd {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int kBM = 128, kBN = 128, kBK = 64;
-constexpr int kPitch = 72;                         // bf16 elements per LDS row: 64 + 8 pad
-constexpr int kTileElems = 128 * kPitch;           // one operand tile
-constexpr int kGemmLds = 4 * kTileElems * 2;       // A[2] + B[2], bytes
+constexpr int kGK = 32;        // k per LDS tile
+constexpr int kGPitch = 40;    // bf16 elements per LDS row: 32 + 8 pad
 
-template <int KL>
-__global__ __launch_bounds__(256, 2) void lmhead_gemm_kernel(GemmArgs a) {
+template <int AB, int BB>
+struct GemmCfg {
+  static constexpr int BM = 64 * AB, BN = 64 * BB;
+  static constexpr int kStageElems = (BM + BN) * kGPitch;
+  static constexpr int kLdsBytes = 2 * kStageElems * 2;
+};
+
+// One work unit of one wave: NB = number of this wave's column blocks that hold active rows
+// (0 <= NB <= BB; a wave with NB == 0 still copies tiles and meets the barriers).  Every value of
+// NB has its own fully unrolled loop, so the accumulators stay in place (no data-dependent
+// branches around the MFMAs).
+template <int AB, int BB, int NB>
+__device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int mt, int nt, int n_act, int tid, int wm,
+                                          int wn, int l32, int lh) {
+  using C = GemmCfg<AB, BB>;
+  constexpr int NBR = NB > 0 ? NB : 1;
+  const int KT = a.H / kGK;                                         // even: H is a multiple of 128
+  const int ld_row = tid >> 2, ld_cc = tid & 3;                     // global->LDS copy: 4 x 16 B per row
+  const int st_off = ld_row * kGPitch + ld_cc * 8;
+  // 32-bit element offsets from the two base pointers (V*H and rows*H stay below 2^31 elements)
+  uint32_t aoff[AB], boff[BB];
+#pragma unroll
+  for (int i = 0; i < AB; ++i)
+    aoff[i] = (uint32_t)min(mt * C::BM + ld_row + 64 * i, a.V - 1) * (uint32_t)a.H + ld_cc * 8;
+#pragma unroll
+  for (int i = 0; i < BB; ++i)
+    boff[i] = (uint32_t)a.row_list[min(nt * C::BN + ld_row + 64 * i, n_act - 1)] * (uint32_t)a.H + ld_cc * 8;
+  const int col0 = nt * C::BN + wn * 32 * BB;
+
+  f32x16 acc[AB][NBR];
+#pragma unroll
+  for (int bm = 0; bm < AB; ++bm)
+#pragma unroll
+    for (int bn = 0; bn < NBR; ++bn)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0.f;
+
+  u32x4 a0[AB], b0[BB], a1[AB], b1[BB];
+#define DDD_LOADSET(SA, SB, T)                                                                                      \
+  {                                                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < AB; ++i) SA[i] = *reinterpret_cast<const u32x4*>(a.W + aoff[i] + (T) * kGK);   \
+    _Pragma("unroll") for (int i = 0; i < BB; ++i) SB[i] = *reinterpret_cast<const u32x4*>(a.hid + boff[i] + (T) * kGK); \
+  }
+#define DDD_STORESET(SA, SB, BUF)                                                                                   \
+  {                                                                                                                 \
+    uint16_t* sa_ = lds + (BUF) * C::kStageElems + st_off;                                                          \
+    uint16_t* sb_ = sa_ + C::BM * kGPitch;                                                                          \
+    _Pragma("unroll") for (int i = 0; i < AB; ++i) *reinterpret_cast<u32x4*>(sa_ + 64 * i * kGPitch) = SA[i];       \
+    _Pragma("unroll") for (int i = 0; i < BB; ++i) *reinterpret_cast<u32x4*>(sb_ + 64 * i * kGPitch) = SB[i];       \
+  }
+#define DDD_COMPUTE(BUF)                                                                                            \
+  if (NB > 0) {                                                                                                     \
+    const uint16_t* Ab = lds + (BUF) * C::kStageElems + (wm * 32 * AB + l32) * kGPitch + lh * 8;                    \
+    const uint16_t* Bb = lds + (BUF) * C::kStageElems + (C::BM + wn * 32 * BB + l32) * kGPitch + lh * 8;            \
+    _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                              \
+      bf16x8 af[AB];                                                                                                \
+      _Pragma("unroll") for (int b = 0; b < AB; ++b) af[b] =                                                        \
+          __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + b * 32 * kGPitch + ks * 16));             \
+      _Pragma("unroll") for (int bn = 0; bn < NBR; ++bn) {                                                          \
+        const bf16x8 bf =                                                                                           \
+            __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + bn * 32 * kGPitch + ks * 16));          \
+        _Pragma("unroll") for (int bm = 0; bm < AB; ++bm)                                                           \
+            acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[bm], bf, acc[bm][bn], 0, 0, 0);                \
+      }                                                                                                             \
+    }                                                                                                               \
+  }
+
+  DDD_LOADSET(a0, b0, 0);
+  DDD_LOADSET(a1, b1, 1);
+  __syncthreads();            // every wave is done with the LDS tiles of the previous unit
+  DDD_STORESET(a0, b0, 0);
+  DDD_LOADSET(a0, b0, min(2, KT - 1));
+  __syncthreads();
+  for (int kt = 0; kt < KT; kt += 2) {
+    // tile kt is in LDS[0]; tile kt+1 waits in set 1 (loaded two half-iterations ago)
+    DDD_STORESET(a1, b1, 1);
+    DDD_LOADSET(a1, b1, min(kt + 3, KT - 1));   // always issued: keeps the count of loads in flight static
+    DDD_COMPUTE(0);
+    __syncthreads();
+    // tile kt+1 is in LDS[1]; tile kt+2 waits in set 0
+    DDD_STORESET(a0, b0, 0);
+    DDD_LOADSET(a0, b0, min(kt + 4, KT - 1));
+    DDD_COMPUTE(1);
+    __syncthreads();
+  }
+#undef DDD_LOADSET
+#undef DDD_STORESET
+#undef DDD_COMPUTE
+
+  if (NB == 0) return;
+  // accumulator register q*4+e of block (bm, bn): vocabulary row vb + bm*32 + q*8 + e, hidden row column l32
+  const int vb = mt * C::BM + wm * 32 * AB + lh * 4;
+  const bool v_aligned = (a.V & 3) == 0;
+  static_assert(AB == 2, "a wave covers one group of 64 vocabulary rows");
+  const int grp = (mt * C::BM + wm * 64) >> 6;
+#pragma unroll
+  for (int bn = 0; bn < NBR; ++bn) {
+    const int n = col0 + bn * 32 + l32;
+    // statistics of this hidden row over the wave's 64 vocabulary rows: each of the two lanes that share
+    // the column reduces its 32 values, then the pair is combined (lanes l and l+32)
+    float gm = -INFINITY;
+#pragma unroll
+    for (int bm = 0; bm < AB; ++bm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int v = vb + bm * 32 + (e >> 2) * 8 + (e & 3);
+        const float x = acc[bm][bn][e] + 0.0f;   // -0 -> +0
+        acc[bm][bn][e] = x;
+        if (v < a.V) gm = fmaxf(gm, x);
+      }
+    gm = fmaxf(gm, __shfl_xor(gm, 32, 64));
+    float gs = 0.f;
+#pragma unroll
+    for (int bm = 0; bm < AB; ++bm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int v = vb + bm * 32 + (e >> 2) * 8 + (e & 3);
+        if (v < a.V) gs += __expf(acc[bm][bn][e] - gm);
+      }
+    gs += __shfl_xor(gs, 32, 64);
+    if (n < n_act) {
+      const int orow_id = a.row_list[n];
+      if (lh == 0) {
+        a.grp_max[(size_t)orow_id * a.ngrp + grp] = gm;
+        a.grp_sum[(size_t)orow_id * a.ngrp + grp] = gs;
+      }
+      float* orow = a.logits + (size_t)orow_id * a.V;
+#pragma unroll
+      for (int bm = 0; bm < AB; ++bm)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int v = vb + bm * 32 + q * 8;
+          if (v_aligned && v + 3 < a.V) {
+            const f32x4 o = {acc[bm][bn][q * 4], acc[bm][bn][q * 4 + 1], acc[bm][bn][q * 4 + 2],
+                             acc[bm][bn][q * 4 + 3]};
+            *reinterpret_cast<f32x4*>(orow + v) = o;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (v + e < a.V) orow[v + e] = acc[bm][bn][q * 4 + e];
+          }
+        }
+    }
+  }
+}
+
+template <int AB, int BB>
+__global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(GemmArgs a) {
+  using C = GemmCfg<AB, BB>;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint16_t* As = reinterpret_cast<uint16_t*>(smem_raw);            // [2][128][kPitch]
-  uint16_t* Bs = As + 2 * kTileElems;                              // [2][128][kPitch]
+  uint16_t* lds = reinterpret_cast<uint16_t*>(smem_raw);   // [2][BM + BN][kGPitch]
 
   const int n_act = *a.n_act_ptr;
-  if (n_act <= 0) return;                                          // uniform
+  if (n_act <= 0) return;                                  // uniform
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave & 1, wn = wave >> 1;
   const int l32 = lane & 31, lh = lane >> 5;
-  const int NT = (n_act + kBN - 1) / kBN;
-  const int nunits = a.nslice * NT;
+  const int nmt = (a.V + C::BM - 1) / C::BM;
+  const int NT = (n_act + C::BN - 1) / C::BN;
+  const int nunits = nmt * NT;
   const int G = gridDim.x;
-  const int vg = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);  // neighbours on one XCD get neighbouring units
-  const int KT = a.H / kBK;
-  const int ld_row = tid >> 3, ld_cc = tid & 7;                    // global->LDS copy coordinates
+  const int vg = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);   // neighbours on one XCD get neighbouring units
 
   for (int u = vg; u < nunits; u += G) {
-    const int slice = u / NT, nt = u - slice * NT;
-    const int mt0 = slice * a.tps, mt1 = min(a.nmt, mt0 + a.tps);
-
-    const uint16_t* brow[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int n = min(nt * kBN + ld_row + 32 * i, n_act - 1);
-      brow[i] = a.hid + (size_t)a.row_list[n] * a.H + ld_cc * 8;
+    const int mt = u / NT, nt = u - mt * NT;
+    // column blocks of this wave that hold at least one active row (wave-uniform)
+    const int col0 = nt * C::BN + wn * 32 * BB;
+    const int nb_act = min(BB, max(0, (n_act - col0 + 31) / 32));
+    switch (nb_act) {
+      case 0: gemm_unit<AB, BB, 0>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 1: gemm_unit<AB, BB, 1>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 2: gemm_unit<AB, BB, (BB >= 2 ? 2 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 3: gemm_unit<AB, BB, (BB >= 3 ? 3 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 4: gemm_unit<AB, BB, (BB >= 4 ? 4 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      default: gemm_unit<AB, BB, BB>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
     }
-    // per (lane, column block): hidden row, running max / sum, sorted top-k list
-    int orow[2];
-    bool rvalid[2];
-    float m_run[2], s_run[2];
-    uint64_t list[2][KL];
-#pragma unroll
-    for (int bn = 0; bn < 2; ++bn) {
-      const int n = nt * kBN + wn * 64 + bn * 32 + l32;
-      rvalid[bn] = n < n_act;
-      orow[bn] = a.row_list[min(n, n_act - 1)];
-      m_run[bn] = -INFINITY;
-      s_run[bn] = 0.f;
-#pragma unroll
-      for (int j = 0; j < KL; ++j) list[bn][j] = 0ull;
-    }
-
-    for (int mt = mt0; mt < mt1; ++mt) {
-      const uint16_t* arow[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int v = min(mt * kBM + ld_row + 32 * i, a.V - 1);
-        arow[i] = a.W + (size_t)v * a.H + ld_cc * 8;
-      }
-      f32x16 acc[2][2];
-#pragma unroll
-      for (int bm = 0; bm < 2; ++bm)
-#pragma unroll
-        for (int bn = 0; bn < 2; ++bn)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0.f;
-
-      u32x4 ra[4], rb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ra[i] = *reinterpret_cast<const u32x4*>(arow[i]);
-        rb[i] = *reinterpret_cast<const u32x4*>(brow[i]);
-      }
-      __syncthreads();   // every wave is done with both LDS buffers (previous tile / final merge)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<u32x4*>(As + (ld_row + 32 * i) * kPitch + ld_cc * 8) = ra[i];
-        *reinterpret_cast<u32x4*>(Bs + (ld_row + 32 * i) * kPitch + ld_cc * 8) = rb[i];
-      }
-      __syncthreads();
-
-      for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        const bool more = (kt + 1 < KT);
-        if (more) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            ra[i] = *reinterpret_cast<const u32x4*>(arow[i] + (kt + 1) * kBK);
-            rb[i] = *reinterpret_cast<const u32x4*>(brow[i] + (kt + 1) * kBK);
-          }
-        }
-        const uint16_t* Ab = As + buf * kTileElems + (wm * 64 + l32) * kPitch + lh * 8;
-        const uint16_t* Bb = Bs + buf * kTileElems + (wn * 64 + l32) * kPitch + lh * 8;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          bf16x8 af[2], bf[2];
-#pragma unroll
-          for (int b = 0; b < 2; ++b) {
-            af[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + b * 32 * kPitch + ks * 16));
-            bf[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + b * 32 * kPitch + ks * 16));
-          }
-#pragma unroll
-          for (int bm = 0; bm < 2; ++bm)
-#pragma unroll
-            for (int bn = 0; bn < 2; ++bn)
-              acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[bm], bf[bn], acc[bm][bn], 0, 0, 0);
-        }
-        if (more) {
-          uint16_t* Aw = As + (buf ^ 1) * kTileElems;
-          uint16_t* Bw = Bs + (buf ^ 1) * kTileElems;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<u32x4*>(Aw + (ld_row + 32 * i) * kPitch + ld_cc * 8) = ra[i];
-            *reinterpret_cast<u32x4*>(Bw + (ld_row + 32 * i) * kPitch + ld_cc * 8) = rb[i];
-          }
-        }
-        __syncthreads();
-      }
-
-      // ---- epilogue of this tile: accumulator element e of block (bm, bn) is
-      //      vocabulary row vbase + bm*32 + (e/4)*8 + lh*4 + e%4, hidden-row column l32
-      const int vbase = mt * kBM + wm * 64 + lh * 4;
-#pragma unroll
-      for (int bn = 0; bn < 2; ++bn) {
-        if (!rvalid[bn]) continue;
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int bm = 0; bm < 2; ++bm)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int v = vbase + bm * 32 + (e >> 2) * 8 + (e & 3);
-            const float x = acc[bm][bn][e] + 0.0f;   // -0 -> +0
-            acc[bm][bn][e] = x;
-            if (v < a.V) tmax = fmaxf(tmax, x);
-          }
-        if (a.logits_dbg != nullptr) {
-#pragma unroll
-          for (int bm = 0; bm < 2; ++bm)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int v = vbase + bm * 32 + (e >> 2) * 8 + (e & 3);
-              if (v < a.V) a.logits_dbg[(size_t)orow[bn] * a.V + v] = acc[bm][bn][e];
-            }
-        }
-        const float m_new = fmaxf(m_run[bn], tmax);
-        float s_new = (s_run[bn] == 0.f) ? 0.f : s_run[bn] * __expf(m_run[bn] - m_new);
-        float tail = key_value(list[bn][KL - 1]);
-        const bool full0 = list[bn][KL - 1] != 0ull;
-        bool full = full0;
-#pragma unroll
-        for (int bm = 0; bm < 2; ++bm)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int v = vbase + bm * 32 + (e >> 2) * 8 + (e & 3);
-            const float x = acc[bm][bn][e];
-            if (v < a.V) {
-              s_new += __expf(x - m_new);
-              if (!full || x >= tail) {
-                uint64_t cur = row_key(x, v);
-                if (cur > list[bn][KL - 1]) {
-#pragma unroll
-                  for (int j = 0; j < KL; ++j) {
-                    const bool gt = cur > list[bn][j];
-                    const uint64_t hi = gt ? cur : list[bn][j];
-                    cur = gt ? list[bn][j] : cur;
-                    list[bn][j] = hi;
-                  }
-                  full = list[bn][KL - 1] != 0ull;
-                  tail = key_value(list[bn][KL - 1]);
-                }
-              }
-            }
-          }
-        m_run[bn] = m_new;
-        s_run[bn] = s_new;
-      }
-    }
-
-    // ---- end of the slice: the four (wave, half) owners of a hidden row merge through LDS ----
-    __syncthreads();
-    uint64_t* elist = reinterpret_cast<uint64_t*>(smem_raw);                       // [128][4][KL]
-    float* estat = reinterpret_cast<float*>(smem_raw + (size_t)128 * 4 * KL * 8);  // [128][4][2]
-    const int src = wm * 2 + lh;
-#pragma unroll
-    for (int bn = 0; bn < 2; ++bn) {
-      const int rl = wn * 64 + bn * 32 + l32;
-#pragma unroll
-      for (int j = 0; j < KL; ++j) elist[(rl * 4 + src) * KL + j] = list[bn][j];
-      estat[(rl * 4 + src) * 2] = m_run[bn];
-      estat[(rl * 4 + src) * 2 + 1] = s_run[bn];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-      const int rl = pass * 64 + (tid >> 2);          // quad = one hidden row, lane in quad = source
-      const int n = nt * kBN + rl;
-      const bool ok = n < n_act;
-      const int row = a.row_list[min(n, n_act - 1)];
-      const int slot = rl * 4 + (tid & 3);
-      const float m_l = estat[slot * 2], s_l = estat[slot * 2 + 1];
-      float m_q = fmaxf(m_l, dpp_move_f32<0xB1>(m_l));
-      m_q = fmaxf(m_q, dpp_move_f32<0x4E>(m_q));
-      float s_q = (s_l == 0.f) ? 0.f : s_l * __expf(m_l - m_q);
-      s_q += dpp_move_f32<0xB1>(s_q);
-      s_q += dpp_move_f32<0x4E>(s_q);
-      uint64_t* pk = a.part_key + ((size_t)row * a.nslice + slice) * a.k;
-      int cur = 0;
-      for (int round = 0; round < a.k; ++round) {
-        const uint64_t head = (cur < KL) ? elist[slot * KL + cur] : 0ull;
-        uint64_t q = umax64(head, dpp_move_u64<0xB1>(head));
-        q = umax64(q, dpp_move_u64<0x4E>(q));
-        if (head == q && q != 0ull) ++cur;
-        if (ok && (tid & 3) == 0) pk[round] = q;
-      }
-      if (ok && (tid & 3) == 0) a.part_sum[(size_t)row * a.nslice + slice] = s_q;
-    }
-    // the next unit starts with a barrier before it touches LDS
   }
 }
 
@@ -277,29 +244,36 @@ hipError_t launch_build_row_list(const uint8_t* row_active, int n_rows, int32_t*
   return hipGetLastError();
 }
 
-template <int KL>
-static hipError_t prepare_kl() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_gemm_kernel<KL>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+// Tile shape by the largest number of rows the call can have: 128 x 320 for hundreds of rows
+// (a 256 x 320 tile would halve the LDS traffic again but spills accumulators), smaller column
+// tiles when fewer rows can be active.
+static int pick_shape(int max_rows) { return max_rows > 192 ? 1 : (max_rows > 128 ? 2 : 3); }
+
+template <int AB, int BB>
+static hipError_t prepare_shape() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_gemm_kernel<AB, BB>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, GemmCfg<AB, BB>::kLdsBytes);
 }
 
-hipError_t prepare_lmhead_gemm(int k) {
-  if (k <= 4) return prepare_kl<4>();
-  if (k <= 8) return prepare_kl<8>();
-  if (k <= 10) return prepare_kl<10>();
-  return prepare_kl<16>();
+hipError_t prepare_lmhead_gemm() {
+  hipError_t e = prepare_shape<2, 5>();
+  if (e == hipSuccess) e = prepare_shape<2, 3>();
+  if (e == hipSuccess) e = prepare_shape<2, 2>();
+  return e;
 }
 
-hipError_t launch_lmhead_gemm(const GemmArgs& a, int grid, hipStream_t stream) {
-  const dim3 g(grid), b(256);
-  if (a.k <= 4)
-    hipLaunchKernelGGL((lmhead_gemm_kernel<4>), g, b, kGemmLds, stream, a);
-  else if (a.k <= 8)
-    hipLaunchKernelGGL((lmhead_gemm_kernel<8>), g, b, kGemmLds, stream, a);
-  else if (a.k <= 10)
-    hipLaunchKernelGGL((lmhead_gemm_kernel<10>), g, b, kGemmLds, stream, a);
-  else
-    hipLaunchKernelGGL((lmhead_gemm_kernel<16>), g, b, kGemmLds, stream, a);
+template <int AB, int BB>
+static void launch_shape(const GemmArgs& a, int grid, hipStream_t stream) {
+  constexpr int lds_bytes = GemmCfg<AB, BB>::kLdsBytes;
+  hipLaunchKernelGGL((lmhead_gemm_kernel<AB, BB>), dim3(grid), dim3(256), lds_bytes, stream, a);
+}
+
+hipError_t launch_lmhead_gemm(const GemmArgs& a, int max_rows, int grid, hipStream_t stream) {
+  switch (pick_shape(max_rows)) {
+    case 1: launch_shape<2, 5>(a, grid, stream); break;
+    case 2: launch_shape<2, 3>(a, grid, stream); break;
+    default: launch_shape<2, 2>(a, grid, stream); break;
+  }
   return hipGetLastError();
 }
 

@@ -133,12 +133,14 @@ __global__ void next_round_kernel(int64_t* ctr) { *ctr += 1; }
 
 __global__ void round_stats_kernel(int64_t* ctr, const int32_t* steps, const int32_t* accept_len, int B,
                                    int64_t* depth_hist, int64_t* accept_hist) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  for (int b = 0; b < B; ++b) {
-    if (depth_hist != nullptr && steps != nullptr) depth_hist[min(max(steps[b], 0), 31)] += 1;
-    if (accept_hist != nullptr && accept_len != nullptr) accept_hist[min(max(accept_len[b], 0), 31)] += 1;
+  // one workgroup; integer atomics, so the totals do not depend on the order
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    if (depth_hist != nullptr && steps != nullptr)
+      atomicAdd(reinterpret_cast<unsigned long long*>(depth_hist + min(max(steps[b], 0), 31)), 1ull);
+    if (accept_hist != nullptr && accept_len != nullptr)
+      atomicAdd(reinterpret_cast<unsigned long long*>(accept_hist + min(max(accept_len[b], 0), 31)), 1ull);
   }
-  *ctr += 1;
+  if (threadIdx.x == 0) *ctr += 1;
 }
 
 // Each thread reads 16-byte words with a grid stride and folds them into one word.
@@ -200,7 +202,7 @@ int ddd_synth_next_round(int64_t* round_ctr, void* stream) {
 int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_t* accept_len, int32_t B,
                           int64_t* depth_hist, int64_t* accept_hist, void* stream) {
   if (round_ctr == nullptr || B < 1) return DDD_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(round_stats_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), round_ctr, steps,
+  hipLaunchKernelGGL(round_stats_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), round_ctr, steps,
                      accept_len, B, depth_hist, accept_hist);
   return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
 }

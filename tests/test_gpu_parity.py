@@ -89,6 +89,39 @@ def test_lmhead_topk_against_oracle(gpu, case):
         assert np.max(np.abs(g_lp[r].astype(np.float64) - o_lp)) <= LOGPROB_TOL
 
 
+@pytest.mark.parametrize("R", [3, 20])
+def test_lmhead_topk_all_logits_equal(gpu, R):
+    """Degenerate rows: a zero hidden state makes every logit 0, so the top-k is tokens 0..k-1 (lower id wins)
+    and lse = log V; on the GEMM path this is the case where every element ties with the threshold."""
+    torch, D, SD = gpu
+    B, k, H, V = 4, 8, 256, 5000
+    print(f"[case] lmhead_topk constant logits R={R}", flush=True)
+    rng = np.random.default_rng(21)
+    W_bits = synth.make_lm_head(V, H, 0.05, seed=4)
+    hid_bits = _rand_hid_bits(rng, R, H, 4.0)
+    hid_bits[1] = 0                       # +0.0 in bf16
+    hid_bits[R - 1] = 0
+    cfg = D.make_config(B, H, V, k, 4, 8, 0.3)
+    ctx = D.ddd_create(cfg)
+    try:
+        W, hid = SD.upload_bits(W_bits), SD.upload_bits(hid_bits)
+        tok = torch.full((R, k), -7, dtype=torch.int32, device="cuda")
+        lp = torch.zeros(R, k, dtype=torch.float32, device="cuda")
+        lse = torch.zeros(R, dtype=torch.float32, device="cuda")
+        D.ddd_lmhead_topk(ctx, W, hid, R, None, tok, lp, lse, None)
+        torch.cuda.synchronize()
+        t, l, p = tok.cpu().numpy(), lse.cpu().numpy(), lp.cpu().numpy()
+        logits = O.lmhead_logits(W_bits, hid_bits)
+        for r in (1, R - 1):
+            assert list(t[r]) == list(range(k))
+            assert abs(float(l[r]) - np.log(V)) <= LOGPROB_TOL
+            assert np.max(np.abs(p[r] + np.log(V))) <= LOGPROB_TOL
+        for r in range(R):
+            assert set(t[r]) == set(O.row_topk(logits[r], k).tolist()) or r in (1, R - 1)
+    finally:
+        D.ddd_destroy(ctx)
+
+
 def test_lmhead_topk_gemm_path_row_active(gpu):
     """More than 16 rows: only the active rows are multiplied, the others are left untouched."""
     torch, D, SD = gpu
