@@ -12,7 +12,7 @@
 //
 // W is the A operand, so an accumulator lane owns one hidden row and four consecutive vocabulary
 // rows per register quad: the output is stored as float4 along V.  Both operands go through
-// double-buffered LDS tiles of 32 k (80-byte pitch, conflict-free 16-byte reads); the K loop is
+// double-buffered LDS tiles of 64 k (144-byte pitch, conflict-free 16-byte reads); the K loop is
 // unrolled by two with two static register sets so that the loads of tile kt+2 are in flight
 // while tile kt is multiplied.  Only active rows are multiplied: the B rows are gathered through
 // the compacted row list and column blocks past the last active row are skipped per wave.
@@ -29,7 +29,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kGK = 32;        // k per LDS tile
-constexpr int kGPitch = 40;    // bf16 elements per LDS row: 32 + 8 pad
+constexpr int kGPitch = 40;    // bf16 elements per LDS row: 32 + 8 pad (80 B: conflict-free 16-byte reads)
+constexpr int kCPR = kGK / 8;  // 16-byte chunks per tile row
+constexpr int kRPP = 256 / kCPR;   // rows copied per pass of the 256 threads
 
 template <int AB, int BB>
 struct GemmCfg {
@@ -48,16 +50,17 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
   using C = GemmCfg<AB, BB>;
   constexpr int NBR = NB > 0 ? NB : 1;
   const int KT = a.H / kGK;                                         // even: H is a multiple of 128
-  const int ld_row = tid >> 2, ld_cc = tid & 3;                     // global->LDS copy: 4 x 16 B per row
+  const int ld_row = tid / kCPR, ld_cc = tid % kCPR;                // global->LDS copy: kCPR x 16 B per row
   const int st_off = ld_row * kGPitch + ld_cc * 8;
+  constexpr int NA = C::BM / kRPP, NBL = C::BN / kRPP;              // copy passes per tile
   // 32-bit element offsets from the two base pointers (V*H and rows*H stay below 2^31 elements)
-  uint32_t aoff[AB], boff[BB];
+  uint32_t aoff[NA], boff[NBL];
 #pragma unroll
-  for (int i = 0; i < AB; ++i)
-    aoff[i] = (uint32_t)min(mt * C::BM + ld_row + 64 * i, a.V - 1) * (uint32_t)a.H + ld_cc * 8;
+  for (int i = 0; i < NA; ++i)
+    aoff[i] = (uint32_t)min(mt * C::BM + ld_row + kRPP * i, a.V - 1) * (uint32_t)a.H + ld_cc * 8;
 #pragma unroll
-  for (int i = 0; i < BB; ++i)
-    boff[i] = (uint32_t)a.row_list[min(nt * C::BN + ld_row + 64 * i, n_act - 1)] * (uint32_t)a.H + ld_cc * 8;
+  for (int i = 0; i < NBL; ++i)
+    boff[i] = (uint32_t)a.row_list[min(nt * C::BN + ld_row + kRPP * i, n_act - 1)] * (uint32_t)a.H + ld_cc * 8;
   const int col0 = nt * C::BN + wn * 32 * BB;
 
   f32x16 acc[AB][NBR];
@@ -68,33 +71,37 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0.f;
 
-  u32x4 a0[AB], b0[BB], a1[AB], b1[BB];
+  u32x4 a0[NA], b0[NBL], a1[NA], b1[NBL];
 #define DDD_LOADSET(SA, SB, T)                                                                                      \
   {                                                                                                                 \
-    _Pragma("unroll") for (int i = 0; i < AB; ++i) SA[i] = *reinterpret_cast<const u32x4*>(a.W + aoff[i] + (T) * kGK);   \
-    _Pragma("unroll") for (int i = 0; i < BB; ++i) SB[i] = *reinterpret_cast<const u32x4*>(a.hid + boff[i] + (T) * kGK); \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i) SA[i] = *reinterpret_cast<const u32x4*>(a.W + aoff[i] + (T) * kGK);    \
+    _Pragma("unroll") for (int i = 0; i < NBL; ++i) SB[i] = *reinterpret_cast<const u32x4*>(a.hid + boff[i] + (T) * kGK); \
   }
 #define DDD_STORESET(SA, SB, BUF)                                                                                   \
   {                                                                                                                 \
     uint16_t* sa_ = lds + (BUF) * C::kStageElems + st_off;                                                          \
     uint16_t* sb_ = sa_ + C::BM * kGPitch;                                                                          \
-    _Pragma("unroll") for (int i = 0; i < AB; ++i) *reinterpret_cast<u32x4*>(sa_ + 64 * i * kGPitch) = SA[i];       \
-    _Pragma("unroll") for (int i = 0; i < BB; ++i) *reinterpret_cast<u32x4*>(sb_ + 64 * i * kGPitch) = SB[i];       \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(sa_ + kRPP * i * kGPitch) = SA[i];     \
+    _Pragma("unroll") for (int i = 0; i < NBL; ++i) *reinterpret_cast<u32x4*>(sb_ + kRPP * i * kGPitch) = SB[i];    \
   }
 #define DDD_COMPUTE(BUF)                                                                                            \
   if (NB > 0) {                                                                                                     \
     const uint16_t* Ab = lds + (BUF) * C::kStageElems + (wm * 32 * AB + l32) * kGPitch + lh * 8;                    \
     const uint16_t* Bb = lds + (BUF) * C::kStageElems + (C::BM + wn * 32 * BB + l32) * kGPitch + lh * 8;            \
-    _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                              \
-      bf16x8 af[AB];                                                                                                \
-      _Pragma("unroll") for (int b = 0; b < AB; ++b) af[b] =                                                        \
-          __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Ab + b * 32 * kGPitch + ks * 16));             \
-      _Pragma("unroll") for (int bn = 0; bn < NBR; ++bn) {                                                          \
-        const bf16x8 bf =                                                                                           \
-            __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bb + bn * 32 * kGPitch + ks * 16));          \
-        _Pragma("unroll") for (int bm = 0; bm < AB; ++bm)                                                           \
-            acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[bm], bf, acc[bm][bn], 0, 0, 0);                \
+    /* fragments are requested two k-steps at a time: the second k-step's reads land during the first   */         \
+    /* one's MFMAs                                                                                        */         \
+    _Pragma("unroll") for (int kp = 0; kp < kGK / 32; ++kp) {                                                       \
+      bf16x8 af[2][AB], bf[2][NBR];                                                                                 \
+      _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                            \
+        _Pragma("unroll") for (int b = 0; b < AB; ++b) af[ks][b] = __builtin_bit_cast(                              \
+            bf16x8, *reinterpret_cast<const u32x4*>(Ab + b * 32 * kGPitch + (kp * 2 + ks) * 16));                   \
+        _Pragma("unroll") for (int b = 0; b < NBR; ++b) bf[ks][b] = __builtin_bit_cast(                             \
+            bf16x8, *reinterpret_cast<const u32x4*>(Bb + b * 32 * kGPitch + (kp * 2 + ks) * 16));                   \
       }                                                                                                             \
+      _Pragma("unroll") for (int ks = 0; ks < 2; ++ks)                                                              \
+        _Pragma("unroll") for (int bn = 0; bn < NBR; ++bn)                                                          \
+          _Pragma("unroll") for (int bm = 0; bm < AB; ++bm)                                                         \
+              acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][bm], bf[ks][bn], acc[bm][bn], 0, 0, 0);  \
     }                                                                                                               \
   }
 
