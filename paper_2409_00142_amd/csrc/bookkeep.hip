@@ -1,117 +1,8 @@
-// Per-row merge of the weight-stream partials, beam update and DDD stop test.
-//
-// merge_row      one wave per hidden row: combines the per-slice (max, sum of exponentials)
-//                into lse, and picks the row's top-k tokens: the k slices with the best
-//                heads contain every global top-k element, so only their k*k keys are ranked.
-// beam_update    one wave per sequence: score = logprobsum[parent] + logprob (one fp32 add),
-//                all k*k candidates go to the node pool, the k best by (score desc, token asc,
-//                flat index asc) become the new beam (Algorithm 1, "postprocess ... to
-//                produce the new beam", "calculate logprobsum").
-// stop_test      Eq. 1 in the probability domain: P = sum_i exp(logprobsum[i]) in fp64, index
-//                order; continue iff another call is allowed and (step not in S or P >= t).
-#include "ddd_device.hpp"
-#include "ddd_kernels.hpp"
-#include "tree_device.hpp"
+// Stand-alone kernels of the per-call bookkeeping (device code in bookkeep_device.hpp) and the
+// row reduction of materialised logits.
+#include "bookkeep_device.hpp"
 
 namespace ddd {
-
-constexpr int kKM = DDD_KMAX;
-
-// All 64 lanes of the calling wave must be active.  On return lane j < k holds the rank-j key.
-constexpr int kHPL = 8;   // heads per lane: up to 512 slices
-
-// Issue the loads of a row's slice heads, runners-up and sums (lane handles slices lane, lane+64, ...).
-__device__ __forceinline__ void merge_load_heads(const uint64_t* __restrict__ pk, const float* __restrict__ ps,
-                                                 int nslice, int k, int lane, uint64_t (&head)[kHPL],
-                                                 uint64_t (&second)[kHPL], float (&psum)[kHPL]) {
-#pragma unroll
-  for (int i = 0; i < kHPL; ++i) {
-    const int s = lane + 64 * i;
-    head[i] = (s < nslice) ? pk[(size_t)s * k] : 0ull;
-    second[i] = (s < nslice && k > 1) ? pk[(size_t)s * k + 1] : 0ull;
-    psum[i] = (s < nslice) ? ps[s] : 0.f;
-  }
-}
-
-// All 64 lanes of the calling wave must be active.  On return lane j < k holds the rank-j key.
-//
-// The k slices with the best heads contain every global top-k element.  If none of their
-// runners-up beats the k-th best head, the k best heads are the answer (the common case);
-// otherwise the k*k keys of those slices are fetched and ranked.
-template <int HPL>
-__device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, uint64_t (&head)[kHPL],
-                                          const uint64_t (&second)[kHPL], const float (&psum)[kHPL], int k, int lane,
-                                          int* wl, uint64_t& my_key, float& lse) {
-  uint64_t loc = 0;
-#pragma unroll
-  for (int i = 0; i < HPL; ++i) loc = umax64(loc, head[i]);
-  const float M = unord32(wave_max_u32((uint32_t)(loc >> 32)));
-  float acc = 0.f;
-#pragma unroll
-  for (int i = 0; i < HPL; ++i)
-    if (head[i] != 0ull) acc += psum[i] * __expf(key_value(head[i]) - M);
-  lse = M + __logf(wave_sum_f32(acc));
-
-  my_key = 0ull;
-  uint64_t best = 0ull, sec_of_winners = 0ull;
-  for (int round = 0; round < k; ++round) {
-    loc = 0;
-#pragma unroll
-    for (int i = 0; i < HPL; ++i) loc = umax64(loc, head[i]);
-    best = wave_max_u64(loc);
-    if (lane == round) my_key = best;
-    if (best == 0ull) {
-      if (lane == 0) wl[round] = -1;
-    } else {
-#pragma unroll
-      for (int i = 0; i < HPL; ++i)
-        if (head[i] == best) {
-          wl[round] = lane + 64 * i;
-          head[i] = 0ull;
-          sec_of_winners = umax64(sec_of_winners, second[i]);
-        }
-    }
-  }
-  // `best` is now the k-th best head (0 if there are fewer than k non-empty slices)
-  const uint64_t best_second = wave_max_u64(sec_of_winners);
-  if (best != 0ull && best_second < best) return;   // uniform: the heads are the top-k
-
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  uint64_t cand[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int cidx = lane + 64 * i;
-    cand[i] = 0ull;
-    if (cidx < k * k) {
-      const int s = wl[cidx / k];
-      if (s >= 0) cand[i] = pk[(size_t)s * k + (cidx % k)];
-    }
-  }
-  my_key = 0ull;
-  for (int round = 0; round < k; ++round) {
-    loc = umax64(umax64(cand[0], cand[1]), umax64(cand[2], cand[3]));
-    best = wave_max_u64(loc);
-    if (lane == round) my_key = best;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (cand[i] == best) cand[i] = 0ull;
-  }
-}
-
-__device__ __forceinline__ void merge_row_dispatch(const uint64_t* pk, uint64_t (&head)[kHPL],
-                                                   const uint64_t (&second)[kHPL], const float (&psum)[kHPL],
-                                                   int nslice, int k, int lane, int* wl, uint64_t& my_key,
-                                                   float& lse) {
-  if (nslice <= 64)
-    merge_row<1>(pk, head, second, psum, k, lane, wl, my_key, lse);
-  else if (nslice <= 128)
-    merge_row<2>(pk, head, second, psum, k, lane, wl, my_key, lse);
-  else if (nslice <= 256)
-    merge_row<4>(pk, head, second, psum, k, lane, wl, my_key, lse);
-  else
-    merge_row<8>(pk, head, second, psum, k, lane, wl, my_key, lse);
-}
 
 // ---- standalone merge: one wave per row ------------------------------------------------------
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
@@ -294,104 +185,6 @@ hipError_t launch_row_topk(const RowTopkArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// ---- beam update by one wave (all 64 lanes active) -------------------------------------------
-// tok/lp: rows of k entries with the given row stride (LDS or global).  old_lps / old_node: the
-// current beam as loaded by lane i < k (ignored for step 0).
-// Returns the new logprobsum of beam slot `lane` (lanes >= k: 0).
-__device__ __forceinline__ float beam_update(const BeamArgs& a, int b, int lane, const int32_t* tok, const float* lp,
-                                             int stride, float old_lps, int old_node) {
-  const int k = a.k, step = a.step;
-  float* lps = a.st.logprobsum + (size_t)b * k;
-  int32_t* bnode = a.st.beam_node + (size_t)b * k;
-  int32_t* btok = a.st.beam_token + (size_t)b * k;
-  int32_t* bslot = a.st.beam_parent_slot + (size_t)b * k;
-  int32_t* ptok = a.st.pool_token + (size_t)b * a.nmax;
-  int32_t* ppar = a.st.pool_parent + (size_t)b * a.nmax;
-  int32_t* pdep = a.st.pool_depth + (size_t)b * a.nmax;
-  float* psc = a.st.pool_score + (size_t)b * a.nmax;
-
-  float new_lps = 0.f;
-  if (step == 0) {
-    if (lane < k) {
-      const int nid = 1 + lane;
-      const int t = tok[lane];
-      const float s = lp[lane];
-      ptok[nid] = t;
-      ppar[nid] = 0;
-      pdep[nid] = 1;
-      psc[nid] = s;
-      bnode[lane] = nid;
-      btok[lane] = t;
-      bslot[lane] = 0;
-      lps[lane] = s;
-      new_lps = s;
-    }
-    if (lane == 0) a.st.n_nodes[b] = 1 + k;
-  } else {
-    const int base = 1 + k + (step - 1) * k * k;
-    uint64_t cand[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int f = lane + 64 * i;
-      cand[i] = 0ull;
-      const int slot = min(f / k, k - 1), j = f - slot * k;
-      const float plps = __shfl(old_lps, slot, 64);   // parent's logprobsum and pool id
-      const int pnode = __shfl(old_node, slot, 64);
-      if (f < k * k) {
-        const int t = tok[slot * stride + j];
-        const float sc = __fadd_rn(plps, lp[slot * stride + j]);
-        ptok[base + f] = t;
-        ppar[base + f] = pnode;
-        pdep[base + f] = step + 1;
-        psc[base + f] = sc;
-        cand[i] = beam_key(sc, t, f);
-      }
-    }
-    uint64_t mine = 0ull;
-    for (int round = 0; round < k; ++round) {
-      const uint64_t loc = umax64(umax64(cand[0], cand[1]), umax64(cand[2], cand[3]));
-      const uint64_t best = wave_max_u64(loc);
-      if (lane == round) mine = best;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (cand[i] == best) cand[i] = 0ull;
-    }
-    if (lane < k) {
-      const int f = beam_key_flat(mine);
-      const int t = (int)(0xFFFFFFu - (((uint32_t)mine >> 8) & 0xFFFFFFu));
-      new_lps = key_value(mine);
-      bnode[lane] = base + f;
-      btok[lane] = t;
-      bslot[lane] = f / k;
-      lps[lane] = new_lps;
-    }
-    if (lane == 0) a.st.n_nodes[b] = base + k * k;
-  }
-  if (lane == 0) a.st.steps[b] = step + 1;
-  return new_lps;
-}
-
-// Stop test by one wave; lane i < k passes its logprobsum.  steps_done = draft calls made so far.
-__device__ __forceinline__ bool stop_test(const BeamArgs& a, int b, int lane, float my_lps, int steps_done) {
-  const double e = (lane < a.k) ? exp((double)my_lps) : 0.0;
-  const unsigned long long eb = (unsigned long long)__double_as_longlong(e);
-  double P = 0.0;
-#pragma unroll
-  for (int i = 0; i < kKM; ++i) {   // index order; lanes >= k contribute exactly +0.0
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)eb, i);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(eb >> 32), i);
-    P += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-  }
-  bool cont = steps_done < a.D;
-  if (cont && ((a.check_mask >> steps_done) & 1u) && P < (double)a.threshold) cont = false;
-  if (lane == 0) {
-    a.st.conf[b] = P;
-    a.st.active[b] = cont ? 1 : 0;
-  }
-  if (lane < a.k) a.st.row_active[(size_t)b * a.k + lane] = cont ? 1 : 0;
-  return cont;
-}
-
 __global__ __launch_bounds__(64) void beam_select_kernel(BeamArgs a) {
   const int b = blockIdx.x, lane = threadIdx.x;
   if (!a.st.active[b]) return;
@@ -418,57 +211,11 @@ hipError_t launch_depth_continue(const BeamArgs& a, int steps_done, hipStream_t 
   return hipGetLastError();
 }
 
-// ---- one launch per draft call: merge of the sequence's rows, beam update, stop test, and the
-// final tree as soon as the sequence stops ---------------------------------------------------------
+// ---- one launch per draft call (rows that came through the GEMM path, or a caller that runs
+// the weight stream separately): one workgroup per sequence ---------------------------------------
 __global__ __launch_bounds__(1024) void step_bookkeep_kernel(StepArgs a) {
-  __shared__ int wl[kKM][kKM];
-  __shared__ int s_tok[kKM][kKM];
-  __shared__ float s_lp[kKM][kKM];
-  __shared__ int s_stopped;
-  __shared__ TreeSmem tsm;
-  const BeamArgs& g = a.beam;
-  const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int rows = (g.step == 0) ? 1 : g.k;
-  const size_t row0 = (g.step == 0) ? (size_t)b : (size_t)b * g.k;
-  // Issue every independent load first: the flag, this wave's slice heads, the current beam.
-  const uint8_t active = g.st.active[b];
-  const size_t row = row0 + min(wave, rows - 1);
-  const bool dense = (a.nslice == 0);             // keys already final (rows came through the GEMM path)
-  const uint64_t* pk = a.part_key + row * (dense ? 1 : a.nslice) * g.k;
-  uint64_t head[kHPL], second[kHPL];
-  float psum[kHPL];
-  uint64_t dkey = 0ull;
-  float dlse = 0.f;
-  if (dense) {
-    dkey = pk[min(lane, g.k - 1)];
-    dlse = a.part_sum[row];
-  } else {
-    merge_load_heads(pk, a.part_sum + row * a.nslice, a.nslice, g.k, lane, head, second, psum);
-  }
-  const int li = min(lane, g.k - 1);
-  const float old_lps = g.st.logprobsum[(size_t)b * g.k + li];
-  const int old_node = g.st.beam_node[(size_t)b * g.k + li];
-  if (!active) return;                            // uniform over the workgroup
-  if (threadIdx.x == 0) s_stopped = 0;
-  if (wave < rows) {
-    uint64_t key = dkey;
-    float lse = dlse;
-    if (!dense) merge_row_dispatch(pk, head, second, psum, a.nslice, g.k, lane, wl[wave], key, lse);
-    if (lane < g.k) {
-      s_tok[wave][lane] = key_token(key);
-      s_lp[wave][lane] = key_value(key) - lse;
-    }
-    if (a.lse_dbg != nullptr && lane == 0) a.lse_dbg[row] = lse;
-  }
-  __syncthreads();
-  if (wave == 0) {
-    const float v = beam_update(g, b, lane, &s_tok[0][0], &s_lp[0][0], kKM, old_lps, old_node);
-    const bool cont = stop_test(g, b, lane, v, g.step + 1);
-    if (lane == 0 && !cont) s_stopped = 1;
-  }
-  __syncthreads();                                // also orders wave 0's pool writes before the reads below
-  if (a.tree.mask != nullptr && s_stopped)
-    tree_finalize_block(g.st, a.tree, b, a.m, g.nmax, threadIdx.x, blockDim.x, tsm);
+  __shared__ StepSmem sm;
+  step_bookkeep_block(a, blockIdx.x, threadIdx.x, blockDim.x, sm);
 }
 
 hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream) {

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -372,8 +373,6 @@ int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd
   const int n_rows = (step == 0) ? c->cfg.B : c->cfg.B * c->cfg.k;
   // step 0 rows are one per sequence: active[] is the row flag; later rows use row_active[]
   const uint8_t* flags = (step == 0) ? st->active : st->row_active;
-  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, s);
-  if (rc != DDD_OK) return rc;
   StepArgs a;
   a.beam = beam_args(c, st, step);
   a.part_key = c->part_key;
@@ -385,6 +384,8 @@ int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd
     std::memset(&a.tree, 0, sizeof(a.tree));
   a.nslice = slices_for(c, n_rows);
   a.m = c->cfg.m;
+  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, s);
+  if (rc != DDD_OK) return rc;
   DDD_HIP(launch_step_bookkeep(a, s));
   return DDD_OK;
 }

@@ -7,19 +7,6 @@
 
 namespace ddd {
 
-// ---- LM-head weight stream (lmhead_stream.hip) ------------------------------------------------
-struct StreamArgs {
-  const uint16_t* W;          // bf16 [V,H]
-  const uint16_t* hid;        // bf16 [R,H], first row of this pass
-  const uint8_t* row_active;  // [R] or null
-  uint64_t* part_key;         // [R][nslice][k], first row of this pass
-  float* part_sum;            // [R][nslice]
-  float* logits_dbg;          // fp32 [R][V] or null
-  int H, V, R, k, ntiles, nw;
-};
-// G = 128-wide K groups per streaming wave (1, 2 or 4); H == 128 * G * nw.
-hipError_t launch_lmhead_stream(const StreamArgs& a, int G, int nslice, hipStream_t stream);
-
 // ---- LM-head MFMA GEMM for more than 16 rows (lmhead_gemm.hip) --------------------------------
 struct GemmArgs {
   const uint16_t* W;          // bf16 [V,H]
@@ -83,6 +70,19 @@ struct StepArgs {             // merge + beam select + stop test in one launch
   int nslice, m;
 };
 hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream);
+
+// ---- LM-head weight stream (lmhead_stream.hip) ------------------------------------------------
+struct StreamArgs {
+  const uint16_t* W;          // bf16 [V,H]
+  const uint16_t* hid;        // bf16 [R,H], first row of this pass
+  const uint8_t* row_active;  // [R] or null
+  uint64_t* part_key;         // [R][nslice][k], first row of this pass
+  float* part_sum;            // [R][nslice]
+  float* logits_dbg;          // fp32 [R][V] or null
+  int H, V, R, k, ntiles, nw;
+};
+// G = 128-wide K groups per streaming wave (1, 2 or 4); H == 128 * G * nw.
+hipError_t launch_lmhead_stream(const StreamArgs& a, int G, int nslice, hipStream_t stream);
 
 struct ResetArgs {
   ddd_state st;

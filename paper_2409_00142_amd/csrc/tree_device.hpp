@@ -11,7 +11,8 @@ constexpr int kTreeMax = DDD_MMAX + 1;
 constexpr int kMaskWords = (kTreeMax + 31) / 32;
 
 struct TreeSmem {
-  uint64_t keys[kPoolMax];
+  uint64_t keys[kPoolMax + 2];          // rerank keys of pool nodes 1..N (+ padding)
+  int pick[kTreeMax];                   // pool ids of the m best nodes in rerank order
   int sel[kTreeMax];                    // pool ids of tree indices 0..n_sel (0 = root)
   int par[kTreeMax];                    // tree index of the parent
   uint32_t bits[kTreeMax][kMaskWords];  // ancestor bit rows
@@ -30,35 +31,29 @@ __device__ __forceinline__ void tree_finalize_block(const ddd_state& st, const d
   const int32_t* pdep = st.pool_depth + (size_t)b * nmax;
   const int32_t* ptok = st.pool_token + (size_t)b * nmax;
 
-  int N2 = 64;
-  while (N2 < N) N2 <<= 1;
-  for (int i = tid; i < N2; i += nthr)
-    sm.keys[i] =
-        (i < N) ? (((uint64_t)ord32(psc[i + 1]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)(i + 1))) : 0ull;
+  for (int i = tid; i < N; i += nthr)
+    sm.keys[i] = ((uint64_t)ord32(psc[i + 1]) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)(i + 1));
+  if (tid == 0) sm.keys[N] = 0ull;   // pad: the counting loop below reads keys in pairs
   __syncthreads();
-  // bitonic sort, descending
-  for (int size = 2; size <= N2; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int p = tid; p < (N2 >> 1); p += nthr) {
-        const int pos = 2 * stride * (p / stride) + (p % stride);
-        const int partner = pos + stride;
-        const bool desc = ((pos & size) == 0);
-        const uint64_t x = sm.keys[pos], y = sm.keys[partner];
-        if ((x < y) == desc) {
-          sm.keys[pos] = y;
-          sm.keys[partner] = x;
-        }
-      }
-      __syncthreads();
+  // Rank by counting: keys are distinct (the id is part of the key), so the number of larger keys
+  // is the node's position in the rerank order; the m_eff best are kept.
+  for (int i = tid; i < N; i += nthr) {
+    const uint64_t mine = sm.keys[i];
+    int rank = 0;
+    for (int j = 0; j < N; j += 2) {
+      const uint64_t x = sm.keys[j], y = sm.keys[j + 1];
+      rank += (x > mine ? 1 : 0) + (y > mine ? 1 : 0);
     }
+    if (rank < m_eff) sm.pick[rank] = i + 1;
   }
-  // chosen ids in ascending order: rank by counting
+  __syncthreads();
+  // chosen ids in ascending order: rank by counting again
   if (tid == 0) sm.sel[0] = 0;
   for (int i = tid; i < m_eff; i += nthr) {
-    const uint32_t id = 0xFFFFFFFFu - (uint32_t)sm.keys[i];
+    const int id = sm.pick[i];
     int rank = 0;
-    for (int j = 0; j < m_eff; ++j) rank += ((0xFFFFFFFFu - (uint32_t)sm.keys[j]) < id) ? 1 : 0;
-    sm.sel[1 + rank] = (int)id;
+    for (int j = 0; j < m_eff; ++j) rank += (sm.pick[j] < id) ? 1 : 0;
+    sm.sel[1 + rank] = id;
   }
   __syncthreads();
   // parents as tree indices (a parent has a smaller id, hence a smaller tree index)
