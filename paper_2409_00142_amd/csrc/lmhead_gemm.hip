@@ -5,14 +5,14 @@
 // With hundreds of rows the projection is bound by the matrix cores, not by HBM, and on this chip
 // by the LDS bandwidth that feeds them: a 64 x 64 wave tile needs one 1 KB fragment read per
 // MFMA, which measured LDS-bound at about a quarter of the MFMA peak.  The kernel therefore uses
-// large wave tiles - AB x BB blocks of v_mfma_f32_32x32x16_bf16 per wave, 2 x 2 waves per
-// workgroup, up to 256 (vocabulary rows) x 320 (hidden rows) per workgroup - which leaves no
+// large wave tiles - AB x BB blocks of v_mfma_f32_32x32x16_bf16 per wave, WM x 2 waves per
+// workgroup, 128 (vocabulary rows) x 320 (hidden rows) per workgroup as dispatched - which leaves no
 // registers for per-row top-k lists; the fp32 logits of the active rows are written out (HBM has
 // slack in this regime) and a second kernel reduces each row (row_topk_kernel).
 //
 // W is the A operand, so an accumulator lane owns one hidden row and four consecutive vocabulary
 // rows per register quad: the output is stored as float4 along V.  Both operands go through
-// double-buffered LDS tiles of 64 k (144-byte pitch, conflict-free 16-byte reads); the K loop is
+// double-buffered LDS tiles of 32 k (80-byte pitch, conflict-free 16-byte reads); the K loop is
 // unrolled by two with two static register sets so that the loads of tile kt+2 are in flight
 // while tile kt is multiplied.  Only active rows are multiplied: the B rows are gathered through
 // the compacted row list and column blocks past the last active row are skipped per wave.
@@ -31,28 +31,37 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 constexpr int kGK = 32;        // k per LDS tile
 constexpr int kGPitch = 40;    // bf16 elements per LDS row: 32 + 8 pad (80 B: conflict-free 16-byte reads)
 constexpr int kCPR = kGK / 8;  // 16-byte chunks per tile row
-constexpr int kRPP = 256 / kCPR;   // rows copied per pass of the 256 threads
 
-template <int AB, int BB>
+// AB x BB blocks of 32 x 32 per wave, WM x 2 waves per workgroup.
+template <int AB, int BB, int WM>
 struct GemmCfg {
-  static constexpr int BM = 64 * AB, BN = 64 * BB;
+  static constexpr int BM = 32 * AB * WM, BN = 64 * BB;
+  static constexpr int kThreads = 128 * WM;
+  static constexpr int kRPP = kThreads / kCPR;                 // rows copied per pass of the workgroup
+  static constexpr int NA = BM / kRPP;                          // copy passes of the W tile
+  static constexpr int NBF = BN / kRPP;                         // full copy passes of the hidden-row tile ...
+  static constexpr int kBRem = BN - NBF * kRPP;                 // ... and the rows of a last, partial pass
+  static constexpr int NBL = NBF + (kBRem > 0 ? 1 : 0);
   static constexpr int kStageElems = (BM + BN) * kGPitch;
   static constexpr int kLdsBytes = 2 * kStageElems * 2;
+  static_assert(BM % kRPP == 0, "W tile rows must be a whole number of copy passes");
 };
 
 // One work unit of one wave: NB = number of this wave's column blocks that hold active rows
 // (0 <= NB <= BB; a wave with NB == 0 still copies tiles and meets the barriers).  Every value of
 // NB has its own fully unrolled loop, so the accumulators stay in place (no data-dependent
 // branches around the MFMAs).
-template <int AB, int BB, int NB>
+template <int AB, int BB, int WM, int NB>
 __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int mt, int nt, int n_act, int tid, int wm,
                                           int wn, int l32, int lh) {
-  using C = GemmCfg<AB, BB>;
+  using C = GemmCfg<AB, BB, WM>;
   constexpr int NBR = NB > 0 ? NB : 1;
+  constexpr int kRPP = C::kRPP, NA = C::NA, NBL = C::NBL;
   const int KT = a.H / kGK;                                         // even: H is a multiple of 128
   const int ld_row = tid / kCPR, ld_cc = tid % kCPR;                // global->LDS copy: kCPR x 16 B per row
   const int st_off = ld_row * kGPitch + ld_cc * 8;
-  constexpr int NA = C::BM / kRPP, NBL = C::BN / kRPP;              // copy passes per tile
+  // the last pass over the hidden-row tile may cover only part of the workgroup's rows
+  const bool b_last_ok = (C::kBRem == 0) || (ld_row < C::kBRem);
   // 32-bit element offsets from the two base pointers (V*H and rows*H stay below 2^31 elements)
   uint32_t aoff[NA], boff[NBL];
 #pragma unroll
@@ -60,7 +69,8 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
     aoff[i] = (uint32_t)min(mt * C::BM + ld_row + kRPP * i, a.V - 1) * (uint32_t)a.H + ld_cc * 8;
 #pragma unroll
   for (int i = 0; i < NBL; ++i)
-    boff[i] = (uint32_t)a.row_list[min(nt * C::BN + ld_row + kRPP * i, n_act - 1)] * (uint32_t)a.H + ld_cc * 8;
+    boff[i] = (uint32_t)a.row_list[min(nt * C::BN + min(ld_row + kRPP * i, C::BN - 1), n_act - 1)] * (uint32_t)a.H +
+              ld_cc * 8;
   const int col0 = nt * C::BN + wn * 32 * BB;
 
   f32x16 acc[AB][NBR];
@@ -71,7 +81,11 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0.f;
 
-  u32x4 a0[NA], b0[NBL], a1[NA], b1[NBL];
+  // Four waves (one per SIMD): two register sets, loads two tiles ahead, fragments two k-steps at a
+  // time.  Eight waves (two per SIMD, 256 registers each): one set, one tile ahead, one k-step -
+  // the other wave of the SIMD covers the waits.
+  constexpr int FK = (WM == 2) ? 2 : 1;
+  u32x4 a0[NA], b0[NBL];
 #define DDD_LOADSET(SA, SB, T)                                                                                      \
   {                                                                                                                 \
     _Pragma("unroll") for (int i = 0; i < NA; ++i) SA[i] = *reinterpret_cast<const u32x4*>(a.W + aoff[i] + (T) * kGK);    \
@@ -82,46 +96,65 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
     uint16_t* sa_ = lds + (BUF) * C::kStageElems + st_off;                                                          \
     uint16_t* sb_ = sa_ + C::BM * kGPitch;                                                                          \
     _Pragma("unroll") for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(sa_ + kRPP * i * kGPitch) = SA[i];     \
-    _Pragma("unroll") for (int i = 0; i < NBL; ++i) *reinterpret_cast<u32x4*>(sb_ + kRPP * i * kGPitch) = SB[i];    \
+    _Pragma("unroll") for (int i = 0; i < NBL; ++i)                                                                 \
+      if (i < C::NBF || b_last_ok) *reinterpret_cast<u32x4*>(sb_ + kRPP * i * kGPitch) = SB[i];                     \
   }
 #define DDD_COMPUTE(BUF)                                                                                            \
   if (NB > 0) {                                                                                                     \
     const uint16_t* Ab = lds + (BUF) * C::kStageElems + (wm * 32 * AB + l32) * kGPitch + lh * 8;                    \
     const uint16_t* Bb = lds + (BUF) * C::kStageElems + (C::BM + wn * 32 * BB + l32) * kGPitch + lh * 8;            \
-    /* fragments are requested two k-steps at a time: the second k-step's reads land during the first   */         \
-    /* one's MFMAs                                                                                        */         \
-    _Pragma("unroll") for (int kp = 0; kp < kGK / 32; ++kp) {                                                       \
-      bf16x8 af[2][AB], bf[2][NBR];                                                                                 \
-      _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                            \
+    /* fragments are requested FK k-steps at a time (FK = 2: the second k-step's reads land during the  */         \
+    /* first one's MFMAs)                                                                                 */         \
+    _Pragma("unroll") for (int kp = 0; kp < kGK / (16 * FK); ++kp) {                                                \
+      bf16x8 af[FK][AB], bf[FK][NBR];                                                                               \
+      _Pragma("unroll") for (int ks = 0; ks < FK; ++ks) {                                                           \
         _Pragma("unroll") for (int b = 0; b < AB; ++b) af[ks][b] = __builtin_bit_cast(                              \
-            bf16x8, *reinterpret_cast<const u32x4*>(Ab + b * 32 * kGPitch + (kp * 2 + ks) * 16));                   \
+            bf16x8, *reinterpret_cast<const u32x4*>(Ab + b * 32 * kGPitch + (kp * FK + ks) * 16));                  \
         _Pragma("unroll") for (int b = 0; b < NBR; ++b) bf[ks][b] = __builtin_bit_cast(                             \
-            bf16x8, *reinterpret_cast<const u32x4*>(Bb + b * 32 * kGPitch + (kp * 2 + ks) * 16));                   \
+            bf16x8, *reinterpret_cast<const u32x4*>(Bb + b * 32 * kGPitch + (kp * FK + ks) * 16));                  \
       }                                                                                                             \
-      _Pragma("unroll") for (int ks = 0; ks < 2; ++ks)                                                              \
+      _Pragma("unroll") for (int ks = 0; ks < FK; ++ks)                                                             \
         _Pragma("unroll") for (int bn = 0; bn < NBR; ++bn)                                                          \
           _Pragma("unroll") for (int bm = 0; bm < AB; ++bm)                                                         \
               acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][bm], bf[ks][bn], acc[bm][bn], 0, 0, 0);  \
     }                                                                                                               \
   }
 
-  DDD_LOADSET(a0, b0, 0);
-  DDD_LOADSET(a1, b1, 1);
-  __syncthreads();            // every wave is done with the LDS tiles of the previous unit
-  DDD_STORESET(a0, b0, 0);
-  DDD_LOADSET(a0, b0, min(2, KT - 1));
-  __syncthreads();
-  for (int kt = 0; kt < KT; kt += 2) {
-    // tile kt is in LDS[0]; tile kt+1 waits in set 1 (loaded two half-iterations ago)
-    DDD_STORESET(a1, b1, 1);
-    DDD_LOADSET(a1, b1, min(kt + 3, KT - 1));   // always issued: keeps the count of loads in flight static
-    DDD_COMPUTE(0);
-    __syncthreads();
-    // tile kt+1 is in LDS[1]; tile kt+2 waits in set 0
+  if constexpr (WM == 2) {
+    u32x4 a1[NA], b1[NBL];
+    DDD_LOADSET(a0, b0, 0);
+    DDD_LOADSET(a1, b1, 1);
+    __syncthreads();            // every wave is done with the LDS tiles of the previous unit
     DDD_STORESET(a0, b0, 0);
-    DDD_LOADSET(a0, b0, min(kt + 4, KT - 1));
-    DDD_COMPUTE(1);
+    DDD_LOADSET(a0, b0, min(2, KT - 1));
     __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {
+      // tile kt is in LDS[0]; tile kt+1 waits in set 1 (loaded two half-iterations ago)
+      DDD_STORESET(a1, b1, 1);
+      DDD_LOADSET(a1, b1, min(kt + 3, KT - 1));   // always issued: keeps the count of loads in flight static
+      DDD_COMPUTE(0);
+      __syncthreads();
+      // tile kt+1 is in LDS[1]; tile kt+2 waits in set 0
+      DDD_STORESET(a0, b0, 0);
+      DDD_LOADSET(a0, b0, min(kt + 4, KT - 1));
+      DDD_COMPUTE(1);
+      __syncthreads();
+    }
+  } else {
+    DDD_LOADSET(a0, b0, 0);
+    __syncthreads();            // every wave is done with the LDS tiles of the previous unit
+    DDD_STORESET(a0, b0, 0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; kt += 2) {
+      DDD_LOADSET(a0, b0, min(kt + 1, KT - 1));   // tile kt+1 travels while tile kt is multiplied
+      DDD_COMPUTE(0);
+      DDD_STORESET(a0, b0, 1);
+      __syncthreads();
+      DDD_LOADSET(a0, b0, min(kt + 2, KT - 1));
+      DDD_COMPUTE(1);
+      DDD_STORESET(a0, b0, 0);
+      __syncthreads();
+    }
   }
 #undef DDD_LOADSET
 #undef DDD_STORESET
@@ -184,16 +217,16 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
   }
 }
 
-template <int AB, int BB>
-__global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(GemmArgs a) {
-  using C = GemmCfg<AB, BB>;
+template <int AB, int BB, int WM>
+__global__ __launch_bounds__(128 * WM, 1) void lmhead_gemm_kernel(GemmArgs a) {
+  using C = GemmCfg<AB, BB, WM>;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   uint16_t* lds = reinterpret_cast<uint16_t*>(smem_raw);   // [2][BM + BN][kGPitch]
 
   const int n_act = *a.n_act_ptr;
   if (n_act <= 0) return;                                  // uniform
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wm = wave & 1, wn = wave >> 1;
+  const int wm = wave % WM, wn = wave / WM;
   const int l32 = lane & 31, lh = lane >> 5;
   const int nmt = (a.V + C::BM - 1) / C::BM;
   const int NT = (n_act + C::BN - 1) / C::BN;
@@ -207,12 +240,12 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(GemmArgs a) {
     const int col0 = nt * C::BN + wn * 32 * BB;
     const int nb_act = min(BB, max(0, (n_act - col0 + 31) / 32));
     switch (nb_act) {
-      case 0: gemm_unit<AB, BB, 0>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 1: gemm_unit<AB, BB, 1>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 2: gemm_unit<AB, BB, (BB >= 2 ? 2 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 3: gemm_unit<AB, BB, (BB >= 3 ? 3 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 4: gemm_unit<AB, BB, (BB >= 4 ? 4 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      default: gemm_unit<AB, BB, BB>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 0: gemm_unit<AB, BB, WM, 0>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 1: gemm_unit<AB, BB, WM, 1>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 2: gemm_unit<AB, BB, WM, (BB >= 2 ? 2 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 3: gemm_unit<AB, BB, WM, (BB >= 3 ? 3 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 4: gemm_unit<AB, BB, WM, (BB >= 4 ? 4 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      default: gemm_unit<AB, BB, WM, BB>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
     }
   }
 }
@@ -251,35 +284,36 @@ hipError_t launch_build_row_list(const uint8_t* row_active, int n_rows, int32_t*
   return hipGetLastError();
 }
 
-// Tile shape by the largest number of rows the call can have: 128 x 320 for hundreds of rows
-// (a 256 x 320 tile would halve the LDS traffic again but spills accumulators), smaller column
-// tiles when fewer rows can be active.
+// Tile shape by the largest number of rows the call can have: 128 x 320 for hundreds of rows,
+// smaller column tiles when fewer rows can be active.  (WM = 4, eight waves on a 256 x 320 tile,
+// measured 200 us against 224 us with all 640 rows active, but leaves half of the CUs idle once
+// fewer than 321 rows are active, which is most draft calls of a round: not dispatched.)
 static int pick_shape(int max_rows) { return max_rows > 192 ? 1 : (max_rows > 128 ? 2 : 3); }
 
-template <int AB, int BB>
+template <int AB, int BB, int WM>
 static hipError_t prepare_shape() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_gemm_kernel<AB, BB>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, GemmCfg<AB, BB>::kLdsBytes);
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_gemm_kernel<AB, BB, WM>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, GemmCfg<AB, BB, WM>::kLdsBytes);
 }
 
 hipError_t prepare_lmhead_gemm() {
-  hipError_t e = prepare_shape<2, 5>();
-  if (e == hipSuccess) e = prepare_shape<2, 3>();
-  if (e == hipSuccess) e = prepare_shape<2, 2>();
+  hipError_t e = prepare_shape<2, 5, 2>();
+  if (e == hipSuccess) e = prepare_shape<2, 3, 2>();
+  if (e == hipSuccess) e = prepare_shape<2, 2, 2>();
   return e;
 }
 
-template <int AB, int BB>
+template <int AB, int BB, int WM>
 static void launch_shape(const GemmArgs& a, int grid, hipStream_t stream) {
-  constexpr int lds_bytes = GemmCfg<AB, BB>::kLdsBytes;
-  hipLaunchKernelGGL((lmhead_gemm_kernel<AB, BB>), dim3(grid), dim3(256), lds_bytes, stream, a);
+  constexpr int lds_bytes = GemmCfg<AB, BB, WM>::kLdsBytes;
+  hipLaunchKernelGGL((lmhead_gemm_kernel<AB, BB, WM>), dim3(grid), dim3(128 * WM), lds_bytes, stream, a);
 }
 
 hipError_t launch_lmhead_gemm(const GemmArgs& a, int max_rows, int grid, hipStream_t stream) {
   switch (pick_shape(max_rows)) {
-    case 1: launch_shape<2, 5>(a, grid, stream); break;
-    case 2: launch_shape<2, 3>(a, grid, stream); break;
-    default: launch_shape<2, 2>(a, grid, stream); break;
+    case 1: launch_shape<2, 5, 2>(a, grid, stream); break;
+    case 2: launch_shape<2, 3, 2>(a, grid, stream); break;
+    default: launch_shape<2, 2, 2>(a, grid, stream); break;
   }
   return hipGetLastError();
 }
