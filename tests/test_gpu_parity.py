@@ -309,11 +309,12 @@ def test_synth_draft_body_matches_numpy_generator(gpu):
 # ------------------------------------------------------------------------------------------------
 # L2: whole rounds, the oracle replaying the GPU's logits and lse
 # ------------------------------------------------------------------------------------------------
-def _compare_round(g, snap, wl, rnd, thr, logits_dbg, lse_dbg, check_own_logits_steps=0):
-    """Replay sequence by sequence; returns the list of oracle step counts."""
+def _compare_round(g, snap, wl, rnd, thr, logits_dbg, lse_dbg, check_own_logits_steps=0, seqs=None, own_seqs=None):
+    """Replay sequence by sequence (all, or those in `seqs`); returns the list of oracle step counts.
+    The oracle's own projection is compared for the sequences in `own_seqs` (default: all replayed)."""
     k = wl.k
     steps_out = []
-    for b in range(wl.B):
+    for b in (range(wl.B) if seqs is None else seqs):
         def logits_fn(s, hid, b=b):
             rows = slice(b, b + 1) if s == 0 else slice(b * k, (b + 1) * k)
             return logits_dbg[s, rows], lse_dbg[s, rows].astype(np.float64)
@@ -350,6 +351,8 @@ def _compare_round(g, snap, wl, rnd, thr, logits_dbg, lse_dbg, check_own_logits_
             for va, vb in wl.dup_pairs:
                 assert np.array_equal(logits_dbg[s, rows][:, va], logits_dbg[s, rows][:, vb]), ctx_msg
         # the oracle's own projection of the same hidden rows agrees with the GPU's logits
+        if own_seqs is not None and b not in own_seqs:
+            continue
         for s in range(min(check_own_logits_steps, res.steps)):
             rows = slice(b, b + 1) if s == 0 else slice(b * k, (b + 1) * k)
             own = O.lmhead_logits(g.W_bits, res.records[s].hid_bits)
@@ -468,3 +471,47 @@ def test_7b_shape_round_parity(gpu):
         print(f"[info] 7b depths {depths}", flush=True)
     finally:
         g.close()
+
+
+FULL_CASES = [
+    # name, workload, rounds, sequences replayed by the oracle (None = all), sequences whose logits the oracle recomputes
+    ("13b_b1", synth.WORKLOADS["13b_b1"], 6, None, (0,)),
+    ("7b_b64", synth.WORKLOADS["7b_b64"], 2, None, (0, 37)),
+    ("large_vocab", synth.WORKLOADS["large_vocab"], 2, None, (5,)),
+]
+
+
+@pytest.mark.parametrize("case", FULL_CASES, ids=[c[0] for c in FULL_CASES])
+def test_full_size_round_parity(gpu, case):
+    """The other workloads at their full sizes, launched as the captured graph the benchmark times: every
+    sequence's round is replayed by the oracle from the GPU's dumped logits (bit-exact integers and scores), the
+    oracle's own fp64 projection is compared on sampled sequences, and the same rounds launched without the
+    debug buffers (exactly the benchmark's configuration) leave byte-identical state."""
+    torch, D, SD = gpu
+    name, wl, n_rounds, seqs, own_seqs = case
+    print(f"[case] full-size {name} B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D}", flush=True)
+    g = SD.GpuWorkload(wl, debug=True)
+    g2 = None
+    try:
+        side = torch.cuda.Stream()
+        g.capture(side)
+        g2 = SD.GpuWorkload(wl, W_bits=g.W_bits, debug=False)
+        g2.capture(side)
+        torch.cuda.synchronize()
+        for rnd in range(n_rounds):
+            g.set_round(rnd)
+            g2.set_round(rnd)
+            torch.cuda.synchronize()
+            g.launch(side.cuda_stream)
+            g2.launch(side.cuda_stream)
+            side.synchronize()
+            snap = g.snapshot()
+            depths = _compare_round(g, snap, wl, rnd, wl.threshold, g.logits_dbg.cpu().numpy(),
+                                    g.lse_dbg.cpu().numpy(), check_own_logits_steps=2 if rnd == 0 else 0,
+                                    seqs=seqs, own_seqs=own_seqs)
+            _same_round(g2.snapshot(), snap)
+            print(f"[info] {name} round {rnd} depths {depths}", flush=True)
+    finally:
+        g.close()
+        if g2 is not None:
+            g2.close()
