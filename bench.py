@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="7b_b1", help="synthetic workload name (see synth/inputs.py)")
     ap.add_argument("--threshold", type=float, default=None, help="stop threshold t (default: the workload's)")
+    ap.add_argument("--mode", choices=["default", "paper", "strict", "eagle2"], default="default",
+                    help="paper: the paper's setting n=11, S={5,7,9}, x=-0.3 (t=exp(x)); strict: the same with the "
+                         "test after every call; eagle2: fixed depth 6, no stop test (Section 3.1, Table 1 baselines)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--profile-iters", type=int, default=200)
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
@@ -77,6 +80,12 @@ def main():
         sys.exit("bench.py needs a gfx950 GPU (the HIP path has no CPU fallback)")
     D.load_library()
     wl = synth.WORKLOADS[args.workload]
+    if args.mode == "paper":      # Section 3.1: n = 11 draft calls at most, checks after calls 5, 7, 9, x = -0.3
+        wl = wl.with_(D=11, check_mask=(1 << 5) | (1 << 7) | (1 << 9), threshold=float(np.float32(np.exp(-0.3))))
+    elif args.mode == "strict":   # Section 3.3 ablation: the same, checked after every call
+        wl = wl.with_(D=11, check_mask=0xFFFFFFFF, threshold=float(np.float32(np.exp(-0.3))))
+    elif args.mode == "eagle2":   # EAGLE-2's fixed depth: 6 calls, never stops early
+        wl = wl.with_(D=6, threshold=0.0)
     thr = wl.threshold if args.threshold is None else args.threshold
     log(f"[bench] workload {wl.name}: B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} m={wl.m} t={thr} gain={wl.gain}")
     t0 = time.perf_counter()
@@ -135,8 +144,7 @@ def main():
         alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * D.ddd_num_slices(g.ctx) * (wl.k * 8 + 4)
     else:
         kernel_name = "lmhead_gemm_kernel"
-        n_slices = -(-((wl.V + 127) // 128) // (-(-((wl.V + 127) // 128) // 256)))
-        alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * n_slices * (wl.k * 8 + 4)
+        alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * (wl.k * 8 + 4)   # W, hidden rows, k keys + lse per row
     alg_flops = 2.0 * wl.V * wl.H * n_rows
     achieved = alg_bytes / (mean_ms * 1e-3) / 1e9
     achieved_tflops = alg_flops / (mean_ms * 1e-3) / 1e12
@@ -194,7 +202,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
-                   "threshold": thr, "hidden_gain": wl.gain,
+                   "threshold": thr, "check_mask": int(wl.check_mask), "mode": args.mode, "hidden_gain": wl.gain,
                    "launch": "one hipGraph per round" if args.launch == "graph" else "stream launches",
                    "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},
                    "accept_len_hist": {str(d): int(c) for d, c in enumerate(accept_hist) if c},

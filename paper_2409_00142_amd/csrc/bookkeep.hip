@@ -38,18 +38,54 @@ hipError_t launch_merge(const MergeArgs& a, hipStream_t stream) {
 // ---- row reduction of materialised logits (GEMM path) ------------------------------------------
 // One workgroup per row.  The GEMM left, for every group of 64 consecutive vocabulary rows, the
 // group's max and sum of exponentials.  lse follows from those alone.  The k-th largest group max
-// T is a lower bound of the row's k-th largest logit (k distinct elements are >= T), so one
-// compare-only pass over the row collects the few candidates >= T, and the exact top-k by
-// (logit desc, token asc) is taken among them.  If more candidates than fit turn up (massive
-// ties, e.g. constant logits), an exact but slow path takes over: k passes over the row, each
-// finding the largest key below the previous winner.
+// T is a lower bound of the row's k-th largest logit (k distinct elements are >= T), and only the
+// groups whose max reaches T - k of them, or a few more - can hold an element >= T: those groups'
+// logits are read (64 values each), the candidates >= T collected, and the exact top-k by (logit
+// desc, token asc) taken among them.  Massive ties (e.g. constant logits) overflow the lists: with
+// too many candidate groups the whole row is scanned instead, and with too many candidates an
+// exact but slow path takes over: k passes over the row, each finding the largest key below the
+// previous winner.
 constexpr int kCandMax = 1024;
+constexpr int kGrpListMax = 256;   // groups that may hold a candidate; more than that: the row is scanned
+
+// k-th largest of the group maxima as an ordered key (0 if there are fewer than k groups), by one
+// wave: lane holds groups lane, lane + 64, ... (S slots).
+template <int S>
+__device__ __forceinline__ uint32_t kth_largest_group_max(const float* gmax, int ngrp_valid, int k, int lane) {
+  uint32_t loc[S];
+#pragma unroll
+  for (int i = 0; i < S; ++i) {
+    const int g = lane + 64 * i;
+    loc[i] = (g < ngrp_valid) ? ord32(gmax[g]) : 0u;
+  }
+  uint32_t T = 0u;
+  for (int round = 0; round < k; ++round) {
+    uint32_t lm = 0u;
+#pragma unroll
+    for (int i = 0; i < S; ++i) lm = umax32(lm, loc[i]);
+    T = wave_max_u32(lm);
+    if (T == 0u) break;                                    // uniform: fewer than k groups
+    // remove one holder of the maximum (the lowest lane, its lowest slot)
+    const unsigned long long holders = __ballot(lm == T);
+    if (lane == __ffsll((long long)holders) - 1) {
+      bool done = false;
+#pragma unroll
+      for (int i = 0; i < S; ++i)
+        if (!done && loc[i] == T) {
+          loc[i] = 0u;
+          done = true;
+        }
+    }
+  }
+  return T;
+}
 
 __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
   __shared__ uint64_t s_cand[kCandMax];
   __shared__ float s_red[8];
   __shared__ float s_T;
-  __shared__ int s_cnt;
+  __shared__ int s_cnt, s_ng;
+  __shared__ int s_glist[kGrpListMax];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (a.row_active != nullptr && !a.row_active[row]) return;   // uniform
   const int ngrp_valid = (a.V + 63) >> 6;
@@ -68,43 +104,50 @@ __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
   acc = wave_sum_f32(acc);
   if (lane == 0) s_red[4 + wave] = acc;
   // ---- T = k-th largest group max (or -inf if there are fewer than k groups): wave 0 -------------
-  if (tid == 0) s_cnt = 0;
+  if (tid == 0) {
+    s_cnt = 0;
+    s_ng = 0;
+  }
   if (wave == 0) {
-    // up to 2048 groups (V <= 131072): 32 per lane, kept as ordered keys, k rounds of wave max
-    uint32_t loc[32];
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      const int g = lane + 64 * i;
-      loc[i] = (g < ngrp_valid) ? ord32(gmax[g]) : 0u;
-    }
-    uint32_t T = 0u;
-    for (int round = 0; round < a.k; ++round) {
-      uint32_t lm = 0u;
-#pragma unroll
-      for (int i = 0; i < 32; ++i) lm = umax32(lm, loc[i]);
-      T = wave_max_u32(lm);
-      if (T == 0u) break;                                    // uniform: fewer than k groups
-      // remove one holder of the maximum (the lowest lane, its lowest slot)
-      const unsigned long long holders = __ballot(lm == T);
-      if (lane == __ffsll((long long)holders) - 1) {
-        bool done = false;
-#pragma unroll
-        for (int i = 0; i < 32; ++i)
-          if (!done && loc[i] == T) {
-            loc[i] = 0u;
-            done = true;
-          }
-      }
-    }
+    // up to 2048 groups (V <= 131072): up to 32 per lane, kept as ordered keys, k rounds of wave max
+    const uint32_t T = (ngrp_valid <= 512)    ? kth_largest_group_max<8>(gmax, ngrp_valid, a.k, lane)
+                       : (ngrp_valid <= 1024) ? kth_largest_group_max<16>(gmax, ngrp_valid, a.k, lane)
+                                              : kth_largest_group_max<32>(gmax, ngrp_valid, a.k, lane);
     if (lane == 0) s_T = (T == 0u) ? -INFINITY : unord32(T);
   }
   __syncthreads();
   const float lse = M + __logf(s_red[4] + s_red[5] + s_red[6] + s_red[7]);
 
   // ---- collect candidates >= T ------------------------------------------------------------------
+  // Only groups whose max reaches T can hold one: usually k or a few more of them, so the row's
+  // logits are read group by group (64 consecutive values, one per lane) rather than scanned.
   const float* x = a.logits + (size_t)row * a.V;
   const float T = s_T;
-  if ((a.V & 3) == 0) {
+  for (int g = tid; g < ngrp_valid; g += 256)
+    if (gmax[g] >= T) {
+      const int p = atomicAdd(&s_ng, 1);
+      if (p < kGrpListMax) s_glist[p] = g;
+    }
+  __syncthreads();
+  const int ng = s_ng;
+  if (ng <= kGrpListMax) {                                     // uniform
+    for (int i0 = wave; i0 < ng; i0 += 16) {
+      float xv[4];
+      int vv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {                            // four independent loads in flight
+        const int i = i0 + 4 * u;
+        vv[u] = (i < ng) ? s_glist[i] * 64 + lane : a.V;
+        xv[u] = (vv[u] < a.V) ? x[vv[u]] : -INFINITY;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (vv[u] < a.V && xv[u] >= T) {
+          const int p = atomicAdd(&s_cnt, 1);
+          if (p < kCandMax) s_cand[p] = row_key(xv[u], vv[u]);
+        }
+    }
+  } else if ((a.V & 3) == 0) {                                 // too many groups tie at T: scan the row
     const int nchunk = a.V >> 2;
     for (int c0 = tid; c0 < nchunk; c0 += 8 * 256) {
       float4 q[8];   // eight independent 16-byte loads in flight before any is consumed
@@ -117,23 +160,23 @@ __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int c = c0 + u * 256;
-        const float xv[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
-        if (c < nchunk && fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])) >= T) {
+        const float xq[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+        if (c < nchunk && fmaxf(fmaxf(xq[0], xq[1]), fmaxf(xq[2], xq[3])) >= T) {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            if (xv[e] >= T) {
+            if (xq[e] >= T) {
               const int p = atomicAdd(&s_cnt, 1);
-              if (p < kCandMax) s_cand[p] = row_key(xv[e], 4 * c + e);
+              if (p < kCandMax) s_cand[p] = row_key(xq[e], 4 * c + e);
             }
         }
       }
     }
   } else {
     for (int v = tid; v < a.V; v += 256) {
-      const float xv = x[v];
-      if (xv >= T) {
+      const float xs = x[v];
+      if (xs >= T) {
         const int p = atomicAdd(&s_cnt, 1);
-        if (p < kCandMax) s_cand[p] = row_key(xv, v);
+        if (p < kCandMax) s_cand[p] = row_key(xs, v);
       }
     }
   }
