@@ -144,15 +144,17 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
     DDD_LOADSET(a0, b0, 0);
     __syncthreads();            // every wave is done with the LDS tiles of the previous unit
     DDD_STORESET(a0, b0, 0);
+    DDD_LOADSET(a0, b0, min(1, KT - 1));
     __syncthreads();
     for (int kt = 0; kt < KT; kt += 2) {
-      DDD_LOADSET(a0, b0, min(kt + 1, KT - 1));   // tile kt+1 travels while tile kt is multiplied
-      DDD_COMPUTE(0);
+      // tile kt is in LDS[0]; tile kt+1 waits in the register set (loaded one half-iteration ago)
       DDD_STORESET(a0, b0, 1);
-      __syncthreads();
       DDD_LOADSET(a0, b0, min(kt + 2, KT - 1));
-      DDD_COMPUTE(1);
+      DDD_COMPUTE(0);
+      __syncthreads();
       DDD_STORESET(a0, b0, 0);
+      DDD_LOADSET(a0, b0, min(kt + 3, KT - 1));
+      DDD_COMPUTE(1);
       __syncthreads();
     }
   }
@@ -286,8 +288,8 @@ hipError_t launch_build_row_list(const uint8_t* row_active, int n_rows, int32_t*
 
 // Tile shape by the largest number of rows the call can have: 128 x 320 for hundreds of rows,
 // smaller column tiles when fewer rows can be active.  (WM = 4, eight waves on a 256 x 320 tile,
-// measured 200 us against 224 us with all 640 rows active, but leaves half of the CUs idle once
-// fewer than 321 rows are active, which is most draft calls of a round: not dispatched.)
+// measured 199 us against 224 us with all 640 rows active, but leaves half of the CUs idle once
+// fewer than 321 rows are active, which is most draft calls of a round: not instantiated.)
 static int pick_shape(int max_rows) { return max_rows > 192 ? 1 : (max_rows > 128 ? 2 : 3); }
 
 template <int AB, int BB, int WM>

@@ -72,9 +72,9 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
   if (a.row_active != nullptr) {  // nothing to do if every row of this pass is inactive (uniform)
-    int any = 0;
-    for (int r = 0; r < a.R; ++r) any |= a.row_active[r];
-    if (!any) return;
+    // one load per lane and a ballot: a single memory round trip before the launch can retire
+    const int on = (lane < a.R) ? a.row_active[lane] : 0;
+    if (__ballot(on != 0) == 0ull) return;
   }
 
   const int nslice = gridDim.x, slice = blockIdx.x;
