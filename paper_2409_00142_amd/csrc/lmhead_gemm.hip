@@ -166,38 +166,47 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
   // accumulator register q*4+e of block (bm, bn): vocabulary row vb + bm*32 + q*8 + e, hidden row column l32
   const int vb = mt * C::BM + wm * 32 * AB + lh * 4;
   const bool v_aligned = (a.V & 3) == 0;
-  static_assert(AB == 2, "a wave covers one group of 64 vocabulary rows");
-  const int grp = (mt * C::BM + wm * 64) >> 6;
+  static_assert(AB % 2 == 0, "a wave covers whole groups of 64 vocabulary rows");
+  constexpr int NGW = AB / 2;                                  // groups per wave
+  const int grp0 = (mt * C::BM + wm * 32 * AB) >> 6;
 #pragma unroll
   for (int bn = 0; bn < NBR; ++bn) {
     const int n = col0 + bn * 32 + l32;
-    // statistics of this hidden row over the wave's 64 vocabulary rows: each of the two lanes that share
-    // the column reduces its 32 values, then the pair is combined (lanes l and l+32)
-    float gm = -INFINITY;
+    // statistics of this hidden row over each group of 64 vocabulary rows the wave covers: each of the two
+    // lanes that share the column reduces its 32 values, then the pair is combined (lanes l and l+32)
+    float gm[NGW], gs[NGW];
 #pragma unroll
-    for (int bm = 0; bm < AB; ++bm)
+    for (int gp = 0; gp < NGW; ++gp) {
+      gm[gp] = -INFINITY;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int v = vb + bm * 32 + (e >> 2) * 8 + (e & 3);
-        const float x = acc[bm][bn][e] + 0.0f;   // -0 -> +0
-        acc[bm][bn][e] = x;
-        if (v < a.V) gm = fmaxf(gm, x);
-      }
-    gm = fmaxf(gm, __shfl_xor(gm, 32, 64));
-    float gs = 0.f;
+      for (int bm = 2 * gp; bm < 2 * gp + 2; ++bm)
 #pragma unroll
-    for (int bm = 0; bm < AB; ++bm)
+        for (int e = 0; e < 16; ++e) {
+          const int v = vb + bm * 32 + (e >> 2) * 8 + (e & 3);
+          const float x = acc[bm][bn][e] + 0.0f;   // -0 -> +0
+          acc[bm][bn][e] = x;
+          if (v < a.V) gm[gp] = fmaxf(gm[gp], x);
+        }
+      gm[gp] = fmaxf(gm[gp], __shfl_xor(gm[gp], 32, 64));
+      gs[gp] = 0.f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int v = vb + bm * 32 + (e >> 2) * 8 + (e & 3);
-        if (v < a.V) gs += __expf(acc[bm][bn][e] - gm);
-      }
-    gs += __shfl_xor(gs, 32, 64);
+      for (int bm = 2 * gp; bm < 2 * gp + 2; ++bm)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int v = vb + bm * 32 + (e >> 2) * 8 + (e & 3);
+          if (v < a.V) gs[gp] += __expf(acc[bm][bn][e] - gm[gp]);
+        }
+      gs[gp] += __shfl_xor(gs[gp], 32, 64);
+    }
     if (n < n_act) {
       const int orow_id = a.row_list[n];
       if (lh == 0) {
-        a.grp_max[(size_t)orow_id * a.ngrp + grp] = gm;
-        a.grp_sum[(size_t)orow_id * a.ngrp + grp] = gs;
+#pragma unroll
+        for (int gp = 0; gp < NGW; ++gp)
+          if ((grp0 + gp) * 64 < a.V) {   // groups past the vocabulary (ragged last tile) are not stored
+            a.grp_max[(size_t)orow_id * a.ngrp + grp0 + gp] = gm[gp];
+            a.grp_sum[(size_t)orow_id * a.ngrp + grp0 + gp] = gs[gp];
+          }
       }
       float* orow = a.logits + (size_t)orow_id * a.V;
 #pragma unroll
@@ -290,7 +299,13 @@ hipError_t launch_build_row_list(const uint8_t* row_active, int n_rows, int32_t*
 // smaller column tiles when fewer rows can be active.  (WM = 4, eight waves on a 256 x 320 tile,
 // measured 199 us against 224 us with all 640 rows active, but leaves half of the CUs idle once
 // fewer than 321 rows are active, which is most draft calls of a round: not instantiated.)
-static int pick_shape(int max_rows) { return max_rows > 192 ? 1 : (max_rows > 128 ? 2 : 3); }
+// With at most 128 rows and a vocabulary large enough to give every CU a unit, 256 vocabulary rows per
+// workgroup (128 x 64 wave tiles) cut the LDS and L2 traffic per MFMA by a quarter.
+static int pick_shape(int max_rows, int V, int grid) {
+  if (max_rows > 192) return 1;
+  if (max_rows > 128) return 2;
+  return ((V + 255) / 256 >= grid) ? 4 : 3;
+}
 
 template <int AB, int BB, int WM>
 static hipError_t prepare_shape() {
@@ -302,6 +317,7 @@ hipError_t prepare_lmhead_gemm() {
   hipError_t e = prepare_shape<2, 5, 2>();
   if (e == hipSuccess) e = prepare_shape<2, 3, 2>();
   if (e == hipSuccess) e = prepare_shape<2, 2, 2>();
+  if (e == hipSuccess) e = prepare_shape<4, 2, 2>();
   return e;
 }
 
@@ -312,9 +328,10 @@ static void launch_shape(const GemmArgs& a, int grid, hipStream_t stream) {
 }
 
 hipError_t launch_lmhead_gemm(const GemmArgs& a, int max_rows, int grid, hipStream_t stream) {
-  switch (pick_shape(max_rows)) {
+  switch (pick_shape(max_rows, a.V, grid)) {
     case 1: launch_shape<2, 5, 2>(a, grid, stream); break;
     case 2: launch_shape<2, 3, 2>(a, grid, stream); break;
+    case 4: launch_shape<4, 2, 2>(a, grid, stream); break;
     default: launch_shape<2, 2, 2>(a, grid, stream); break;
   }
   return hipGetLastError();

@@ -44,6 +44,8 @@ LM_CASES = [
     ("gemm_ragged_V_rows40", 4, 10, 1024, 5003, 40, 0.03, 3.0, ((7, 5002),)),
     ("gemm_rows130_k16", 9, 16, 256, 3000, 130, 0.06, 3.0, ()),
     ("gemm_two_tiles_per_slice", 5, 4, 128, 128 * 300 - 5, 20, 0.2, 2.0, ((100, 38000),)),
+    # a vocabulary large enough for the 256-row GEMM tile, with a ragged last tile and a ragged last group
+    ("gemm_tall_tile_ragged_V", 8, 16, 256, 256 * 260 + 37, 100, 0.2, 2.0, ((300, 66596),)),
 ]
 
 
