@@ -379,6 +379,13 @@ ROUND_CASES = [
                                                                dup_pairs=((1000, 5000), (1997, 4009)), n_plant=2),
      None, 4, 4),
     ("13b_shape_small_V", synth.WORKLOADS["13b_b1"].with_(V=4000, D=5), None, 4, 2),
+    # the library's limits: widest beam with the deepest round that fits the node pool (3857 of 4096 nodes),
+    # largest final tree (128 nodes, mask 129 x 129), fixed depth (t = 0) so that every call runs
+    ("max_k16_D16_m128", synth.WORKLOADS["tiny"].with_(V=2000, k=16, D=16, m=128, gain=4.0), 0.0, 1, 1),
+    ("max_k16_D16_m128_gemm_rows", synth.WORKLOADS["tiny"].with_(B=2, V=2000, k=16, D=16, m=128, gain=4.0), 0.0, 1, 0),
+    # deepest round the check mask can express (31 calls)
+    ("max_D31", synth.WORKLOADS["tiny"].with_(D=31, m=64), 0.0, 1, 0),
+    ("max_D31_checked", synth.WORKLOADS["tiny"].with_(D=31, m=64, gain=12.0), 0.05, 3, 0),
 ]
 
 
