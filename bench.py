@@ -108,6 +108,7 @@ def main():
         side.synchronize()
         g.depth_hist.zero_()
         g.accept_hist.zero_()
+        g.batch_depth_hist.zero_()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         w0 = time.perf_counter()
@@ -187,7 +188,9 @@ def main():
         with open(tpath) as f:
             traffic = json.load(f).get("bytes")
 
-    us_per_depth_step = 1e6 * wall / max(1, exec_steps) if wl.B == 1 else None
+    # a depth step of the batch = one LM-head pass: a round executes as many as its deepest sequence
+    batch_steps = int(sum(d * int(c) for d, c in enumerate(g.batch_depth_hist.cpu().numpy())))
+    us_per_depth_step = 1e6 * wall / max(1, batch_steps)
     out = {
         "metric": "DDD draft rounds/sec (7B-shaped synthetic draft round, whole hot path per round)",
         "value": rounds_per_s,
@@ -206,7 +209,7 @@ def main():
                    "launch": "one hipGraph per round" if args.launch == "graph" else "stream launches",
                    "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},
                    "accept_len_hist": {str(d): int(c) for d, c in enumerate(accept_hist) if c},
-                   "executed_depth_steps": exec_steps,
+                   "executed_depth_steps": exec_steps, "executed_batch_steps": batch_steps,
                    "us_per_depth_step": us_per_depth_step,
                    "mean_depth": exec_steps / max(1, n_round_seq)},
         "roofline": ({"bound": "mfma", "achieved": achieved_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",

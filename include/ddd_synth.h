@@ -43,10 +43,11 @@ int ddd_synth_target_argmax(const ddd_synth_params* p, const ddd_state* st, cons
 int ddd_synth_next_round(int64_t* round_ctr, void* stream);
 
 /* End-of-round statistics kept on the device (no host synchronisation): for every sequence
- * depth_hist[steps[b]] += 1 and accept_hist[accept_len[b]] += 1 (device int64[32] each, either
- * may be NULL), then *round_ctr += 1. */
+ * depth_hist[steps[b]] += 1 and accept_hist[accept_len[b]] += 1, and once per round
+ * batch_depth_hist[max_b steps[b]] += 1 (the draft calls the batch executed); device int64[32]
+ * each, any may be NULL; then *round_ctr += 1. */
 int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_t* accept_len, int32_t B,
-                          int64_t* depth_hist, int64_t* accept_hist, void* stream);
+                          int64_t* depth_hist, int64_t* accept_hist, int64_t* batch_depth_hist, void* stream);
 
 /* Plain coalesced read of n_bytes (multiple of 16) into a 4-byte checksum: the practical
  * HBM read ceiling the weight stream is compared with. */

@@ -99,7 +99,7 @@ def load_library() -> C.CDLL:
         "ddd_synth_target_argmax": (C.c_int, [C.POINTER(ddd_synth_params), stp, trp, vp, vp]),
         "ddd_synth_next_round": (C.c_int, [vp, vp]),
         "ddd_synth_read_stream": (C.c_int, [vp, sz, vp, i32, vp]),
-        "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp]),
+        "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "ddd_profile_lmhead": (C.c_int, [vp, vp, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
     }
     for name, (res, args) in sig.items():
@@ -290,9 +290,10 @@ def ddd_synth_next_round(round_ctr, stream=None):
            "ddd_synth_next_round")
 
 
-def ddd_synth_round_stats(round_ctr, steps, accept_len, B, depth_hist, accept_hist, stream=None):
+def ddd_synth_round_stats(round_ctr, steps, accept_len, B, depth_hist, accept_hist, batch_depth_hist=None, stream=None):
     _check(load_library().ddd_synth_round_stats(_ptr(round_ctr), _ptr(steps), _ptr(accept_len), B, _ptr(depth_hist),
-                                                _ptr(accept_hist), current_stream() if stream is None else stream),
+                                                _ptr(accept_hist), _ptr(batch_depth_hist),
+                                                current_stream() if stream is None else stream),
            "ddd_synth_round_stats")
 
 

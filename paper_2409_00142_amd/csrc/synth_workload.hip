@@ -132,15 +132,23 @@ __global__ __launch_bounds__(256) void synth_target_kernel(TargetArgs a) {
 __global__ void next_round_kernel(int64_t* ctr) { *ctr += 1; }
 
 __global__ void round_stats_kernel(int64_t* ctr, const int32_t* steps, const int32_t* accept_len, int B,
-                                   int64_t* depth_hist, int64_t* accept_hist) {
+                                   int64_t* depth_hist, int64_t* accept_hist, int64_t* batch_depth_hist) {
   // one workgroup; integer atomics, so the totals do not depend on the order
+  __shared__ int s_max;
+  if (threadIdx.x == 0) s_max = 0;
+  __syncthreads();
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    if (steps != nullptr) atomicMax(&s_max, min(max(steps[b], 0), 31));
     if (depth_hist != nullptr && steps != nullptr)
       atomicAdd(reinterpret_cast<unsigned long long*>(depth_hist + min(max(steps[b], 0), 31)), 1ull);
     if (accept_hist != nullptr && accept_len != nullptr)
       atomicAdd(reinterpret_cast<unsigned long long*>(accept_hist + min(max(accept_len[b], 0), 31)), 1ull);
   }
-  if (threadIdx.x == 0) *ctr += 1;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (batch_depth_hist != nullptr) batch_depth_hist[s_max] += 1;   // LM-head passes this round needed
+    *ctr += 1;
+  }
 }
 
 // Each thread reads 16-byte words with a grid stride and folds them into one word.
@@ -200,10 +208,10 @@ int ddd_synth_next_round(int64_t* round_ctr, void* stream) {
 }
 
 int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_t* accept_len, int32_t B,
-                          int64_t* depth_hist, int64_t* accept_hist, void* stream) {
+                          int64_t* depth_hist, int64_t* accept_hist, int64_t* batch_depth_hist, void* stream) {
   if (round_ctr == nullptr || B < 1) return DDD_ERR_INVALID_ARG;
   hipLaunchKernelGGL(round_stats_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), round_ctr, steps,
-                     accept_len, B, depth_hist, accept_hist);
+                     accept_len, B, depth_hist, accept_hist, batch_depth_hist);
   return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
 }
 

@@ -46,6 +46,7 @@ class GpuWorkload:
         self.bonus = torch.zeros(B, dtype=torch.int32, device="cuda")
         self.depth_hist = torch.zeros(32, dtype=torch.int64, device="cuda")
         self.accept_hist = torch.zeros(32, dtype=torch.int64, device="cuda")
+        self.batch_depth_hist = torch.zeros(32, dtype=torch.int64, device="cuda")
         self.logits_dbg = torch.zeros(Dm, B * k, V, dtype=torch.float32, device="cuda") if debug else None
         self.lse_dbg = torch.zeros(Dm, B * k, dtype=torch.float32, device="cuda") if debug else None
         p = D.ddd_synth_params()
@@ -70,7 +71,7 @@ class GpuWorkload:
             D.ddd_verify_accept(self.ctx, self.tree, self.target, self.accept_len, self.accept_path, self.bonus,
                                 stream=stream)
             D.ddd_synth_round_stats(self.round_ctr, self.st_t["steps"], self.accept_len, self.wl.B, self.depth_hist,
-                                    self.accept_hist, stream=stream)
+                                    self.accept_hist, self.batch_depth_hist, stream=stream)
             return 0
         except D.DDDError as e:
             return e.code
