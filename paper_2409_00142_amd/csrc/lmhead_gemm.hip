@@ -228,14 +228,10 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
   }
 }
 
+// All work units of one workgroup for a column-tile width of 64 * BB rows.
 template <int AB, int BB, int WM>
-__global__ __launch_bounds__(128 * WM, 1) void lmhead_gemm_kernel(GemmArgs a) {
+__device__ __forceinline__ void gemm_units(const GemmArgs& a, uint16_t* lds, int n_act) {
   using C = GemmCfg<AB, BB, WM>;
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint16_t* lds = reinterpret_cast<uint16_t*>(smem_raw);   // [2][BM + BN][kGPitch]
-
-  const int n_act = *a.n_act_ptr;
-  if (n_act <= 0) return;                                  // uniform
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave % WM, wn = wave / WM;
   const int l32 = lane & 31, lh = lane >> 5;
@@ -259,6 +255,27 @@ __global__ __launch_bounds__(128 * WM, 1) void lmhead_gemm_kernel(GemmArgs a) {
       default: gemm_unit<AB, BB, WM, BB>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
     }
   }
+}
+
+// BB is the widest column tile the launch may need (64 * BB rows per workgroup).  The number of
+// active rows is only known on the device, so the kernel narrows the column tile itself when few
+// rows are left: with 64 active rows a 320-row tile would still copy 320 (repeated) rows per
+// K tile through LDS.
+template <int AB, int BB, int WM>
+__global__ __launch_bounds__(128 * WM, 1) void lmhead_gemm_kernel(GemmArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  uint16_t* lds = reinterpret_cast<uint16_t*>(smem_raw);   // [2][BM + BN][kGPitch] of the chosen width
+
+  const int n_act = *a.n_act_ptr;
+  if (n_act <= 0) return;                                  // uniform
+  if (BB >= 5 && n_act > 192)
+    gemm_units<AB, BB, WM>(a, lds, n_act);
+  else if (BB >= 3 && n_act > 128)
+    gemm_units<AB, (BB >= 3 ? 3 : BB), WM>(a, lds, n_act);
+  else if (BB >= 2 && n_act > 64)
+    gemm_units<AB, (BB >= 2 ? 2 : BB), WM>(a, lds, n_act);
+  else
+    gemm_units<AB, 1, WM>(a, lds, n_act);
 }
 
 // ---- compaction of the active rows ------------------------------------------------------------
