@@ -172,6 +172,22 @@ def main():
             gbs = 20 * w_bytes / (r0.elapsed_time(r1) * 1e-3) / 1e9
             best = gbs if best is None else max(best, gbs)
     log(f"[bench] plain read-stream kernel over W: {best:.0f} GB/s ({100 * best / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
+    # ---- register-resident MFMA loop on random operands: the practical matrix-core ceiling -------
+    mfma_ceiling = None
+    if mfma_bound:
+        fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        with torch.cuda.stream(side):
+            iters, blocks = 4000, 512          # 2 waves per SIMD; 512*4*4000*8 MFMAs of 32768 flop
+            D.ddd_synth_mfma_rate(fsink, 200, blocks, stream=side.cuda_stream)
+            m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            m0.record(side)
+            D.ddd_synth_mfma_rate(fsink, iters, blocks, stream=side.cuda_stream)
+            m1.record(side)
+            side.synchronize()
+        mfma_ceiling = blocks * 4 * iters * 8 * 32768.0 / (m0.elapsed_time(m1) * 1e-3) / 1e12
+        log(f"[bench] register-resident MFMA loop on random bf16 operands: {mfma_ceiling:.0f} TFLOP/s "
+            f"({100 * mfma_ceiling / MFMA_PEAK_TFLOPS:.1f}% of {MFMA_PEAK_TFLOPS:.0f})")
+
     # a plain device-to-device copy of W (known size: reads and writes V*H*2 bytes): the reference the
     # rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by
     with torch.cuda.stream(side):
@@ -221,7 +237,8 @@ def main():
     out["roofline"].update({"traffic": traffic, "kernel": kernel_name, "rows": n_rows,
                             "us_per_launch": mean_ms * 1e3, "us_per_launch_min": min_ms * 1e3,
                             "algorithmic_bytes_per_launch": alg_bytes, "algorithmic_flops_per_launch": alg_flops,
-                            "launches_timed": args.profile_iters, "read_stream_ceiling_GBs": best})
+                            "launches_timed": args.profile_iters, "read_stream_ceiling_GBs": best,
+                            "mfma_loop_ceiling_TFLOPs": mfma_ceiling})
     if args.cpu_budget > 0:
         log(f"[bench] timing the CPU oracle for about {args.cpu_budget:.0f} s ...")
         out["cpu_baseline"] = cpu_baseline(wl, g.W_bits, g.plant_dir_np if wl.n_plant else None, thr, args.cpu_budget)

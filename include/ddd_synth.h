@@ -53,6 +53,11 @@ int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_
  * HBM read ceiling the weight stream is compared with. */
 int ddd_synth_read_stream(const void* src, size_t n_bytes, uint32_t* sink, int32_t n_blocks, void* stream);
 
+/* Register-resident loop of bf16 32x32x16 MFMAs on pseudo-random operands, no memory traffic:
+ * n_blocks workgroups of 4 waves, each wave issues iters * 8 MFMAs (32768 flop each).  The
+ * practical matrix-core ceiling the batched LM-head GEMM is compared with.  sink: device fp32[1]. */
+int ddd_synth_mfma_rate(float* sink, int32_t iters, int32_t n_blocks, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

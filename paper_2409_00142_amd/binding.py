@@ -99,6 +99,7 @@ def load_library() -> C.CDLL:
         "ddd_synth_target_argmax": (C.c_int, [C.POINTER(ddd_synth_params), stp, trp, vp, vp]),
         "ddd_synth_next_round": (C.c_int, [vp, vp]),
         "ddd_synth_read_stream": (C.c_int, [vp, sz, vp, i32, vp]),
+        "ddd_synth_mfma_rate": (C.c_int, [vp, i32, i32, vp]),
         "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "ddd_profile_lmhead": (C.c_int, [vp, vp, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
     }
@@ -304,6 +305,11 @@ def ddd_profile_lmhead(ctx, W, hid, n_rows, iters, stream=None):
                                                     current_stream() if stream is None else stream),
            "ddd_profile_lmhead")
     return mean.value, mn.value
+
+
+def ddd_synth_mfma_rate(sink, iters, n_blocks, stream=None):
+    _check(load_library().ddd_synth_mfma_rate(_ptr(sink), iters, n_blocks, current_stream() if stream is None else stream),
+           "ddd_synth_mfma_rate")
 
 
 def ddd_synth_read_stream(src, n_bytes, sink, n_blocks, stream=None):

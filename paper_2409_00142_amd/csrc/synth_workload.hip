@@ -167,6 +167,45 @@ __global__ __launch_bounds__(256) void read_stream_kernel(const uint4* __restric
   if (acc == 0x9E3779B9u) *sink = acc;   // practically never: keeps the loads alive without a store
 }
 
+// Register-resident MFMA loop with pseudo-random bf16 operands: the matrix-core rate this chip
+// sustains on data that toggles like real data (the clock drops under it), with no memory traffic.
+typedef __attribute__((ext_vector_type(8))) __bf16 mr_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float mr_f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int mr_u32x4;
+__device__ __forceinline__ unsigned mr_mix(unsigned x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+__device__ __forceinline__ unsigned mr_pair(unsigned h) { return (h & 0x807f807fu) | 0x3f003f00u; }   // |x| in [0.5, 1)
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float* sink, int iters, unsigned seed) {
+  constexpr int NACC = 8;
+  mr_bf16x8 a[NACC], b[NACC];
+#pragma unroll
+  for (int j = 0; j < NACC; ++j) {
+    const unsigned h = mr_mix(seed + threadIdx.x * 131u + j * 977u + blockIdx.x * 7919u);
+    const mr_u32x4 ua = {mr_pair(h), mr_pair(mr_mix(h + 1)), mr_pair(mr_mix(h + 2)), mr_pair(mr_mix(h + 3))};
+    const mr_u32x4 ub = {mr_pair(mr_mix(h + 4)), mr_pair(mr_mix(h + 5)), mr_pair(mr_mix(h + 6)), mr_pair(mr_mix(h + 7))};
+    a[j] = __builtin_bit_cast(mr_bf16x8, ua);
+    b[j] = __builtin_bit_cast(mr_bf16x8, ub);
+  }
+  mr_f32x16 acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < NACC; ++i)
+      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[(i * 3 + 1) % NACC], acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[i][e];
+  if (s == 1.2345f) sink[0] = s;   // practically never: keeps the loop alive without a store
+}
+
 }  // namespace
 
 extern "C" {
@@ -219,6 +258,12 @@ int ddd_synth_read_stream(const void* src, size_t n_bytes, uint32_t* sink, int32
   if (src == nullptr || sink == nullptr || n_bytes % 16 != 0 || n_blocks < 1) return DDD_ERR_INVALID_ARG;
   hipLaunchKernelGGL(read_stream_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const uint4*>(src), n_bytes / 16, sink);
+  return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
+}
+
+int ddd_synth_mfma_rate(float* sink, int32_t iters, int32_t n_blocks, void* stream) {
+  if (sink == nullptr || iters < 1 || iters > (1 << 20) || n_blocks < 1 || n_blocks > 65536) return DDD_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(stream), sink, iters, 7u);
   return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
 }
 
