@@ -563,3 +563,42 @@ def test_free_running_rounds_agree_with_oracle(gpu):
     print(f"[info] free-running: {exact}/{total} rounds identical; differing (round, seq, gpu steps, oracle steps): "
           f"{differ}", flush=True)
     assert exact >= total - 2, differ
+
+
+def test_context_lifecycle_and_recapture(gpu):
+    """Contexts are created and destroyed repeatedly without leaking device memory; a context can capture its
+    round again (new buffers) and the replays of the second capture are still right."""
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS["tiny"].with_(B=2)
+    print("[case] context lifecycle", flush=True)
+    cfg = D.make_config(64, 4096, 32000, 10, 10, 60, 0.3)         # the largest scratch of the workloads (~100 MB)
+    for _ in range(5):                                            # lets the runtime settle what it keeps mapped
+        D.ddd_destroy(D.ddd_create(cfg))
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(40):
+        D.ddd_destroy(D.ddd_create(cfg))
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    print(f"[info] free device memory before / after 40 create-destroy cycles: {free0} / {free1}", flush=True)
+    assert free0 - free1 < 32 << 20, (free0, free1)              # nothing of the 40 x ~100 MB contexts is left
+    g = SD.GpuWorkload(wl, debug=False)
+    try:
+        side = torch.cuda.Stream()
+        g.capture(side)
+        g.set_round(3)
+        torch.cuda.synchronize()
+        g.launch(side.cuda_stream)
+        side.synchronize()
+        first = g.snapshot()
+        g.capture(side)                                           # second capture replaces the first graph
+        g.set_round(3)
+        torch.cuda.synchronize()
+        g.launch(side.cuda_stream)
+        side.synchronize()
+        _same_round(g.snapshot(), first)
+        g.set_round(3)
+        g.enqueue_round()
+        _same_round(g.snapshot(), first)
+    finally:
+        g.close()
