@@ -31,11 +31,13 @@
 extern "C" {
 #endif
 
-#define DDD_KMAX 16          /* largest beam width k                         */
-#define DDD_MMAX 128         /* largest final tree size m                    */
-#define DDD_DMAX 31          /* largest max_depth (check_mask has 32 bits)   */
-#define DDD_POOL_MAX 4096    /* largest node pool per sequence               */
-#define DDD_STREAM_ROWS 16   /* rows handled by one pass of the weight stream */
+#define DDD_KMAX 16          /* largest beam width k of the register/LDS-resident path            */
+#define DDD_KWIDE_MAX 128    /* largest beam width k at all (wide beams: Appendix, Table 2)       */
+#define DDD_MMAX 128         /* largest final tree size m                                         */
+#define DDD_DMAX 31          /* largest max_depth (check_mask has 32 bits)                        */
+#define DDD_POOL_MAX 4096    /* largest node pool per sequence for k <= DDD_KMAX                  */
+#define DDD_POOL_WIDE_MAX 65536 /* largest node pool per sequence for wider beams                 */
+#define DDD_STREAM_ROWS 16   /* rows handled by one pass of the weight stream                     */
 
 typedef enum ddd_status {
   DDD_OK = 0,
@@ -51,8 +53,9 @@ typedef enum ddd_status {
 typedef struct ddd_config {
   int32_t B;           /* independent sequences, each with its own beam and stop decision */
   int32_t H;           /* hidden size: H = 128*G*nw with G in {1,2,4} and 1 <= nw <= 10 (so H <= 5120)    */
-  int32_t V;           /* vocabulary size, k <= V < 2^24                                  */
-  int32_t k;           /* beam width w, 1..DDD_KMAX                                       */
+  int32_t V;           /* vocabulary size, k <= V < 2^24 (V < 2^18 if k > DDD_KMAX)       */
+  int32_t k;           /* beam width w, 1..DDD_KWIDE_MAX; the node pool 1 + k + (max_depth-1)*k*k must
+                          not exceed DDD_POOL_MAX (k <= DDD_KMAX) or DDD_POOL_WIDE_MAX (wider beams) */
   int32_t max_depth;   /* n: maximum number of draft-model calls per round, 1..DDD_DMAX   */
   int32_t m;           /* final tree size in draft nodes (root not counted), 1..DDD_MMAX  */
   float threshold;     /* t: continue iff sum_i exp(logprobsum[i]) >= t  (Eq. 1, t = exp(x)) */

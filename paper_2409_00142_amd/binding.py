@@ -21,9 +21,11 @@ DDD_ERR_UNIMPLEMENTED = -5
 DDD_ERR_STATE = -6
 
 DDD_KMAX = 16
+DDD_KWIDE_MAX = 128
 DDD_MMAX = 128
 DDD_DMAX = 31
 DDD_POOL_MAX = 4096
+DDD_POOL_WIDE_MAX = 65536
 
 
 class DDDError(RuntimeError):

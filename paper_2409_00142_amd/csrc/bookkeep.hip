@@ -11,12 +11,19 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   const int row = blockIdx.x * 4 + wave;
   if (row >= a.n_rows) return;                                 // wave-uniform
   if (a.row_active != nullptr && !a.row_active[row]) return;   // wave-uniform
+  if (a.nslice == 0) {   // dense format: the keys are final (any k up to DDD_KWIDE_MAX)
+    const float lse = a.part_sum[row];
+    for (int j = lane; j < a.k; j += 64) {
+      const uint64_t key = a.part_key[(size_t)row * a.k + j];
+      a.topk_token[(size_t)row * a.k + j] = key_token(key);
+      a.topk_logprob[(size_t)row * a.k + j] = key_value(key) - lse;
+    }
+    if (lane == 0) a.lse[row] = lse;
+    return;
+  }
   uint64_t key;
   float lse;
-  if (a.nslice == 0) {   // dense format: the keys are final
-    key = a.part_key[(size_t)row * a.k + min(lane, a.k - 1)];
-    lse = a.part_sum[row];
-  } else {
+  {
     uint64_t head[kHPL], second[kHPL];
     float psum[kHPL];
     const uint64_t* pk = a.part_key + (size_t)row * a.nslice * a.k;
@@ -45,7 +52,7 @@ hipError_t launch_merge(const MergeArgs& a, hipStream_t stream) {
 // too many candidate groups the whole row is scanned instead, and with too many candidates an
 // exact but slow path takes over: k passes over the row, each finding the largest key below the
 // previous winner.
-constexpr int kCandMax = 1024;
+constexpr int kCandMax = 2048;
 constexpr int kGrpListMax = 256;   // groups that may hold a candidate; more than that: the row is scanned
 
 // k-th largest of the group maxima as an ordered key (0 if there are fewer than k groups), by one
@@ -186,18 +193,19 @@ __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
   if (cnt <= kCandMax) {                                       // uniform
     // ---- exact top-k among the candidates: wave 0, k rounds of wave max over its strided share ---
     if (wave == 0) {
-      uint64_t mine = 0ull;
+      uint64_t mine[2] = {0ull, 0ull};                         // ranks lane and lane + 64
       for (int round = 0; round < a.k; ++round) {
         uint64_t loc = 0ull;
         for (int i = lane; i < cnt; i += 64) loc = umax64(loc, s_cand[i]);
         const uint64_t best = wave_max_u64(loc);
-        if (lane == round) mine = best;
+        if (lane == (round & 63)) mine[round >> 6] = best;
         for (int i = lane; i < cnt; i += 64)
           if (s_cand[i] == best) s_cand[i] = 0ull;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
       }
-      if (lane < a.k) a.part_key[(size_t)row * a.k + lane] = mine;
+      if (lane < a.k) a.part_key[(size_t)row * a.k + lane] = mine[0];
+      if (lane + 64 < a.k) a.part_key[(size_t)row * a.k + lane + 64] = mine[1];
       if (lane == 0) a.part_sum[row] = lse;
     }
   } else {

@@ -84,6 +84,20 @@ BeamArgs beam_args(const ddd_ctx* c, const ddd_state* st, int step) {
   return a;
 }
 
+WideStepArgs wide_args(const ddd_ctx* c, const BeamArgs& beam) {
+  WideStepArgs w;
+  w.beam = beam;
+  w.part_key = nullptr;
+  w.part_lse = nullptr;
+  w.lse_dbg = nullptr;
+  std::memset(&w.tree, 0, sizeof(w.tree));
+  w.m = c->cfg.m;
+  w.do_select = 0;
+  w.do_stop = 0;
+  w.steps_done = 0;
+  return w;
+}
+
 // MFMA GEMM over the rows listed in the context's row list, logits into `out`.
 int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, int max_rows, float* out, hipStream_t s) {
   GemmArgs g;
@@ -102,13 +116,15 @@ int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, int max_rows, float
 }
 
 // Slices of the path that handles n_rows rows (0 = dense results of the GEMM path).
-int slices_for(const ddd_ctx* c, int n_rows) { return n_rows <= DDD_STREAM_ROWS ? c->nslice : 0; }
+// Wide beams always take the GEMM path: the weight stream keeps at most DDD_KMAX keys per row.
+bool gemm_path(const ddd_ctx* c, int n_rows) { return n_rows > DDD_STREAM_ROWS || c->cfg.k > DDD_KMAX; }
+int slices_for(const ddd_ctx* c, int n_rows) { return gemm_path(c, n_rows) ? 0 : c->nslice; }
 
 // LM head over n_rows rows, partials into the context scratch: the weight stream for up to
 // DDD_STREAM_ROWS rows, the MFMA GEMM over the compacted active rows otherwise.
 int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const uint8_t* row_active, float* logits_dbg,
                    hipStream_t s) {
-  if (n_rows > DDD_STREAM_ROWS) {
+  if (gemm_path(c, n_rows)) {
     float* out = logits_dbg ? logits_dbg : c->logits;
     DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
     int rc = enqueue_gemm(c, W, hid, n_rows, out, s);
@@ -168,8 +184,9 @@ const char* ddd_last_hip_error(void) { return g_hip_err; }
 int ddd_config_validate(const ddd_config* cfg) {
   if (cfg == nullptr) return DDD_ERR_INVALID_ARG;
   if (cfg->B < 1 || cfg->B > 4096) return DDD_ERR_INVALID_ARG;
-  if (cfg->k < 1 || cfg->k > DDD_KMAX) return DDD_ERR_INVALID_ARG;
-  if (cfg->V < cfg->k || cfg->V >= (1 << 24)) return DDD_ERR_INVALID_ARG;
+  if (cfg->k < 1 || cfg->k > DDD_KWIDE_MAX) return DDD_ERR_INVALID_ARG;
+  const bool wide = cfg->k > DDD_KMAX;
+  if (cfg->V < cfg->k || cfg->V >= (wide ? (1 << 18) : (1 << 24))) return DDD_ERR_INVALID_ARG;
   if (cfg->max_depth < 1 || cfg->max_depth > DDD_DMAX) return DDD_ERR_INVALID_ARG;
   if (cfg->m < 1 || cfg->m > DDD_MMAX) return DDD_ERR_INVALID_ARG;
   if (!(cfg->threshold >= 0.0f)) return DDD_ERR_INVALID_ARG;   // also rejects NaN
@@ -177,7 +194,7 @@ int ddd_config_validate(const ddd_config* cfg) {
   int G, nw;
   if (cfg->H < 128 || !pick_split(cfg->H, &G, &nw)) return DDD_ERR_INVALID_ARG;
   const long long nmax = 1LL + cfg->k + (long long)(cfg->max_depth - 1) * cfg->k * cfg->k;
-  if (nmax > DDD_POOL_MAX) return DDD_ERR_INVALID_ARG;
+  if (nmax > (wide ? DDD_POOL_WIDE_MAX : DDD_POOL_MAX)) return DDD_ERR_INVALID_ARG;
   return DDD_OK;
 }
 
@@ -188,9 +205,9 @@ size_t ddd_pool_capacity(const ddd_config* cfg) {
 
 size_t ddd_scratch_bytes(const ddd_config* cfg) {
   if (ddd_config_validate(cfg) != DDD_OK) return 0;
-  const size_t rows = (size_t)cfg->B * cfg->k, max_slices = 512;
+  const size_t rows = (size_t)cfg->B * cfg->k, max_slices = (cfg->k > DDD_KMAX) ? 1 : 512;
   size_t n = rows * max_slices * cfg->k * sizeof(uint64_t) + rows * max_slices * sizeof(float) + rows * 4 + 4;
-  if (rows > DDD_STREAM_ROWS)   // logits and per-group statistics of the GEMM path
+  if (rows > DDD_STREAM_ROWS || cfg->k > DDD_KMAX)   // logits and per-group statistics of the GEMM path
     n += rows * (size_t)cfg->V * sizeof(float) + 2 * rows * (size_t)(((cfg->V + 63) / 64 + 3) & ~3) * sizeof(float);
   return n;
 }
@@ -228,16 +245,17 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->grp_sum = nullptr;
   c->ngrp = ((cfg->V + 63) / 64 + 3) & ~3;
   const size_t rows = (size_t)cfg->B * cfg->k;
-  const size_t ns = (size_t)c->nslice;
+  const size_t ns = (cfg->k > DDD_KMAX) ? 1 : (size_t)c->nslice;   // wide beams only use the dense format
   hipError_t e = hipMalloc(&c->part_key, rows * ns * cfg->k * sizeof(uint64_t));
   if (e == hipSuccess) e = hipMalloc(&c->part_sum, rows * ns * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(&c->row_list, rows * sizeof(int32_t));
   if (e == hipSuccess) e = hipMalloc(&c->n_act, sizeof(int32_t));
-  if (e == hipSuccess && rows > DDD_STREAM_ROWS) {
+  if (e == hipSuccess && (rows > DDD_STREAM_ROWS || cfg->k > DDD_KMAX)) {
     e = hipMalloc(&c->logits, rows * (size_t)cfg->V * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&c->grp_max, rows * (size_t)c->ngrp * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&c->grp_sum, rows * (size_t)c->ngrp * sizeof(float));
     if (e == hipSuccess) e = prepare_lmhead_gemm();
+    if (e == hipSuccess && cfg->k > DDD_KMAX) e = prepare_wide();
   }
   if (e != hipSuccess) {
     if (c->logits) (void)hipFree(c->logits);
@@ -277,7 +295,7 @@ int ddd_profile_lmhead(ddd_ctx* c, const void* W, const void* hid, int32_t n_row
     return DDD_ERR_INVALID_ARG;
   if (n_rows < 1 || n_rows > c->cfg.B * c->cfg.k || iters < 1 || iters > 4096) return DDD_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool gemm = n_rows > DDD_STREAM_ROWS;
+  const bool gemm = gemm_path(c, n_rows);
   if (gemm) DDD_HIP(launch_build_row_list(nullptr, n_rows, c->row_list, c->n_act, s));
   std::vector<hipEvent_t> ev(2 * (size_t)iters, nullptr);
   int rc = DDD_OK;
@@ -352,6 +370,12 @@ int ddd_beam_select(ddd_ctx* c, int32_t step, const int32_t* topk_token, const f
   BeamArgs a = beam_args(c, st, step);
   a.topk_token = topk_token;
   a.topk_logprob = topk_logprob;
+  if (c->cfg.k > DDD_KMAX) {
+    WideStepArgs w = wide_args(c, a);
+    w.do_select = 1;
+    DDD_HIP(launch_step_wide(w, static_cast<hipStream_t>(stream)));
+    return DDD_OK;
+  }
   DDD_HIP(launch_beam_select(a, static_cast<hipStream_t>(stream)));
   return DDD_OK;
 }
@@ -360,6 +384,13 @@ int ddd_depth_continue(ddd_ctx* c, int32_t steps_done, ddd_state* st, void* stre
   if (c == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
   if (steps_done < 1 || steps_done > c->cfg.max_depth) return DDD_ERR_INVALID_ARG;
   BeamArgs a = beam_args(c, st, steps_done - 1);
+  if (c->cfg.k > DDD_KMAX) {
+    WideStepArgs w = wide_args(c, a);
+    w.do_stop = 1;
+    w.steps_done = steps_done;
+    DDD_HIP(launch_step_wide(w, static_cast<hipStream_t>(stream)));
+    return DDD_OK;
+  }
   DDD_HIP(launch_depth_continue(a, steps_done, static_cast<hipStream_t>(stream)));
   return DDD_OK;
 }
@@ -386,6 +417,17 @@ int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd
   a.m = c->cfg.m;
   int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, s);
   if (rc != DDD_OK) return rc;
+  if (c->cfg.k > DDD_KMAX) {
+    WideStepArgs w = wide_args(c, a.beam);
+    w.part_key = c->part_key;
+    w.part_lse = c->part_sum;
+    w.lse_dbg = lse_dbg;
+    w.tree = a.tree;
+    w.do_select = 1;
+    w.do_stop = 1;
+    DDD_HIP(launch_step_wide(w, s));
+    return DDD_OK;
+  }
   DDD_HIP(launch_step_bookkeep(a, s));
   return DDD_OK;
 }
@@ -399,7 +441,10 @@ int ddd_tree_finalize(ddd_ctx* c, const ddd_state* st, ddd_tree* out, void* stre
   a.k = c->cfg.k;
   a.m = c->cfg.m;
   a.nmax = c->nmax;
-  DDD_HIP(launch_tree_finalize(a, static_cast<hipStream_t>(stream)));
+  if (c->nmax > DDD_POOL_MAX)
+    DDD_HIP(launch_tree_finalize_wide(a, static_cast<hipStream_t>(stream)));
+  else
+    DDD_HIP(launch_tree_finalize(a, static_cast<hipStream_t>(stream)));
   return DDD_OK;
 }
 

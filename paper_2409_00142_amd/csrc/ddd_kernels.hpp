@@ -84,6 +84,24 @@ struct StreamArgs {
 // G = 128-wide K groups per streaming wave (1, 2 or 4); H == 128 * G * nw.
 hipError_t launch_lmhead_stream(const StreamArgs& a, int G, int nslice, hipStream_t stream);
 
+// ---- wide beams, DDD_KMAX < k <= DDD_KWIDE_MAX (wide.hip) ---------------------------------------
+// One workgroup per sequence; the k*k candidate keys sit in LDS and the new beam is found by a
+// radix select.  Candidates come either as dense keys + lse (rows through the GEMM path) or as
+// the top-k token / logprob arrays of the stand-alone call.
+struct WideStepArgs {
+  BeamArgs beam;
+  const uint64_t* part_key;   // [rows][k] final keys in order, or null: use beam.topk_token / topk_logprob
+  const float* part_lse;      // [rows] lse of each row (with part_key)
+  float* lse_dbg;             // [rows] or null
+  ddd_tree tree;              // tree.mask == null: do not build the final tree here
+  int m;
+  int do_select;              // run the beam update
+  int do_stop;                // run the stop test (steps_done = beam.step + 1 after a beam update)
+  int steps_done;             // draft calls made so far, for a stop test without a beam update
+};
+hipError_t prepare_wide();    // once per process: enables the kernels' LDS sizes
+hipError_t launch_step_wide(const WideStepArgs& a, hipStream_t stream);
+
 struct ResetArgs {
   ddd_state st;
   const int32_t* root_token;  // [B] or null
@@ -98,6 +116,7 @@ struct FinalizeArgs {
   int B, k, m, nmax;
 };
 hipError_t launch_tree_finalize(const FinalizeArgs& a, hipStream_t stream);
+hipError_t launch_tree_finalize_wide(const FinalizeArgs& a, hipStream_t stream);   // pools beyond DDD_POOL_MAX
 
 struct VerifyArgs {
   ddd_tree tree;

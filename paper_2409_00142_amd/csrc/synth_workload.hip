@@ -88,26 +88,40 @@ struct TargetArgs {
   int32_t* out;
 };
 
-// grid: B; block 256.  The rank-0 / rank-1 children of every pool node (its two lowest-id
-// children) are first scattered into LDS tables, then thread i handles tree index i.
+// grid: B; block 256.  The rank-0 / rank-1 children (the two lowest-id children) of every tree
+// node are found by one pass over the pool: a node of sibling rank 0 or 1 looks its parent up in
+// the sorted list of selected ids.  Then thread i handles tree index i.
 __global__ __launch_bounds__(256) void synth_target_kernel(TargetArgs a) {
-  __shared__ int kid0[DDD_POOL_MAX], kid1[DDD_POOL_MAX];
+  __shared__ int sel[DDD_MMAX + 1], kid0[DDD_MMAX + 1], kid1[DDD_MMAX + 1];
   const int b = blockIdx.x, tid = threadIdx.x;
   const int k = a.p.cfg.k, m = a.p.cfg.m, T = m + 1;
   const size_t nmax = 1 + (size_t)k + (size_t)(a.p.cfg.max_depth - 1) * k * k;
   const int32_t* ppar = a.st.pool_parent + (size_t)b * nmax;
   const int32_t* ptok = a.st.pool_token + (size_t)b * nmax;
-  const int n_nodes = min(a.st.n_nodes[b], DDD_POOL_MAX);
-  const int n_sel = a.tree.n_sel[b];
-  for (int c = tid; c < n_nodes; c += 256) {
-    kid0[c] = -1;
-    kid1[c] = -1;
+  const int n_nodes = min(a.st.n_nodes[b], (int)nmax);
+  const int n_sel = min(a.tree.n_sel[b], m);
+  for (int i = tid; i <= n_sel; i += 256) {
+    sel[i] = (i == 0) ? 0 : a.tree.sel_node[(size_t)b * m + i - 1];   // ascending ids
+    kid0[i] = -1;
+    kid1[i] = -1;
   }
   __syncthreads();
   for (int c = 1 + tid; c < n_nodes; c += 256) {
     const int j = (c <= k) ? (c - 1) : ((c - 1 - k) % k);   // rank of node c among its siblings
-    if (j == 0) kid0[ppar[c]] = c;
-    if (j == 1) kid1[ppar[c]] = c;
+    if (j > 1) continue;
+    const int p = ppar[c];
+    int lo = 0, hi = n_sel;                                  // binary search of p in sel[0..n_sel]
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (sel[mid] < p)
+        lo = mid + 1;
+      else
+        hi = mid;
+    }
+    if (sel[lo] == p) {
+      if (j == 0) kid0[lo] = c;
+      else kid1[lo] = c;
+    }
   }
   __syncthreads();
   const int i = tid;
@@ -116,16 +130,16 @@ __global__ __launch_bounds__(256) void synth_target_kernel(TargetArgs a) {
     a.out[(size_t)b * T + i] = -1;
     return;
   }
-  const int node = (i == 0) ? 0 : a.tree.sel_node[(size_t)b * m + i - 1];
+  const int node = sel[i];
   const uint64_t skey = stream_key(a.p.seed, b, *a.p.round_ctr);
   const uint64_t tk = mix64(skey ^ mix64(kTarget + (uint64_t)node));
   const uint32_t u = (uint32_t)(tk >> 40);
   const int uni = (int)((tk & 0xFFFFFFFFull) % (uint64_t)a.p.cfg.V);
   int out = uni;
-  if (u < kU24_070 && kid0[node] >= 0)
-    out = ptok[kid0[node]];
-  else if (u >= kU24_070 && u < kU24_085 && kid1[node] >= 0)
-    out = ptok[kid1[node]];
+  if (u < kU24_070 && kid0[i] >= 0)
+    out = ptok[kid0[i]];
+  else if (u >= kU24_070 && u < kU24_085 && kid1[i] >= 0)
+    out = ptok[kid1[i]];
   a.out[(size_t)b * T + i] = out;
 }
 

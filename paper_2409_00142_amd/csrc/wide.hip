@@ -1,0 +1,277 @@
+// Wide beams (DDD_KMAX < k <= DDD_KWIDE_MAX): beam update, stop test and final tree of one
+// sequence by one workgroup (Appendix, Table 2: draft speed against beam width).
+//
+// With up to 128 x 128 candidates per draft call and tens of thousands of pool nodes nothing fits
+// in registers any more: the k*k candidate keys (score desc, token asc, flat index asc) are built
+// in LDS and the k-th largest is found by a radix select (8-bit digits from the top: histogram in
+// LDS, the digit holding the wanted rank narrows the prefix); the keys at or above it are the new
+// beam, sorted by a small bitonic network.  The final rerank selects the m best pool nodes the
+// same way with keys computed on the fly from the pool scores in global memory (L2-resident).
+// Everything else (Eq. 1 in fp64 in index order, parents, ancestor rows, mask) is as for narrow
+// beams.
+#include "bookkeep_device.hpp"
+#include "tree_device.hpp"
+
+namespace ddd {
+
+constexpr int kKW = DDD_KWIDE_MAX;
+constexpr int kWideThreads = 1024;
+constexpr int kFlatBits = 14;                      // k*k <= 16384 flat indices
+constexpr uint32_t kFlatMask = (1u << kFlatBits) - 1u;
+constexpr uint32_t kTokMaskW = (1u << (32 - kFlatBits)) - 1u;   // tokens below 2^18
+
+__device__ __forceinline__ uint64_t wide_beam_key(float score, int token, int flat) {
+  const uint32_t lo = ((kTokMaskW - (uint32_t)token) << kFlatBits) | (kFlatMask - (uint32_t)flat);
+  return ((uint64_t)ord32(score) << 32) | lo;
+}
+__device__ __forceinline__ int wide_key_flat(uint64_t key) { return (int)(kFlatMask - ((uint32_t)key & kFlatMask)); }
+__device__ __forceinline__ int wide_key_token(uint64_t key) {
+  return (int)(kTokMaskW - (((uint32_t)key >> kFlatBits) & kTokMaskW));
+}
+
+struct WideSmem {
+  unsigned hist[256];
+  int digit, rem, cnt, stopped;
+  float lps_old[kKW];
+  int node_old[kKW];
+  uint64_t sel[kKW];
+  double e[kKW];
+  TreeEmitSmem te;
+};
+
+// The key of rank `want` (0-based, descending) among n distinct keys key_of(0..n-1), n > want.
+// Every thread of the block calls it with the same arguments; the result is uniform.
+template <class KeyFn>
+__device__ __forceinline__ uint64_t block_select_kth(int n, int want, KeyFn key_of, WideSmem& sm, int tid, int nthr) {
+  uint64_t prefix = 0ull;
+  int rem = want;
+  for (int shift = 56; shift >= 0; shift -= 8) {
+    for (int i = tid; i < 256; i += nthr) sm.hist[i] = 0u;
+    __syncthreads();
+    const uint64_t hi_mask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
+    for (int i = tid; i < n; i += nthr) {
+      const uint64_t key = key_of(i);
+      if ((key & hi_mask) == prefix) atomicAdd(&sm.hist[(unsigned)(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {   // wave 0: lane l owns digits 255-4l .. 252-4l; running count from the top digit down
+      const int lane = tid;
+      unsigned h[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) h[q] = sm.hist[255 - 4 * lane - q];
+      const unsigned s = h[0] + h[1] + h[2] + h[3];
+      unsigned incl = s;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const unsigned t = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += t;
+      }
+      const unsigned excl = incl - s;
+      if ((unsigned)rem >= excl && (unsigned)rem < incl) {   // exactly one lane
+        unsigned c = excl;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if ((unsigned)rem >= c && (unsigned)rem < c + h[q]) {
+            sm.digit = 255 - 4 * lane - q;
+            sm.rem = (int)((unsigned)rem - c);
+          }
+          c += h[q];
+        }
+      }
+    }
+    __syncthreads();
+    prefix |= (uint64_t)(unsigned)sm.digit << shift;
+    rem = sm.rem;
+  }
+  return prefix;
+}
+
+// Descending bitonic sort of sm.sel[0..127] (unused slots hold 0) by the first 64 threads.
+__device__ __forceinline__ void sort_sel_desc(WideSmem& sm, int tid) {
+  for (int size = 2; size <= kKW; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      if (tid < kKW / 2) {
+        const int pos = 2 * stride * (tid / stride) + (tid % stride);
+        const int partner = pos + stride;
+        const bool desc = ((pos & size) == 0);
+        const uint64_t x = sm.sel[pos], y = sm.sel[partner];
+        if ((x < y) == desc) {
+          sm.sel[pos] = y;
+          sm.sel[partner] = x;
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// Final tree for a pool of any size: radix select of the m best rerank keys, then the common part.
+__device__ __forceinline__ void tree_finalize_wide_block(const ddd_state& st, const ddd_tree& tree, int b, int m, int nmax,
+                                                         int tid, int nthr, WideSmem& sm) {
+  const int N = st.n_nodes[b] - 1;
+  const int m_eff = min(m, N);
+  const float* psc = st.pool_score + (size_t)b * nmax;
+  auto key_of = [&](int i) { return rerank_key(psc[i + 1], i + 1); };
+  uint64_t kth = 0ull;                       // every key is at least 1
+  if (m_eff < N) kth = block_select_kth(N, m_eff - 1, key_of, sm, tid, nthr);
+  if (tid == 0) sm.cnt = 0;
+  __syncthreads();
+  for (int i = tid; i < N; i += nthr)
+    if (key_of(i) >= kth) {
+      const int p = atomicAdd(&sm.cnt, 1);
+      if (p < kTreeMax) sm.te.pick[p] = i + 1;   // exactly m_eff of them: keys are distinct
+    }
+  __syncthreads();
+  tree_emit_block(st, tree, b, m, m_eff, nmax, tid, nthr, sm.te);
+}
+
+__global__ __launch_bounds__(kWideThreads) void step_wide_kernel(WideStepArgs a) {
+  extern __shared__ __align__(16) unsigned char wsm_raw[];
+  const BeamArgs& g = a.beam;
+  const int b = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
+  const int k = g.k, step = g.step;
+  uint64_t* keys = reinterpret_cast<uint64_t*>(wsm_raw);                       // [k*k]
+  WideSmem& sm = *reinterpret_cast<WideSmem*>(wsm_raw + (((size_t)k * k * 8 + 15) & ~(size_t)15));
+  if (!g.st.active[b]) return;               // uniform over the workgroup
+
+  float* lps = g.st.logprobsum + (size_t)b * k;
+  int32_t* bnode = g.st.beam_node + (size_t)b * k;
+  int32_t* btok = g.st.beam_token + (size_t)b * k;
+  int32_t* bslot = g.st.beam_parent_slot + (size_t)b * k;
+  int32_t* ptok = g.st.pool_token + (size_t)b * g.nmax;
+  int32_t* ppar = g.st.pool_parent + (size_t)b * g.nmax;
+  int32_t* pdep = g.st.pool_depth + (size_t)b * g.nmax;
+  float* psc = g.st.pool_score + (size_t)b * g.nmax;
+  const bool from_keys = (a.part_key != nullptr);
+  const size_t row0 = (step == 0) ? (size_t)b : (size_t)b * k;
+  int steps_done = a.steps_done;
+
+  if (a.do_select) {
+    steps_done = step + 1;
+    if (step == 0) {
+      // the prompt call: nodes 1..k in rank order are the first beam
+      for (int j = tid; j < k; j += nthr) {
+        int t;
+        float s;
+        if (from_keys) {
+          const uint64_t key = a.part_key[row0 * k + j];
+          t = key_token(key);
+          s = key_value(key) - a.part_lse[row0];
+        } else {
+          t = g.topk_token[row0 * k + j];
+          s = g.topk_logprob[row0 * k + j];
+        }
+        const int nid = 1 + j;
+        ptok[nid] = t;
+        ppar[nid] = 0;
+        pdep[nid] = 1;
+        psc[nid] = s;
+        bnode[j] = nid;
+        btok[j] = t;
+        bslot[j] = 0;
+        lps[j] = s;
+      }
+      if (tid == 0) {
+        g.st.n_nodes[b] = 1 + k;
+        g.st.steps[b] = 1;
+        if (a.lse_dbg != nullptr && from_keys) a.lse_dbg[row0] = a.part_lse[row0];
+      }
+    } else {
+      const int base = 1 + k + (step - 1) * k * k;
+      for (int i = tid; i < k; i += nthr) {
+        sm.lps_old[i] = lps[i];
+        sm.node_old[i] = bnode[i];
+        if (a.lse_dbg != nullptr && from_keys) a.lse_dbg[row0 + i] = a.part_lse[row0 + i];
+      }
+      __syncthreads();
+      for (int f = tid; f < k * k; f += nthr) {
+        const int i = f / k, j = f - i * k;
+        int t;
+        float lp;
+        if (from_keys) {
+          const uint64_t key = a.part_key[(row0 + i) * k + j];
+          t = key_token(key);
+          lp = key_value(key) - a.part_lse[row0 + i];
+        } else {
+          t = g.topk_token[(row0 + i) * k + j];
+          lp = g.topk_logprob[(row0 + i) * k + j];
+        }
+        const float sc = __fadd_rn(sm.lps_old[i], lp);
+        ptok[base + f] = t;
+        ppar[base + f] = sm.node_old[i];
+        pdep[base + f] = step + 1;
+        psc[base + f] = sc;
+        keys[f] = wide_beam_key(sc, t, f);
+      }
+      __syncthreads();
+      const uint64_t kth = block_select_kth(k * k, k - 1, [&](int i) { return keys[i]; }, sm, tid, nthr);
+      for (int i = tid; i < kKW; i += nthr) sm.sel[i] = 0ull;
+      if (tid == 0) sm.cnt = 0;
+      __syncthreads();
+      for (int f = tid; f < k * k; f += nthr)
+        if (keys[f] >= kth) {
+          const int p = atomicAdd(&sm.cnt, 1);
+          if (p < kKW) sm.sel[p] = keys[f];     // exactly k of them: keys are distinct
+        }
+      __syncthreads();
+      sort_sel_desc(sm, tid);
+      for (int r = tid; r < k; r += nthr) {
+        const uint64_t key = sm.sel[r];
+        const int f = wide_key_flat(key);
+        bnode[r] = base + f;
+        btok[r] = wide_key_token(key);
+        bslot[r] = f / k;
+        lps[r] = key_value(key);
+      }
+      if (tid == 0) {
+        g.st.n_nodes[b] = base + k * k;
+        g.st.steps[b] = step + 1;
+      }
+    }
+    __syncthreads();   // the new beam is visible to the block
+  }
+
+  if (tid == 0) sm.stopped = 0;
+  if (a.do_stop) {
+    for (int i = tid; i < k; i += nthr) sm.e[i] = exp((double)lps[i]);
+    __syncthreads();
+    if (tid == 0) {
+      double P = 0.0;
+      for (int i = 0; i < k; ++i) P += sm.e[i];   // index order
+      bool cont = steps_done < g.D;
+      if (cont && ((g.check_mask >> steps_done) & 1u) && P < (double)g.threshold) cont = false;
+      g.st.conf[b] = P;
+      g.st.active[b] = cont ? 1 : 0;
+      sm.stopped = cont ? 0 : 1;
+    }
+    __syncthreads();
+    const uint8_t on = sm.stopped ? 0 : 1;
+    for (int i = tid; i < k; i += nthr) g.st.row_active[(size_t)b * k + i] = on;
+  }
+  __syncthreads();   // also orders the pool writes before the reads below
+  if (a.tree.mask != nullptr && sm.stopped) tree_finalize_wide_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm);
+}
+
+__global__ __launch_bounds__(kWideThreads) void tree_finalize_wide_kernel(FinalizeArgs a) {
+  __shared__ WideSmem sm;
+  tree_finalize_wide_block(a.st, a.tree, blockIdx.x, a.m, a.nmax, threadIdx.x, blockDim.x, sm);
+}
+
+static size_t wide_lds_bytes(int k) { return (((size_t)k * k * 8 + 15) & ~(size_t)15) + sizeof(WideSmem); }
+
+hipError_t prepare_wide() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&step_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)wide_lds_bytes(kKW));
+}
+
+hipError_t launch_step_wide(const WideStepArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(step_wide_kernel, dim3(a.beam.B), dim3(kWideThreads), wide_lds_bytes(a.beam.k), stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_tree_finalize_wide(const FinalizeArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(tree_finalize_wide_kernel, dim3(a.B), dim3(kWideThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace ddd

@@ -46,6 +46,12 @@ LM_CASES = [
     ("gemm_two_tiles_per_slice", 5, 4, 128, 128 * 300 - 5, 20, 0.2, 2.0, ((100, 38000),)),
     # a vocabulary large enough for the 256-row GEMM tile, with a ragged last tile and a ragged last group
     ("gemm_tall_tile_ragged_V", 8, 16, 256, 256 * 260 + 37, 100, 0.2, 2.0, ((300, 66596),)),
+    # wide beams: always the GEMM path, one row included; k above 64 (two keys per lane in the row reduction);
+    # fewer groups than k (every element is a candidate: the exact slow path)
+    ("wide_k100_one_row", 1, 100, 256, 8000, 1, 0.2, 2.0, ()),
+    ("wide_k100_rows100", 1, 100, 256, 8000, 100, 0.2, 2.0, ((10, 7000),)),
+    ("wide_k40_ragged_V", 2, 40, 512, 5003, 70, 0.1, 2.0, ()),
+    ("wide_k128_few_groups", 1, 128, 256, 3000, 128, 0.2, 2.0, ()),
 ]
 
 
@@ -208,11 +214,22 @@ def _upload_f32(torch, a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-@pytest.mark.parametrize("wname,rnd,thr", [("tiny", 0, 0.0), ("tiny", 3, 0.35), ("tiny", 7, 0.35)])
+# wide beams (k > 16): the LDS radix-select path; pools beyond 4096 nodes use the wide final tree as well
+WIDE = {
+    "wide_k20": synth.WORKLOADS["tiny"].with_(V=3000, k=20, D=4, m=60, gain=4.0),
+    "wide_k50": synth.WORKLOADS["tiny"].with_(V=4000, k=50, D=4, m=128, gain=4.0),
+    "wide_k100": synth.WORKLOADS["tiny"].with_(V=6000, k=100, D=3, m=80, gain=4.0),
+    "wide_k128": synth.WORKLOADS["tiny"].with_(V=5000, k=128, D=3, m=128, gain=4.0),
+}
+BOOK_CASES = [("tiny", 0, 0.0), ("tiny", 3, 0.35), ("tiny", 7, 0.35), ("wide_k20", 1, 0.0), ("wide_k50", 0, 0.0),
+              ("wide_k50", 2, 0.5), ("wide_k100", 0, 0.0), ("wide_k128", 1, 0.0)]
+
+
+@pytest.mark.parametrize("wname,rnd,thr", BOOK_CASES, ids=[f"{c[0]}-r{c[1]}-t{c[2]}" for c in BOOK_CASES])
 def test_bookkeeping_calls_teacher_forced(gpu, wname, rnd, thr):
     torch, D, SD = gpu
-    wl = synth.WORKLOADS[wname]
-    print(f"[case] bookkeeping {wname} round={rnd} t={thr}", flush=True)
+    wl = WIDE[wname] if wname in WIDE else synth.WORKLOADS[wname]
+    print(f"[case] bookkeeping {wname} round={rnd} t={thr} k={wl.k}", flush=True)
     W_bits = synth.make_lm_head(wl.V, wl.H, wl.sigma_w, wl.seed)
     res, tgt, (o_len, o_path, o_bonus) = SR.oracle_round(wl, W_bits, None, 0, rnd, threshold=thr)
     k, Dm, m = wl.k, wl.D, wl.m
@@ -386,6 +403,12 @@ ROUND_CASES = [
     # deepest round the check mask can express (31 calls)
     ("max_D31", synth.WORKLOADS["tiny"].with_(D=31, m=64), 0.0, 1, 0),
     ("max_D31_checked", synth.WORKLOADS["tiny"].with_(D=31, m=64, gain=12.0), 0.05, 3, 0),
+    # wide beams through the whole round (LM head on the GEMM path even for one row)
+    ("wide_k20", WIDE["wide_k20"], None, 3, 2),
+    ("wide_k20_t0_b2", WIDE["wide_k20"].with_(B=2), 0.0, 1, 1),
+    ("wide_k50", WIDE["wide_k50"], 0.2, 2, 1),
+    ("wide_k100_t0", WIDE["wide_k100"], 0.0, 1, 1),
+    ("wide_k128_b2", WIDE["wide_k128"].with_(B=2), 0.1, 1, 0),
 ]
 
 
