@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="7b_b1", help="synthetic workload name (see synth/inputs.py)")
     ap.add_argument("--threshold", type=float, default=None, help="stop threshold t (default: the workload's)")
+    ap.add_argument("--k", type=int, default=None, help="beam width override (wide beams above 16; Appendix, Table 2)")
+    ap.add_argument("--max-depth", type=int, default=None, help="maximum number of draft calls override")
+    ap.add_argument("--m", type=int, default=None, help="final tree size override")
     ap.add_argument("--mode", choices=["default", "paper", "strict", "eagle2"], default="default",
                     help="paper: the paper's setting n=11, S={5,7,9}, x=-0.3 (t=exp(x)); strict: the same with the "
                          "test after every call; eagle2: fixed depth 6, no stop test (Section 3.1, Table 1 baselines)")
@@ -86,6 +89,9 @@ def main():
         wl = wl.with_(D=11, check_mask=0xFFFFFFFF, threshold=float(np.float32(np.exp(-0.3))))
     elif args.mode == "eagle2":   # EAGLE-2's fixed depth: 6 calls, never stops early
         wl = wl.with_(D=6, threshold=0.0)
+    over = {n: v for n, v in (("k", args.k), ("D", args.max_depth), ("m", args.m)) if v is not None}
+    if over:
+        wl = wl.with_(**over)
     thr = wl.threshold if args.threshold is None else args.threshold
     log(f"[bench] workload {wl.name}: B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} m={wl.m} t={thr} gain={wl.gain}")
     t0 = time.perf_counter()

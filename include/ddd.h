@@ -53,7 +53,7 @@ typedef enum ddd_status {
 typedef struct ddd_config {
   int32_t B;           /* independent sequences, each with its own beam and stop decision */
   int32_t H;           /* hidden size: H = 128*G*nw with G in {1,2,4} and 1 <= nw <= 10 (so H <= 5120)    */
-  int32_t V;           /* vocabulary size, k <= V < 2^24 (V < 2^18 if k > DDD_KMAX)       */
+  int32_t V;           /* vocabulary size, k <= V < 2^24; V <= 2^17 if B*k > DDD_STREAM_ROWS or k > DDD_KMAX */
   int32_t k;           /* beam width w, 1..DDD_KWIDE_MAX; the node pool 1 + k + (max_depth-1)*k*k must
                           not exceed DDD_POOL_MAX (k <= DDD_KMAX) or DDD_POOL_WIDE_MAX (wider beams) */
   int32_t max_depth;   /* n: maximum number of draft-model calls per round, 1..DDD_DMAX   */

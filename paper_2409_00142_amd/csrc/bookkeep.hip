@@ -87,6 +87,26 @@ __device__ __forceinline__ uint32_t kth_largest_group_max(const float* gmax, int
   return T;
 }
 
+// Descending bitonic sort of n2 (a power of two) 64-bit keys in LDS by the whole block.
+__device__ __forceinline__ void block_sort_desc(uint64_t* keys, int n2, int tid, int nthr) {
+  for (int size = 2; size <= n2; size <<= 1)
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int p = tid; p < (n2 >> 1); p += nthr) {
+        const int pos = 2 * stride * (p / stride) + (p % stride);
+        const int partner = pos + stride;
+        const bool desc = ((pos & size) == 0);
+        const uint64_t x = keys[pos], y = keys[partner];
+        if ((x < y) == desc) {
+          keys[pos] = y;
+          keys[partner] = x;
+        }
+      }
+      __syncthreads();
+    }
+}
+
+constexpr int kSortFromK = 17;   // beams wider than DDD_KMAX: sorts replace the k rounds of wave maxima
+
 __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
   __shared__ uint64_t s_cand[kCandMax];
   __shared__ float s_red[8];
@@ -115,7 +135,15 @@ __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
     s_cnt = 0;
     s_ng = 0;
   }
-  if (wave == 0) {
+  if (a.k >= kSortFromK) {
+    // wide beams: sort the group maxima (at most 2048) and read off the k-th
+    int n2 = 64;
+    while (n2 < ngrp_valid) n2 <<= 1;
+    for (int g = tid; g < n2; g += 256) s_cand[g] = (g < ngrp_valid) ? (uint64_t)ord32(gmax[g]) : 0ull;
+    __syncthreads();
+    block_sort_desc(s_cand, n2, tid, 256);
+    if (tid == 0) s_T = (a.k <= ngrp_valid) ? unord32((uint32_t)s_cand[a.k - 1]) : -INFINITY;
+  } else if (wave == 0) {
     // up to 2048 groups (V <= 131072): up to 32 per lane, kept as ordered keys, k rounds of wave max
     const uint32_t T = (ngrp_valid <= 512)    ? kth_largest_group_max<8>(gmax, ngrp_valid, a.k, lane)
                        : (ngrp_valid <= 1024) ? kth_largest_group_max<16>(gmax, ngrp_valid, a.k, lane)
@@ -190,7 +218,16 @@ __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
   __syncthreads();
   const int cnt = s_cnt;
 
-  if (cnt <= kCandMax) {                                       // uniform
+  if (cnt <= kCandMax && a.k >= kSortFromK) {                  // uniform
+    // ---- wide beams: sort the candidates, the first k are the answer ------------------------------
+    int n2 = 64;
+    while (n2 < cnt) n2 <<= 1;
+    for (int i = cnt + tid; i < n2; i += 256) s_cand[i] = 0ull;
+    __syncthreads();
+    block_sort_desc(s_cand, n2, tid, 256);
+    for (int j = tid; j < a.k; j += 256) a.part_key[(size_t)row * a.k + j] = s_cand[j];
+    if (tid == 0) a.part_sum[row] = lse;
+  } else if (cnt <= kCandMax) {                                // uniform
     // ---- exact top-k among the candidates: wave 0, k rounds of wave max over its strided share ---
     if (wave == 0) {
       uint64_t mine[2] = {0ull, 0ull};                         // ranks lane and lane + 64

@@ -186,7 +186,10 @@ int ddd_config_validate(const ddd_config* cfg) {
   if (cfg->B < 1 || cfg->B > 4096) return DDD_ERR_INVALID_ARG;
   if (cfg->k < 1 || cfg->k > DDD_KWIDE_MAX) return DDD_ERR_INVALID_ARG;
   const bool wide = cfg->k > DDD_KMAX;
-  if (cfg->V < cfg->k || cfg->V >= (wide ? (1 << 18) : (1 << 24))) return DDD_ERR_INVALID_ARG;
+  if (cfg->V < cfg->k || cfg->V >= (1 << 24)) return DDD_ERR_INVALID_ARG;
+  // the GEMM path (more than DDD_STREAM_ROWS rows, or wide beams) keeps per-row statistics of at most
+  // 2048 groups of 64 vocabulary rows; wide beam keys hold the token in 18 bits
+  if ((wide || (long long)cfg->B * cfg->k > DDD_STREAM_ROWS) && cfg->V > (1 << 17)) return DDD_ERR_INVALID_ARG;
   if (cfg->max_depth < 1 || cfg->max_depth > DDD_DMAX) return DDD_ERR_INVALID_ARG;
   if (cfg->m < 1 || cfg->m > DDD_MMAX) return DDD_ERR_INVALID_ARG;
   if (!(cfg->threshold >= 0.0f)) return DDD_ERR_INVALID_ARG;   // also rejects NaN

@@ -106,9 +106,22 @@ __global__ __launch_bounds__(256) void synth_target_kernel(TargetArgs a) {
     kid1[i] = -1;
   }
   __syncthreads();
-  for (int c = 1 + tid; c < n_nodes; c += 256) {
-    const int j = (c <= k) ? (c - 1) : ((c - 1 - k) % k);   // rank of node c among its siblings
-    if (j > 1) continue;
+  // nodes of sibling rank 0 and 1 have ids 1, 2 (prompt call) and base_s + i*k + {0, 1} (later calls)
+  const int kk = k * k;
+  const int calls = (n_nodes - 1 - k) / kk;                  // later calls that have been made
+  const int n_items = 2 + calls * k * 2;
+  for (int it = tid; it < n_items; it += 256) {
+    int c, j;
+    if (it < 2) {
+      c = 1 + it;
+      j = it;
+    } else {
+      const int q = it - 2;
+      j = q & 1;
+      const int si = q >> 1;                                 // call index * k + beam slot
+      c = 1 + k + si * k + j;
+    }
+    if (c >= n_nodes || (j == 1 && k < 2)) continue;
     const int p = ppar[c];
     int lo = 0, hi = n_sel;                                  // binary search of p in sel[0..n_sel]
     while (lo < hi) {

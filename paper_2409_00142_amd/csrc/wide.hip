@@ -31,7 +31,8 @@ __device__ __forceinline__ int wide_key_token(uint64_t key) {
 
 struct WideSmem {
   unsigned hist[256];
-  int digit, rem, cnt, stopped;
+  int digit, rem, alone, cnt, stopped;
+  unsigned or_lo, or_hi, and_lo, and_hi, found_lo, found_hi;
   float lps_old[kKW];
   int node_old[kKW];
   uint64_t sel[kKW];
@@ -39,23 +40,100 @@ struct WideSmem {
   TreeEmitSmem te;
 };
 
+// One count for this lane's digit into the histogram.  Scores cluster (a handful of exponents), so
+// most lanes of a wave often hit the same bin, which an LDS atomic serialises lane by lane: up to
+// eight distinct digits per wave are therefore counted with a ballot and added once by a leader
+// (`clustered`: the first digit examined, where the keys still share their leading bits); whatever
+// is left, and every later digit, goes through plain atomics (spread digits rarely collide).
+__device__ __forceinline__ void hist_add(unsigned* hist, unsigned digit, bool valid, int lane, bool clustered) {
+  unsigned long long remaining = __ballot(valid);
+  for (int it = 0; clustered && it < 8 && remaining != 0ull; ++it) {
+    const int leader = __ffsll((long long)remaining) - 1;
+    const unsigned d = (unsigned)__shfl((int)digit, leader, 64);
+    const unsigned long long same = __ballot(valid && digit == d) & remaining;
+    if (lane == leader) atomicAdd(&hist[d], (unsigned)__popcll(same));
+    remaining &= ~same;
+  }
+  if ((remaining >> lane) & 1ull) atomicAdd(&hist[digit], 1u);
+}
+
 // The key of rank `want` (0-based, descending) among n distinct keys key_of(0..n-1), n > want.
 // Every thread of the block calls it with the same arguments; the result is uniform.
+// Radix select, 8-bit digits from the top; the bytes above the first one in which any two keys
+// differ are skipped, and the search ends as soon as the wanted key is alone in its bin.
+// One pass over keys 0..n-1 by the whole block (1024 threads): element i = tid + j * 1024.  Eight
+// keys are fetched before any is used, so a pass over keys that come from global memory pays one
+// memory latency per eight elements.  fn(key, in) is called for every slot of a chunk that holds
+// at least one element, by all threads (in == false past the end): it may use wave-wide operations.
+template <class KeyFn, class Fn>
+__device__ __forceinline__ void sweep_keys(int n, int tid, KeyFn key_of, Fn fn) {
+  for (int j0 = 0; j0 * kWideThreads < n; j0 += 8) {
+    uint64_t kk[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = tid + (j0 + u) * kWideThreads;
+      kk[u] = (i < n) ? key_of(i) : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i0 = (j0 + u) * kWideThreads;
+      if (i0 < n) fn(kk[u], tid + i0 < n);
+    }
+  }
+}
+
+// The key of rank `want` (0-based, descending) among the n distinct keys key_of(0..n-1), n > want.
+// Every thread of the block calls it with the same arguments; the result is uniform.  Radix
+// select, 8-bit digits from the top; the bytes above the first one in which any two keys differ
+// are skipped, and the search ends as soon as the wanted key is alone in its bin.
 template <class KeyFn>
-__device__ __forceinline__ uint64_t block_select_kth(int n, int want, KeyFn key_of, WideSmem& sm, int tid, int nthr) {
-  uint64_t prefix = 0ull;
+__device__ __forceinline__ uint64_t block_select_kth(int n, int want, KeyFn key_of, WideSmem& sm, int tid) {
+  const int lane = tid & 63;
+  // bits in which the keys differ: OR of all keys against AND of all keys
+  uint64_t vor = 0ull, vand = ~0ull;
+  sweep_keys(n, tid, key_of, [&](uint64_t key, bool in) {
+    if (in) {
+      vor |= key;
+      vand &= key;
+    }
+  });
+  uint32_t olo = (uint32_t)vor, ohi = (uint32_t)(vor >> 32), alo = (uint32_t)vand, ahi = (uint32_t)(vand >> 32);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    olo |= (uint32_t)__shfl_xor((int)olo, off, 64);
+    ohi |= (uint32_t)__shfl_xor((int)ohi, off, 64);
+    alo &= (uint32_t)__shfl_xor((int)alo, off, 64);
+    ahi &= (uint32_t)__shfl_xor((int)ahi, off, 64);
+  }
+  if (tid == 0) {
+    sm.or_lo = 0u;
+    sm.or_hi = 0u;
+    sm.and_lo = ~0u;
+    sm.and_hi = ~0u;
+  }
+  __syncthreads();
+  if (lane == 0) {
+    atomicOr(&sm.or_lo, olo);
+    atomicOr(&sm.or_hi, ohi);
+    atomicAnd(&sm.and_lo, alo);
+    atomicAnd(&sm.and_hi, ahi);
+  }
+  __syncthreads();
+  const uint64_t all_or = ((uint64_t)sm.or_hi << 32) | sm.or_lo, all_and = ((uint64_t)sm.and_hi << 32) | sm.and_lo;
+  const uint64_t diff = all_or ^ all_and;
+  if (diff == 0ull) return all_or;                    // a single key
+  const int top_byte = (63 - __clzll((long long)diff)) >> 3;
+  uint64_t prefix = (top_byte == 7) ? 0ull : (all_and & (~0ull << (8 * (top_byte + 1))));
   int rem = want;
-  for (int shift = 56; shift >= 0; shift -= 8) {
-    for (int i = tid; i < 256; i += nthr) sm.hist[i] = 0u;
+  for (int shift = 8 * top_byte; shift >= 0; shift -= 8) {
+    for (int i = tid; i < 256; i += kWideThreads) sm.hist[i] = 0u;
     __syncthreads();
     const uint64_t hi_mask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
-    for (int i = tid; i < n; i += nthr) {
-      const uint64_t key = key_of(i);
-      if ((key & hi_mask) == prefix) atomicAdd(&sm.hist[(unsigned)(key >> shift) & 255u], 1u);
-    }
+    sweep_keys(n, tid, key_of, [&](uint64_t key, bool in) {
+      hist_add(sm.hist, (unsigned)(key >> shift) & 255u, in && (key & hi_mask) == prefix, lane, shift == 8 * top_byte);
+    });
     __syncthreads();
     if (tid < 64) {   // wave 0: lane l owns digits 255-4l .. 252-4l; running count from the top digit down
-      const int lane = tid;
       unsigned h[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) h[q] = sm.hist[255 - 4 * lane - q];
@@ -74,6 +152,7 @@ __device__ __forceinline__ uint64_t block_select_kth(int n, int want, KeyFn key_
           if ((unsigned)rem >= c && (unsigned)rem < c + h[q]) {
             sm.digit = 255 - 4 * lane - q;
             sm.rem = (int)((unsigned)rem - c);
+            sm.alone = (h[q] == 1u) ? 1 : 0;
           }
           c += h[q];
         }
@@ -82,25 +161,36 @@ __device__ __forceinline__ uint64_t block_select_kth(int n, int want, KeyFn key_
     __syncthreads();
     prefix |= (uint64_t)(unsigned)sm.digit << shift;
     rem = sm.rem;
+    if (sm.alone && shift > 0) {                      // uniform: the wanted key is the only one with this prefix
+      const uint64_t pm = ~0ull << shift;
+      sweep_keys(n, tid, key_of, [&](uint64_t key, bool in) {
+        if (in && (key & pm) == prefix) {
+          sm.found_lo = (uint32_t)key;
+          sm.found_hi = (uint32_t)(key >> 32);
+        }
+      });
+      __syncthreads();
+      return ((uint64_t)sm.found_hi << 32) | sm.found_lo;
+    }
   }
   return prefix;
 }
 
-// Descending bitonic sort of sm.sel[0..127] (unused slots hold 0) by the first 64 threads.
-__device__ __forceinline__ void sort_sel_desc(WideSmem& sm, int tid) {
+// Descending bitonic sort of sm.sel[0..127] (unused slots hold 0) by one wave (all 64 lanes): each
+// stage is one compare-exchange per lane, ordered by wave barriers instead of block barriers.
+__device__ __forceinline__ void sort_sel_desc_wave(WideSmem& sm, int lane) {
   for (int size = 2; size <= kKW; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      if (tid < kKW / 2) {
-        const int pos = 2 * stride * (tid / stride) + (tid % stride);
-        const int partner = pos + stride;
-        const bool desc = ((pos & size) == 0);
-        const uint64_t x = sm.sel[pos], y = sm.sel[partner];
-        if ((x < y) == desc) {
-          sm.sel[pos] = y;
-          sm.sel[partner] = x;
-        }
+      const int pos = 2 * stride * (lane / stride) + (lane % stride);
+      const int partner = pos + stride;
+      const bool desc = ((pos & size) == 0);
+      const uint64_t x = sm.sel[pos], y = sm.sel[partner];
+      if ((x < y) == desc) {
+        sm.sel[pos] = y;
+        sm.sel[partner] = x;
       }
-      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
@@ -113,14 +203,15 @@ __device__ __forceinline__ void tree_finalize_wide_block(const ddd_state& st, co
   const float* psc = st.pool_score + (size_t)b * nmax;
   auto key_of = [&](int i) { return rerank_key(psc[i + 1], i + 1); };
   uint64_t kth = 0ull;                       // every key is at least 1
-  if (m_eff < N) kth = block_select_kth(N, m_eff - 1, key_of, sm, tid, nthr);
+  if (m_eff < N) kth = block_select_kth(N, m_eff - 1, key_of, sm, tid);
   if (tid == 0) sm.cnt = 0;
   __syncthreads();
-  for (int i = tid; i < N; i += nthr)
-    if (key_of(i) >= kth) {
+  sweep_keys(N, tid, key_of, [&](uint64_t key, bool in) {
+    if (in && key >= kth) {
       const int p = atomicAdd(&sm.cnt, 1);
-      if (p < kTreeMax) sm.te.pick[p] = i + 1;   // exactly m_eff of them: keys are distinct
+      if (p < kTreeMax) sm.te.pick[p] = (int)(0xFFFFFFFFu - (uint32_t)key);   // exactly m_eff: keys are distinct
     }
+  });
   __syncthreads();
   tree_emit_block(st, tree, b, m, m_eff, nmax, tid, nthr, sm.te);
 }
@@ -184,27 +275,42 @@ __global__ __launch_bounds__(kWideThreads) void step_wide_kernel(WideStepArgs a)
         if (a.lse_dbg != nullptr && from_keys) a.lse_dbg[row0 + i] = a.part_lse[row0 + i];
       }
       __syncthreads();
-      for (int f = tid; f < k * k; f += nthr) {
-        const int i = f / k, j = f - i * k;
-        int t;
-        float lp;
-        if (from_keys) {
-          const uint64_t key = a.part_key[(row0 + i) * k + j];
-          t = key_token(key);
-          lp = key_value(key) - a.part_lse[row0 + i];
-        } else {
-          t = g.topk_token[(row0 + i) * k + j];
-          lp = g.topk_logprob[(row0 + i) * k + j];
+      for (int f0 = 0; f0 < k * k; f0 += 4 * nthr) {      // four candidates per thread in flight
+        int t[4];
+        float lp[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int f = f0 + u * nthr + tid;
+          t[u] = 0;
+          lp[u] = 0.f;
+          if (f < k * k) {
+            const int i = f / k, j = f - i * k;
+            if (from_keys) {
+              const uint64_t key = a.part_key[(row0 + i) * k + j];
+              t[u] = key_token(key);
+              lp[u] = key_value(key) - a.part_lse[row0 + i];
+            } else {
+              t[u] = g.topk_token[(row0 + i) * k + j];
+              lp[u] = g.topk_logprob[(row0 + i) * k + j];
+            }
+          }
         }
-        const float sc = __fadd_rn(sm.lps_old[i], lp);
-        ptok[base + f] = t;
-        ppar[base + f] = sm.node_old[i];
-        pdep[base + f] = step + 1;
-        psc[base + f] = sc;
-        keys[f] = wide_beam_key(sc, t, f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int f = f0 + u * nthr + tid;
+          if (f < k * k) {
+            const int i = f / k;
+            const float sc = __fadd_rn(sm.lps_old[i], lp[u]);
+            ptok[base + f] = t[u];
+            ppar[base + f] = sm.node_old[i];
+            pdep[base + f] = step + 1;
+            psc[base + f] = sc;
+            keys[f] = wide_beam_key(sc, t[u], f);
+          }
+        }
       }
       __syncthreads();
-      const uint64_t kth = block_select_kth(k * k, k - 1, [&](int i) { return keys[i]; }, sm, tid, nthr);
+      const uint64_t kth = block_select_kth(k * k, k - 1, [&](int i) { return keys[i]; }, sm, tid);
       for (int i = tid; i < kKW; i += nthr) sm.sel[i] = 0ull;
       if (tid == 0) sm.cnt = 0;
       __syncthreads();
@@ -214,7 +320,8 @@ __global__ __launch_bounds__(kWideThreads) void step_wide_kernel(WideStepArgs a)
           if (p < kKW) sm.sel[p] = keys[f];     // exactly k of them: keys are distinct
         }
       __syncthreads();
-      sort_sel_desc(sm, tid);
+      if (tid < 64) sort_sel_desc_wave(sm, tid);
+      __syncthreads();
       for (int r = tid; r < k; r += nthr) {
         const uint64_t key = sm.sel[r];
         const int f = wide_key_flat(key);

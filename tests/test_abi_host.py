@@ -58,7 +58,8 @@ def test_config_validation(D):
         assert D.ddd_pool_capacity(cfg) == wl.pool_capacity
     bad = [
         dict(B=0), dict(k=0), dict(k=129), dict(V=5), dict(V=1 << 24), dict(max_depth=0), dict(max_depth=32),
-        dict(k=17, V=1 << 18), dict(k=100, max_depth=8), dict(k=128, max_depth=6),   # wide beams: V < 2^18, pool <= 65536
+        dict(k=17, V=(1 << 17) + 1), dict(B=2, V=(1 << 17) + 1), dict(k=100, max_depth=8), dict(k=128, max_depth=6),
+        # ^ the GEMM path (wide beams, or more than 16 rows): V <= 2^17; wide pools <= 65536
         dict(m=0), dict(m=129), dict(H=100), dict(H=4096 + 64), dict(H=128 * 64), dict(H=5632), dict(threshold=-0.1),
         dict(threshold=float("nan")), dict(k=16, max_depth=20),
     ]
@@ -68,7 +69,7 @@ def test_config_validation(D):
         cfg = D.make_config(**kw)
         assert D.ddd_config_validate(cfg) == D.DDD_ERR_INVALID_ARG, b
         assert D.ddd_pool_capacity(cfg) == 0
-    for good in (dict(k=17), dict(k=100, max_depth=6), dict(k=128, max_depth=4), dict(k=64, V=(1 << 18) - 1)):
+    for good in (dict(k=17), dict(k=100, max_depth=6), dict(k=128, max_depth=4), dict(k=64, V=1 << 17), dict(V=(1 << 24) - 1)):
         cfg = D.make_config(**dict(base, **good))
         assert D.ddd_config_validate(cfg) == D.DDD_OK, good
         assert D.ddd_pool_capacity(cfg) == 1 + cfg.k + (cfg.max_depth - 1) * cfg.k * cfg.k
