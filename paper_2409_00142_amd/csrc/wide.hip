@@ -16,6 +16,7 @@ namespace ddd {
 
 constexpr int kKW = DDD_KWIDE_MAX;
 constexpr int kWideThreads = 1024;
+constexpr int kGlobalChunk = 8;                    // loads in flight per thread when the keys come from global memory
 constexpr int kFlatBits = 14;                      // k*k <= 16384 flat indices
 constexpr uint32_t kFlatMask = (1u << kFlatBits) - 1u;
 constexpr uint32_t kTokMaskW = (1u << (32 - kFlatBits)) - 1u;   // tokens below 2^18
@@ -61,21 +62,21 @@ __device__ __forceinline__ void hist_add(unsigned* hist, unsigned digit, bool va
 // Every thread of the block calls it with the same arguments; the result is uniform.
 // Radix select, 8-bit digits from the top; the bytes above the first one in which any two keys
 // differ are skipped, and the search ends as soon as the wanted key is alone in its bin.
-// One pass over keys 0..n-1 by the whole block (1024 threads): element i = tid + j * 1024.  Eight
+// One pass over keys 0..n-1 by the whole block (1024 threads): element i = tid + j * 1024.  CH
 // keys are fetched before any is used, so a pass over keys that come from global memory pays one
-// memory latency per eight elements.  fn(key, in) is called for every slot of a chunk that holds
+// memory latency per CH elements.  fn(key, in) is called for every slot of a chunk that holds
 // at least one element, by all threads (in == false past the end): it may use wave-wide operations.
-template <class KeyFn, class Fn>
+template <int CH, class KeyFn, class Fn>
 __device__ __forceinline__ void sweep_keys(int n, int tid, KeyFn key_of, Fn fn) {
-  for (int j0 = 0; j0 * kWideThreads < n; j0 += 8) {
-    uint64_t kk[8];
+  for (int j0 = 0; j0 * kWideThreads < n; j0 += CH) {
+    uint64_t kk[CH];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < CH; ++u) {
       const int i = tid + (j0 + u) * kWideThreads;
       kk[u] = (i < n) ? key_of(i) : 0ull;
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < CH; ++u) {
       const int i0 = (j0 + u) * kWideThreads;
       if (i0 < n) fn(kk[u], tid + i0 < n);
     }
@@ -86,12 +87,12 @@ __device__ __forceinline__ void sweep_keys(int n, int tid, KeyFn key_of, Fn fn) 
 // Every thread of the block calls it with the same arguments; the result is uniform.  Radix
 // select, 8-bit digits from the top; the bytes above the first one in which any two keys differ
 // are skipped, and the search ends as soon as the wanted key is alone in its bin.
-template <class KeyFn>
+template <int CH, class KeyFn>
 __device__ __forceinline__ uint64_t block_select_kth(int n, int want, KeyFn key_of, WideSmem& sm, int tid) {
   const int lane = tid & 63;
   // bits in which the keys differ: OR of all keys against AND of all keys
   uint64_t vor = 0ull, vand = ~0ull;
-  sweep_keys(n, tid, key_of, [&](uint64_t key, bool in) {
+  sweep_keys<CH>(n, tid, key_of, [&](uint64_t key, bool in) {
     if (in) {
       vor |= key;
       vand &= key;
@@ -129,7 +130,7 @@ __device__ __forceinline__ uint64_t block_select_kth(int n, int want, KeyFn key_
     for (int i = tid; i < 256; i += kWideThreads) sm.hist[i] = 0u;
     __syncthreads();
     const uint64_t hi_mask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
-    sweep_keys(n, tid, key_of, [&](uint64_t key, bool in) {
+    sweep_keys<CH>(n, tid, key_of, [&](uint64_t key, bool in) {
       hist_add(sm.hist, (unsigned)(key >> shift) & 255u, in && (key & hi_mask) == prefix, lane, shift == 8 * top_byte);
     });
     __syncthreads();
@@ -163,7 +164,7 @@ __device__ __forceinline__ uint64_t block_select_kth(int n, int want, KeyFn key_
     rem = sm.rem;
     if (sm.alone && shift > 0) {                      // uniform: the wanted key is the only one with this prefix
       const uint64_t pm = ~0ull << shift;
-      sweep_keys(n, tid, key_of, [&](uint64_t key, bool in) {
+      sweep_keys<CH>(n, tid, key_of, [&](uint64_t key, bool in) {
         if (in && (key & pm) == prefix) {
           sm.found_lo = (uint32_t)key;
           sm.found_hi = (uint32_t)(key >> 32);
@@ -203,10 +204,10 @@ __device__ __forceinline__ void tree_finalize_wide_block(const ddd_state& st, co
   const float* psc = st.pool_score + (size_t)b * nmax;
   auto key_of = [&](int i) { return rerank_key(psc[i + 1], i + 1); };
   uint64_t kth = 0ull;                       // every key is at least 1
-  if (m_eff < N) kth = block_select_kth(N, m_eff - 1, key_of, sm, tid);
+  if (m_eff < N) kth = block_select_kth<kGlobalChunk>(N, m_eff - 1, key_of, sm, tid);
   if (tid == 0) sm.cnt = 0;
   __syncthreads();
-  sweep_keys(N, tid, key_of, [&](uint64_t key, bool in) {
+  sweep_keys<kGlobalChunk>(N, tid, key_of, [&](uint64_t key, bool in) {
     if (in && key >= kth) {
       const int p = atomicAdd(&sm.cnt, 1);
       if (p < kTreeMax) sm.te.pick[p] = (int)(0xFFFFFFFFu - (uint32_t)key);   // exactly m_eff: keys are distinct
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(kWideThreads) void step_wide_kernel(WideStepArgs a)
         }
       }
       __syncthreads();
-      const uint64_t kth = block_select_kth(k * k, k - 1, [&](int i) { return keys[i]; }, sm, tid);
+      const uint64_t kth = block_select_kth<8>(k * k, k - 1, [&](int i) { return keys[i]; }, sm, tid);
       for (int i = tid; i < kKW; i += nthr) sm.sel[i] = 0ull;
       if (tid == 0) sm.cnt = 0;
       __syncthreads();
