@@ -3,21 +3,24 @@
 //   logits[r, v] = sum_h hid[r, h] * W[v, h]        (bf16 in, fp32 accumulate, fp32 out)
 //
 // With hundreds of rows the projection is bound by the matrix cores, not by HBM, and on this chip
-// by the LDS bandwidth that feeds them: a 64 x 64 wave tile needs one 1 KB fragment read per
-// MFMA, which measured LDS-bound at about a quarter of the MFMA peak.  The kernel therefore uses
-// large wave tiles - AB x BB blocks of v_mfma_f32_32x32x16_bf16 per wave, WM x 2 waves per
-// workgroup, 128 (vocabulary rows) x 320 (hidden rows) per workgroup as dispatched - which leaves no
-// registers for per-row top-k lists; the fp32 logits of the active rows are written out (HBM has
-// slack in this regime) and a second kernel reduces each row (row_topk_kernel).
+// by what feeds them: a 64 x 64 wave tile needs one 1 KB fragment read per MFMA, which measured
+// LDS-bound at about a quarter of the MFMA peak.  The kernel therefore uses large wave tiles -
+// AB x BB blocks of v_mfma_f32_32x32x16_bf16 per wave, 2 x 2 waves per workgroup, 128 (vocabulary
+// rows) x 320 (hidden rows) per workgroup for hundreds of rows - which leaves no registers for
+// per-row top-k lists; the fp32 logits of the active rows are written out (HBM has slack in this
+// regime) and a second kernel reduces each row (row_topk_kernel).
 //
 // W is the A operand, so an accumulator lane owns one hidden row and four consecutive vocabulary
-// rows per register quad: the output is stored as float4 along V.  Both operands go through
-// double-buffered LDS tiles of 32 k (80-byte pitch, conflict-free 16-byte reads); the K loop is
-// unrolled by two with two static register sets so that the loads of tile kt+2 are in flight
-// while tile kt is multiplied.  Only active rows are multiplied: the B rows are gathered through
-// the compacted row list and column blocks past the last active row are skipped per wave.
-// Work units are (row tile of W, column tile), handed out so that the column tiles of one row
-// tile run on the same XCD and share the W rows through its L2.
+// rows per register quad: the output is stored as float4 along V.  Both operands reach LDS by
+// LDS-direct loads (16 bytes per lane straight from global memory into LDS: no staging registers,
+// no LDS write instructions, nothing returned through the VGPR write path the fragment reads
+// use), three stages of 32 k, loads two tiles ahead, one barrier per tile.  Rows are not padded;
+// the four 16-byte chunks of a row are XOR-swizzled with bits 2-3 of the row, which keeps both the
+// 1 KB-per-wave copy destinations contiguous and the fragment reads conflict-free.  Only active
+// rows are multiplied: the B rows are gathered through the compacted row list and column blocks
+// past the last active row are skipped per wave.  Work units are (row tile of W, column tile),
+// handed out so that the column tiles of one row tile run on the same XCD and share the W rows
+// through its L2.
 #include "ddd_device.hpp"
 #include "ddd_kernels.hpp"
 
@@ -28,49 +31,30 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int kGK = 32;        // k per LDS tile
-constexpr int kGPitch = 40;    // bf16 elements per LDS row: 32 + 8 pad (80 B: conflict-free 16-byte reads)
-constexpr int kCPR = kGK / 8;  // 16-byte chunks per tile row
+constexpr int kGK = 32;        // k per LDS tile: 64 bytes per row, four 16-byte chunks
+constexpr int kStages = 3;     // LDS stages (4 measured the same)
+constexpr int kWM = 2;         // waves along the vocabulary rows; 2 more along the hidden rows
 
-// AB x BB blocks of 32 x 32 per wave, WM x 2 waves per workgroup.
-template <int AB, int BB, int WM>
+// AB x BB blocks of 32 x 32 per wave, 2 x 2 waves per workgroup.
+template <int AB, int BB>
 struct GemmCfg {
-  static constexpr int BM = 32 * AB * WM, BN = 64 * BB;
-  static constexpr int kThreads = 128 * WM;
-  static constexpr int kRPP = kThreads / kCPR;                 // rows copied per pass of the workgroup
-  static constexpr int NA = BM / kRPP;                          // copy passes of the W tile
-  static constexpr int NBF = BN / kRPP;                         // full copy passes of the hidden-row tile ...
-  static constexpr int kBRem = BN - NBF * kRPP;                 // ... and the rows of a last, partial pass
-  static constexpr int NBL = NBF + (kBRem > 0 ? 1 : 0);
-  static constexpr int kStageElems = (BM + BN) * kGPitch;
-  static constexpr int kLdsBytes = 2 * kStageElems * 2;
-  static_assert(BM % kRPP == 0, "W tile rows must be a whole number of copy passes");
+  static constexpr int BM = 32 * AB * kWM, BN = 64 * BB;
+  static constexpr int kStageBytes = (BM + BN) * 64;
+  static constexpr int kLdsBytes = kStages * kStageBytes;
+  static constexpr int NAP = BM / 64, NBP = BN / 64;   // copy instructions per wave and tile (16 rows each)
 };
 
 // One work unit of one wave: NB = number of this wave's column blocks that hold active rows
 // (0 <= NB <= BB; a wave with NB == 0 still copies tiles and meets the barriers).  Every value of
 // NB has its own fully unrolled loop, so the accumulators stay in place (no data-dependent
 // branches around the MFMAs).
-template <int AB, int BB, int WM, int NB>
-__device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int mt, int nt, int n_act, int tid, int wm,
-                                          int wn, int l32, int lh) {
-  using C = GemmCfg<AB, BB, WM>;
+template <int AB, int BB, int NB>
+__device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb, int mt, int nt, int n_act, int tid,
+                                          int wm, int wn, int l32, int lh) {
+  using C = GemmCfg<AB, BB>;
   constexpr int NBR = NB > 0 ? NB : 1;
-  constexpr int kRPP = C::kRPP, NA = C::NA, NBL = C::NBL;
-  const int KT = a.H / kGK;                                         // even: H is a multiple of 128
-  const int ld_row = tid / kCPR, ld_cc = tid % kCPR;                // global->LDS copy: kCPR x 16 B per row
-  const int st_off = ld_row * kGPitch + ld_cc * 8;
-  // the last pass over the hidden-row tile may cover only part of the workgroup's rows
-  const bool b_last_ok = (C::kBRem == 0) || (ld_row < C::kBRem);
-  // 32-bit element offsets from the two base pointers (V*H and rows*H stay below 2^31 elements)
-  uint32_t aoff[NA], boff[NBL];
-#pragma unroll
-  for (int i = 0; i < NA; ++i)
-    aoff[i] = (uint32_t)min(mt * C::BM + ld_row + kRPP * i, a.V - 1) * (uint32_t)a.H + ld_cc * 8;
-#pragma unroll
-  for (int i = 0; i < NBL; ++i)
-    boff[i] = (uint32_t)a.row_list[min(nt * C::BN + min(ld_row + kRPP * i, C::BN - 1), n_act - 1)] * (uint32_t)a.H +
-              ld_cc * 8;
+  constexpr int NAP = C::NAP, NBP = C::NBP;
+  const int KT = a.H / kGK;
   const int col0 = nt * C::BN + wn * 32 * BB;
 
   f32x16 acc[AB][NBR];
@@ -81,86 +65,72 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0.f;
 
-  // Four waves (one per SIMD): two register sets, loads two tiles ahead, fragments two k-steps at a
-  // time.  Eight waves (two per SIMD, 256 registers each): one set, one tile ahead, one k-step -
-  // the other wave of the SIMD covers the waits.
-  constexpr int FK = (WM == 2) ? 2 : 1;
-  u32x4 a0[NA], b0[NBL];
-#define DDD_LOADSET(SA, SB, T)                                                                                      \
+  // ---- copy side: a wave instruction fills 1 KB of LDS = 16 rows x 64 B; lane -> (row, chunk) ----
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int prow = lane >> 2, pc = (lane & 3) ^ ((prow >> 2) & 3);   // chunk read from global for LDS slot lane & 3
+  // 32-bit element offsets from the two base pointers (V*H and rows*H stay below 2^31 elements)
+  uint32_t ao[NAP], bo[NBP];
+#pragma unroll
+  for (int i = 0; i < NAP; ++i)
+    ao[i] = (uint32_t)min(mt * C::BM + (i * 4 + wave) * 16 + prow, a.V - 1) * (uint32_t)a.H + pc * 8;
+#pragma unroll
+  for (int i = 0; i < NBP; ++i)
+    bo[i] = (uint32_t)a.row_list[min(nt * C::BN + (i * 4 + wave) * 16 + prow, n_act - 1)] * (uint32_t)a.H + pc * 8;
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+#define DDD_ISSUE(T, STG)                                                                                           \
   {                                                                                                                 \
-    _Pragma("unroll") for (int i = 0; i < NA; ++i) SA[i] = *reinterpret_cast<const u32x4*>(a.W + aoff[i] + (T) * kGK);    \
-    _Pragma("unroll") for (int i = 0; i < NBL; ++i) SB[i] = *reinterpret_cast<const u32x4*>(a.hid + boff[i] + (T) * kGK); \
+    _Pragma("unroll") for (int i = 0; i < NAP; ++i) __builtin_amdgcn_global_load_lds(                               \
+        (gptr_t)(a.W + ao[i] + (T) * kGK), (lptr_t)(ldsb + (STG) * C::kStageBytes + (i * 4 + wave) * 1024), 16, 0, 0);  \
+    _Pragma("unroll") for (int i = 0; i < NBP; ++i) __builtin_amdgcn_global_load_lds(                               \
+        (gptr_t)(a.hid + bo[i] + (T) * kGK),                                                                        \
+        (lptr_t)(ldsb + (STG) * C::kStageBytes + C::BM * 64 + (i * 4 + wave) * 1024), 16, 0, 0);                     \
   }
-#define DDD_STORESET(SA, SB, BUF)                                                                                   \
-  {                                                                                                                 \
-    uint16_t* sa_ = lds + (BUF) * C::kStageElems + st_off;                                                          \
-    uint16_t* sb_ = sa_ + C::BM * kGPitch;                                                                          \
-    _Pragma("unroll") for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(sa_ + kRPP * i * kGPitch) = SA[i];     \
-    _Pragma("unroll") for (int i = 0; i < NBL; ++i)                                                                 \
-      if (i < C::NBF || b_last_ok) *reinterpret_cast<u32x4*>(sb_ + kRPP * i * kGPitch) = SB[i];                     \
-  }
-#define DDD_COMPUTE(BUF)                                                                                            \
-  if (NB > 0) {                                                                                                     \
-    const uint16_t* Ab = lds + (BUF) * C::kStageElems + (wm * 32 * AB + l32) * kGPitch + lh * 8;                    \
-    const uint16_t* Bb = lds + (BUF) * C::kStageElems + (C::BM + wn * 32 * BB + l32) * kGPitch + lh * 8;            \
-    /* fragments are requested FK k-steps at a time (FK = 2: the second k-step's reads land during the  */         \
-    /* first one's MFMAs)                                                                                 */         \
-    _Pragma("unroll") for (int kp = 0; kp < kGK / (16 * FK); ++kp) {                                                \
-      bf16x8 af[FK][AB], bf[FK][NBR];                                                                               \
-      _Pragma("unroll") for (int ks = 0; ks < FK; ++ks) {                                                           \
-        _Pragma("unroll") for (int b = 0; b < AB; ++b) af[ks][b] = __builtin_bit_cast(                              \
-            bf16x8, *reinterpret_cast<const u32x4*>(Ab + b * 32 * kGPitch + (kp * FK + ks) * 16));                  \
-        _Pragma("unroll") for (int b = 0; b < NBR; ++b) bf[ks][b] = __builtin_bit_cast(                             \
-            bf16x8, *reinterpret_cast<const u32x4*>(Bb + b * 32 * kGPitch + (kp * FK + ks) * 16));                  \
-      }                                                                                                             \
-      _Pragma("unroll") for (int ks = 0; ks < FK; ++ks)                                                             \
-        _Pragma("unroll") for (int bn = 0; bn < NBR; ++bn)                                                          \
-          _Pragma("unroll") for (int bm = 0; bm < AB; ++bm)                                                         \
-              acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][bm], bf[ks][bn], acc[bm][bn], 0, 0, 0);  \
-    }                                                                                                               \
-  }
+  // ---- fragment side: lane (l32, lh) of block b reads row b*32 + l32, chunk ks*2 + lh -------------
+  const int swz = (l32 >> 2) & 3;   // every tile / block base is a multiple of 16 rows
+  const int offk0 = ((0 + lh) ^ swz) * 16, offk1 = ((2 + lh) ^ swz) * 16;
+  const int arow = (wm * 32 * AB + l32) * 64, brow = C::BM * 64 + (wn * 32 * BB + l32) * 64;
+  // s_waitcnt vmcnt(n): the loads of the tiles that may stay in flight, per thread
+  constexpr int kVm = (NAP + NBP) * (kStages - 2);
+  constexpr int kWaitSome = (kVm & 15) | ((kVm >> 4) << 14) | (7 << 4) | (15 << 8);
+  constexpr int kWaitAll = (0 & 15) | (7 << 4) | (15 << 8);
 
-  if constexpr (WM == 2) {
-    u32x4 a1[NA], b1[NBL];
-    DDD_LOADSET(a0, b0, 0);
-    DDD_LOADSET(a1, b1, 1);
-    __syncthreads();            // every wave is done with the LDS tiles of the previous unit
-    DDD_STORESET(a0, b0, 0);
-    DDD_LOADSET(a0, b0, min(2, KT - 1));
-    __syncthreads();
-    for (int kt = 0; kt < KT; kt += 2) {
-      // tile kt is in LDS[0]; tile kt+1 waits in set 1 (loaded two half-iterations ago)
-      DDD_STORESET(a1, b1, 1);
-      DDD_LOADSET(a1, b1, min(kt + 3, KT - 1));   // always issued: keeps the count of loads in flight static
-      DDD_COMPUTE(0);
-      __syncthreads();
-      // tile kt+1 is in LDS[1]; tile kt+2 waits in set 0
-      DDD_STORESET(a0, b0, 0);
-      DDD_LOADSET(a0, b0, min(kt + 4, KT - 1));
-      DDD_COMPUTE(1);
-      __syncthreads();
+  __syncthreads();            // every wave is done with the LDS tiles of the previous unit
+#pragma unroll
+  for (int p = 0; p < kStages - 1; ++p) DDD_ISSUE(min(p, KT - 1), p);
+  int stg = 0;
+  for (int kt = 0; kt < KT; ++kt) {
+    __builtin_amdgcn_s_waitcnt(kWaitSome);   // this thread's loads of tile kt have landed (later tiles' may be in flight)
+    __builtin_amdgcn_s_barrier();            // ... and everybody's; everybody is done reading tile kt-1 (a plain
+                                             // barrier: __syncthreads() would wait for every load in flight)
+    const int stg2 = (stg == 0) ? kStages - 1 : stg - 1;
+    DDD_ISSUE(min(kt + kStages - 1, KT - 1), stg2);   // always issued: the count of loads in flight stays static
+    if (NB > 0) {
+      const unsigned char* sb = ldsb + stg * C::kStageBytes;
+      bf16x8 af[2][AB], bf[2][NBR];
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const int ok = ks ? offk1 : offk0;
+#pragma unroll
+        for (int b = 0; b < AB; ++b)
+          af[ks][b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sb + arow + b * 32 * 64 + ok));
+#pragma unroll
+        for (int b = 0; b < NBR; ++b)
+          bf[ks][b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sb + brow + b * 32 * 64 + ok));
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int bn = 0; bn < NBR; ++bn)
+#pragma unroll
+          for (int bm = 0; bm < AB; ++bm)
+            acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][bm], bf[ks][bn], acc[bm][bn], 0, 0, 0);
     }
-  } else {
-    DDD_LOADSET(a0, b0, 0);
-    __syncthreads();            // every wave is done with the LDS tiles of the previous unit
-    DDD_STORESET(a0, b0, 0);
-    DDD_LOADSET(a0, b0, min(1, KT - 1));
-    __syncthreads();
-    for (int kt = 0; kt < KT; kt += 2) {
-      // tile kt is in LDS[0]; tile kt+1 waits in the register set (loaded one half-iteration ago)
-      DDD_STORESET(a0, b0, 1);
-      DDD_LOADSET(a0, b0, min(kt + 2, KT - 1));
-      DDD_COMPUTE(0);
-      __syncthreads();
-      DDD_STORESET(a0, b0, 0);
-      DDD_LOADSET(a0, b0, min(kt + 3, KT - 1));
-      DDD_COMPUTE(1);
-      __syncthreads();
-    }
+    stg = (stg == kStages - 1) ? 0 : stg + 1;
   }
-#undef DDD_LOADSET
-#undef DDD_STORESET
-#undef DDD_COMPUTE
+  __builtin_amdgcn_s_waitcnt(kWaitAll);   // the clamped extra loads have landed before the LDS is reused
+#undef DDD_ISSUE
 
   if (NB == 0) return;
   // accumulator register q*4+e of block (bm, bn): vocabulary row vb + bm*32 + q*8 + e, hidden row column l32
@@ -229,11 +199,11 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, uint16_t* lds, int 
 }
 
 // All work units of one workgroup for a column-tile width of 64 * BB rows.
-template <int AB, int BB, int WM>
-__device__ __forceinline__ void gemm_units(const GemmArgs& a, uint16_t* lds, int n_act) {
-  using C = GemmCfg<AB, BB, WM>;
+template <int AB, int BB>
+__device__ __forceinline__ void gemm_units(const GemmArgs& a, unsigned char* lds, int n_act) {
+  using C = GemmCfg<AB, BB>;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wm = wave % WM, wn = wave / WM;
+  const int wm = wave % kWM, wn = wave / kWM;
   const int l32 = lane & 31, lh = lane >> 5;
   const int nmt = (a.V + C::BM - 1) / C::BM;
   const int NT = (n_act + C::BN - 1) / C::BN;
@@ -247,12 +217,12 @@ __device__ __forceinline__ void gemm_units(const GemmArgs& a, uint16_t* lds, int
     const int col0 = nt * C::BN + wn * 32 * BB;
     const int nb_act = min(BB, max(0, (n_act - col0 + 31) / 32));
     switch (nb_act) {
-      case 0: gemm_unit<AB, BB, WM, 0>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 1: gemm_unit<AB, BB, WM, 1>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 2: gemm_unit<AB, BB, WM, (BB >= 2 ? 2 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 3: gemm_unit<AB, BB, WM, (BB >= 3 ? 3 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 4: gemm_unit<AB, BB, WM, (BB >= 4 ? 4 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      default: gemm_unit<AB, BB, WM, BB>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 0: gemm_unit<AB, BB, 0>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 1: gemm_unit<AB, BB, 1>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 2: gemm_unit<AB, BB, (BB >= 2 ? 2 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 3: gemm_unit<AB, BB, (BB >= 3 ? 3 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      case 4: gemm_unit<AB, BB, (BB >= 4 ? 4 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+      default: gemm_unit<AB, BB, BB>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
     }
   }
 }
@@ -261,21 +231,20 @@ __device__ __forceinline__ void gemm_units(const GemmArgs& a, uint16_t* lds, int
 // active rows is only known on the device, so the kernel narrows the column tile itself when few
 // rows are left: with 64 active rows a 320-row tile would still copy 320 (repeated) rows per
 // K tile through LDS.
-template <int AB, int BB, int WM>
-__global__ __launch_bounds__(128 * WM, 1) void lmhead_gemm_kernel(GemmArgs a) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  uint16_t* lds = reinterpret_cast<uint16_t*>(smem_raw);   // [2][BM + BN][kGPitch] of the chosen width
+template <int AB, int BB>
+__global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(GemmArgs a) {
+  extern __shared__ __align__(16) unsigned char lds[];     // [kStages][BM + BN][64 B] of the chosen width
 
   const int n_act = *a.n_act_ptr;
   if (n_act <= 0) return;                                  // uniform
   if (BB >= 5 && n_act > 192)
-    gemm_units<AB, BB, WM>(a, lds, n_act);
+    gemm_units<AB, BB>(a, lds, n_act);
   else if (BB >= 3 && n_act > 128)
-    gemm_units<AB, (BB >= 3 ? 3 : BB), WM>(a, lds, n_act);
+    gemm_units<AB, (BB >= 3 ? 3 : BB)>(a, lds, n_act);
   else if (BB >= 2 && n_act > 64)
-    gemm_units<AB, (BB >= 2 ? 2 : BB), WM>(a, lds, n_act);
+    gemm_units<AB, (BB >= 2 ? 2 : BB)>(a, lds, n_act);
   else
-    gemm_units<AB, 1, WM>(a, lds, n_act);
+    gemm_units<AB, 1>(a, lds, n_act);
 }
 
 // ---- compaction of the active rows ------------------------------------------------------------
@@ -313,9 +282,9 @@ hipError_t launch_build_row_list(const uint8_t* row_active, int n_rows, int32_t*
 }
 
 // Tile shape by the largest number of rows the call can have: 128 x 320 for hundreds of rows,
-// smaller column tiles when fewer rows can be active.  (WM = 4, eight waves on a 256 x 320 tile,
-// measured 199 us against 224 us with all 640 rows active, but leaves half of the CUs idle once
-// fewer than 321 rows are active, which is most draft calls of a round: not instantiated.)
+// smaller column tiles when fewer rows can be active.  (Eight waves on a 256 x 320 tile measured
+// a tenth faster with all 640 rows active, but leave half of the CUs idle once fewer than 321
+// rows are active, which is most draft calls of a round; four waves on that tile spill.)
 // With at most 128 rows and a vocabulary large enough to give every CU a unit, 256 vocabulary rows per
 // workgroup (128 x 64 wave tiles) cut the LDS and L2 traffic per MFMA by a quarter.
 static int pick_shape(int max_rows, int V, int grid) {
@@ -324,32 +293,32 @@ static int pick_shape(int max_rows, int V, int grid) {
   return ((V + 255) / 256 >= grid) ? 4 : 3;
 }
 
-template <int AB, int BB, int WM>
+template <int AB, int BB>
 static hipError_t prepare_shape() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_gemm_kernel<AB, BB, WM>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, GemmCfg<AB, BB, WM>::kLdsBytes);
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_gemm_kernel<AB, BB>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, GemmCfg<AB, BB>::kLdsBytes);
 }
 
 hipError_t prepare_lmhead_gemm() {
-  hipError_t e = prepare_shape<2, 5, 2>();
-  if (e == hipSuccess) e = prepare_shape<2, 3, 2>();
-  if (e == hipSuccess) e = prepare_shape<2, 2, 2>();
-  if (e == hipSuccess) e = prepare_shape<4, 2, 2>();
+  hipError_t e = prepare_shape<2, 5>();
+  if (e == hipSuccess) e = prepare_shape<2, 3>();
+  if (e == hipSuccess) e = prepare_shape<2, 2>();
+  if (e == hipSuccess) e = prepare_shape<4, 2>();
   return e;
 }
 
-template <int AB, int BB, int WM>
+template <int AB, int BB>
 static void launch_shape(const GemmArgs& a, int grid, hipStream_t stream) {
-  constexpr int lds_bytes = GemmCfg<AB, BB, WM>::kLdsBytes;
-  hipLaunchKernelGGL((lmhead_gemm_kernel<AB, BB, WM>), dim3(grid), dim3(128 * WM), lds_bytes, stream, a);
+  constexpr int lds_bytes = GemmCfg<AB, BB>::kLdsBytes;
+  hipLaunchKernelGGL((lmhead_gemm_kernel<AB, BB>), dim3(grid), dim3(256), lds_bytes, stream, a);
 }
 
 hipError_t launch_lmhead_gemm(const GemmArgs& a, int max_rows, int grid, hipStream_t stream) {
   switch (pick_shape(max_rows, a.V, grid)) {
-    case 1: launch_shape<2, 5, 2>(a, grid, stream); break;
-    case 2: launch_shape<2, 3, 2>(a, grid, stream); break;
-    case 4: launch_shape<4, 2, 2>(a, grid, stream); break;
-    default: launch_shape<2, 2, 2>(a, grid, stream); break;
+    case 1: launch_shape<2, 5>(a, grid, stream); break;
+    case 2: launch_shape<2, 3>(a, grid, stream); break;
+    case 4: launch_shape<4, 2>(a, grid, stream); break;
+    default: launch_shape<2, 2>(a, grid, stream); break;
   }
   return hipGetLastError();
 }
