@@ -31,17 +31,21 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int kGK = 32;        // k per LDS tile: 64 bytes per row, four 16-byte chunks
-constexpr int kStages = 3;     // LDS stages (4 measured the same)
+constexpr int kGK = 64;        // k per LDS tile: 128 bytes per row = one cache line, eight 16-byte chunks
+constexpr int kRowB = 2 * kGK; // bytes of a tile row in LDS
 constexpr int kWM = 2;         // waves along the vocabulary rows; 2 more along the hidden rows
 
-// AB x BB blocks of 32 x 32 per wave, 2 x 2 waves per workgroup.
+// AB x BB blocks of 32 x 32 per wave, 2 x 2 waves per workgroup.  The W tiles (from HBM: long
+// latency) and the hidden-row tiles (shared by every workgroup: L2 hits) sit in rings of their own
+// depth, as deep as the 160 KB of LDS allow.
 template <int AB, int BB>
 struct GemmCfg {
   static constexpr int BM = 32 * AB * kWM, BN = 64 * BB;
-  static constexpr int kStageBytes = (BM + BN) * 64;
-  static constexpr int kLdsBytes = kStages * kStageBytes;
-  static constexpr int NAP = BM / 64, NBP = BN / 64;   // copy instructions per wave and tile (16 rows each)
+  static constexpr int kSA = (AB >= 4) ? 3 : 4, kSB = (BB >= 5) ? 2 : 3;   // ring depths, kSB <= kSA
+  static constexpr int kABytes = BM * kRowB, kBBytes = BN * kRowB;
+  static constexpr int kLdsBytes = kSA * kABytes + kSB * kBBytes;
+  static constexpr int NAP = BM / 32, NBP = BN / 32;   // copy instructions per wave and tile (8 rows each)
+  static_assert(kSB <= kSA && kLdsBytes <= 160 * 1024, "ring depths");
 };
 
 // One work unit of one wave: NB = number of this wave's column blocks that hold active rows
@@ -53,7 +57,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
                                           int wm, int wn, int l32, int lh) {
   using C = GemmCfg<AB, BB>;
   constexpr int NBR = NB > 0 ? NB : 1;
-  constexpr int NAP = C::NAP, NBP = C::NBP;
+  constexpr int NAP = C::NAP, NBP = C::NBP, kSA = C::kSA, kSB = C::kSB;
   const int KT = a.H / kGK;
   const int col0 = nt * C::BN + wn * 32 * BB;
 
@@ -65,72 +69,111 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[bm][bn][e] = 0.f;
 
-  // ---- copy side: a wave instruction fills 1 KB of LDS = 16 rows x 64 B; lane -> (row, chunk) ----
+  // ---- copy side: a wave instruction fills 1 KB of LDS = 8 rows x 128 B, each row one whole cache
+  // line of its matrix (half lines cost the L1 -> L2 path two requests per line: nothing of a
+  // line survives in L1 until the next tile); lane -> (row, 16-byte slot) ----------------------
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int prow = lane >> 2, pc = (lane & 3) ^ ((prow >> 2) & 3);   // chunk read from global for LDS slot lane & 3
-  // 32-bit element offsets from the two base pointers (V*H and rows*H stay below 2^31 elements)
+  // slot s of tile row r holds chunk s ^ ((r >> 1) & 7); r = (i*4 + wave)*8 + prow
+  const int prow = lane >> 3, pc = (lane & 7) ^ ((wave & 1) * 4 + (prow >> 1));
+  // byte offsets from the two base pointers (V*H and rows*H elements stay below 2^31)
   uint32_t ao[NAP], bo[NBP];
 #pragma unroll
   for (int i = 0; i < NAP; ++i)
-    ao[i] = (uint32_t)min(mt * C::BM + (i * 4 + wave) * 16 + prow, a.V - 1) * (uint32_t)a.H + pc * 8;
+    ao[i] = ((uint32_t)min(mt * C::BM + (i * 4 + wave) * 8 + prow, a.V - 1) * (uint32_t)a.H + pc * 8) * 2u;
 #pragma unroll
   for (int i = 0; i < NBP; ++i)
-    bo[i] = (uint32_t)a.row_list[min(nt * C::BN + (i * 4 + wave) * 16 + prow, n_act - 1)] * (uint32_t)a.H + pc * 8;
+    bo[i] = ((uint32_t)a.row_list[min(nt * C::BN + (i * 4 + wave) * 8 + prow, n_act - 1)] * (uint32_t)a.H + pc * 8) * 2u;
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
-#define DDD_ISSUE(T, STG)                                                                                           \
-  {                                                                                                                 \
-    _Pragma("unroll") for (int i = 0; i < NAP; ++i) __builtin_amdgcn_global_load_lds(                               \
-        (gptr_t)(a.W + ao[i] + (T) * kGK), (lptr_t)(ldsb + (STG) * C::kStageBytes + (i * 4 + wave) * 1024), 16, 0, 0);  \
-    _Pragma("unroll") for (int i = 0; i < NBP; ++i) __builtin_amdgcn_global_load_lds(                               \
-        (gptr_t)(a.hid + bo[i] + (T) * kGK),                                                                        \
-        (lptr_t)(ldsb + (STG) * C::kStageBytes + C::BM * 64 + (i * 4 + wave) * 1024), 16, 0, 0);                     \
+  const unsigned char* Wb = reinterpret_cast<const unsigned char*>(a.W);
+  const unsigned char* Hb = reinterpret_cast<const unsigned char*>(a.hid);
+  unsigned char* const ldsA = ldsb;
+  unsigned char* const ldsB = ldsb + kSA * C::kABytes;
+#define DDD_ISSUE_A(T, STG)                                                                          \
+  _Pragma("unroll") for (int i = 0; i < NAP; ++i) __builtin_amdgcn_global_load_lds(                  \
+      (gptr_t)(Wb + (size_t)(T) * kRowB + ao[i]), (lptr_t)(ldsA + (STG) * C::kABytes + (i * 4 + wave) * 1024), 16, 0, 0);
+#define DDD_ISSUE_B(T, STG)                                                                          \
+  _Pragma("unroll") for (int i = 0; i < NBP; ++i) __builtin_amdgcn_global_load_lds(                  \
+      (gptr_t)(Hb + (size_t)(T) * kRowB + bo[i]), (lptr_t)(ldsB + (STG) * C::kBBytes + (i * 4 + wave) * 1024), 16, 0, 0);
+  // ---- fragment side: lane (l32, lh) of block b reads row b*32 + l32, chunk ks*2 + lh ------------
+  const int swz = (l32 >> 1) & 7;   // every tile / block base is a multiple of 32 rows
+  int offk[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) offk[ks] = ((ks * 2 + lh) ^ swz) * 16;
+  const int arow = (wm * 32 * AB + l32) * kRowB, brow = (wn * 32 * BB + l32) * kRowB;
+#define DDD_VMCNT(N) (((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
+#define DDD_READ(AF, BF, SA, SB, OK)                                                                          \
+  {                                                                                                           \
+    _Pragma("unroll") for (int b = 0; b < AB; ++b) AF[b] =                                                    \
+        __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>((SA) + arow + b * 32 * kRowB + (OK)));     \
+    _Pragma("unroll") for (int b = 0; b < NBR; ++b) BF[b] =                                                   \
+        __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>((SB) + brow + b * 32 * kRowB + (OK)));     \
   }
-  // ---- fragment side: lane (l32, lh) of block b reads row b*32 + l32, chunk ks*2 + lh -------------
-  const int swz = (l32 >> 2) & 3;   // every tile / block base is a multiple of 16 rows
-  const int offk0 = ((0 + lh) ^ swz) * 16, offk1 = ((2 + lh) ^ swz) * 16;
-  const int arow = (wm * 32 * AB + l32) * 64, brow = C::BM * 64 + (wn * 32 * BB + l32) * 64;
-  // s_waitcnt vmcnt(n): the loads of the tiles that may stay in flight, per thread
-  constexpr int kVm = (NAP + NBP) * (kStages - 2);
-  constexpr int kWaitSome = (kVm & 15) | ((kVm >> 4) << 14) | (7 << 4) | (15 << 8);
-  constexpr int kWaitAll = (0 & 15) | (7 << 4) | (15 << 8);
-
+#define DDD_MFMA(AF, BF)                                                                                      \
+  {                                                                                                           \
+    _Pragma("unroll") for (int bn = 0; bn < NBR; ++bn) _Pragma("unroll") for (int bm = 0; bm < AB; ++bm)      \
+        acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(AF[bm], BF[bn], acc[bm][bn], 0, 0, 0);          \
+  }
+  // One step = 16 k: the fragments of the next step are read (into the other of two register
+  // sets) in front of the MFMAs of this one, so the LDS latency runs under the matrix cores (with
+  // one wave per SIMD nothing else would hide it).  The wait for a set is written out, at the end
+  // of the MFMA group its reads ran under: left to the compiler it lands behind the reads of the
+  // other set and, after an LDS-direct load, always waits for every read in flight.
+  constexpr int kLgkm0 = (7 << 4) | (0 << 8);     // lgkmcnt(0), expcnt free; the vmcnt bits are added
+#define DDD_WAIT(VM) __builtin_amdgcn_s_waitcnt(kLgkm0 | ((VM) & 15) | (((VM) >> 4) << 14))
+#define DDD_STEP(AFN, BFN, SA, SB, OK, AFC, BFC)  \
+  if (NB > 0) {                                   \
+    DDD_READ(AFN, BFN, SA, SB, OK);               \
+    __builtin_amdgcn_sched_barrier(0);            \
+    DDD_MFMA(AFC, BFC);                           \
+    __builtin_amdgcn_sched_barrier(0);            \
+  }
+  // Copies are issued per tile as (hidden rows, then W rows); in flight behind the tile that is
+  // needed next are, per thread, at most kInFlight of them.
+  constexpr int kInFlight = (kSB < kSA ? NAP : 0) + (kSB - 2) * (NAP + NBP);
+  static_assert(kInFlight < 64 && (kSA - 1) * NAP + (kSB - 1) * NBP < 64, "vmcnt is a 6-bit counter");
+  bf16x8 af0[AB], bf0[NBR], af1[AB], bf1[NBR];
   __syncthreads();            // every wave is done with the LDS tiles of the previous unit
 #pragma unroll
-  for (int p = 0; p < kStages - 1; ++p) DDD_ISSUE(min(p, KT - 1), p);
-  int stg = 0;
-  for (int kt = 0; kt < KT; ++kt) {
-    __builtin_amdgcn_s_waitcnt(kWaitSome);   // this thread's loads of tile kt have landed (later tiles' may be in flight)
-    __builtin_amdgcn_s_barrier();            // ... and everybody's; everybody is done reading tile kt-1 (a plain
-                                             // barrier: __syncthreads() would wait for every load in flight)
-    const int stg2 = (stg == 0) ? kStages - 1 : stg - 1;
-    DDD_ISSUE(min(kt + kStages - 1, KT - 1), stg2);   // always issued: the count of loads in flight stays static
-    if (NB > 0) {
-      const unsigned char* sb = ldsb + stg * C::kStageBytes;
-      bf16x8 af[2][AB], bf[2][NBR];
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const int ok = ks ? offk1 : offk0;
-#pragma unroll
-        for (int b = 0; b < AB; ++b)
-          af[ks][b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sb + arow + b * 32 * 64 + ok));
-#pragma unroll
-        for (int b = 0; b < NBR; ++b)
-          bf[ks][b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sb + brow + b * 32 * 64 + ok));
-      }
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int bn = 0; bn < NBR; ++bn)
-#pragma unroll
-          for (int bm = 0; bm < AB; ++bm)
-            acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][bm], bf[ks][bn], acc[bm][bn], 0, 0, 0);
-    }
-    stg = (stg == kStages - 1) ? 0 : stg + 1;
+  for (int p = 0; p < kSA; ++p) {
+    if (p < kSB) DDD_ISSUE_B(min(p, KT - 1), p);
+    DDD_ISSUE_A(min(p, KT - 1), p);
   }
-  __builtin_amdgcn_s_waitcnt(kWaitAll);   // the clamped extra loads have landed before the LDS is reused
-#undef DDD_ISSUE
+  __builtin_amdgcn_s_waitcnt(DDD_VMCNT((kSA - 1) * NAP + (kSB - 1) * NBP));   // tile 0 has landed
+  __builtin_amdgcn_s_barrier();
+  if (NB > 0) DDD_READ(af0, bf0, ldsA, ldsB, offk[0]);
+  DDD_WAIT(63);
+  int sa = 0, sb = 0;         // ring slots of tile kt
+  for (int kt = 0; kt < KT; ++kt) {
+    const unsigned char* pa = ldsA + sa * C::kABytes;
+    const unsigned char* pb = ldsB + sb * C::kBBytes;
+    const int sa1 = (sa == kSA - 1) ? 0 : sa + 1, sb1 = (sb == kSB - 1) ? 0 : sb + 1;
+    DDD_STEP(af1, bf1, pa, pb, offk[1], af0, bf0);
+    DDD_WAIT(63);
+    DDD_STEP(af0, bf0, pa, pb, offk[2], af1, bf1);
+    DDD_WAIT(63);
+    DDD_STEP(af1, bf1, pa, pb, offk[3], af0, bf0);
+    // every read of tile kt is back; this thread's copies of tile kt+1 have landed ...
+    DDD_WAIT(kInFlight);
+    // ... and everybody's; everybody is done with the slots of tile kt, which the next copies overwrite
+    // (a plain barrier: __syncthreads() would wait for every load in flight)
+    __builtin_amdgcn_s_barrier();
+    DDD_ISSUE_B(min(kt + kSB, KT - 1), sb);   // past the end: the last tile again, so the counts stay static
+    DDD_ISSUE_A(min(kt + kSA, KT - 1), sa);
+    DDD_STEP(af0, bf0, ldsA + sa1 * C::kABytes, ldsB + sb1 * C::kBBytes, offk[0], af1, bf1);
+    DDD_WAIT(63);
+    sa = sa1;
+    sb = sb1;
+  }
+  __builtin_amdgcn_s_waitcnt(DDD_VMCNT(0));   // the copies past the end have landed before the LDS is reused
+#undef DDD_STEP
+#undef DDD_WAIT
+#undef DDD_READ
+#undef DDD_MFMA
+#undef DDD_VMCNT
+#undef DDD_ISSUE_A
+#undef DDD_ISSUE_B
 
   if (NB == 0) return;
   // accumulator register q*4+e of block (bm, bn): vocabulary row vb + bm*32 + q*8 + e, hidden row column l32
@@ -233,7 +276,7 @@ __device__ __forceinline__ void gemm_units(const GemmArgs& a, unsigned char* lds
 // K tile through LDS.
 template <int AB, int BB>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(GemmArgs a) {
-  extern __shared__ __align__(16) unsigned char lds[];     // [kStages][BM + BN][64 B] of the chosen width
+  extern __shared__ __align__(16) unsigned char lds[];     // the two tile rings of the chosen width
 
   const int n_act = *a.n_act_ptr;
   if (n_act <= 0) return;                                  // uniform
