@@ -90,12 +90,13 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
   const unsigned char* Hb = reinterpret_cast<const unsigned char*>(a.hid);
   unsigned char* const ldsA = ldsb;
   unsigned char* const ldsB = ldsb + kSA * C::kABytes;
-#define DDD_ISSUE_A(T, STG)                                                                          \
-  _Pragma("unroll") for (int i = 0; i < NAP; ++i) __builtin_amdgcn_global_load_lds(                  \
-      (gptr_t)(Wb + (size_t)(T) * kRowB + ao[i]), (lptr_t)(ldsA + (STG) * C::kABytes + (i * 4 + wave) * 1024), 16, 0, 0);
-#define DDD_ISSUE_B(T, STG)                                                                          \
-  _Pragma("unroll") for (int i = 0; i < NBP; ++i) __builtin_amdgcn_global_load_lds(                  \
-      (gptr_t)(Hb + (size_t)(T) * kRowB + bo[i]), (lptr_t)(ldsB + (STG) * C::kBBytes + (i * 4 + wave) * 1024), 16, 0, 0);
+  // copy instruction i of a tile of W (A) / of the hidden rows (B)
+#define DDD_COPY_A(T, STG, i)                                                                        \
+  __builtin_amdgcn_global_load_lds((gptr_t)(Wb + (size_t)(T) * kRowB + ao[i]),                       \
+                                   (lptr_t)(ldsA + (STG) * C::kABytes + ((i) * 4 + wave) * 1024), 16, 0, 0)
+#define DDD_COPY_B(T, STG, i)                                                                        \
+  __builtin_amdgcn_global_load_lds((gptr_t)(Hb + (size_t)(T) * kRowB + bo[i]),                       \
+                                   (lptr_t)(ldsB + (STG) * C::kBBytes + ((i) * 4 + wave) * 1024), 16, 0, 0)
   // ---- fragment side: lane (l32, lh) of block b reads row b*32 + l32, chunk ks*2 + lh ------------
   const int swz = (l32 >> 1) & 7;   // every tile / block base is a multiple of 32 rows
   int offk[4];
@@ -110,59 +111,82 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
     _Pragma("unroll") for (int b = 0; b < NBR; ++b) BF[b] =                                                   \
         __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>((SB) + brow + b * 32 * kRowB + (OK)));     \
   }
-#define DDD_MFMA(AF, BF)                                                                                      \
-  {                                                                                                           \
-    _Pragma("unroll") for (int bn = 0; bn < NBR; ++bn) _Pragma("unroll") for (int bm = 0; bm < AB; ++bm)      \
-        acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(AF[bm], BF[bn], acc[bm][bn], 0, 0, 0);          \
-  }
   // One step = 16 k: the fragments of the next step are read (into the other of two register
   // sets) in front of the MFMAs of this one, so the LDS latency runs under the matrix cores (with
   // one wave per SIMD nothing else would hide it).  The wait for a set is written out, at the end
   // of the MFMA group its reads ran under: left to the compiler it lands behind the reads of the
   // other set and, after an LDS-direct load, always waits for every read in flight.
+  // The copy instructions I0 <= i < I1 of the step are spread between its MFMAs: issued in one
+  // burst they fill the queue of the address unit, and a wave that cannot issue its next load
+  // cannot issue its next MFMA either.
   constexpr int kLgkm0 = (7 << 4) | (0 << 8);     // lgkmcnt(0), expcnt free; the vmcnt bits are added
+  constexpr int NM = AB * NBR;                    // MFMAs of a step
 #define DDD_WAIT(VM) __builtin_amdgcn_s_waitcnt(kLgkm0 | ((VM) & 15) | (((VM) >> 4) << 14))
-#define DDD_STEP(AFN, BFN, SA, SB, OK, AFC, BFC)  \
-  if (NB > 0) {                                   \
-    DDD_READ(AFN, BFN, SA, SB, OK);               \
-    __builtin_amdgcn_sched_barrier(0);            \
-    DDD_MFMA(AFC, BFC);                           \
-    __builtin_amdgcn_sched_barrier(0);            \
+#define DDD_STEP(AFN, BFN, SA, SB, OK, AFC, BFC, COPY, T, STG, I0, I1)                                         \
+  if (NB > 0) {                                                                                                \
+    DDD_READ(AFN, BFN, SA, SB, OK);                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                                         \
+    _Pragma("unroll") for (int mi = 0; mi < NM; ++mi) {                                                        \
+      acc[mi % AB][mi / AB] =                                                                                  \
+          __builtin_amdgcn_mfma_f32_32x32x16_bf16(AFC[mi % AB], BFC[mi / AB], acc[mi % AB][mi / AB], 0, 0, 0); \
+      _Pragma("unroll") for (int ci = (I0); ci < (I1); ++ci) if (((ci - (I0)) * NM) / ((I1) - (I0)) == mi) {   \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+        COPY(T, STG, ci);                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+      }                                                                                                        \
+    }                                                                                                          \
+    __builtin_amdgcn_sched_barrier(0);                                                                         \
+  } else {                                                                                                     \
+    _Pragma("unroll") for (int ci = (I0); ci < (I1); ++ci) COPY(T, STG, ci);                                   \
   }
-  // Copies are issued per tile as (hidden rows, then W rows); in flight behind the tile that is
-  // needed next are, per thread, at most kInFlight of them.
-  constexpr int kInFlight = (kSB < kSA ? NAP : 0) + (kSB - 2) * (NAP + NBP);
-  static_assert(kInFlight < 64 && (kSA - 1) * NAP + (kSB - 1) * NBP < 64, "vmcnt is a 6-bit counter");
+  // Copy schedule.  The barrier of tile kt (in front of its last step) frees the ring slots of
+  // tile kt; the hidden rows of tile kt+kSB go there during that last step and the first step of
+  // tile kt+1, the W rows of tile kt+kSA during the two middle steps of tile kt+1.  Behind the
+  // copies of tile kt+1, which the wait of tile kt needs, each thread then has issued kInFlight more.
+  constexpr int NBa = NBP / 2, NAa = NAP / 2;
+  constexpr int kInFlight = (kSA - 2) * (NAP + NBP) < NAP + (kSB - 2) * (NAP + NBP) ? (kSA - 2) * (NAP + NBP)
+                                                                                      : NAP + (kSB - 2) * (NAP + NBP);
+  static_assert(kInFlight < 64, "vmcnt is a 6-bit counter");
   bf16x8 af0[AB], bf0[NBR], af1[AB], bf1[NBR];
   __syncthreads();            // every wave is done with the LDS tiles of the previous unit
+  // everything the steps before tile 0 would have issued
 #pragma unroll
-  for (int p = 0; p < kSA; ++p) {
-    if (p < kSB) DDD_ISSUE_B(min(p, KT - 1), p);
-    DDD_ISSUE_A(min(p, KT - 1), p);
+  for (int p = 0; p < kSA - 1; ++p) {
+    if (p < kSB - 1) {
+#pragma unroll
+      for (int i = 0; i < NBP; ++i) DDD_COPY_B(min(p, KT - 1), p, i);
+    }
+#pragma unroll
+    for (int i = 0; i < NAP; ++i) DDD_COPY_A(min(p, KT - 1), p, i);
   }
-  __builtin_amdgcn_s_waitcnt(DDD_VMCNT((kSA - 1) * NAP + (kSB - 1) * NBP));   // tile 0 has landed
+#pragma unroll
+  for (int i = 0; i < NBa; ++i) DDD_COPY_B(min(kSB - 1, KT - 1), kSB - 1, i);
+  __builtin_amdgcn_s_waitcnt(DDD_VMCNT(0));       // all of it has landed: the static count below holds from tile 0 on
   __builtin_amdgcn_s_barrier();
   if (NB > 0) DDD_READ(af0, bf0, ldsA, ldsB, offk[0]);
   DDD_WAIT(63);
-  int sa = 0, sb = 0;         // ring slots of tile kt
+  int sa = 0, sb = 0;                             // ring slots of tile kt
+  int sap = kSA - 1, sbp = kSB - 1;               // ... and of tile kt-1
   for (int kt = 0; kt < KT; ++kt) {
     const unsigned char* pa = ldsA + sa * C::kABytes;
     const unsigned char* pb = ldsB + sb * C::kBBytes;
     const int sa1 = (sa == kSA - 1) ? 0 : sa + 1, sb1 = (sb == kSB - 1) ? 0 : sb + 1;
-    DDD_STEP(af1, bf1, pa, pb, offk[1], af0, bf0);
+    const int tb = min(kt + kSB - 1, KT - 1), ta = min(kt + kSA - 1, KT - 1);   // past the end: the last tile again
+    DDD_STEP(af1, bf1, pa, pb, offk[1], af0, bf0, DDD_COPY_B, tb, sbp, NBa, NBP);
     DDD_WAIT(63);
-    DDD_STEP(af0, bf0, pa, pb, offk[2], af1, bf1);
+    DDD_STEP(af0, bf0, pa, pb, offk[2], af1, bf1, DDD_COPY_A, ta, sap, 0, NAa);
     DDD_WAIT(63);
-    DDD_STEP(af1, bf1, pa, pb, offk[3], af0, bf0);
+    DDD_STEP(af1, bf1, pa, pb, offk[3], af0, bf0, DDD_COPY_A, ta, sap, NAa, NAP);
     // every read of tile kt is back; this thread's copies of tile kt+1 have landed ...
     DDD_WAIT(kInFlight);
     // ... and everybody's; everybody is done with the slots of tile kt, which the next copies overwrite
     // (a plain barrier: __syncthreads() would wait for every load in flight)
     __builtin_amdgcn_s_barrier();
-    DDD_ISSUE_B(min(kt + kSB, KT - 1), sb);   // past the end: the last tile again, so the counts stay static
-    DDD_ISSUE_A(min(kt + kSA, KT - 1), sa);
-    DDD_STEP(af0, bf0, ldsA + sa1 * C::kABytes, ldsB + sb1 * C::kBBytes, offk[0], af1, bf1);
+    DDD_STEP(af0, bf0, ldsA + sa1 * C::kABytes, ldsB + sb1 * C::kBBytes, offk[0], af1, bf1, DDD_COPY_B,
+             min(kt + kSB, KT - 1), sb, 0, NBa);
     DDD_WAIT(63);
+    sap = sa;
+    sbp = sb;
     sa = sa1;
     sb = sb1;
   }
@@ -170,10 +194,9 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
 #undef DDD_STEP
 #undef DDD_WAIT
 #undef DDD_READ
-#undef DDD_MFMA
 #undef DDD_VMCNT
-#undef DDD_ISSUE_A
-#undef DDD_ISSUE_B
+#undef DDD_COPY_A
+#undef DDD_COPY_B
 
   if (NB == 0) return;
   // accumulator register q*4+e of block (bm, bn): vocabulary row vb + bm*32 + q*8 + e, hidden row column l32
