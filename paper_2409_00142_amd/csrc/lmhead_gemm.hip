@@ -48,18 +48,18 @@ struct GemmCfg {
   static_assert(kSB <= kSA && kLdsBytes <= 160 * 1024, "ring depths");
 };
 
-// One work unit of one wave: NB = number of this wave's column blocks that hold active rows
-// (0 <= NB <= BB; a wave with NB == 0 still copies tiles and meets the barriers).  Every value of
-// NB has its own fully unrolled loop, so the accumulators stay in place (no data-dependent
-// branches around the MFMAs).
+// One work unit of one wave.  The column tile starts at active row tile_col0; this wave multiplies
+// NB blocks of 32 rows from block wblk0 of the tile on (0 <= NB <= BB; a wave with NB == 0 still
+// copies tiles and meets the barriers).  Every value of NB has its own fully unrolled loop, so the
+// accumulators stay in place (no data-dependent branches around the MFMAs).
 template <int AB, int BB, int NB>
-__device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb, int mt, int nt, int n_act, int tid,
-                                          int wm, int wn, int l32, int lh) {
+__device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb, int mt, int tile_col0, int wblk0,
+                                          int n_act, int tid, int wm, int l32, int lh) {
   using C = GemmCfg<AB, BB>;
   constexpr int NBR = NB > 0 ? NB : 1;
   constexpr int NAP = C::NAP, NBP = C::NBP, kSA = C::kSA, kSB = C::kSB;
   const int KT = a.H / kGK;
-  const int col0 = nt * C::BN + wn * 32 * BB;
+  const int col0 = tile_col0 + wblk0 * 32;
 
   f32x16 acc[AB][NBR];
 #pragma unroll
@@ -83,7 +83,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
     ao[i] = ((uint32_t)min(mt * C::BM + (i * 4 + wave) * 8 + prow, a.V - 1) * (uint32_t)a.H + pc * 8) * 2u;
 #pragma unroll
   for (int i = 0; i < NBP; ++i)
-    bo[i] = ((uint32_t)a.row_list[min(nt * C::BN + (i * 4 + wave) * 8 + prow, n_act - 1)] * (uint32_t)a.H + pc * 8) * 2u;
+    bo[i] = ((uint32_t)a.row_list[min(tile_col0 + (i * 4 + wave) * 8 + prow, n_act - 1)] * (uint32_t)a.H + pc * 8) * 2u;
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
   const unsigned char* Wb = reinterpret_cast<const unsigned char*>(a.W);
@@ -102,7 +102,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
   int offk[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) offk[ks] = ((ks * 2 + lh) ^ swz) * 16;
-  const int arow = (wm * 32 * AB + l32) * kRowB, brow = (wn * 32 * BB + l32) * kRowB;
+  const int arow = (wm * 32 * AB + l32) * kRowB, brow = (wblk0 * 32 + l32) * kRowB;
 #define DDD_VMCNT(N) (((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
 #define DDD_READ(AF, BF, SA, SB, OK)                                                                          \
   {                                                                                                           \
@@ -264,7 +264,10 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
   }
 }
 
-// All work units of one workgroup for a column-tile width of 64 * BB rows.
+// All work units of one workgroup for column tiles of at most 64 * BB rows.  The blocks of 32
+// active rows are dealt evenly: to the column tiles, and inside a tile to the two waves along the
+// hidden rows, so that 400 active rows cost 7 + 6 blocks in two tiles of (4, 3) and (3, 3) per
+// wave pair instead of 10 + 3 in tiles of (5, 5) and (3, 0).
 template <int AB, int BB>
 __device__ __forceinline__ void gemm_units(const GemmArgs& a, unsigned char* lds, int n_act) {
   using C = GemmCfg<AB, BB>;
@@ -272,23 +275,26 @@ __device__ __forceinline__ void gemm_units(const GemmArgs& a, unsigned char* lds
   const int wm = wave % kWM, wn = wave / kWM;
   const int l32 = lane & 31, lh = lane >> 5;
   const int nmt = (a.V + C::BM - 1) / C::BM;
-  const int NT = (n_act + C::BN - 1) / C::BN;
+  const int nblk_all = (n_act + 31) >> 5;
+  const int NT = (nblk_all + 2 * BB - 1) / (2 * BB);
+  const int bpt = (nblk_all + NT - 1) / NT;          // blocks per column tile, <= 2 * BB
   const int nunits = nmt * NT;
   const int G = gridDim.x;
   const int vg = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);   // neighbours on one XCD get neighbouring units
 
   for (int u = vg; u < nunits; u += G) {
     const int mt = u / NT, nt = u - mt * NT;
-    // column blocks of this wave that hold at least one active row (wave-uniform)
-    const int col0 = nt * C::BN + wn * 32 * BB;
-    const int nb_act = min(BB, max(0, (n_act - col0 + 31) / 32));
-    switch (nb_act) {
-      case 0: gemm_unit<AB, BB, 0>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 1: gemm_unit<AB, BB, 1>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 2: gemm_unit<AB, BB, (BB >= 2 ? 2 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 3: gemm_unit<AB, BB, (BB >= 3 ? 3 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      case 4: gemm_unit<AB, BB, (BB >= 4 ? 4 : BB)>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
-      default: gemm_unit<AB, BB, BB>(a, lds, mt, nt, n_act, tid, wm, wn, l32, lh); break;
+    const int nblk = min(bpt, nblk_all - nt * bpt);  // >= 1
+    const int h0 = (nblk + 1) >> 1;
+    const int wblk0 = wn ? h0 : 0, nb = wn ? nblk - h0 : h0;   // wave-uniform
+    const int tc0 = nt * bpt * 32;
+    switch (nb) {
+      case 0: gemm_unit<AB, BB, 0>(a, lds, mt, tc0, wblk0, n_act, tid, wm, l32, lh); break;
+      case 1: gemm_unit<AB, BB, 1>(a, lds, mt, tc0, wblk0, n_act, tid, wm, l32, lh); break;
+      case 2: gemm_unit<AB, BB, (BB >= 2 ? 2 : BB)>(a, lds, mt, tc0, wblk0, n_act, tid, wm, l32, lh); break;
+      case 3: gemm_unit<AB, BB, (BB >= 3 ? 3 : BB)>(a, lds, mt, tc0, wblk0, n_act, tid, wm, l32, lh); break;
+      case 4: gemm_unit<AB, BB, (BB >= 4 ? 4 : BB)>(a, lds, mt, tc0, wblk0, n_act, tid, wm, l32, lh); break;
+      default: gemm_unit<AB, BB, BB>(a, lds, mt, tc0, wblk0, n_act, tid, wm, l32, lh); break;
     }
   }
 }
