@@ -41,7 +41,7 @@ constexpr int kWM = 2;         // waves along the vocabulary rows; 2 more along 
 template <int AB, int BB>
 struct GemmCfg {
   static constexpr int BM = 32 * AB * kWM, BN = 64 * BB;
-  static constexpr int kSA = (AB >= 4) ? 3 : 4, kSB = (BB >= 5) ? 2 : 3;   // ring depths, kSB <= kSA
+  static constexpr int kSA = (AB >= 4) ? 3 : 4, kSB = (BB >= 4) ? 2 : 3;   // ring depths, kSB <= kSA
   static constexpr int kABytes = BM * kRowB, kBBytes = BN * kRowB;
   static constexpr int kLdsBytes = kSA * kABytes + kSB * kBBytes;
   static constexpr int NAP = BM / 32, NBP = BN / 32;   // copy instructions per wave and tile (8 rows each)
@@ -269,15 +269,13 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
 // hidden rows, so that 400 active rows cost 7 + 6 blocks in two tiles of (4, 3) and (3, 3) per
 // wave pair instead of 10 + 3 in tiles of (5, 5) and (3, 0).
 template <int AB, int BB>
-__device__ __forceinline__ void gemm_units(const GemmArgs& a, unsigned char* lds, int n_act) {
+__device__ __forceinline__ void gemm_units(const GemmArgs& a, unsigned char* lds, int n_act, int NT, int bpt) {
   using C = GemmCfg<AB, BB>;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave % kWM, wn = wave / kWM;
   const int l32 = lane & 31, lh = lane >> 5;
   const int nmt = (a.V + C::BM - 1) / C::BM;
   const int nblk_all = (n_act + 31) >> 5;
-  const int NT = (nblk_all + 2 * BB - 1) / (2 * BB);
-  const int bpt = (nblk_all + NT - 1) / NT;          // blocks per column tile, <= 2 * BB
   const int nunits = nmt * NT;
   const int G = gridDim.x;
   const int vg = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);   // neighbours on one XCD get neighbouring units
@@ -300,23 +298,29 @@ __device__ __forceinline__ void gemm_units(const GemmArgs& a, unsigned char* lds
 }
 
 // BB is the widest column tile the launch may need (64 * BB rows per workgroup).  The number of
-// active rows is only known on the device, so the kernel narrows the column tile itself when few
-// rows are left: with 64 active rows a 320-row tile would still copy 320 (repeated) rows per
-// K tile through LDS.
+// active rows is only known on the device, so the kernel picks the column tiling itself: as few
+// tiles as BB allows, the blocks dealt evenly to them, and the narrowest tile that holds a share
+// (with 64 active rows a 320-row tile would still copy 320 repeated rows per K tile through LDS).
 template <int AB, int BB>
 __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(GemmArgs a) {
   extern __shared__ __align__(16) unsigned char lds[];     // the two tile rings of the chosen width
 
   const int n_act = *a.n_act_ptr;
   if (n_act <= 0) return;                                  // uniform
-  if (BB >= 5 && n_act > 192)
-    gemm_units<AB, BB>(a, lds, n_act);
-  else if (BB >= 3 && n_act > 128)
-    gemm_units<AB, (BB >= 3 ? 3 : BB)>(a, lds, n_act);
-  else if (BB >= 2 && n_act > 64)
-    gemm_units<AB, (BB >= 2 ? 2 : BB)>(a, lds, n_act);
+  const int nblk_all = (n_act + 31) >> 5;
+  const int NT = (nblk_all + 2 * BB - 1) / (2 * BB);
+  const int bpt = (nblk_all + NT - 1) / NT;                // blocks per column tile, <= 2 * BB
+  const int bb = (bpt + 1) >> 1;                           // blocks per wave, <= BB
+  if (BB >= 5 && bb >= 5)
+    gemm_units<AB, (BB >= 5 ? 5 : BB)>(a, lds, n_act, NT, bpt);
+  else if (BB >= 4 && bb == 4)
+    gemm_units<AB, (BB >= 4 ? 4 : BB)>(a, lds, n_act, NT, bpt);
+  else if (BB >= 3 && bb == 3)
+    gemm_units<AB, (BB >= 3 ? 3 : BB)>(a, lds, n_act, NT, bpt);
+  else if (BB >= 2 && bb == 2)
+    gemm_units<AB, (BB >= 2 ? 2 : BB)>(a, lds, n_act, NT, bpt);
   else
-    gemm_units<AB, 1>(a, lds, n_act);
+    gemm_units<AB, 1>(a, lds, n_act, NT, bpt);
 }
 
 // ---- compaction of the active rows ------------------------------------------------------------
