@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--profile-iters", type=int, default=200)
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="one captured hipGraph per round (default) or plain stream launches")
+    ap.add_argument("--pack-weights", choices=["auto", "on", "off"], default="auto",
+                    help="tile-major copy of W for the GEMM path (ddd_weights_pack); auto: when the GEMM path is used "
+                         "and W is larger than the 256 MB Infinity Cache, i.e. really streams from HBM")
     ap.add_argument("--traffic", default=None,
                     help="JSON file with the HBM bytes per launch from rocprofv3 --pmc runs "
                          "(default: profiles/traffic_<workload>.json)")
@@ -99,6 +102,12 @@ def main():
     log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s; "
         f"stream slices={D.ddd_num_slices(g.ctx)}")
 
+    uses_gemm = wl.B * wl.k > 16 or wl.k > 16
+    pack = args.pack_weights == "on" or (args.pack_weights == "auto" and uses_gemm and wl.V * wl.H * 2 > 256 * 2**20)
+    if pack:
+        D.ddd_weights_pack(g.ctx, g.W)
+        torch.cuda.synchronize()
+        log("[bench] GEMM path reads W from its tile-major copy (ddd_weights_pack)")
     side = torch.cuda.Stream()
     if args.launch == "graph":
         g.capture(side)
@@ -229,6 +238,7 @@ def main():
         "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
                    "threshold": thr, "check_mask": int(wl.check_mask), "mode": args.mode, "hidden_gain": wl.gain,
                    "launch": "one hipGraph per round" if args.launch == "graph" else "stream launches",
+                   "packed_weights": bool(pack),
                    "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},
                    "accept_len_hist": {str(d): int(c) for d, c in enumerate(accept_hist) if c},
                    "executed_depth_steps": exec_steps, "executed_batch_steps": batch_steps,

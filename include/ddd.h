@@ -189,6 +189,18 @@ int ddd_round_capture(ddd_ctx* ctx, const void* W_bf16, ddd_state* st, ddd_tree*
                       float* logits_dbg, float* lse_dbg, void* stream);
 int ddd_round_launch(ddd_ctx* ctx, void* stream);
 
+/* Optional tile-major copy of the LM-head weights for the calls that take the MFMA path (more
+ * than DDD_STREAM_ROWS rows, or wide beams).  Section 1's projection reads W once per draft call;
+ * when W is too large for the chip's caches (a 128k vocabulary: 1 GB) the MFMA path would fetch it
+ * from HBM in 128-byte pieces 2*H bytes apart, and reads the same bytes a quarter faster from a copy
+ * whose tiles are contiguous.  Results are bit-identical with and without the copy.
+ *   W_bf16  device, bf16 [V,H] row-major; NULL forgets the copy and frees it.
+ * The context allocates ceil(V/256)*256*H*2 bytes on first use, fills them on `stream`, and from
+ * then on reads the copy whenever a call passes this same pointer as W (the row-major W is still
+ * needed: calls of up to DDD_STREAM_ROWS rows stream it).  Call again after changing W's contents,
+ * and before ddd_round_capture (a captured graph keeps the operands it was captured with). */
+int ddd_weights_pack(ddd_ctx* ctx, const void* W_bf16, void* stream);
+
 /* Introspection used by the benchmark: number of weight-stream workgroups (slices). */
 int ddd_num_slices(const ddd_ctx* ctx);
 

@@ -103,6 +103,7 @@ def load_library() -> C.CDLL:
         "ddd_synth_read_stream": (C.c_int, [vp, sz, vp, i32, vp]),
         "ddd_synth_mfma_rate": (C.c_int, [vp, i32, i32, vp]),
         "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
+        "ddd_weights_pack": (C.c_int, [vp, vp, vp]),
         "ddd_profile_lmhead": (C.c_int, [vp, vp, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
     }
     for name, (res, args) in sig.items():
@@ -298,6 +299,12 @@ def ddd_synth_round_stats(round_ctr, steps, accept_len, B, depth_hist, accept_hi
                                                 _ptr(accept_hist), _ptr(batch_depth_hist),
                                                 current_stream() if stream is None else stream),
            "ddd_synth_round_stats")
+
+
+def ddd_weights_pack(ctx, W, stream=None):
+    """Tile-major copy of W for the GEMM path (W=None forgets it)."""
+    _check(load_library().ddd_weights_pack(ctx, _ptr(W), current_stream() if stream is None else stream),
+           "ddd_weights_pack")
 
 
 def ddd_profile_lmhead(ctx, W, hid, n_rows, iters, stream=None):

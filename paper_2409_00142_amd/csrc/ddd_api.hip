@@ -27,6 +27,8 @@ struct ddd_ctx {
   float* grp_max;       // [B*k][ngrp] per-group max / sum-exp of the GEMM path
   float* grp_sum;
   int ngrp;
+  const void* pack_src; // W pointer whose tile-major copy is in pack (null: none)
+  uint16_t* pack;       // [ceil(V/256)*256][H] tile-major copy for the GEMM path, owned
   hipGraph_t graph;
   hipGraphExec_t graph_exec;
 };
@@ -102,6 +104,7 @@ WideStepArgs wide_args(const ddd_ctx* c, const BeamArgs& beam) {
 int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, int max_rows, float* out, hipStream_t s) {
   GemmArgs g;
   g.W = static_cast<const uint16_t*>(W);
+  g.Wp = (c->pack_src != nullptr && c->pack_src == W) ? c->pack : nullptr;
   g.hid = static_cast<const uint16_t*>(hid);
   g.row_list = c->row_list;
   g.n_act_ptr = c->n_act;
@@ -246,6 +249,8 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->logits = nullptr;
   c->grp_max = nullptr;
   c->grp_sum = nullptr;
+  c->pack_src = nullptr;
+  c->pack = nullptr;
   c->ngrp = ((cfg->V + 63) / 64 + 3) & ~3;
   const size_t rows = (size_t)cfg->B * cfg->k;
   const size_t ns = (cfg->k > DDD_KMAX) ? 1 : (size_t)c->nslice;   // wide beams only use the dense format
@@ -286,7 +291,26 @@ int ddd_destroy(ddd_ctx* c) {
   if (c->logits) (void)hipFree(c->logits);
   if (c->grp_max) (void)hipFree(c->grp_max);
   if (c->grp_sum) (void)hipFree(c->grp_sum);
+  if (c->pack) (void)hipFree(c->pack);
   delete c;
+  return DDD_OK;
+}
+
+int ddd_weights_pack(ddd_ctx* c, const void* W, void* stream) {
+  if (c == nullptr) return DDD_ERR_INVALID_ARG;
+  c->pack_src = nullptr;
+  if (W == nullptr) {   // forget the copy and give its memory back
+    if (c->pack) DDD_HIP(hipFree(c->pack));
+    c->pack = nullptr;
+    return DDD_OK;
+  }
+  if (c->pack == nullptr) {
+    const size_t elems = (size_t)((c->cfg.V + 255) / 256) * 256 * (size_t)c->cfg.H;
+    DDD_HIP(hipMalloc(reinterpret_cast<void**>(&c->pack), elems * sizeof(uint16_t)));
+  }
+  DDD_HIP(launch_pack_weights(static_cast<const uint16_t*>(W), c->pack, c->cfg.V, c->cfg.H,
+                              static_cast<hipStream_t>(stream)));
+  c->pack_src = W;
   return DDD_OK;
 }
 

@@ -10,6 +10,7 @@ namespace ddd {
 // ---- LM-head MFMA GEMM for more than 16 rows (lmhead_gemm.hip) --------------------------------
 struct GemmArgs {
   const uint16_t* W;          // bf16 [V,H]
+  const uint16_t* Wp;         // null, or the tile-major copy of W written by launch_pack_weights
   const uint16_t* hid;        // bf16 [rows,H]
   const int32_t* row_list;    // [n_act] ids of the active rows, ascending
   const int32_t* n_act_ptr;   // device scalar
@@ -21,6 +22,10 @@ struct GemmArgs {
 hipError_t prepare_lmhead_gemm();   // once per process: enables the kernels' LDS sizes
 // max_rows: the largest number of rows this call can have (picks the tile shape)
 hipError_t launch_lmhead_gemm(const GemmArgs& a, int max_rows, int grid, hipStream_t stream);
+// Tile-major copy of W for the GEMM: blocks of 256 vocabulary rows x 64 k, each 32 KB contiguous
+// ([row in block][64 bf16]), blocks ordered (row block, k block); rows past V repeat row V-1.
+// Wp holds ceil(V/256)*256*H elements.
+hipError_t launch_pack_weights(const uint16_t* W, uint16_t* Wp, int V, int H, hipStream_t stream);
 hipError_t launch_build_row_list(const uint8_t* row_active, int n_rows, int32_t* row_list, int32_t* n_act,
                                  hipStream_t stream);
 

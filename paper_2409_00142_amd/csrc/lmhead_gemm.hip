@@ -76,23 +76,30 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // slot s of tile row r holds chunk s ^ ((r >> 1) & 7); r = (i*4 + wave)*8 + prow
   const int prow = lane >> 3, pc = (lane & 7) ^ ((wave & 1) * 4 + (prow >> 1));
-  // byte offsets from the two base pointers (V*H and rows*H elements stay below 2^31)
+  // byte offsets from the two base pointers (V*H and rows*H elements stay below 2^31).  W is read
+  // row-major (a k tile of a row tile = BM pieces of 128 bytes, one per row) or from its tile-major
+  // copy (the same pieces contiguous: 256 rows x 128 bytes per block, the next k tile 32 KB on)
+  const bool packed = a.Wp != nullptr;
+  const unsigned char* Wb = reinterpret_cast<const unsigned char*>(packed ? a.Wp : a.W);
+  const uint32_t a_tile_stride = packed ? 256u * kRowB : (uint32_t)kRowB;
   uint32_t ao[NAP], bo[NBP];
 #pragma unroll
-  for (int i = 0; i < NAP; ++i)
-    ao[i] = ((uint32_t)min(mt * C::BM + (i * 4 + wave) * 8 + prow, a.V - 1) * (uint32_t)a.H + pc * 8) * 2u;
+  for (int i = 0; i < NAP; ++i) {
+    const int vrow = mt * C::BM + (i * 4 + wave) * 8 + prow;
+    ao[i] = packed ? ((uint32_t)(vrow >> 8) * (uint32_t)KT * 256u + (uint32_t)(vrow & 255)) * kRowB + pc * 16
+                   : ((uint32_t)min(vrow, a.V - 1) * (uint32_t)a.H + pc * 8) * 2u;
+  }
 #pragma unroll
   for (int i = 0; i < NBP; ++i)
     bo[i] = ((uint32_t)a.row_list[min(tile_col0 + (i * 4 + wave) * 8 + prow, n_act - 1)] * (uint32_t)a.H + pc * 8) * 2u;
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
-  const unsigned char* Wb = reinterpret_cast<const unsigned char*>(a.W);
   const unsigned char* Hb = reinterpret_cast<const unsigned char*>(a.hid);
   unsigned char* const ldsA = ldsb;
   unsigned char* const ldsB = ldsb + kSA * C::kABytes;
   // copy instruction i of a tile of W (A) / of the hidden rows (B)
 #define DDD_COPY_A(T, STG, i)                                                                        \
-  __builtin_amdgcn_global_load_lds((gptr_t)(Wb + (size_t)(T) * kRowB + ao[i]),                       \
+  __builtin_amdgcn_global_load_lds((gptr_t)(Wb + (size_t)(T) * a_tile_stride + ao[i]),                       \
                                    (lptr_t)(ldsA + (STG) * C::kABytes + ((i) * 4 + wave) * 1024), 16, 0, 0)
 #define DDD_COPY_B(T, STG, i)                                                                        \
   __builtin_amdgcn_global_load_lds((gptr_t)(Hb + (size_t)(T) * kRowB + bo[i]),                       \
@@ -321,6 +328,25 @@ __global__ __launch_bounds__(256, 1) void lmhead_gemm_kernel(GemmArgs a) {
     gemm_units<AB, (BB >= 2 ? 2 : BB)>(a, lds, n_act, NT, bpt);
   else
     gemm_units<AB, 1>(a, lds, n_act, NT, bpt);
+}
+
+// ---- tile-major copy of W ------------------------------------------------------------------------
+// One workgroup per (block of 256 rows, block of 64 k); thread t copies the 128 bytes of row t.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ Wp,
+                                                           int V, int H) {
+  const int KT = H / kGK;
+  const int kt = blockIdx.x % KT, mb = blockIdx.x / KT;
+  const int row = min(mb * 256 + (int)threadIdx.x, V - 1);
+  const u32x4* src = reinterpret_cast<const u32x4*>(W + (size_t)row * H + (size_t)kt * kGK);
+  u32x4* dst = reinterpret_cast<u32x4*>(Wp + ((size_t)blockIdx.x * 256 + threadIdx.x) * kGK);
+#pragma unroll
+  for (int c = 0; c < 8; ++c) dst[c] = src[c];
+}
+
+hipError_t launch_pack_weights(const uint16_t* W, uint16_t* Wp, int V, int H, hipStream_t stream) {
+  const int nblk = ((V + 255) / 256) * (H / kGK);
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(nblk), dim3(256), 0, stream, W, Wp, V, H);
+  return hipGetLastError();
 }
 
 // ---- compaction of the active rows ------------------------------------------------------------

@@ -97,6 +97,61 @@ def test_lmhead_topk_against_oracle(gpu, case):
         assert np.max(np.abs(g_lp[r].astype(np.float64) - o_lp)) <= LOGPROB_TOL
 
 
+PACK_CASES = [
+    # name,  B, k,  H,    V,    R
+    ("rows24_ragged_V", 3, 8, 512, 2003, 24),           # one 256-row block short of full, narrow column tile
+    ("rows130_k16", 9, 16, 256, 3000, 130),              # two waves' worth of column blocks
+    ("rows400_two_tiles", 40, 10, 256, 1300, 400),       # two balanced column tiles
+    ("tall_tile", 8, 16, 256, 256 * 260 + 37, 100),      # 256-row GEMM tile, ragged last block
+    ("wide_k40", 2, 40, 512, 5003, 70),
+]
+
+
+@pytest.mark.parametrize("case", PACK_CASES, ids=[c[0] for c in PACK_CASES])
+def test_lmhead_topk_with_packed_weights_is_bit_identical(gpu, case):
+    """ddd_weights_pack: the MFMA path reads W from its tile-major copy; every output bit is the same, the
+    stream path (<= 16 rows) is not affected, and forgetting the copy goes back to the row-major W."""
+    torch, D, SD = gpu
+    name, B, k, H, V, R = case
+    print(f"[case] packed weights {name} B={B} k={k} H={H} V={V} R={R}", flush=True)
+    rng = np.random.default_rng(abs(hash(name)) % (1 << 31))
+    W_bits = synth.make_lm_head(V, H, 0.05, seed=5)
+    hid_bits = _rand_hid_bits(rng, R, H, 3.0)
+    cfg = D.make_config(B, H, V, k, 4, 8, 0.3)
+    ctx = D.ddd_create(cfg)
+
+    def run(rows):
+        tok = torch.full((rows, k), -7, dtype=torch.int32, device="cuda")
+        lp = torch.zeros(rows, k, dtype=torch.float32, device="cuda")
+        lse = torch.zeros(rows, dtype=torch.float32, device="cuda")
+        dbg = torch.full((rows, V), float("nan"), dtype=torch.float32, device="cuda")
+        D.ddd_lmhead_topk(ctx, W, hid, rows, None, tok, lp, lse, dbg)
+        torch.cuda.synchronize()
+        return tok, lp, lse, dbg
+
+    try:
+        W, hid = SD.upload_bits(W_bits), SD.upload_bits(hid_bits)
+        plain = run(R)
+        few_plain = run(min(R, 8))                       # weight-stream path when k <= 16
+        D.ddd_weights_pack(ctx, W)
+        packed = run(R)
+        few_packed = run(min(R, 8))
+        D.ddd_weights_pack(ctx, W)                       # packing again reuses the allocation
+        packed2 = run(R)
+        D.ddd_weights_pack(ctx, None)
+        plain2 = run(R)
+    finally:
+        D.ddd_destroy(ctx)
+    for other in (packed, packed2, plain2):
+        for a, b in zip(plain, other):
+            assert torch.equal(a, b)
+    for a, b in zip(few_plain, few_packed):
+        assert torch.equal(a, b)
+    assert not torch.isnan(plain[3]).any()
+    o_logits = O.lmhead_logits(W_bits, hid_bits)
+    assert np.max(np.abs(packed[3].cpu().numpy().astype(np.float64) - o_logits.astype(np.float64))) <= LOGIT_TOL
+
+
 @pytest.mark.parametrize("R", [3, 20])
 def test_lmhead_topk_all_logits_equal(gpu, R):
     """Degenerate rows: a zero hidden state makes every logit 0, so the top-k is tokens 0..k-1 (lower id wins)
