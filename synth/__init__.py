@@ -13,6 +13,8 @@ from .inputs import (  # noqa: F401
     bf16_bits_to_f32,
     make_lm_head,
     make_plant_table,
+    make_body_weights,
+    make_prompt_context,
     mix64,
     stream_key,
     node_key,

@@ -174,6 +174,45 @@ def make_lm_head(V: int, H: int, sigma_w: float, seed: int = 0,
     return out
 
 
+# --------------------------------------------------------------------------
+# stand-in draft layer: weights and prompt context (random numbers only, no arithmetic of the layer)
+# --------------------------------------------------------------------------
+def _normal_bits(rng, shape, sigma: float) -> np.ndarray:
+    rows = shape[0]
+    out = np.empty(shape, dtype=np.uint16)
+    step = max(1, (1 << 24) // max(1, int(np.prod(shape[1:]))))
+    for r0 in range(0, rows, step):
+        r1 = min(rows, r0 + step)
+        blk = rng.standard_normal((r1 - r0,) + tuple(shape[1:]), dtype=np.float32) * np.float32(sigma)
+        out[r0:r1] = f32_to_bf16_bits(blk)
+    return out
+
+
+def make_body_weights(V: int, H: int, F: int, seed: int = 0) -> dict:
+    """bf16 bit patterns / fp32 gains of a one-layer draft body: embedding E[V,H], Wfc[H,2H], g1[H],
+    Wqkv[3H,H] (q, k, v rows), Wo[H,H], g2[H], Wgu[2F,H] (gate, up rows), Wd[H,F].  Variances are
+    1/fan_in, so activations stay of order one."""
+    rng = np.random.default_rng(1000 + seed)
+    return {
+        "E": _normal_bits(rng, (V, H), 1.0),
+        "Wfc": _normal_bits(rng, (H, 2 * H), (2 * H) ** -0.5),
+        "g1": (1.0 + 0.1 * rng.standard_normal(H)).astype(np.float32),
+        "Wqkv": _normal_bits(rng, (3 * H, H), H ** -0.5),
+        "Wo": _normal_bits(rng, (H, H), H ** -0.5),
+        "g2": (1.0 + 0.1 * rng.standard_normal(H)).astype(np.float32),
+        "Wgu": _normal_bits(rng, (2 * F, H), H ** -0.5),
+        "Wd": _normal_bits(rng, (H, F), F ** -0.5),
+    }
+
+
+def make_prompt_context(L: int, H: int, seed: int = 0) -> dict:
+    """Cached keys K[L,H], values V[L,H] of L prompt positions and the feature f_root[H] of the last
+    prompt token, all bf16 bit patterns ~ N(0,1)."""
+    rng = np.random.default_rng(2000 + seed)
+    return {"K": _normal_bits(rng, (L, H), 1.0), "V": _normal_bits(rng, (L, H), 1.0),
+            "f_root": _normal_bits(rng, (1, H), 1.0)[0]}
+
+
 def make_plant_table(W_bits: np.ndarray, wl: Workload) -> Tuple[np.ndarray, np.ndarray]:
     """(plant_tokens int32[n_plant], plant_dir fp32[n_plant,H]) or empty arrays."""
     if wl.n_plant <= 0:
