@@ -62,6 +62,18 @@ class ddd_synth_params(C.Structure):
                 ("plant_dir", C.c_void_p), ("plant_round_p24", C.c_uint32), ("plant_row_p24", C.c_uint32)]
 
 
+class ddd_body_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "k", "H", "F", "V", "max_depth", "L")]
+
+
+class ddd_body_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("E", "Wfc", "g1", "Wqkv", "Wo", "g2", "Wgu", "Wd")]
+
+
+class ddd_body_prompt(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("K", "V", "f_root", "root_token")]
+
+
 DRAFT_BODY_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int32, C.POINTER(ddd_state), C.c_void_p, C.c_void_p)
 POST_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(ddd_state), C.POINTER(ddd_tree), C.c_void_p)
 
@@ -104,6 +116,11 @@ def load_library() -> C.CDLL:
         "ddd_synth_mfma_rate": (C.c_int, [vp, i32, i32, vp]),
         "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "ddd_weights_pack": (C.c_int, [vp, vp, vp]),
+        "ddd_body_create": (C.c_int, [C.POINTER(ddd_body_config), C.POINTER(vp)]),
+        "ddd_body_destroy": (C.c_int, [vp]),
+        "ddd_body_bind": (C.c_int, [vp, C.POINTER(ddd_body_weights), C.POINTER(ddd_body_prompt)]),
+        "ddd_body_step": (C.c_int, [vp, i32, C.POINTER(ddd_state), vp, vp]),
+        "ddd_body_linear": (C.c_int, [vp, vp, i32, i32, vp, i32, vp, i32, vp]),
         "ddd_profile_lmhead": (C.c_int, [vp, vp, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]),
     }
     for name, (res, args) in sig.items():
@@ -305,6 +322,39 @@ def ddd_weights_pack(ctx, W, stream=None):
     """Tile-major copy of W for the GEMM path (W=None forgets it)."""
     _check(load_library().ddd_weights_pack(ctx, _ptr(W), current_stream() if stream is None else stream),
            "ddd_weights_pack")
+
+
+# ---- stand-in draft layer (include/ddd_body.h) -------------------------------------------------
+def ddd_body_create(cfg: ddd_body_config) -> int:
+    out = C.c_void_p()
+    _check(load_library().ddd_body_create(C.byref(cfg), C.byref(out)), "ddd_body_create")
+    return out.value
+
+
+def ddd_body_destroy(body: int) -> None:
+    _check(load_library().ddd_body_destroy(body), "ddd_body_destroy")
+
+
+def ddd_body_bind(body: int, weights: Dict[str, "object"], prompt: Dict[str, "object"]) -> None:
+    """weights / prompt: dicts of device tensors named as the struct fields; the caller keeps them alive."""
+    w = ddd_body_weights(*[_ptr(weights[n]) for n, _ in ddd_body_weights._fields_])
+    p = ddd_body_prompt(*[_ptr(prompt[n]) for n, _ in ddd_body_prompt._fields_])
+    _check(load_library().ddd_body_bind(body, C.byref(w), C.byref(p)), "ddd_body_bind")
+
+
+def body_step_ptr() -> int:
+    """Address of ddd_body_step, usable as the `body` argument of the round calls (user = the body handle)."""
+    return C.cast(load_library().ddd_body_step, C.c_void_p).value
+
+
+def ddd_body_step(body: int, step, st: ddd_state, hid_out, stream=None):
+    _check(load_library().ddd_body_step(body, step, C.byref(st), _ptr(hid_out),
+                                        current_stream() if stream is None else stream), "ddd_body_step")
+
+
+def ddd_body_linear(body: int, W, N, K, x, R, y, accumulate=False, stream=None):
+    _check(load_library().ddd_body_linear(body, _ptr(W), N, K, _ptr(x), R, _ptr(y), 1 if accumulate else 0,
+                                          current_stream() if stream is None else stream), "ddd_body_linear")
 
 
 def ddd_profile_lmhead(ctx, W, hid, n_rows, iters, stream=None):

@@ -1,0 +1,242 @@
+// C ABI of the stand-in draft layer (include/ddd_body.h): argument checks, scratch, and the
+// sequence of launches of one draft call.
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "body_kernels.hpp"
+#include "../../include/ddd_body.h"
+
+using namespace ddd;
+
+struct ddd_body {
+  ddd_body_config cfg;
+  int n_cu;
+  ddd_body_weights w;
+  ddd_body_prompt p;
+  bool bound;
+  uint16_t* x0;      // bf16 [16][2H]
+  float* r;          // fp32 [16][H]   residual stream
+  uint16_t* xn;      // bf16 [16][H]   normalised rows / attention output
+  float* qkv;        // fp32 [16][3H]
+  float* gu;         // fp32 [16][2F]
+  uint16_t* act;     // bf16 [16][F]
+  uint16_t* h_hist;  // bf16 [D][16][H]
+  uint16_t* k_hist;
+  uint16_t* v_hist;
+  int32_t* par_hist; // [D][16]
+};
+
+namespace {
+
+int hip_status(hipError_t e) { return e == hipSuccess ? DDD_OK : DDD_ERR_HIP; }
+#define BODY_HIP(call)                       \
+  do {                                       \
+    const int rc_ = hip_status(call);        \
+    if (rc_ != DDD_OK) return rc_;           \
+  } while (0)
+
+// Largest K range one launch of the weight stream covers: 128 * G * nw with G in {1,2,4}, nw <= 10.
+bool pick_range(int units, int* G, int* nw) {   // units = remaining K / 128
+  int best = 0;
+  for (int g = 4; g >= 1; g >>= 1)
+    for (int w = 10; w >= 1; --w)
+      if (g * w <= units && g * w > best) {
+        best = g * w;
+        *G = g;
+        *nw = w;
+      }
+  return best > 0;
+}
+
+int enqueue_linear(const ddd_body* b, const void* W, int N, int K, const uint16_t* x, int ldx, int R,
+                   const uint8_t* row_active, float* y, int ldy, int accumulate, hipStream_t s) {
+  const int ntiles = (N + 15) / 16;
+  const int nslice = ntiles < b->n_cu ? ntiles : b->n_cu;
+  int k0 = 0;
+  while (k0 < K) {
+    int G = 1, nw = 1;
+    pick_range((K - k0) / 128, &G, &nw);
+    LinearArgs a;
+    a.W = static_cast<const uint16_t*>(W) + k0;
+    a.x = x + k0;
+    a.row_active = row_active;
+    a.y = y;
+    a.ldw = K;
+    a.ldx = ldx;
+    a.ldy = ldy;
+    a.N = N;
+    a.R = R;
+    a.ntiles = ntiles;
+    a.nw = nw;
+    a.accumulate = (accumulate || k0 > 0) ? 1 : 0;
+    BODY_HIP(launch_linear_stream(a, G, nslice, s));
+    k0 += 128 * G * nw;
+  }
+  return DDD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
+  if (cfg == nullptr || out == nullptr) return DDD_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (cfg->B < 1 || cfg->k < 1 || cfg->B * cfg->k > kBodyRows) return DDD_ERR_INVALID_ARG;
+  if (cfg->H < 128 || cfg->H % 128 != 0 || cfg->F < 128 || cfg->F % 128 != 0 || cfg->V < 1) return DDD_ERR_INVALID_ARG;
+  if (cfg->max_depth < 1 || cfg->max_depth > DDD_DMAX || cfg->L < 0 || cfg->L > DDD_BODY_LMAX)
+    return DDD_ERR_INVALID_ARG;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return DDD_ERR_NO_DEVICE;
+  hipDeviceProp_t prop;
+  BODY_HIP(hipGetDeviceProperties(&prop, dev));
+  ddd_body* b = new (std::nothrow) ddd_body();
+  if (b == nullptr) return DDD_ERR_INVALID_ARG;
+  b->cfg = *cfg;
+  b->n_cu = prop.multiProcessorCount;
+  b->bound = false;
+  const size_t H = cfg->H, F = cfg->F, D = cfg->max_depth, R = kBodyRows;
+  hipError_t e = hipMalloc(&b->x0, R * 2 * H * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMalloc(&b->r, R * H * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(&b->xn, R * H * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMalloc(&b->qkv, R * 3 * H * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(&b->gu, R * 2 * F * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(&b->act, R * F * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMalloc(&b->h_hist, D * R * H * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMalloc(&b->k_hist, D * R * H * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMalloc(&b->v_hist, D * R * H * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMalloc(&b->par_hist, D * R * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMemset(b->x0, 0, R * 2 * H * sizeof(uint16_t));   // rows never written stay finite
+  if (e == hipSuccess) e = hipMemset(b->xn, 0, R * H * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMemset(b->act, 0, R * F * sizeof(uint16_t));
+  if (e == hipSuccess) e = hipMemset(b->par_hist, 0, D * R * sizeof(int32_t));
+  if (e != hipSuccess) {
+    ddd_body_destroy(b);
+    return DDD_ERR_HIP;
+  }
+  *out = b;
+  return DDD_OK;
+}
+
+int ddd_body_destroy(ddd_body* b) {
+  if (b == nullptr) return DDD_ERR_INVALID_ARG;
+  (void)hipFree(b->x0);
+  (void)hipFree(b->r);
+  (void)hipFree(b->xn);
+  (void)hipFree(b->qkv);
+  (void)hipFree(b->gu);
+  (void)hipFree(b->act);
+  (void)hipFree(b->h_hist);
+  (void)hipFree(b->k_hist);
+  (void)hipFree(b->v_hist);
+  (void)hipFree(b->par_hist);
+  delete b;
+  return DDD_OK;
+}
+
+int ddd_body_bind(ddd_body* b, const ddd_body_weights* w, const ddd_body_prompt* p) {
+  if (b == nullptr || w == nullptr || p == nullptr) return DDD_ERR_INVALID_ARG;
+  if (!w->E || !w->Wfc || !w->g1 || !w->Wqkv || !w->Wo || !w->g2 || !w->Wgu || !w->Wd) return DDD_ERR_INVALID_ARG;
+  if (!p->f_root || !p->root_token || (b->cfg.L > 0 && (!p->K || !p->V))) return DDD_ERR_INVALID_ARG;
+  b->w = *w;
+  b->p = *p;
+  b->bound = true;
+  return DDD_OK;
+}
+
+int ddd_body_linear(ddd_body* b, const void* W, int32_t N, int32_t K, const void* x, int32_t R, float* y,
+                    int32_t accumulate, void* stream) {
+  if (b == nullptr || W == nullptr || x == nullptr || y == nullptr) return DDD_ERR_INVALID_ARG;
+  if (N < 1 || K < 128 || K % 128 != 0 || R < 1 || R > kBodyRows) return DDD_ERR_INVALID_ARG;
+  return enqueue_linear(b, W, N, K, static_cast<const uint16_t*>(x), K, R, nullptr, y, N, accumulate,
+                        static_cast<hipStream_t>(stream));
+}
+
+int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, void* stream) {
+  ddd_body* b = static_cast<ddd_body*>(user);
+  if (b == nullptr || st == nullptr || hid_out == nullptr) return DDD_ERR_INVALID_ARG;
+  if (!b->bound) return DDD_ERR_STATE;
+  if (step < 0 || step >= b->cfg.max_depth) return DDD_ERR_INVALID_ARG;
+  if (st->beam_token == nullptr || st->beam_parent_slot == nullptr || st->row_active == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int H = b->cfg.H, F = b->cfg.F;
+  const int R = (step == 0) ? b->cfg.B : b->cfg.B * b->cfg.k;
+  const uint8_t* act = (step == 0) ? nullptr : st->row_active;   // a round starts with every sequence drafting
+  const size_t hist = (size_t)step * kBodyRows * H;
+
+  BodyGatherArgs g;
+  g.E = static_cast<const uint16_t*>(b->w.E);
+  g.beam_token = st->beam_token;
+  g.beam_parent_slot = st->beam_parent_slot;
+  g.root_token = b->p.root_token;
+  g.f_root = static_cast<const uint16_t*>(b->p.f_root);
+  g.h_prev = (step == 0) ? nullptr : b->h_hist + hist - (size_t)kBodyRows * H;
+  g.row_active = act;
+  g.x0 = b->x0;
+  g.par_out = b->par_hist + (size_t)step * kBodyRows;
+  g.H = H;
+  g.k = b->cfg.k;
+  g.step = step;
+  g.R = R;
+  BODY_HIP(launch_body_gather(g, s));
+  int rc = enqueue_linear(b, b->w.Wfc, H, 2 * H, b->x0, 2 * H, R, act, b->r, H, 0, s);
+  if (rc != DDD_OK) return rc;
+
+  RmsNormArgs n1;
+  n1.x = b->r;
+  n1.g = b->w.g1;
+  n1.row_active = act;
+  n1.out = b->xn;
+  n1.H = H;
+  n1.R = R;
+  BODY_HIP(launch_rmsnorm(n1, s));
+  rc = enqueue_linear(b, b->w.Wqkv, 3 * H, H, b->xn, H, R, act, b->qkv, 3 * H, 0, s);
+  if (rc != DDD_OK) return rc;
+
+  BodyAttnArgs t;
+  t.qkv = b->qkv;
+  t.Kp = static_cast<const uint16_t*>(b->p.K);
+  t.Vp = static_cast<const uint16_t*>(b->p.V);
+  t.k_hist = b->k_hist;
+  t.v_hist = b->v_hist;
+  t.par_hist = b->par_hist;
+  t.row_active = act;
+  t.o = b->xn;                     // the normalised rows are consumed: reuse their buffer
+  t.H = H;
+  t.L = b->cfg.L;
+  t.k = b->cfg.k;
+  t.step = step;
+  t.R = R;
+  BODY_HIP(launch_body_attention(t, s));
+  rc = enqueue_linear(b, b->w.Wo, H, H, b->xn, H, R, act, b->r, H, 1, s);   // r1 = r0 + o Wo^T
+  if (rc != DDD_OK) return rc;
+
+  RmsNormArgs n2 = n1;
+  n2.g = b->w.g2;
+  BODY_HIP(launch_rmsnorm(n2, s));
+  rc = enqueue_linear(b, b->w.Wgu, 2 * F, H, b->xn, H, R, act, b->gu, 2 * F, 0, s);
+  if (rc != DDD_OK) return rc;
+  SiluMulArgs m;
+  m.gu = b->gu;
+  m.row_active = act;
+  m.a = b->act;
+  m.F = F;
+  m.R = R;
+  BODY_HIP(launch_silu_mul(m, s));
+  rc = enqueue_linear(b, b->w.Wd, H, F, b->act, F, R, act, b->r, H, 1, s);   // r1 + a Wd^T
+  if (rc != DDD_OK) return rc;
+
+  BodyFinalArgs f;
+  f.r = b->r;
+  f.row_active = act;
+  f.hid_out = static_cast<uint16_t*>(hid_out);
+  f.h_hist = b->h_hist + hist;
+  f.H = H;
+  f.R = R;
+  BODY_HIP(launch_body_final(f, s));
+  return DDD_OK;
+}
+
+}  // extern "C"

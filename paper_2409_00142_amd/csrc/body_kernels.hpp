@@ -1,0 +1,81 @@
+// Kernels of the stand-in draft layer (an EAGLE-shaped body with synthetic weights: embedding
+// gather + FC, one decoder layer with tree attention over the beam's ancestors); host launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ddd {
+
+constexpr int kBodyRows = 16;      // rows per call (B*k): one pass of the weight stream
+constexpr int kHeadDim = 128;
+
+// y[r][n] (+)= sum_k x[r][k] * W[n][k] for one K range of 128*G*nw elements: the LM head's weight
+// stream with a plain store epilogue.  W and x point at the first element of the range.
+struct LinearArgs {
+  const uint16_t* W;          // bf16, row pitch ldw
+  const uint16_t* x;          // bf16 [R], row pitch ldx
+  const uint8_t* row_active;  // [R] or null: the launch does nothing if every row is inactive
+  float* y;                   // fp32 [R], row pitch ldy
+  int ldw, ldx, ldy, N, R, ntiles, nw, accumulate;
+};
+hipError_t launch_linear_stream(const LinearArgs& a, int G, int nslice, hipStream_t stream);
+
+struct BodyGatherArgs {
+  const uint16_t* E;                // bf16 [V][H]
+  const int32_t* beam_token;        // [B*k]
+  const int32_t* beam_parent_slot;  // [B*k]
+  const int32_t* root_token;        // [B]
+  const uint16_t* f_root;           // bf16 [B][H]
+  const uint16_t* h_prev;           // bf16 rows of the previous call
+  const uint8_t* row_active;        // [R] or null
+  uint16_t* x0;                     // bf16 [R][2H]
+  int32_t* par_out;                 // [R] parent slot of each row (step >= 1)
+  int H, k, step, R;
+};
+hipError_t launch_body_gather(const BodyGatherArgs& a, hipStream_t stream);
+
+// out[r] = bf16( x[r] / sqrt(mean(x[r]^2) + eps) * g )
+struct RmsNormArgs {
+  const float* x;             // fp32 [R][H]
+  const float* g;             // fp32 [H]
+  const uint8_t* row_active;
+  uint16_t* out;              // bf16 [R][H]
+  int H, R;
+};
+hipError_t launch_rmsnorm(const RmsNormArgs& a, hipStream_t stream);
+
+// RoPE of q and k at position L + step, k and v stored as bf16, attention of every row over the
+// prompt, its ancestors and itself.
+struct BodyAttnArgs {
+  const float* qkv;           // fp32 [R][3H]
+  const uint16_t* Kp;         // bf16 [B][L][H] keys of the prompt (as cached)
+  const uint16_t* Vp;
+  uint16_t* k_hist;           // bf16 [D][kBodyRows][H]
+  uint16_t* v_hist;
+  const int32_t* par_hist;    // [D][kBodyRows]
+  const uint8_t* row_active;
+  uint16_t* o;                // bf16 [R][H]
+  int H, L, k, step, R;
+};
+hipError_t launch_body_attention(const BodyAttnArgs& a, hipStream_t stream);
+
+// a[r][f] = bf16( silu(gu[r][f]) * gu[r][F + f] )
+struct SiluMulArgs {
+  const float* gu;            // fp32 [R][2F]
+  const uint8_t* row_active;
+  uint16_t* a;                // bf16 [R][F]
+  int F, R;
+};
+hipError_t launch_silu_mul(const SiluMulArgs& a, hipStream_t stream);
+
+// h = bf16(r): the hidden rows for the LM head and this call's features
+struct BodyFinalArgs {
+  const float* r;             // fp32 [R][H]
+  const uint8_t* row_active;
+  uint16_t* hid_out;          // bf16 [R][H]
+  uint16_t* h_hist;           // bf16 [R][H] slot of this call
+  int H, R;
+};
+hipError_t launch_body_final(const BodyFinalArgs& a, hipStream_t stream);
+
+}  // namespace ddd
