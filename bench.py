@@ -66,6 +66,12 @@ def main():
     ap.add_argument("--profile-iters", type=int, default=200)
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="one captured hipGraph per round (default) or plain stream launches")
+    ap.add_argument("--body", choices=["hash", "layer"], default="hash",
+                    help="draft body between the LM-head calls: the hash-based hidden-state generator of the workload "
+                         "(default: the LM head and the bookkeeping are all a round does), or the stand-in draft layer "
+                         "(embedding + FC + one decoder layer with tree attention, synthetic weights; <= 16 rows per call)")
+    ap.add_argument("--ffn", type=int, default=None, help="MLP width of the draft layer (default 11008, 13824 for H=5120)")
+    ap.add_argument("--prompt-len", type=int, default=256, help="prompt positions every draft row attends to")
     ap.add_argument("--pack-weights", choices=["auto", "on", "off"], default="auto",
                     help="tile-major copy of W for the GEMM path (ddd_weights_pack); auto: when the GEMM path is used "
                          "and W is larger than the 256 MB Infinity Cache, i.e. really streams from HBM")
@@ -102,6 +108,14 @@ def main():
     log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s; "
         f"stream slices={D.ddd_num_slices(g.ctx)}")
 
+    if args.body == "layer":
+        if wl.B * wl.k > 16:
+            sys.exit("--body layer handles at most 16 rows per call (B*k <= 16)")
+        F = args.ffn if args.ffn is not None else (13824 if wl.H == 5120 else 11008)
+        t1 = time.perf_counter()
+        g.use_layer_body(F, args.prompt_len)
+        log(f"[bench] draft layer: F={F}, prompt length {args.prompt_len}, {g.body_bytes / 1e6:.1f} MB of layer weights "
+            f"streamed per call ({time.perf_counter() - t1:.1f} s to generate and upload)")
     uses_gemm = wl.B * wl.k > 16 or wl.k > 16
     pack = args.pack_weights == "on" or (args.pack_weights == "auto" and uses_gemm and wl.V * wl.H * 2 > 256 * 2**20)
     if pack:
@@ -238,7 +252,8 @@ def main():
         "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
                    "threshold": thr, "check_mask": int(wl.check_mask), "mode": args.mode, "hidden_gain": wl.gain,
                    "launch": "one hipGraph per round" if args.launch == "graph" else "stream launches",
-                   "packed_weights": bool(pack),
+                   "packed_weights": bool(pack), "body": args.body,
+                   "body_weight_bytes_per_call": int(getattr(g, "body_bytes", 0)),
                    "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},
                    "accept_len_hist": {str(d): int(c) for d, c in enumerate(accept_hist) if c},
                    "executed_depth_steps": exec_steps, "executed_batch_steps": batch_steps,

@@ -15,7 +15,7 @@
  *   [q,k,v] = xn Wqkv^T, q and k rotated to position L + d (rotate-half RoPE, base 10000, heads of
  *   128), k and v kept as bf16           o = bf16(softmax(q k_j / sqrt(128)) v_j) over the prompt, the
  *   row's ancestors and itself           r1 = r0 + o Wo^T          xn2 = bf16(rmsnorm(r1) g2)
- *   a = bf16(silu(xn2 Wg^T) * (xn2 Wu^T))                         h = bf16(r1 + a Wd^T)
+ *   a = bf16(silu(xn2 Wg^T) * (xn2 Wu^T))  (gate and up rows interleaved in Wgu)   h = bf16(r1 + a Wd^T)
  * h is the hidden row handed to the LM head and the feature f of this node.  rmsnorm uses eps 1e-6.
  *
  * Conventions are those of ddd.h (device buffers are caller-owned, calls only enqueue, status
@@ -34,7 +34,7 @@ extern "C" {
 
 typedef struct ddd_body_config {
   int32_t B, k;        /* as in ddd_config; B*k <= DDD_STREAM_ROWS                       */
-  int32_t H;           /* hidden size, a multiple of 128 (heads of 128)                  */
+  int32_t H;           /* hidden size: H = 128*G*nw as in ddd_config (heads of 128)      */
   int32_t F;           /* MLP width, a multiple of 128                                   */
   int32_t V;           /* rows of the embedding                                          */
   int32_t max_depth;   /* draft calls per round, 1..DDD_DMAX                             */
@@ -49,7 +49,7 @@ typedef struct ddd_body_weights {
   const void* Wqkv;   /* [3H,H]  rows: q, then k, then v            */
   const void* Wo;     /* [H,H]                                      */
   const float* g2;    /* [H] fp32                                   */
-  const void* Wgu;    /* [2F,H]  rows: gate, then up                */
+  const void* Wgu;    /* [2F,H]  row 2i: gate i, row 2i+1: up i     */
   const void* Wd;     /* [H,F]                                      */
 } ddd_body_weights;
 

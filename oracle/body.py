@@ -110,7 +110,7 @@ class LayerWeights:
     Wqkv_bits: np.ndarray   # uint16 [3H,H]  rows: q, then k, then v
     Wo_bits: np.ndarray     # uint16 [H,H]
     g2: np.ndarray          # fp32 [H]
-    Wgu_bits: np.ndarray    # uint16 [2F,H]  rows: gate, then up
+    Wgu_bits: np.ndarray    # uint16 [2F,H]  row 2i: gate i, row 2i+1: up i
     Wd_bits: np.ndarray     # uint16 [H,F]
 
 
@@ -144,8 +144,7 @@ def layer_rows(w: LayerWeights, x0_bits: np.ndarray, pos: int, visible_K: List[n
     r1 = r0 + o @ bf16_bits_to_f64(w.Wo_bits).T
     xn2 = round_bf16(rmsnorm(r1, w.g2.astype(np.float64)))
     gu = xn2 @ bf16_bits_to_f64(w.Wgu_bits).T
-    F = w.Wgu_bits.shape[0] // 2
-    a = round_bf16(silu(gu[:, :F]) * gu[:, F:])
+    a = round_bf16(silu(gu[:, 0::2]) * gu[:, 1::2])
     h = r1 + a @ bf16_bits_to_f64(w.Wd_bits).T
     return f64_to_bf16_bits(h), k_bits, v_bits
 

@@ -9,7 +9,8 @@
 //   body_gather_kernel     x0 = [E[token], feature of the parent row]
 //   rmsnorm_kernel         bf16(x / sqrt(mean x^2 + eps) * g)
 //   body_attention_kernel  RoPE, bf16 key / value store, softmax over prompt + ancestors + self
-//   silu_mul_kernel, body_final_kernel
+//   The SiLU gate and the final bf16 rounding of the hidden rows ride in the epilogues of the
+//   linears that produce their inputs.
 // Rows of stopped sequences are skipped; a launch whose rows are all inactive exits at once.
 #include "body_kernels.hpp"
 #include "ddd_device.hpp"
@@ -95,11 +96,28 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
       for (int w = 0; w < NW; ++w)   // fixed order
         s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + lane * 4);
       const int v0 = (t0 + t) * 16 + vb * 4;
-      if (r < a.R) {
-        float* yp = a.y + (size_t)r * a.ldy + v0;
+      if (r < a.R && (a.row_active == nullptr || a.row_active[r] != 0)) {   // rows of stopped sequences stay untouched
+        if (a.mode == kLinearSiluPairs) {   // outputs (v0, v0+1) and (v0+2, v0+3) are (gate, up) pairs
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (v0 + e < a.N) yp[e] = a.accumulate ? yp[e] + s[e] : s[e];
+          for (int e = 0; e < 4; e += 2)
+            if (v0 + e + 1 < a.N) {
+              const float g = s[e], u = s[e + 1];
+              a.out16[(size_t)r * a.ld16 + ((v0 + e) >> 1)] = f32_to_bf16_rne(g / (1.0f + __expf(-g)) * u);
+            }
+        } else {
+          float* yp = a.y + (size_t)r * a.ldy + v0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (v0 + e < a.N) {
+              const float y = (a.mode == kLinearAccumulate) ? yp[e] + s[e] : s[e];
+              yp[e] = y;
+              if (a.out16 != nullptr) {
+                const uint16_t yb = f32_to_bf16_rne(y);
+                a.out16[(size_t)r * a.ld16 + v0 + e] = yb;
+                if (a.out16b != nullptr) a.out16b[(size_t)r * a.ld16 + v0 + e] = yb;
+              }
+            }
+        }
       }
     }
   }
@@ -155,156 +173,179 @@ hipError_t launch_body_gather(const BodyGatherArgs& a, hipStream_t stream) {
 }
 
 // ---- rmsnorm ----------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rmsnorm_kernel(RmsNormArgs a) {
-  __shared__ float part[4];
+__global__ __launch_bounds__(1024) void rmsnorm_kernel(RmsNormArgs a) {
+  __shared__ float part[16];
   const int r = blockIdx.x, tid = threadIdx.x;
   if (a.row_active != nullptr && a.row_active[r] == 0) return;   // uniform over the block
   const float* x = a.x + (size_t)r * a.H;
+  float xv[8];                                                   // H <= 8192
   float ss = 0.f;
-  for (int i = tid; i < a.H; i += 256) ss += x[i] * x[i];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int i = tid + 1024 * j;
+    xv[j] = (i < a.H) ? x[i] : 0.f;
+    ss += xv[j] * xv[j];
+  }
   ss = wave_sum_f32(ss);
   if ((tid & 63) == 0) part[tid >> 6] = ss;
   __syncthreads();
-  const float tot = ((part[0] + part[1]) + part[2]) + part[3];
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) tot += part[w];                  // fixed order
   const float inv = 1.0f / sqrtf(tot / (float)a.H + 1e-6f);
-  for (int i = tid; i < a.H; i += 256) a.out[(size_t)r * a.H + i] = f32_to_bf16_rne(x[i] * inv * a.g[i]);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int i = tid + 1024 * j;
+    if (i < a.H) a.out[(size_t)r * a.H + i] = f32_to_bf16_rne(xv[j] * inv * a.g[i]);
+  }
 }
 
 hipError_t launch_rmsnorm(const RmsNormArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(rmsnorm_kernel, dim3(a.R), dim3(256), 0, stream, a);
+  if (a.H > 8192) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rmsnorm_kernel, dim3(a.R), dim3(1024), 0, stream, a);
   return hipGetLastError();
 }
 
-// ---- RoPE + key/value store + tree attention: one wave per (row, head) ---------------------------
-__global__ __launch_bounds__(64) void body_attention_kernel(BodyAttnArgs a) {
+// ---- RoPE + key/value store + tree attention: one workgroup of 16 waves per (row, head) ----------
+// Every phase is a few dependent memory round trips deep at most: keys are dealt one per thread,
+// values to 8 groups of 128 threads (one per element of the head).
+constexpr int kAttnThreads = 1024;
+
+__device__ __forceinline__ float block_max_f32(float x, float* red, int tid) {
+  x = wave_max_f32(x);
+  __syncthreads();              // red may still be read from an earlier reduction
+  if ((tid & 63) == 0) red[tid >> 6] = x;
+  __syncthreads();
+  float m = red[0];
+#pragma unroll
+  for (int w = 1; w < kAttnThreads / 64; ++w) m = fmaxf(m, red[w]);
+  return m;
+}
+__device__ __forceinline__ float block_sum_f32(float x, float* red, int tid) {
+  x = wave_sum_f32(x);
+  __syncthreads();
+  if ((tid & 63) == 0) red[tid >> 6] = x;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < kAttnThreads / 64; ++w) s += red[w];      // fixed order
+  return s;
+}
+
+__global__ __launch_bounds__(kAttnThreads) void body_attention_kernel(BodyAttnArgs a) {
   extern __shared__ __align__(16) float sm[];
   const int nh = a.H / kHeadDim;
-  const int r = blockIdx.x / nh, h = blockIdx.x % nh, lane = threadIdx.x;
+  const int r = blockIdx.x / nh, h = blockIdx.x % nh, tid = threadIdx.x;
   if (a.row_active != nullptr && a.row_active[r] == 0) return;   // uniform
   const int b = (a.step == 0) ? r : r / a.k;
   const int n_vis = a.L + a.step + 1;
   float* qs = sm;                  // [128] rotated query
   float* ks = sm + 128;            // [128] own key as stored (bf16 values)
   float* vs = sm + 256;            // [128] own value as stored
-  float* sc = sm + 384;            // [n_vis] scores, then weights
-  int* anc = reinterpret_cast<int*>(sc + ((n_vis + 3) & ~3));   // [step] row of the ancestor in each earlier call
+  float* red = sm + 384;           // [16] block reductions
+  float* part = sm + 400;          // [8][128] partial outputs
+  float* sc = sm + 400 + 8 * kHeadDim;                            // [n_vis] scores, then weights
+  int* anc = reinterpret_cast<int*>(sc + ((n_vis + 3) & ~3));    // [step] row of the ancestor in each earlier call
 
-  {
-    // pair (lane, lane + 64) of the head rotates by pos * base^(-2*lane/128)
-    const float inv_freq = exp2f(-(float)(2 * lane) / (float)kHeadDim * 13.287712379549449f);   // log2(10000)
+  if (tid < 64) {
+    // pair (tid, tid + 64) of the head rotates by pos * base^(-2*tid/128)
+    const float inv_freq = exp2f(-(float)(2 * tid) / (float)kHeadDim * 13.287712379549449f);   // log2(10000)
     float sn, cs;
     sincosf((float)(a.L + a.step) * inv_freq, &sn, &cs);
     const float* row = a.qkv + (size_t)r * 3 * a.H + h * kHeadDim;
-    const float q0 = row[lane], q1 = row[lane + 64];
-    const float k0 = row[a.H + lane], k1 = row[a.H + lane + 64];
-    const float v0 = row[2 * a.H + lane], v1 = row[2 * a.H + lane + 64];
-    qs[lane] = q0 * cs - q1 * sn;
-    qs[lane + 64] = q1 * cs + q0 * sn;
+    const float q0 = row[tid], q1 = row[tid + 64];
+    const float k0 = row[a.H + tid], k1 = row[a.H + tid + 64];
+    const float v0 = row[2 * a.H + tid], v1 = row[2 * a.H + tid + 64];
+    qs[tid] = q0 * cs - q1 * sn;
+    qs[tid + 64] = q1 * cs + q0 * sn;
     const uint16_t kb0 = f32_to_bf16_rne(k0 * cs - k1 * sn), kb1 = f32_to_bf16_rne(k1 * cs + k0 * sn);
     const uint16_t vb0 = f32_to_bf16_rne(v0), vb1 = f32_to_bf16_rne(v1);
     const size_t slot = ((size_t)a.step * kBodyRows + r) * a.H + h * kHeadDim;
-    a.k_hist[slot + lane] = kb0;
-    a.k_hist[slot + lane + 64] = kb1;
-    a.v_hist[slot + lane] = vb0;
-    a.v_hist[slot + lane + 64] = vb1;
-    ks[lane] = bf16_to_f32(kb0);
-    ks[lane + 64] = bf16_to_f32(kb1);
-    vs[lane] = bf16_to_f32(vb0);
-    vs[lane + 64] = bf16_to_f32(vb1);
-    if (lane < a.step) {   // walk the parent slots back from this row to call number `lane`
-      int cur = r;
-      for (int s = a.step; s > lane; --s) {
-        const int pslot = a.par_hist[s * kBodyRows + cur];
-        cur = (s - 1 == 0) ? b : b * a.k + pslot;
-      }
-      anc[lane] = cur;
+    a.k_hist[slot + tid] = kb0;
+    a.k_hist[slot + tid + 64] = kb1;
+    a.v_hist[slot + tid] = vb0;
+    a.v_hist[slot + tid + 64] = vb1;
+    ks[tid] = bf16_to_f32(kb0);
+    ks[tid + 64] = bf16_to_f32(kb1);
+    vs[tid] = bf16_to_f32(vb0);
+    vs[tid + 64] = bf16_to_f32(vb1);
+  } else if (tid < 64 + a.step) {   // walk the parent slots back from this row to call number c
+    const int c = tid - 64;
+    int cur = r;
+    for (int s = a.step; s > c; --s) {
+      const int pslot = a.par_hist[s * kBodyRows + cur];
+      cur = (s - 1 == 0) ? b : b * a.k + pslot;
     }
+    anc[c] = cur;
   }
   __syncthreads();
 
+  // scores: one key per thread
   const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
   float mx = -INFINITY;
-  for (int j = lane; j < n_vis; j += 64) {
+  for (int j = tid; j < n_vis; j += kAttnThreads) {
     float dot = 0.f;
     if (j == n_vis - 1) {
       for (int i = 0; i < kHeadDim; ++i) dot += qs[i] * ks[i];
     } else {
       const uint16_t* kp = (j < a.L) ? a.Kp + ((size_t)(b * a.L + j) * a.H + h * kHeadDim)
                                      : a.k_hist + (((size_t)(j - a.L) * kBodyRows + anc[j - a.L]) * a.H + h * kHeadDim);
-      for (int c = 0; c < kHeadDim / 8; ++c) {
-        const u32x4 u = *reinterpret_cast<const u32x4*>(kp + c * 8);
+      u32x4 u[kHeadDim / 8];
+#pragma unroll
+      for (int c = 0; c < kHeadDim / 8; ++c) u[c] = *reinterpret_cast<const u32x4*>(kp + c * 8);
+#pragma unroll
+      for (int c = 0; c < kHeadDim / 8; ++c)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          dot += qs[c * 8 + 2 * e] * __uint_as_float(u[e] << 16);
-          dot += qs[c * 8 + 2 * e + 1] * __uint_as_float(u[e] & 0xFFFF0000u);
+          dot += qs[c * 8 + 2 * e] * __uint_as_float(u[c][e] << 16);
+          dot += qs[c * 8 + 2 * e + 1] * __uint_as_float(u[c][e] & 0xFFFF0000u);
         }
-      }
     }
     dot *= scale;
     sc[j] = dot;
     mx = fmaxf(mx, dot);
   }
-  mx = wave_max_f32(mx);
+  mx = block_max_f32(mx, red, tid);
   float sum = 0.f;
-  for (int j = lane; j < n_vis; j += 64) {
+  for (int j = tid; j < n_vis; j += kAttnThreads) {
     const float p = __expf(sc[j] - mx);
     sc[j] = p;
     sum += p;
   }
-  sum = wave_sum_f32(sum);
-  __syncthreads();
+  sum = block_sum_f32(sum, red, tid);   // its barriers also publish the weights
 
-  float o0 = 0.f, o1 = 0.f;
-  for (int j = 0; j < n_vis; ++j) {
-    const float p = sc[j];
-    if (j == n_vis - 1) {
-      o0 += p * vs[lane];
-      o1 += p * vs[lane + 64];
-    } else {
-      const uint16_t* vp = (j < a.L) ? a.Vp + ((size_t)(b * a.L + j) * a.H + h * kHeadDim)
-                                     : a.v_hist + (((size_t)(j - a.L) * kBodyRows + anc[j - a.L]) * a.H + h * kHeadDim);
-      o0 += p * bf16_to_f32(vp[lane]);
-      o1 += p * bf16_to_f32(vp[lane + 64]);
+  // values: element d of the head, keys grp, grp + 8, ...
+  const int d = tid & (kHeadDim - 1), grp = tid >> 7;
+  float o = 0.f;
+  {
+    const uint16_t* vbase = a.Vp + ((size_t)b * a.L * a.H + h * kHeadDim + d);
+    int j = grp;
+    for (; j + 8 * 15 < a.L; j += 8 * 16) {   // sixteen keys of this group in flight
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = bf16_to_f32(vbase[(size_t)(j + 8 * i) * a.H]);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o += sc[j + 8 * i] * v[i];
     }
+    for (; j < a.L; j += 8) o += sc[j] * bf16_to_f32(vbase[(size_t)j * a.H]);
+    for (int c = grp; c < a.step; c += 8)
+      o += sc[a.L + c] * bf16_to_f32(a.v_hist[((size_t)c * kBodyRows + anc[c]) * a.H + h * kHeadDim + d]);
+    if (grp == 0) o += sc[n_vis - 1] * vs[d];
   }
-  uint16_t* op = a.o + (size_t)r * a.H + h * kHeadDim;
-  op[lane] = f32_to_bf16_rne(o0 / sum);
-  op[lane + 64] = f32_to_bf16_rne(o1 / sum);
+  part[grp * kHeadDim + d] = o;
+  __syncthreads();
+  if (tid < kHeadDim) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) t += part[g * kHeadDim + tid];   // fixed order
+    a.o[(size_t)r * a.H + h * kHeadDim + tid] = f32_to_bf16_rne(t / sum);
+  }
 }
 
 hipError_t launch_body_attention(const BodyAttnArgs& a, hipStream_t stream) {
   const int n_vis = a.L + a.step + 1;
-  const size_t lds = (size_t)(384 + ((n_vis + 3) & ~3) + 32) * sizeof(float);
-  hipLaunchKernelGGL(body_attention_kernel, dim3(a.R * (a.H / kHeadDim)), dim3(64), lds, stream, a);
-  return hipGetLastError();
-}
-
-// ---- a = bf16(silu(gate) * up) ---------------------------------------------------------------------
-__global__ __launch_bounds__(256) void silu_mul_kernel(SiluMulArgs a) {
-  const int r = blockIdx.y, f = blockIdx.x * 256 + threadIdx.x;
-  if (a.row_active != nullptr && a.row_active[r] == 0) return;
-  if (f >= a.F) return;
-  const float g = a.gu[(size_t)r * 2 * a.F + f], u = a.gu[(size_t)r * 2 * a.F + a.F + f];
-  a.a[(size_t)r * a.F + f] = f32_to_bf16_rne(g / (1.0f + __expf(-g)) * u);
-}
-
-hipError_t launch_silu_mul(const SiluMulArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(silu_mul_kernel, dim3((a.F + 255) / 256, a.R), dim3(256), 0, stream, a);
-  return hipGetLastError();
-}
-
-// ---- h = bf16(r) -------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void body_final_kernel(BodyFinalArgs a) {
-  const int r = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
-  if (a.row_active != nullptr && a.row_active[r] == 0) return;
-  if (i >= a.H) return;
-  const uint16_t hb = f32_to_bf16_rne(a.r[(size_t)r * a.H + i]);
-  a.hid_out[(size_t)r * a.H + i] = hb;
-  a.h_hist[(size_t)r * a.H + i] = hb;
-}
-
-hipError_t launch_body_final(const BodyFinalArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(body_final_kernel, dim3((a.H + 255) / 256, a.R), dim3(256), 0, stream, a);
+  const size_t lds = (size_t)(400 + 8 * kHeadDim + ((n_vis + 3) & ~3) + 32) * sizeof(float);
+  hipLaunchKernelGGL(body_attention_kernel, dim3(a.R * (a.H / kHeadDim)), dim3(kAttnThreads), lds, stream, a);
   return hipGetLastError();
 }
 

@@ -19,7 +19,6 @@ struct ddd_body {
   float* r;          // fp32 [16][H]   residual stream
   uint16_t* xn;      // bf16 [16][H]   normalised rows / attention output
   float* qkv;        // fp32 [16][3H]
-  float* gu;         // fp32 [16][2F]
   uint16_t* act;     // bf16 [16][F]
   uint16_t* h_hist;  // bf16 [D][16][H]
   uint16_t* k_hist;
@@ -49,27 +48,35 @@ bool pick_range(int units, int* G, int* nw) {   // units = remaining K / 128
   return best > 0;
 }
 
+// mode: LinearMode of the whole product; out16 / out16b: bf16 copies written by the pass that completes it
 int enqueue_linear(const ddd_body* b, const void* W, int N, int K, const uint16_t* x, int ldx, int R,
-                   const uint8_t* row_active, float* y, int ldy, int accumulate, hipStream_t s) {
+                   const uint8_t* row_active, float* y, int ldy, int mode, uint16_t* out16, uint16_t* out16b, int ld16,
+                   hipStream_t s) {
   const int ntiles = (N + 15) / 16;
   const int nslice = ntiles < b->n_cu ? ntiles : b->n_cu;
   int k0 = 0;
   while (k0 < K) {
     int G = 1, nw = 1;
     pick_range((K - k0) / 128, &G, &nw);
+    const bool last = k0 + 128 * G * nw >= K;
     LinearArgs a;
     a.W = static_cast<const uint16_t*>(W) + k0;
     a.x = x + k0;
     a.row_active = row_active;
     a.y = y;
+    a.out16 = last ? out16 : nullptr;
+    a.out16b = last ? out16b : nullptr;
     a.ldw = K;
     a.ldx = ldx;
     a.ldy = ldy;
+    a.ld16 = ld16;
     a.N = N;
     a.R = R;
     a.ntiles = ntiles;
     a.nw = nw;
-    a.accumulate = (accumulate || k0 > 0) ? 1 : 0;
+    // the gate needs the whole sum: a product split over K ranges accumulates in y and cannot use the pair mode
+    if (mode == kLinearSiluPairs && !(k0 == 0 && last)) return DDD_ERR_INVALID_ARG;
+    a.mode = (k0 > 0) ? (int)kLinearAccumulate : mode;
     BODY_HIP(launch_linear_stream(a, G, nslice, s));
     k0 += 128 * G * nw;
   }
@@ -84,7 +91,11 @@ int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
   if (cfg == nullptr || out == nullptr) return DDD_ERR_INVALID_ARG;
   *out = nullptr;
   if (cfg->B < 1 || cfg->k < 1 || cfg->B * cfg->k > kBodyRows) return DDD_ERR_INVALID_ARG;
-  if (cfg->H < 128 || cfg->H % 128 != 0 || cfg->F < 128 || cfg->F % 128 != 0 || cfg->V < 1) return DDD_ERR_INVALID_ARG;
+  if (cfg->H < 128 || cfg->H > 5120 || cfg->H % 128 != 0 || cfg->F < 128 || cfg->F % 128 != 0 || cfg->V < 1) return DDD_ERR_INVALID_ARG;
+  {
+    int G = 0, nw = 0;   // H must fit one K range of the weight stream (the gated linear needs complete sums)
+    if (!pick_range(cfg->H / 128, &G, &nw) || G * nw != cfg->H / 128) return DDD_ERR_INVALID_ARG;
+  }
   if (cfg->max_depth < 1 || cfg->max_depth > DDD_DMAX || cfg->L < 0 || cfg->L > DDD_BODY_LMAX)
     return DDD_ERR_INVALID_ARG;
   int dev = 0;
@@ -101,7 +112,6 @@ int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
   if (e == hipSuccess) e = hipMalloc(&b->r, R * H * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(&b->xn, R * H * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMalloc(&b->qkv, R * 3 * H * sizeof(float));
-  if (e == hipSuccess) e = hipMalloc(&b->gu, R * 2 * F * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(&b->act, R * F * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMalloc(&b->h_hist, D * R * H * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMalloc(&b->k_hist, D * R * H * sizeof(uint16_t));
@@ -125,7 +135,6 @@ int ddd_body_destroy(ddd_body* b) {
   (void)hipFree(b->r);
   (void)hipFree(b->xn);
   (void)hipFree(b->qkv);
-  (void)hipFree(b->gu);
   (void)hipFree(b->act);
   (void)hipFree(b->h_hist);
   (void)hipFree(b->k_hist);
@@ -149,7 +158,8 @@ int ddd_body_linear(ddd_body* b, const void* W, int32_t N, int32_t K, const void
                     int32_t accumulate, void* stream) {
   if (b == nullptr || W == nullptr || x == nullptr || y == nullptr) return DDD_ERR_INVALID_ARG;
   if (N < 1 || K < 128 || K % 128 != 0 || R < 1 || R > kBodyRows) return DDD_ERR_INVALID_ARG;
-  return enqueue_linear(b, W, N, K, static_cast<const uint16_t*>(x), K, R, nullptr, y, N, accumulate,
+  return enqueue_linear(b, W, N, K, static_cast<const uint16_t*>(x), K, R, nullptr, y, N,
+                        accumulate ? kLinearAccumulate : kLinearStore, nullptr, nullptr, 0,
                         static_cast<hipStream_t>(stream));
 }
 
@@ -181,7 +191,7 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   g.step = step;
   g.R = R;
   BODY_HIP(launch_body_gather(g, s));
-  int rc = enqueue_linear(b, b->w.Wfc, H, 2 * H, b->x0, 2 * H, R, act, b->r, H, 0, s);
+  int rc = enqueue_linear(b, b->w.Wfc, H, 2 * H, b->x0, 2 * H, R, act, b->r, H, kLinearStore, nullptr, nullptr, 0, s);
   if (rc != DDD_OK) return rc;
 
   RmsNormArgs n1;
@@ -192,7 +202,7 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   n1.H = H;
   n1.R = R;
   BODY_HIP(launch_rmsnorm(n1, s));
-  rc = enqueue_linear(b, b->w.Wqkv, 3 * H, H, b->xn, H, R, act, b->qkv, 3 * H, 0, s);
+  rc = enqueue_linear(b, b->w.Wqkv, 3 * H, H, b->xn, H, R, act, b->qkv, 3 * H, kLinearStore, nullptr, nullptr, 0, s);
   if (rc != DDD_OK) return rc;
 
   BodyAttnArgs t;
@@ -210,32 +220,21 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   t.step = step;
   t.R = R;
   BODY_HIP(launch_body_attention(t, s));
-  rc = enqueue_linear(b, b->w.Wo, H, H, b->xn, H, R, act, b->r, H, 1, s);   // r1 = r0 + o Wo^T
+  rc = enqueue_linear(b, b->w.Wo, H, H, b->xn, H, R, act, b->r, H, kLinearAccumulate, nullptr, nullptr, 0,
+                      s);   // r1 = r0 + o Wo^T
   if (rc != DDD_OK) return rc;
 
   RmsNormArgs n2 = n1;
   n2.g = b->w.g2;
   BODY_HIP(launch_rmsnorm(n2, s));
-  rc = enqueue_linear(b, b->w.Wgu, 2 * F, H, b->xn, H, R, act, b->gu, 2 * F, 0, s);
+  // gate and up rows of Wgu alternate, so the epilogue of their linear forms a = bf16(silu(gate) * up) itself;
+  // it needs the complete sums, i.e. H in one K range (H <= 5120 of the form 128*G*nw)
+  rc = enqueue_linear(b, b->w.Wgu, 2 * F, H, b->xn, H, R, act, nullptr, 0, kLinearSiluPairs, b->act, nullptr, F, s);
   if (rc != DDD_OK) return rc;
-  SiluMulArgs m;
-  m.gu = b->gu;
-  m.row_active = act;
-  m.a = b->act;
-  m.F = F;
-  m.R = R;
-  BODY_HIP(launch_silu_mul(m, s));
-  rc = enqueue_linear(b, b->w.Wd, H, F, b->act, F, R, act, b->r, H, 1, s);   // r1 + a Wd^T
+  // h = bf16(r1 + a Wd^T): the pass that completes the sum also writes the hidden rows and this call's features
+  rc = enqueue_linear(b, b->w.Wd, H, F, b->act, F, R, act, b->r, H, kLinearAccumulate, static_cast<uint16_t*>(hid_out),
+                      b->h_hist + hist, H, s);
   if (rc != DDD_OK) return rc;
-
-  BodyFinalArgs f;
-  f.r = b->r;
-  f.row_active = act;
-  f.hid_out = static_cast<uint16_t*>(hid_out);
-  f.h_hist = b->h_hist + hist;
-  f.H = H;
-  f.R = R;
-  BODY_HIP(launch_body_final(f, s));
   return DDD_OK;
 }
 

@@ -11,12 +11,19 @@ constexpr int kHeadDim = 128;
 
 // y[r][n] (+)= sum_k x[r][k] * W[n][k] for one K range of 128*G*nw elements: the LM head's weight
 // stream with a plain store epilogue.  W and x point at the first element of the range.
+enum LinearMode {
+  kLinearStore = 0,        // y = sum
+  kLinearAccumulate = 1,   // y += sum
+  kLinearSiluPairs = 2     // rows of W come in (gate_i, up_i) pairs: out16[r][i] = bf16(silu(gate) * up), y unused
+};
 struct LinearArgs {
   const uint16_t* W;          // bf16, row pitch ldw
   const uint16_t* x;          // bf16 [R], row pitch ldx
   const uint8_t* row_active;  // [R] or null: the launch does nothing if every row is inactive
   float* y;                   // fp32 [R], row pitch ldy
-  int ldw, ldx, ldy, N, R, ntiles, nw, accumulate;
+  uint16_t* out16;            // null, or bf16 [R] with row pitch ld16: the rounded result (modes 0/1), the activations (mode 2)
+  uint16_t* out16b;           // null, or a second copy of out16 (same pitch)
+  int ldw, ldx, ldy, ld16, N, R, ntiles, nw, mode;
 };
 hipError_t launch_linear_stream(const LinearArgs& a, int G, int nslice, hipStream_t stream);
 
@@ -58,24 +65,5 @@ struct BodyAttnArgs {
   int H, L, k, step, R;
 };
 hipError_t launch_body_attention(const BodyAttnArgs& a, hipStream_t stream);
-
-// a[r][f] = bf16( silu(gu[r][f]) * gu[r][F + f] )
-struct SiluMulArgs {
-  const float* gu;            // fp32 [R][2F]
-  const uint8_t* row_active;
-  uint16_t* a;                // bf16 [R][F]
-  int F, R;
-};
-hipError_t launch_silu_mul(const SiluMulArgs& a, hipStream_t stream);
-
-// h = bf16(r): the hidden rows for the LM head and this call's features
-struct BodyFinalArgs {
-  const float* r;             // fp32 [R][H]
-  const uint8_t* row_active;
-  uint16_t* hid_out;          // bf16 [R][H]
-  uint16_t* h_hist;           // bf16 [R][H] slot of this call
-  int H, R;
-};
-hipError_t launch_body_final(const BodyFinalArgs& a, hipStream_t stream);
 
 }  // namespace ddd

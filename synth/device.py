@@ -79,7 +79,29 @@ class GpuWorkload:
     def set_round(self, rnd: int) -> None:
         self.round_ctr.fill_(rnd)
 
+    def use_layer_body(self, F: int, L: int, seed: int = 0) -> None:
+        """Replace the hash-based draft body by the stand-in draft layer (include/ddd_body.h) with seeded
+        weights and prompt context; the workload must have at most 16 rows per call."""
+        from .inputs import make_body_weights, make_prompt_context
+        wl = self.wl
+        wb = make_body_weights(wl.V, wl.H, F, seed)
+        self.body_w = {n: (upload_bits(a) if a.dtype == np.uint16 else torch.from_numpy(a).cuda())
+                       for n, a in wb.items()}
+        pb = [make_prompt_context(L, wl.H, seed + 10 * b) for b in range(wl.B)]
+        self.body_p = {
+            "K": upload_bits(np.stack([p["K"] for p in pb])),
+            "V": upload_bits(np.stack([p["V"] for p in pb])),
+            "f_root": upload_bits(np.stack([p["f_root"] for p in pb])),
+            "root_token": self.root_token,
+        }
+        self.body = D.ddd_body_create(D.ddd_body_config(wl.B, wl.k, wl.H, F, wl.V, wl.D, L))
+        D.ddd_body_bind(self.body, self.body_w, self.body_p)
+        self.body_bytes = sum(int(np.prod(wb[n].shape)) * 2 for n in ("Wfc", "Wqkv", "Wo", "Wgu", "Wd"))
+
     def _round_args(self):
+        if getattr(self, "body", None) is not None:
+            return (self.ctx, self.W, self.st, self.tree, self.root_token, self.hid, D.body_step_ptr(), self.body,
+                    self._post, None, self.logits_dbg, self.lse_dbg)
         return (self.ctx, self.W, self.st, self.tree, self.root_token, self.hid, D.synth_draft_body_ptr(),
                 C.addressof(self.params), self._post, None, self.logits_dbg, self.lse_dbg)
 
@@ -95,6 +117,9 @@ class GpuWorkload:
         D.ddd_round_launch(self.ctx, stream=stream)
 
     def close(self) -> None:
+        if getattr(self, "body", None) is not None:
+            D.ddd_body_destroy(self.body)
+            self.body = None
         if self.ctx is not None:
             D.ddd_destroy(self.ctx)
             self.ctx = None

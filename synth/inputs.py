@@ -190,7 +190,7 @@ def _normal_bits(rng, shape, sigma: float) -> np.ndarray:
 
 def make_body_weights(V: int, H: int, F: int, seed: int = 0) -> dict:
     """bf16 bit patterns / fp32 gains of a one-layer draft body: embedding E[V,H], Wfc[H,2H], g1[H],
-    Wqkv[3H,H] (q, k, v rows), Wo[H,H], g2[H], Wgu[2F,H] (gate, up rows), Wd[H,F].  Variances are
+    Wqkv[3H,H] (q, k, v rows), Wo[H,H], g2[H], Wgu[2F,H] (gate and up rows alternating), Wd[H,F].  Variances are
     1/fan_in, so activations stay of order one."""
     rng = np.random.default_rng(1000 + seed)
     return {
