@@ -71,6 +71,7 @@ def main():
                          "(default: the LM head and the bookkeeping are all a round does), or the stand-in draft layer "
                          "(embedding + FC + one decoder layer with tree attention, synthetic weights; <= 16 rows per call)")
     ap.add_argument("--ffn", type=int, default=None, help="MLP width of the draft layer (default 11008, 13824 for H=5120)")
+    ap.add_argument("--lm-sigma", type=float, default=None, help="std of the LM-head weights with --body layer (default 0.07)")
     ap.add_argument("--prompt-len", type=int, default=256, help="prompt positions every draft row attends to")
     ap.add_argument("--pack-weights", choices=["auto", "on", "off"], default="auto",
                     help="tile-major copy of W for the GEMM path (ddd_weights_pack); auto: when the GEMM path is used "
@@ -101,6 +102,10 @@ def main():
     over = {n: v for n, v in (("k", args.k), ("D", args.max_depth), ("m", args.m)) if v is not None}
     if over:
         wl = wl.with_(**over)
+    if args.body == "layer":
+        # the layer's output rows have an rms of about 1.4, not the hash body's gain of 3.5: a wider LM head
+        # gives the logits the same spread (std about 4.5), so that rounds again stop at mixed depths
+        wl = wl.with_(sigma_w=args.lm_sigma if args.lm_sigma is not None else 0.07)
     thr = wl.threshold if args.threshold is None else args.threshold
     log(f"[bench] workload {wl.name}: B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} m={wl.m} t={thr} gain={wl.gain}")
     t0 = time.perf_counter()

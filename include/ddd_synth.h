@@ -42,6 +42,10 @@ int ddd_synth_target_argmax(const ddd_synth_params* p, const ddd_state* st, cons
 /* Adds 1 to *round_ctr on the device (enqueued; lets a captured round advance its own id). */
 int ddd_synth_next_round(int64_t* round_ctr, void* stream);
 
+/* tokens[i] = hash(seed, *round_ctr, i) mod V for i < n <= 1024 (device int32[n]): varies the last prompt
+ * token of every sequence from round to round when the draft body is the stand-in layer. */
+int ddd_synth_hash_tokens(const int64_t* round_ctr, int32_t* tokens, int32_t n, int32_t V, uint64_t seed, void* stream);
+
 /* End-of-round statistics kept on the device (no host synchronisation): for every sequence
  * depth_hist[steps[b]] += 1 and accept_hist[accept_len[b]] += 1, and once per round
  * batch_depth_hist[max_b steps[b]] += 1 (the draft calls the batch executed); device int64[32]

@@ -116,6 +116,7 @@ def load_library() -> C.CDLL:
         "ddd_synth_mfma_rate": (C.c_int, [vp, i32, i32, vp]),
         "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "ddd_weights_pack": (C.c_int, [vp, vp, vp]),
+        "ddd_synth_hash_tokens": (C.c_int, [vp, vp, i32, i32, C.c_uint64, vp]),
         "ddd_body_create": (C.c_int, [C.POINTER(ddd_body_config), C.POINTER(vp)]),
         "ddd_body_destroy": (C.c_int, [vp]),
         "ddd_body_bind": (C.c_int, [vp, C.POINTER(ddd_body_weights), C.POINTER(ddd_body_prompt)]),
@@ -316,6 +317,11 @@ def ddd_synth_round_stats(round_ctr, steps, accept_len, B, depth_hist, accept_hi
                                                 _ptr(accept_hist), _ptr(batch_depth_hist),
                                                 current_stream() if stream is None else stream),
            "ddd_synth_round_stats")
+
+
+def ddd_synth_hash_tokens(round_ctr, tokens, n, V, seed, stream=None):
+    _check(load_library().ddd_synth_hash_tokens(_ptr(round_ctr), _ptr(tokens), n, V, seed,
+                                                current_stream() if stream is None else stream), "ddd_synth_hash_tokens")
 
 
 def ddd_weights_pack(ctx, W, stream=None):

@@ -233,6 +233,12 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(float* sink, int iters, 
   if (s == 1.2345f) sink[0] = s;   // practically never: keeps the loop alive without a store
 }
 
+// tokens[i] = hash(seed, round, i) mod V: a different last prompt token per sequence and round
+__global__ void hash_tokens_kernel(const int64_t* round_ctr, int32_t* tokens, int V, uint64_t seed) {
+  const uint64_t z = mix64(mix64(seed ^ (uint64_t)*round_ctr) + (uint64_t)threadIdx.x + 1ull);
+  tokens[threadIdx.x] = (int32_t)(z % (uint64_t)V);
+}
+
 }  // namespace
 
 extern "C" {
@@ -270,6 +276,13 @@ int ddd_synth_target_argmax(const ddd_synth_params* p, const ddd_state* st, cons
 int ddd_synth_next_round(int64_t* round_ctr, void* stream) {
   if (round_ctr == nullptr) return DDD_ERR_INVALID_ARG;
   hipLaunchKernelGGL(next_round_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), round_ctr);
+  return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
+}
+
+int ddd_synth_hash_tokens(const int64_t* round_ctr, int32_t* tokens, int32_t n, int32_t V, uint64_t seed, void* stream) {
+  if (round_ctr == nullptr || tokens == nullptr || n < 1 || n > 1024 || V < 1) return DDD_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(hash_tokens_kernel, dim3(1), dim3(n), 0, static_cast<hipStream_t>(stream), round_ctr, tokens, V,
+                     seed);
   return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
 }
 

@@ -72,6 +72,8 @@ class GpuWorkload:
                                 stream=stream)
             D.ddd_synth_round_stats(self.round_ctr, self.st_t["steps"], self.accept_len, self.wl.B, self.depth_hist,
                                     self.accept_hist, self.batch_depth_hist, stream=stream)
+            if getattr(self, "body", None) is not None:     # the layer's rounds differ by their last prompt token
+                D.ddd_synth_hash_tokens(self.round_ctr, self.root_token, self.wl.B, self.wl.V, self.wl.seed, stream=stream)
             return 0
         except D.DDDError as e:
             return e.code
