@@ -6,7 +6,8 @@
 //   linear_stream_kernel   y (+)= x W^T for <= 16 rows: every weight matrix of the layer is read
 //                          once per call, so these are HBM weight streams like the LM head
 //                          (same streaming waves, plain store epilogue).
-//   body_gather_kernel     x0 = [E[token], feature of the parent row]
+//                          Input rows are gathered in place (embedding row of the token, feature row of
+//                          the parent).
 //   rmsnorm_kernel         bf16(x / sqrt(mean x^2 + eps) * g)
 //   body_attention_kernel  RoPE, bf16 key / value store, softmax over prompt + ancestors + self
 //   The SiLU gate and the final bf16 rounding of the hidden rows ride in the epilogues of the
@@ -48,15 +49,7 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
     // streaming wave: K-slice [wave*128*G, +128*G) of this pass, its share of x resident as B operands
     const int ks = wave * (128 * G);
     const int n = lane & 15, q = lane >> 4;
-    bf16x8 bfrag[G][4];
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        u32x4 u = {0u, 0u, 0u, 0u};
-        if (n < a.R) u = *reinterpret_cast<const u32x4*>(a.x + (size_t)n * a.ldx + ks + g * 128 + j * 32 + q * 8);
-        bfrag[g][j] = __builtin_bit_cast(bf16x8, u);
-      }
+    // the first tile of W is requested before anything else: it flies while the input rows are prepared
     const int lrow = lane >> 4, c = lane & 15;
     unsigned char* mystage = stage + wave * kStageBytes;
     const int wr_off = lrow * kStagePitch + c * 16;
@@ -75,6 +68,21 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
           ring[g][i] = *reinterpret_cast<const u32x4*>(wbase + (size_t)row * a.ldw + g * 128);
         }
     }
+    int src = n;                                     // source row of input row n
+    if (n < a.R) {
+      if (a.gather_mode == kGatherIndex) src = a.gather_idx[n];
+      else if (a.gather_mode == kGatherInBlock) src = (n / a.gather_k) * a.gather_k + a.gather_idx[n];
+      else if (a.gather_mode == kGatherBlock) src = n / a.gather_k;
+    }
+    bf16x8 bfrag[G][4];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        u32x4 u = {0u, 0u, 0u, 0u};
+        if (n < a.R) u = *reinterpret_cast<const u32x4*>(a.x + (size_t)src * a.ldx + ks + g * 128 + j * 32 + q * 8);
+        bfrag[g][j] = __builtin_bit_cast(bf16x8, u);
+      }
     for (int t = 0; t + 1 < nt; ++t) {
       const f32x4 acc =
           stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.ldw, (t0 + t + 1) * 16 + lrow, vlast);
@@ -138,38 +146,6 @@ hipError_t launch_linear_stream(const LinearArgs& a, int G, int nslice, hipStrea
     case 4: return launch_linear_g<4>(a, nslice, stream);
     default: return hipErrorInvalidValue;
   }
-}
-
-// ---- x0 = [E[token], parent feature] -----------------------------------------------------------
-__global__ __launch_bounds__(256) void body_gather_kernel(BodyGatherArgs a) {
-  const int r = blockIdx.x, tid = threadIdx.x;
-  if (a.row_active != nullptr && a.row_active[r] == 0) return;
-  int tok, prev_row, slot = 0;
-  const uint16_t* feat;
-  if (a.step == 0) {
-    tok = a.root_token[r];
-    feat = a.f_root + (size_t)r * a.H;
-  } else {
-    const int b = r / a.k;
-    slot = a.beam_parent_slot[r];
-    tok = a.beam_token[r];
-    prev_row = (a.step == 1) ? b : b * a.k + slot;   // the prompt call has one row per sequence
-    feat = a.h_prev + (size_t)prev_row * a.H;
-    if (tid == 0) a.par_out[r] = slot;
-  }
-  const u32x4* e = reinterpret_cast<const u32x4*>(a.E + (size_t)tok * a.H);
-  const u32x4* f = reinterpret_cast<const u32x4*>(feat);
-  u32x4* x = reinterpret_cast<u32x4*>(a.x0 + (size_t)r * 2 * a.H);
-  const int nv = a.H / 8;
-  for (int i = tid; i < nv; i += 256) {
-    x[i] = e[i];
-    x[nv + i] = f[i];
-  }
-}
-
-hipError_t launch_body_gather(const BodyGatherArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL(body_gather_kernel, dim3(a.R), dim3(256), 0, stream, a);
-  return hipGetLastError();
 }
 
 // ---- rmsnorm ----------------------------------------------------------------------------------
@@ -273,10 +249,13 @@ __global__ __launch_bounds__(kAttnThreads) void body_attention_kernel(BodyAttnAr
     const int c = tid - 64;
     int cur = r;
     for (int s = a.step; s > c; --s) {
-      const int pslot = a.par_hist[s * kBodyRows + cur];
+      // this call's slots are still in the beam (and are recorded below); earlier calls' were recorded then
+      const int pslot = (s == a.step) ? a.beam_parent_slot[cur] : a.par_hist[s * kBodyRows + cur];
       cur = (s - 1 == 0) ? b : b * a.k + pslot;
     }
     anc[c] = cur;
+  } else if (tid == 128 && h == 0 && a.step >= 1) {
+    a.par_hist[a.step * kBodyRows + r] = a.beam_parent_slot[r];
   }
   __syncthreads();
 

@@ -15,7 +15,6 @@ struct ddd_body {
   ddd_body_weights w;
   ddd_body_prompt p;
   bool bound;
-  uint16_t* x0;      // bf16 [16][2H]
   float* r;          // fp32 [16][H]   residual stream
   uint16_t* xn;      // bf16 [16][H]   normalised rows / attention output
   float* qkv;        // fp32 [16][3H]
@@ -48,39 +47,48 @@ bool pick_range(int units, int* G, int* nw) {   // units = remaining K / 128
   return best > 0;
 }
 
-// mode: LinearMode of the whole product; out16 / out16b: bf16 copies written by the pass that completes it
-int enqueue_linear(const ddd_body* b, const void* W, int N, int K, const uint16_t* x, int ldx, int R,
-                   const uint8_t* row_active, float* y, int ldy, int mode, uint16_t* out16, uint16_t* out16b, int ld16,
-                   hipStream_t s) {
-  const int ntiles = (N + 15) / 16;
-  const int nslice = ntiles < b->n_cu ? ntiles : b->n_cu;
+// One product y (+)= x W^T over K = sum of K ranges; `a` carries everything but the per-range fields.
+// a.mode is the LinearMode of the whole product; a.out16 / a.out16b are written by the range that completes it.
+int enqueue_linear(const ddd_body* b, LinearArgs a, int K, hipStream_t s) {
+  a.ntiles = (a.N + 15) / 16;
+  const int nslice = a.ntiles < b->n_cu ? a.ntiles : b->n_cu;
+  const uint16_t* W = a.W;
+  const uint16_t* x = a.x;
+  uint16_t* out16 = a.out16;
+  uint16_t* out16b = a.out16b;
+  const int mode = a.mode;
   int k0 = 0;
   while (k0 < K) {
     int G = 1, nw = 1;
     pick_range((K - k0) / 128, &G, &nw);
     const bool last = k0 + 128 * G * nw >= K;
-    LinearArgs a;
-    a.W = static_cast<const uint16_t*>(W) + k0;
-    a.x = x + k0;
-    a.row_active = row_active;
-    a.y = y;
+    // the gate needs complete sums: such a product must fit one K range
+    if (mode == kLinearSiluPairs && !(k0 == 0 && last)) return DDD_ERR_INVALID_ARG;
+    a.W = W + k0;
+    a.x = x ? x + k0 : nullptr;
     a.out16 = last ? out16 : nullptr;
     a.out16b = last ? out16b : nullptr;
-    a.ldw = K;
-    a.ldx = ldx;
-    a.ldy = ldy;
-    a.ld16 = ld16;
-    a.N = N;
-    a.R = R;
-    a.ntiles = ntiles;
     a.nw = nw;
-    // the gate needs the whole sum: a product split over K ranges accumulates in y and cannot use the pair mode
-    if (mode == kLinearSiluPairs && !(k0 == 0 && last)) return DDD_ERR_INVALID_ARG;
     a.mode = (k0 > 0) ? (int)kLinearAccumulate : mode;
     BODY_HIP(launch_linear_stream(a, G, nslice, s));
     k0 += 128 * G * nw;
   }
   return DDD_OK;
+}
+
+LinearArgs linear_args(const void* W, int ldw, int N, int R, const uint8_t* row_active, float* y, int ldy, int mode) {
+  LinearArgs a = {};
+  a.W = static_cast<const uint16_t*>(W);
+  a.ldw = ldw;
+  a.N = N;
+  a.R = R;
+  a.row_active = row_active;
+  a.y = y;
+  a.ldy = ldy;
+  a.mode = mode;
+  a.gather_mode = kGatherNone;
+  a.gather_k = 1;
+  return a;
 }
 
 }  // namespace
@@ -108,8 +116,7 @@ int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
   b->n_cu = prop.multiProcessorCount;
   b->bound = false;
   const size_t H = cfg->H, F = cfg->F, D = cfg->max_depth, R = kBodyRows;
-  hipError_t e = hipMalloc(&b->x0, R * 2 * H * sizeof(uint16_t));
-  if (e == hipSuccess) e = hipMalloc(&b->r, R * H * sizeof(float));
+  hipError_t e = hipMalloc(&b->r, R * H * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(&b->xn, R * H * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMalloc(&b->qkv, R * 3 * H * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(&b->act, R * F * sizeof(uint16_t));
@@ -117,7 +124,7 @@ int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
   if (e == hipSuccess) e = hipMalloc(&b->k_hist, D * R * H * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMalloc(&b->v_hist, D * R * H * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMalloc(&b->par_hist, D * R * sizeof(int32_t));
-  if (e == hipSuccess) e = hipMemset(b->x0, 0, R * 2 * H * sizeof(uint16_t));   // rows never written stay finite
+  if (e == hipSuccess) e = hipMemset(b->r, 0, R * H * sizeof(float));            // rows never written stay finite
   if (e == hipSuccess) e = hipMemset(b->xn, 0, R * H * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMemset(b->act, 0, R * F * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMemset(b->par_hist, 0, D * R * sizeof(int32_t));
@@ -131,7 +138,6 @@ int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
 
 int ddd_body_destroy(ddd_body* b) {
   if (b == nullptr) return DDD_ERR_INVALID_ARG;
-  (void)hipFree(b->x0);
   (void)hipFree(b->r);
   (void)hipFree(b->xn);
   (void)hipFree(b->qkv);
@@ -158,9 +164,10 @@ int ddd_body_linear(ddd_body* b, const void* W, int32_t N, int32_t K, const void
                     int32_t accumulate, void* stream) {
   if (b == nullptr || W == nullptr || x == nullptr || y == nullptr) return DDD_ERR_INVALID_ARG;
   if (N < 1 || K < 128 || K % 128 != 0 || R < 1 || R > kBodyRows) return DDD_ERR_INVALID_ARG;
-  return enqueue_linear(b, W, N, K, static_cast<const uint16_t*>(x), K, R, nullptr, y, N,
-                        accumulate ? kLinearAccumulate : kLinearStore, nullptr, nullptr, 0,
-                        static_cast<hipStream_t>(stream));
+  LinearArgs a = linear_args(W, K, N, R, nullptr, y, N, accumulate ? kLinearAccumulate : kLinearStore);
+  a.x = static_cast<const uint16_t*>(x);
+  a.ldx = K;
+  return enqueue_linear(b, a, K, static_cast<hipStream_t>(stream));
 }
 
 int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, void* stream) {
@@ -176,22 +183,25 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   const uint8_t* act = (step == 0) ? nullptr : st->row_active;   // a round starts with every sequence drafting
   const size_t hist = (size_t)step * kBodyRows * H;
 
-  BodyGatherArgs g;
-  g.E = static_cast<const uint16_t*>(b->w.E);
-  g.beam_token = st->beam_token;
-  g.beam_parent_slot = st->beam_parent_slot;
-  g.root_token = b->p.root_token;
-  g.f_root = static_cast<const uint16_t*>(b->p.f_root);
-  g.h_prev = (step == 0) ? nullptr : b->h_hist + hist - (size_t)kBodyRows * H;
-  g.row_active = act;
-  g.x0 = b->x0;
-  g.par_out = b->par_hist + (size_t)step * kBodyRows;
-  g.H = H;
-  g.k = b->cfg.k;
-  g.step = step;
-  g.R = R;
-  BODY_HIP(launch_body_gather(g, s));
-  int rc = enqueue_linear(b, b->w.Wfc, H, 2 * H, b->x0, 2 * H, R, act, b->r, H, kLinearStore, nullptr, nullptr, 0, s);
+  // r0 = [E[token], parent feature] Wfc^T as two K ranges of H, the rows read where they are
+  const uint16_t* Wfc = static_cast<const uint16_t*>(b->w.Wfc);
+  LinearArgs fe = linear_args(Wfc, 2 * H, H, R, act, b->r, H, kLinearStore);
+  fe.x = static_cast<const uint16_t*>(b->w.E);
+  fe.ldx = H;
+  fe.gather_mode = kGatherIndex;
+  fe.gather_idx = (step == 0) ? b->p.root_token : st->beam_token;
+  int rc = enqueue_linear(b, fe, H, s);
+  if (rc != DDD_OK) return rc;
+  LinearArgs ff = linear_args(Wfc + H, 2 * H, H, R, act, b->r, H, kLinearAccumulate);
+  ff.x = (step == 0) ? static_cast<const uint16_t*>(b->p.f_root) : b->h_hist + hist - (size_t)kBodyRows * H;
+  ff.ldx = H;
+  ff.gather_k = b->cfg.k;
+  if (step == 1) ff.gather_mode = kGatherBlock;            // the prompt call has one row per sequence
+  if (step >= 2) {
+    ff.gather_mode = kGatherInBlock;
+    ff.gather_idx = st->beam_parent_slot;
+  }
+  rc = enqueue_linear(b, ff, H, s);
   if (rc != DDD_OK) return rc;
 
   RmsNormArgs n1;
@@ -202,7 +212,10 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   n1.H = H;
   n1.R = R;
   BODY_HIP(launch_rmsnorm(n1, s));
-  rc = enqueue_linear(b, b->w.Wqkv, 3 * H, H, b->xn, H, R, act, b->qkv, 3 * H, kLinearStore, nullptr, nullptr, 0, s);
+  LinearArgs lq = linear_args(b->w.Wqkv, H, 3 * H, R, act, b->qkv, 3 * H, kLinearStore);
+  lq.x = b->xn;
+  lq.ldx = H;
+  rc = enqueue_linear(b, lq, H, s);
   if (rc != DDD_OK) return rc;
 
   BodyAttnArgs t;
@@ -212,6 +225,7 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   t.k_hist = b->k_hist;
   t.v_hist = b->v_hist;
   t.par_hist = b->par_hist;
+  t.beam_parent_slot = st->beam_parent_slot;
   t.row_active = act;
   t.o = b->xn;                     // the normalised rows are consumed: reuse their buffer
   t.H = H;
@@ -220,20 +234,32 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   t.step = step;
   t.R = R;
   BODY_HIP(launch_body_attention(t, s));
-  rc = enqueue_linear(b, b->w.Wo, H, H, b->xn, H, R, act, b->r, H, kLinearAccumulate, nullptr, nullptr, 0,
-                      s);   // r1 = r0 + o Wo^T
+  LinearArgs lo = linear_args(b->w.Wo, H, H, R, act, b->r, H, kLinearAccumulate);   // r1 = r0 + o Wo^T
+  lo.x = b->xn;
+  lo.ldx = H;
+  rc = enqueue_linear(b, lo, H, s);
   if (rc != DDD_OK) return rc;
 
+  // gate and up rows of Wgu alternate, so the epilogue of their linear forms a = bf16(silu(gate) * up) itself
   RmsNormArgs n2 = n1;
   n2.g = b->w.g2;
   BODY_HIP(launch_rmsnorm(n2, s));
-  // gate and up rows of Wgu alternate, so the epilogue of their linear forms a = bf16(silu(gate) * up) itself;
-  // it needs the complete sums, i.e. H in one K range (H <= 5120 of the form 128*G*nw)
-  rc = enqueue_linear(b, b->w.Wgu, 2 * F, H, b->xn, H, R, act, nullptr, 0, kLinearSiluPairs, b->act, nullptr, F, s);
+  LinearArgs lg = linear_args(b->w.Wgu, H, 2 * F, R, act, nullptr, 0, kLinearSiluPairs);
+  lg.x = b->xn;
+  lg.ldx = H;
+  lg.out16 = b->act;
+  lg.ld16 = F;
+  rc = enqueue_linear(b, lg, H, s);
   if (rc != DDD_OK) return rc;
-  // h = bf16(r1 + a Wd^T): the pass that completes the sum also writes the hidden rows and this call's features
-  rc = enqueue_linear(b, b->w.Wd, H, F, b->act, F, R, act, b->r, H, kLinearAccumulate, static_cast<uint16_t*>(hid_out),
-                      b->h_hist + hist, H, s);
+
+  // h = bf16(r1 + a Wd^T): the range that completes the sum also writes the hidden rows and this call's features
+  LinearArgs ld = linear_args(b->w.Wd, F, H, R, act, b->r, H, kLinearAccumulate);
+  ld.x = b->act;
+  ld.ldx = F;
+  ld.out16 = static_cast<uint16_t*>(hid_out);
+  ld.out16b = b->h_hist + hist;
+  ld.ld16 = H;
+  rc = enqueue_linear(b, ld, F, s);
   if (rc != DDD_OK) return rc;
   return DDD_OK;
 }

@@ -16,9 +16,18 @@ enum LinearMode {
   kLinearAccumulate = 1,   // y += sum
   kLinearSiluPairs = 2     // rows of W come in (gate_i, up_i) pairs: out16[r][i] = bf16(silu(gate) * up), y unused
 };
+// Where input row n of a linear comes from (the rows of [E[token], parent feature] are read in place).
+enum GatherMode {
+  kGatherNone = 0,     // source row n
+  kGatherIndex = 1,    // source row idx[n]                              (embedding row of the row's token)
+  kGatherInBlock = 2,  // source row (n / gk) * gk + idx[n]              (parent slot inside the sequence's block of gk rows)
+  kGatherBlock = 3     // source row n / gk                              (the single row of the sequence's prompt call)
+};
 struct LinearArgs {
   const uint16_t* W;          // bf16, row pitch ldw
-  const uint16_t* x;          // bf16 [R], row pitch ldx
+  const uint16_t* x;          // bf16 source rows, row pitch ldx
+  const int32_t* gather_idx;  // see GatherMode
+  int gather_mode, gather_k;
   const uint8_t* row_active;  // [R] or null: the launch does nothing if every row is inactive
   float* y;                   // fp32 [R], row pitch ldy
   uint16_t* out16;            // null, or bf16 [R] with row pitch ld16: the rounded result (modes 0/1), the activations (mode 2)
@@ -26,20 +35,6 @@ struct LinearArgs {
   int ldw, ldx, ldy, ld16, N, R, ntiles, nw, mode;
 };
 hipError_t launch_linear_stream(const LinearArgs& a, int G, int nslice, hipStream_t stream);
-
-struct BodyGatherArgs {
-  const uint16_t* E;                // bf16 [V][H]
-  const int32_t* beam_token;        // [B*k]
-  const int32_t* beam_parent_slot;  // [B*k]
-  const int32_t* root_token;        // [B]
-  const uint16_t* f_root;           // bf16 [B][H]
-  const uint16_t* h_prev;           // bf16 rows of the previous call
-  const uint8_t* row_active;        // [R] or null
-  uint16_t* x0;                     // bf16 [R][2H]
-  int32_t* par_out;                 // [R] parent slot of each row (step >= 1)
-  int H, k, step, R;
-};
-hipError_t launch_body_gather(const BodyGatherArgs& a, hipStream_t stream);
 
 // out[r] = bf16( x[r] / sqrt(mean(x[r]^2) + eps) * g )
 struct RmsNormArgs {
@@ -59,7 +54,8 @@ struct BodyAttnArgs {
   const uint16_t* Vp;
   uint16_t* k_hist;           // bf16 [D][kBodyRows][H]
   uint16_t* v_hist;
-  const int32_t* par_hist;    // [D][kBodyRows]
+  int32_t* par_hist;          // [D][kBodyRows] parent slot of every row of every call; this call's row is written here
+  const int32_t* beam_parent_slot;   // [B*k] of the current beam (read for step >= 1)
   const uint8_t* row_active;
   uint16_t* o;                // bf16 [R][H]
   int H, L, k, step, R;
