@@ -163,6 +163,27 @@ int ddd_tree_finalize(ddd_ctx* ctx, const ddd_state* st, ddd_tree* out, void* st
 int ddd_verify_accept(ddd_ctx* ctx, const ddd_tree* tree, const int32_t* target_argmax, int32_t* accept_len,
                       int32_t* accept_path, int32_t* bonus_token, void* stream);
 
+/* Tree attention of the verification pass: what consumes the final tree's mask (Section 1, EAGLE
+ * paragraph: the whole tree is fed to the target model at once, the attention mask adjusted so that
+ * a node sees the prompt, its ancestors and itself).  Per sequence, head and tree index i <= n_sel:
+ *   out[i] = sum_j softmax_j(q_i . k_j / sqrt(128)) v_j  over the L prompt keys and the tree keys j
+ *            with tree->mask[i][j] = 1; rows of tree indices past n_sel are written as zeros.
+ * Heads have 128 elements; queries and keys arrive already rotated (tree->pos holds each node's
+ * depth).  All device, bf16 unless noted:
+ *   q, k_tree   [B, m+1, n_heads, 128]          tree index order
+ *   vt_tree     [B, n_heads, 128, Tp]           values TRANSPOSED (element d, tree index), Tp = m+1
+ *                                               rounded up to 32, the padding must be zero
+ *   k_prompt    [B, L, n_heads, 128]            may be NULL if L = 0
+ *   vt_prompt   [B, n_heads, 128, Lp]           transposed likewise, Lp = L rounded up to 32, padding zero
+ *   workspace   device scratch of at least ddd_tree_attention_workspace(ctx, n_heads, L) bytes
+ *   out         fp32 [B, m+1, n_heads, 128]
+ * Values are kept transposed so that both products of the attention can feed the matrix cores
+ * from memory as stored. */
+size_t ddd_tree_attention_workspace(const ddd_ctx* ctx, int32_t n_heads, int32_t L);
+int ddd_tree_attention(ddd_ctx* ctx, const ddd_tree* tree, const void* q, const void* k_tree, const void* vt_tree,
+                       const void* k_prompt, const void* vt_prompt, int32_t L, int32_t n_heads, void* workspace,
+                       size_t workspace_bytes, float* out, void* stream);
+
 /* Draft-model body supplied by the caller: must enqueue on `stream` the work that writes the
  * hidden rows for draft call number step+1 into hid_out_bf16 ([B,H] for step 0, [B*k,H] after)
  * from the current beam in *st; rows of inactive sequences may be left untouched.  It must not

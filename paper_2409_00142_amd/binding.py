@@ -116,6 +116,8 @@ def load_library() -> C.CDLL:
         "ddd_synth_mfma_rate": (C.c_int, [vp, i32, i32, vp]),
         "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "ddd_weights_pack": (C.c_int, [vp, vp, vp]),
+        "ddd_tree_attention_workspace": (sz, [vp, i32, i32]),
+        "ddd_tree_attention": (C.c_int, [vp, trp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp, vp]),
         "ddd_synth_hash_tokens": (C.c_int, [vp, vp, i32, i32, C.c_uint64, vp]),
         "ddd_body_create": (C.c_int, [C.POINTER(ddd_body_config), C.POINTER(vp)]),
         "ddd_body_destroy": (C.c_int, [vp]),
@@ -322,6 +324,18 @@ def ddd_synth_round_stats(round_ctr, steps, accept_len, B, depth_hist, accept_hi
 def ddd_synth_hash_tokens(round_ctr, tokens, n, V, seed, stream=None):
     _check(load_library().ddd_synth_hash_tokens(_ptr(round_ctr), _ptr(tokens), n, V, seed,
                                                 current_stream() if stream is None else stream), "ddd_synth_hash_tokens")
+
+
+def ddd_tree_attention_workspace(ctx, n_heads, L) -> int:
+    return int(load_library().ddd_tree_attention_workspace(ctx, n_heads, L))
+
+
+def ddd_tree_attention(ctx, tree: ddd_tree, q, k_tree, vt_tree, k_prompt, vt_prompt, L, n_heads, workspace, out,
+                       stream=None):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load_library().ddd_tree_attention(ctx, C.byref(tree), _ptr(q), _ptr(k_tree), _ptr(vt_tree), _ptr(k_prompt),
+                                             _ptr(vt_prompt), L, n_heads, _ptr(workspace), nbytes, _ptr(out),
+                                             current_stream() if stream is None else stream), "ddd_tree_attention")
 
 
 def ddd_weights_pack(ctx, W, stream=None):

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libddd.so")
 SOURCES = ["ddd_api.hip", "lmhead_stream.hip", "lmhead_gemm.hip", "bookkeep.hip", "wide.hip", "tree.hip",
-           "synth_workload.hip", "body.hip", "body_api.hip"]
+           "synth_workload.hip", "body.hip", "body_api.hip", "tree_attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -265,6 +265,7 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
     if (e == hipSuccess) e = prepare_lmhead_gemm();
     if (e == hipSuccess && cfg->k > DDD_KMAX) e = prepare_wide();
   }
+  if (e == hipSuccess) e = prepare_tree_attention();
   if (e != hipSuccess) {
     if (c->logits) (void)hipFree(c->logits);
     if (c->grp_max) (void)hipFree(c->grp_max);
@@ -311,6 +312,55 @@ int ddd_weights_pack(ddd_ctx* c, const void* W, void* stream) {
   DDD_HIP(launch_pack_weights(static_cast<const uint16_t*>(W), c->pack, c->cfg.V, c->cfg.H,
                               static_cast<hipStream_t>(stream)));
   c->pack_src = W;
+  return DDD_OK;
+}
+
+namespace {
+// Key splits of the tree attention: about two workgroups per CU, at least eight 32-key chunks per split.
+int attn_splits(const ddd_ctx* c, int n_heads, int L) {
+  const int T = c->cfg.m + 1, nqt = (T + 63) / 64;
+  const int nchunks = (L + 31) / 32 + (T + 31) / 32;
+  int ns = (2 * c->n_cu) / (c->cfg.B * n_heads * nqt);
+  const int cap = nchunks / 8 > 1 ? nchunks / 8 : 1;
+  if (ns > cap) ns = cap;
+  if (ns > 64) ns = 64;
+  return ns < 1 ? 1 : ns;
+}
+}  // namespace
+
+size_t ddd_tree_attention_workspace(const ddd_ctx* c, int32_t n_heads, int32_t L) {
+  if (c == nullptr || n_heads < 1 || L < 0) return 0;
+  const size_t nqt = (size_t)(c->cfg.m + 1 + 63) / 64;
+  return (size_t)c->cfg.B * n_heads * nqt * attn_splits(c, n_heads, L) * tree_attention_part_floats() * sizeof(float);
+}
+
+int ddd_tree_attention(ddd_ctx* c, const ddd_tree* tree, const void* q, const void* k_tree, const void* vt_tree,
+                       const void* k_prompt, const void* vt_prompt, int32_t L, int32_t n_heads, void* workspace,
+                       size_t workspace_bytes, float* out, void* stream) {
+  if (c == nullptr || !tree_ok(tree) || q == nullptr || k_tree == nullptr || vt_tree == nullptr || out == nullptr ||
+      workspace == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  if (n_heads < 1 || n_heads > 1024 || L < 0 || L > (1 << 20) || (L > 0 && (k_prompt == nullptr || vt_prompt == nullptr)))
+    return DDD_ERR_INVALID_ARG;
+  if (workspace_bytes < ddd_tree_attention_workspace(c, n_heads, L)) return DDD_ERR_INVALID_ARG;
+  TreeAttnArgs a;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_tree = static_cast<const uint16_t*>(k_tree);
+  a.vt_tree = static_cast<const uint16_t*>(vt_tree);
+  a.k_prompt = static_cast<const uint16_t*>(k_prompt);
+  a.vt_prompt = static_cast<const uint16_t*>(vt_prompt);
+  a.mask = tree->mask;
+  a.n_sel = tree->n_sel;
+  a.part = static_cast<float*>(workspace);
+  a.out = out;
+  a.B = c->cfg.B;
+  a.T = c->cfg.m + 1;
+  a.nh = n_heads;
+  a.L = L;
+  a.Lp = (L + 31) & ~31;
+  a.Tp = (a.T + 31) & ~31;
+  a.nsplit = attn_splits(c, n_heads, L);
+  DDD_HIP(launch_tree_attention(a, static_cast<hipStream_t>(stream)));
   return DDD_OK;
 }
 

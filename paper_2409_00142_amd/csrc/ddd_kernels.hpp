@@ -133,4 +133,21 @@ struct VerifyArgs {
 };
 hipError_t launch_verify_accept(const VerifyArgs& a, hipStream_t stream);
 
+// Tree attention over the final tree's mask (tree_attn.hip); heads of 128.
+struct TreeAttnArgs {
+  const uint16_t* q;          // bf16 [B][T][nh][128]   T = m + 1 tree indices
+  const uint16_t* k_tree;     // bf16 [B][T][nh][128]
+  const uint16_t* vt_tree;    // bf16 [B][nh][128][Tp]  values transposed, Tp = T rounded up to 32, padding zero
+  const uint16_t* k_prompt;   // bf16 [B][L][nh][128]
+  const uint16_t* vt_prompt;  // bf16 [B][nh][128][Lp]  Lp = L rounded up to 32, padding zero
+  const uint8_t* mask;        // [B][T][T]
+  const int32_t* n_sel;       // [B]
+  float* part;                // workspace: [B][nh][query tiles][nsplit][tree_attention_part_floats()]
+  float* out;                 // fp32 [B][T][nh][128]
+  int B, T, nh, L, Lp, Tp, nsplit;
+};
+hipError_t prepare_tree_attention();
+size_t tree_attention_part_floats();
+hipError_t launch_tree_attention(const TreeAttnArgs& a, hipStream_t stream);
+
 }  // namespace ddd

@@ -1,0 +1,89 @@
+"""GPU parity of ddd_tree_attention (the consumer of the final tree's mask) against oracle/tree_attention.py,
+through the C ABI."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import bruteforce as BF
+from oracle import tree_attention as OT
+
+pytestmark = pytest.mark.gpu
+
+# The weights of the second product are rounded to bf16 (2^-9 relative) before they meet the values on the
+# matrix cores, and exp is the fast fp32 one; with values of order one (|v| < 5 here) the output error stays
+# below 5 * 2^-9 = 1e-2.
+ATTN_TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a HIP device (run them with gpurun)")
+    import paper_2409_00142_amd as D
+    from synth import device as SD
+    return torch, D, SD
+
+
+def _random_tree(rng, T, n_sel):
+    """parent_idx of a random tree over tree indices 0..n_sel (parents precede children), -1 padded."""
+    parent = [-1] * T
+    for i in range(1, n_sel + 1):
+        parent[i] = int(rng.integers(0, i))
+    return parent
+
+
+CASES = [
+    # name, B, m, n_heads, L, n_sel per sequence
+    ("no_prompt_small", 1, 20, 2, 0, [20]),
+    ("ragged_prompt_two_sequences", 2, 60, 4, 100, [60, 37]),
+    ("two_query_tiles", 1, 127, 3, 1000, [127]),
+    ("short_tree_long_prompt", 1, 60, 8, 2048, [9]),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_tree_attention_against_oracle(gpu, case):
+    torch, D, SD = gpu
+    name, B, m, nh, L, n_sels = case
+    T, d = m + 1, 128
+    print(f"[case] tree attention {name} B={B} m={m} heads={nh} L={L} n_sel={n_sels}", flush=True)
+    rng = np.random.default_rng(abs(hash(name)) % (1 << 31))
+    bits = lambda shape: synth.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    q, kt, vt = bits((B, T, nh, d)), bits((B, T, nh, d)), bits((B, T, nh, d))
+    kp, vp = bits((B, L, nh, d)), bits((B, L, nh, d))
+    Tp, Lp = (T + 31) // 32 * 32, (L + 31) // 32 * 32
+    vt_t = np.zeros((B, nh, d, Tp), dtype=np.uint16)
+    vt_t[:, :, :, :T] = vt.transpose(0, 2, 3, 1)
+    vp_t = np.zeros((B, nh, d, max(Lp, 32)), dtype=np.uint16)
+    vp_t[:, :, :, :L] = vp.transpose(0, 2, 3, 1)
+    parents = [_random_tree(rng, T, n_sels[b]) for b in range(B)]
+    masks = np.zeros((B, T, T), dtype=np.uint8)
+    for b in range(B):
+        n = n_sels[b] + 1
+        masks[b, :n, :n] = np.array(BF.closure_mask(parents[b][:n], n), dtype=np.uint8)
+
+    cfg = D.make_config(B, 256, 1000, 4, 4, m, 0.3)
+    ctx = D.ddd_create(cfg)
+    try:
+        tree, tree_t = D.alloc_tree(cfg)
+        tree_t["mask"].copy_(torch.from_numpy(masks).view_as(tree_t["mask"]))
+        tree_t["n_sel"].copy_(torch.tensor(n_sels, dtype=torch.int32))
+        ws = torch.empty(max(1, D.ddd_tree_attention_workspace(ctx, nh, L) // 4), dtype=torch.float32, device="cuda")
+        out = torch.full((B, T, nh, d), float("nan"), dtype=torch.float32, device="cuda")
+        up = SD.upload_bits
+        args = (up(q), up(kt), up(vt_t), up(kp) if L else None, up(vp_t[:, :, :, :max(Lp, 1)].copy()) if L else None)
+        D.ddd_tree_attention(ctx, tree, *args, L, nh, ws, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        D.ddd_tree_attention(ctx, tree, *args, L, nh, ws, out)     # deterministic: the same bits again
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().astype(np.float64), got)
+    finally:
+        D.ddd_destroy(ctx)
+    f = OT.bf16_bits_to_f64
+    assert not np.isnan(got).any()
+    for b in range(B):
+        want = OT.tree_attention(f(q[b]), f(kt[b]), f(vt[b]), f(kp[b]), f(vp[b]), masks[b], n_sels[b])
+        assert np.max(np.abs(got[b] - want)) <= ATTN_TOL, float(np.max(np.abs(got[b] - want)))
+        assert np.all(got[b, n_sels[b] + 1:] == 0.0)
