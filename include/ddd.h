@@ -171,17 +171,23 @@ int ddd_verify_accept(ddd_ctx* ctx, const ddd_tree* tree, const int32_t* target_
  * Heads have 128 elements; queries and keys arrive already rotated (tree->pos holds each node's
  * depth).  All device, bf16 unless noted:
  *   q, k_tree   [B, m+1, n_heads, 128]          tree index order
- *   vt_tree     [B, n_heads, 128, Tp]           values TRANSPOSED (element d, tree index), Tp = m+1
+ *   vt_tree     [B, n_heads, 128, Tp]           tree values TRANSPOSED (element d, tree index), Tp = m+1
  *                                               rounded up to 32, the padding must be zero
- *   k_prompt    [B, L, n_heads, 128]            may be NULL if L = 0
- *   vt_prompt   [B, n_heads, 128, Lp]           transposed likewise, Lp = L rounded up to 32, padding zero
+ *   k_packed,   the prompt's keys and values as written by ddd_kv_pack, each B * n_heads * ceil(L/32) * 4096
+ *   v_packed    elements; may be NULL if L = 0
  *   workspace   device scratch of at least ddd_tree_attention_workspace(ctx, n_heads, L) bytes
  *   out         fp32 [B, m+1, n_heads, 128]
- * Values are kept transposed so that both products of the attention can feed the matrix cores
- * from memory as stored. */
+ * The prompt cache is read once per call and is what the call's time is made of, so it is kept in the order
+ * the matrix cores take their operands in (every load of a wavefront is 1 KB of consecutive memory): per
+ * sequence, head and chunk c of 32 keys, 8 KB of keys [s = 0..7][lane = 0..63][8] = K[key 32c + lane%32]
+ * [d = 16s + 8*(lane/32) + 0..7], and 8 KB of values [db*2 + t][lane][8] = V[key 32c + 16t + 4*(lane/32) + 0..3,
+ * then 32c + 16t + 8 + 4*(lane/32) + 0..3][d = 32*db + lane%32] (db = 0..3, t = 0..1); keys past L are zero.
+ * ddd_kv_pack writes this from row-major k, v [B, L, n_heads, 128]. */
+int ddd_kv_pack(ddd_ctx* ctx, const void* k, const void* v, int32_t L, int32_t n_heads, void* k_packed, void* v_packed,
+                void* stream);
 size_t ddd_tree_attention_workspace(const ddd_ctx* ctx, int32_t n_heads, int32_t L);
 int ddd_tree_attention(ddd_ctx* ctx, const ddd_tree* tree, const void* q, const void* k_tree, const void* vt_tree,
-                       const void* k_prompt, const void* vt_prompt, int32_t L, int32_t n_heads, void* workspace,
+                       const void* k_packed, const void* v_packed, int32_t L, int32_t n_heads, void* workspace,
                        size_t workspace_bytes, float* out, void* stream);
 
 /* Draft-model body supplied by the caller: must enqueue on `stream` the work that writes the

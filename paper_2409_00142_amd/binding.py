@@ -117,6 +117,7 @@ def load_library() -> C.CDLL:
         "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "ddd_weights_pack": (C.c_int, [vp, vp, vp]),
         "ddd_tree_attention_workspace": (sz, [vp, i32, i32]),
+        "ddd_kv_pack": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp]),
         "ddd_tree_attention": (C.c_int, [vp, trp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp, vp]),
         "ddd_synth_hash_tokens": (C.c_int, [vp, vp, i32, i32, C.c_uint64, vp]),
         "ddd_body_create": (C.c_int, [C.POINTER(ddd_body_config), C.POINTER(vp)]),
@@ -328,6 +329,11 @@ def ddd_synth_hash_tokens(round_ctr, tokens, n, V, seed, stream=None):
 
 def ddd_tree_attention_workspace(ctx, n_heads, L) -> int:
     return int(load_library().ddd_tree_attention_workspace(ctx, n_heads, L))
+
+
+def ddd_kv_pack(ctx, k, v, L, n_heads, k_packed, v_packed, stream=None):
+    _check(load_library().ddd_kv_pack(ctx, _ptr(k), _ptr(v), L, n_heads, _ptr(k_packed), _ptr(v_packed),
+                                      current_stream() if stream is None else stream), "ddd_kv_pack")
 
 
 def ddd_tree_attention(ctx, tree: ddd_tree, q, k_tree, vt_tree, k_prompt, vt_prompt, L, n_heads, workspace, out,

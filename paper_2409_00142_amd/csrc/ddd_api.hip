@@ -334,21 +334,31 @@ size_t ddd_tree_attention_workspace(const ddd_ctx* c, int32_t n_heads, int32_t L
   return (size_t)c->cfg.B * n_heads * nqt * attn_splits(c, n_heads, L) * tree_attention_part_floats() * sizeof(float);
 }
 
+int ddd_kv_pack(ddd_ctx* c, const void* k, const void* v, int32_t L, int32_t n_heads, void* k_packed, void* v_packed,
+                void* stream) {
+  if (c == nullptr || L < 1 || L > (1 << 20) || n_heads < 1 || n_heads > 1024) return DDD_ERR_INVALID_ARG;
+  if (k == nullptr || v == nullptr || k_packed == nullptr || v_packed == nullptr) return DDD_ERR_INVALID_ARG;
+  DDD_HIP(launch_kv_pack(static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
+                         static_cast<uint16_t*>(k_packed), static_cast<uint16_t*>(v_packed), c->cfg.B, L, n_heads,
+                         static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
 int ddd_tree_attention(ddd_ctx* c, const ddd_tree* tree, const void* q, const void* k_tree, const void* vt_tree,
-                       const void* k_prompt, const void* vt_prompt, int32_t L, int32_t n_heads, void* workspace,
+                       const void* k_packed, const void* v_packed, int32_t L, int32_t n_heads, void* workspace,
                        size_t workspace_bytes, float* out, void* stream) {
   if (c == nullptr || !tree_ok(tree) || q == nullptr || k_tree == nullptr || vt_tree == nullptr || out == nullptr ||
       workspace == nullptr)
     return DDD_ERR_INVALID_ARG;
-  if (n_heads < 1 || n_heads > 1024 || L < 0 || L > (1 << 20) || (L > 0 && (k_prompt == nullptr || vt_prompt == nullptr)))
+  if (n_heads < 1 || n_heads > 1024 || L < 0 || L > (1 << 20) || (L > 0 && (k_packed == nullptr || v_packed == nullptr)))
     return DDD_ERR_INVALID_ARG;
   if (workspace_bytes < ddd_tree_attention_workspace(c, n_heads, L)) return DDD_ERR_INVALID_ARG;
   TreeAttnArgs a;
   a.q = static_cast<const uint16_t*>(q);
   a.k_tree = static_cast<const uint16_t*>(k_tree);
   a.vt_tree = static_cast<const uint16_t*>(vt_tree);
-  a.k_prompt = static_cast<const uint16_t*>(k_prompt);
-  a.vt_prompt = static_cast<const uint16_t*>(vt_prompt);
+  a.k_prompt = static_cast<const uint16_t*>(k_packed);
+  a.v_prompt = static_cast<const uint16_t*>(v_packed);
   a.mask = tree->mask;
   a.n_sel = tree->n_sel;
   a.part = static_cast<float*>(workspace);
@@ -357,7 +367,6 @@ int ddd_tree_attention(ddd_ctx* c, const ddd_tree* tree, const void* q, const vo
   a.T = c->cfg.m + 1;
   a.nh = n_heads;
   a.L = L;
-  a.Lp = (L + 31) & ~31;
   a.Tp = (a.T + 31) & ~31;
   a.nsplit = attn_splits(c, n_heads, L);
   DDD_HIP(launch_tree_attention(a, static_cast<hipStream_t>(stream)));

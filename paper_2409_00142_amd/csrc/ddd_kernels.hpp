@@ -138,15 +138,18 @@ struct TreeAttnArgs {
   const uint16_t* q;          // bf16 [B][T][nh][128]   T = m + 1 tree indices
   const uint16_t* k_tree;     // bf16 [B][T][nh][128]
   const uint16_t* vt_tree;    // bf16 [B][nh][128][Tp]  values transposed, Tp = T rounded up to 32, padding zero
-  const uint16_t* k_prompt;   // bf16 [B][L][nh][128]
-  const uint16_t* vt_prompt;  // bf16 [B][nh][128][Lp]  Lp = L rounded up to 32, padding zero
+  const uint16_t* k_prompt;   // bf16 [B][nh][ceil(L/32)][8][64][8]  prompt keys in fragment order (launch_kv_pack)
+  const uint16_t* v_prompt;   // bf16, the same shape: prompt values in fragment order
   const uint8_t* mask;        // [B][T][T]
   const int32_t* n_sel;       // [B]
   float* part;                // workspace: [B][nh][query tiles][nsplit][tree_attention_part_floats()]
   float* out;                 // fp32 [B][T][nh][128]
-  int B, T, nh, L, Lp, Tp, nsplit;
+  int B, T, nh, L, Tp, nsplit;
 };
 hipError_t prepare_tree_attention();
+// k, v: bf16 [B][L][nh][128] -> the fragment-order cache the attention reads (each ceil(L/32)*32*nh*128*B elements)
+hipError_t launch_kv_pack(const uint16_t* k, const uint16_t* v, uint16_t* kp, uint16_t* vp, int B, int L, int nh,
+                          hipStream_t stream);
 size_t tree_attention_part_floats();
 hipError_t launch_tree_attention(const TreeAttnArgs& a, hipStream_t stream);
 

@@ -55,8 +55,6 @@ def test_tree_attention_against_oracle(gpu, case):
     Tp, Lp = (T + 31) // 32 * 32, (L + 31) // 32 * 32
     vt_t = np.zeros((B, nh, d, Tp), dtype=np.uint16)
     vt_t[:, :, :, :T] = vt.transpose(0, 2, 3, 1)
-    vp_t = np.zeros((B, nh, d, max(Lp, 32)), dtype=np.uint16)
-    vp_t[:, :, :, :L] = vp.transpose(0, 2, 3, 1)
     parents = [_random_tree(rng, T, n_sels[b]) for b in range(B)]
     masks = np.zeros((B, T, T), dtype=np.uint8)
     for b in range(B):
@@ -72,7 +70,13 @@ def test_tree_attention_against_oracle(gpu, case):
         ws = torch.empty(max(1, D.ddd_tree_attention_workspace(ctx, nh, L) // 4), dtype=torch.float32, device="cuda")
         out = torch.full((B, T, nh, d), float("nan"), dtype=torch.float32, device="cuda")
         up = SD.upload_bits
-        args = (up(q), up(kt), up(vt_t), up(kp) if L else None, up(vp_t[:, :, :, :max(Lp, 1)].copy()) if L else None)
+        kpk = vpk = None
+        if L:
+            n_packed = B * nh * (Lp // 32) * 4096
+            kpk = torch.full((n_packed,), float("nan"), dtype=torch.bfloat16, device="cuda")
+            vpk = torch.full((n_packed,), float("nan"), dtype=torch.bfloat16, device="cuda")
+            D.ddd_kv_pack(ctx, up(kp), up(vp), L, nh, kpk, vpk)
+        args = (up(q), up(kt), up(vt_t), kpk, vpk)
         D.ddd_tree_attention(ctx, tree, *args, L, nh, ws, out)
         torch.cuda.synchronize()
         got = out.cpu().numpy().astype(np.float64)
