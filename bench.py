@@ -49,6 +49,36 @@ def cpu_baseline(wl, W_bits, plant_dir, threshold, budget_s):
             "us_per_depth_step": 1e6 * el / steps}
 
 
+def time_tree_attention(torch, D, g, wl, L, side):
+    """ddd_tree_attention on the workload's final trees (as left by the last round), random q / k / v."""
+    B, T, nh = wl.B, wl.m + 1, wl.H // 128
+    Tp, Lp = (T + 31) // 32 * 32, (L + 31) // 32 * 32
+    rnd = lambda *s: torch.randn(*s, device="cuda").to(torch.bfloat16)
+    q, kt = rnd(B, T, nh, 128), rnd(B, T, nh, 128)
+    vtt = torch.zeros(B, nh, 128, Tp, device="cuda", dtype=torch.bfloat16)
+    vtt[..., :T] = rnd(B, nh, 128, T)
+    kpk = torch.empty(B * nh * (Lp // 32) * 4096, device="cuda", dtype=torch.bfloat16)
+    vpk = torch.empty_like(kpk)
+    D.ddd_kv_pack(g.ctx, rnd(B, L, nh, 128), rnd(B, L, nh, 128), L, nh, kpk, vpk)
+    ws = torch.empty(max(1, D.ddd_tree_attention_workspace(g.ctx, nh, L) // 4), dtype=torch.float32, device="cuda")
+    res = torch.empty(B, T, nh, 128, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    n = 50
+    with torch.cuda.stream(side):
+        for _ in range(5):
+            D.ddd_tree_attention(g.ctx, g.tree, q, kt, vtt, kpk, vpk, L, nh, ws, res, stream=side.cuda_stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        for _ in range(n):
+            D.ddd_tree_attention(g.ctx, g.tree, q, kt, vtt, kpk, vpk, L, nh, ws, res, stream=side.cuda_stream)
+        e1.record(side)
+        side.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / n
+    alg = 2 * B * (L + T) * nh * 256 + B * T * nh * 128 * (2 + 4)   # keys and values once, queries in, fp32 rows out
+    return {"us_per_call": us, "B": B, "tree_nodes": T, "heads": nh, "prompt_len": L, "algorithmic_bytes": alg,
+            "GBs": alg / us / 1e3, "hbm_frac": alg / us / 1e3 / HBM_PEAK_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +103,9 @@ def main():
     ap.add_argument("--ffn", type=int, default=None, help="MLP width of the draft layer (default 11008, 13824 for H=5120)")
     ap.add_argument("--lm-sigma", type=float, default=None, help="std of the LM-head weights with --body layer (default 0.07)")
     ap.add_argument("--prompt-len", type=int, default=256, help="prompt positions every draft row attends to")
+    ap.add_argument("--tree-attention", type=int, default=0, metavar="L",
+                    help="also time ddd_tree_attention (the consumer of the tree mask) for the workload's B and m, H/128 "
+                         "heads and a prompt of L positions; adds a tree_attention object to the JSON line")
     ap.add_argument("--pack-weights", choices=["auto", "on", "off"], default="auto",
                     help="tile-major copy of W for the GEMM path (ddd_weights_pack); auto: when the GEMM path is used "
                          "and W is larger than the 256 MB Infinity Cache, i.e. really streams from HBM")
@@ -275,6 +308,9 @@ def main():
                             "algorithmic_bytes_per_launch": alg_bytes, "algorithmic_flops_per_launch": alg_flops,
                             "launches_timed": args.profile_iters, "read_stream_ceiling_GBs": best,
                             "mfma_loop_ceiling_TFLOPs": mfma_ceiling})
+    if args.tree_attention > 0:
+        out["tree_attention"] = time_tree_attention(torch, D, g, wl, args.tree_attention, side)
+        log(f"[bench] tree attention: {out['tree_attention']}")
     if args.cpu_budget > 0:
         log(f"[bench] timing the CPU oracle for about {args.cpu_budget:.0f} s ...")
         out["cpu_baseline"] = cpu_baseline(wl, g.W_bits, g.plant_dir_np if wl.n_plant else None, thr, args.cpu_budget)
