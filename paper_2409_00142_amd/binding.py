@@ -336,11 +336,11 @@ def ddd_kv_pack(ctx, k, v, L, n_heads, k_packed, v_packed, stream=None):
                                       current_stream() if stream is None else stream), "ddd_kv_pack")
 
 
-def ddd_tree_attention(ctx, tree: ddd_tree, q, k_tree, vt_tree, k_prompt, vt_prompt, L, n_heads, workspace, out,
+def ddd_tree_attention(ctx, tree: ddd_tree, q, k_tree, vt_tree, k_packed, v_packed, L, n_heads, workspace, out,
                        stream=None):
     nbytes = workspace.numel() * workspace.element_size()
-    _check(load_library().ddd_tree_attention(ctx, C.byref(tree), _ptr(q), _ptr(k_tree), _ptr(vt_tree), _ptr(k_prompt),
-                                             _ptr(vt_prompt), L, n_heads, _ptr(workspace), nbytes, _ptr(out),
+    _check(load_library().ddd_tree_attention(ctx, C.byref(tree), _ptr(q), _ptr(k_tree), _ptr(vt_tree), _ptr(k_packed),
+                                             _ptr(v_packed), L, n_heads, _ptr(workspace), nbytes, _ptr(out),
                                              current_stream() if stream is None else stream), "ddd_tree_attention")
 
 
