@@ -163,6 +163,26 @@ int ddd_tree_finalize(ddd_ctx* ctx, const ddd_state* st, ddd_tree* out, void* st
 int ddd_verify_accept(ddd_ctx* ctx, const ddd_tree* tree, const int32_t* target_argmax, int32_t* accept_len,
                       int32_t* accept_path, int32_t* bonus_token, void* stream);
 
+/* Sampled accept walk at temperature T > 0.  The paper evaluates temperature 0 only (Section 3.1); what it
+ * fixes is that the emitted tokens follow the target model's distribution (Section 1).  A drafted child is a
+ * deterministic proposal, so it is accepted with the probability the target gives its token, and after a
+ * rejection the target distribution continues without that token, renormalised.  With
+ * w_j = exp((x_j - max x) / T) over the current node's logit row x and rem = the weight not yet rejected
+ * (initially sum_j w_j), the children c of the current node are tried in tree-index order:
+ *     accept c  iff  u_accept[c] * rem < w[token_c];      else rem -= w[token_c], w[token_c] = 0.
+ * When none is accepted (or the node has no child) the bonus token is the smallest j whose prefix sum of the
+ * remaining w exceeds u_bonus[node] * rem; if rounding leaves no such j, the last token with w > 0, else the
+ * row's argmax.  All decisions are taken in fp64.
+ *   target_logits device fp32 [B, m+1, V]: the target model's logits after each tree node; every row needs a
+ *                 finite maximum (-inf entries are allowed)
+ *   temperature   > 0, finite
+ *   u_accept      device fp64 [B, m+1] uniforms in [0,1), entry i drives the test of tree index i
+ *   u_bonus       device fp64 [B, m+1] uniforms in [0,1), entry i drives the bonus draw at tree index i
+ *   outputs as for ddd_verify_accept.  Only the logit rows of the accepted path are read. */
+int ddd_verify_sample(ddd_ctx* ctx, const ddd_tree* tree, const float* target_logits, float temperature,
+                      const double* u_accept, const double* u_bonus, int32_t* accept_len, int32_t* accept_path,
+                      int32_t* bonus_token, void* stream);
+
 /* Tree attention of the verification pass: what consumes the final tree's mask (Section 1, EAGLE
  * paragraph: the whole tree is fed to the target model at once, the attention mask adjusted so that
  * a node sees the prompt, its ancestors and itself).  Per sequence, head and tree index i <= n_sel:

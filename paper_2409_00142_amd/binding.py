@@ -106,6 +106,7 @@ def load_library() -> C.CDLL:
         "ddd_draft_step": (C.c_int, [vp, i32, vp, vp, stp, trp, vp, vp, vp]),
         "ddd_tree_finalize": (C.c_int, [vp, stp, trp, vp]),
         "ddd_verify_accept": (C.c_int, [vp, trp, vp, vp, vp, vp, vp]),
+        "ddd_verify_sample": (C.c_int, [vp, trp, vp, C.c_float, vp, vp, vp, vp, vp, vp]),
         "ddd_round_enqueue": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_capture": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_launch": (C.c_int, [vp, vp]),
@@ -263,6 +264,13 @@ def ddd_verify_accept(ctx, tree: ddd_tree, target_argmax, accept_len, accept_pat
     _check(load_library().ddd_verify_accept(ctx, C.byref(tree), _ptr(target_argmax), _ptr(accept_len),
                                             _ptr(accept_path), _ptr(bonus_token),
                                             current_stream() if stream is None else stream), "ddd_verify_accept")
+
+
+def ddd_verify_sample(ctx, tree: ddd_tree, target_logits, temperature, u_accept, u_bonus, accept_len, accept_path,
+                      bonus_token, stream=None):
+    _check(load_library().ddd_verify_sample(ctx, C.byref(tree), _ptr(target_logits), float(temperature), _ptr(u_accept),
+                                            _ptr(u_bonus), _ptr(accept_len), _ptr(accept_path), _ptr(bonus_token),
+                                            current_stream() if stream is None else stream), "ddd_verify_sample")
 
 
 def _fn_ptr(fn) -> Optional[int]:

@@ -552,6 +552,30 @@ int ddd_verify_accept(ddd_ctx* c, const ddd_tree* tree, const int32_t* target_ar
   return DDD_OK;
 }
 
+int ddd_verify_sample(ddd_ctx* c, const ddd_tree* tree, const float* target_logits, float temperature,
+                      const double* u_accept, const double* u_bonus, int32_t* accept_len, int32_t* accept_path,
+                      int32_t* bonus_token, void* stream) {
+  if (c == nullptr || !tree_ok(tree) || target_logits == nullptr || u_accept == nullptr || u_bonus == nullptr ||
+      accept_len == nullptr || accept_path == nullptr || bonus_token == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  if (!(temperature > 0.0f) || !(temperature < 3.0e38f)) return DDD_ERR_INVALID_ARG;
+  VerifySampleArgs a;
+  a.tree = *tree;
+  a.logits = target_logits;
+  a.u_accept = u_accept;
+  a.u_bonus = u_bonus;
+  a.accept_len = accept_len;
+  a.accept_path = accept_path;
+  a.bonus_token = bonus_token;
+  a.temperature = temperature;
+  a.B = c->cfg.B;
+  a.m = c->cfg.m;
+  a.D = c->cfg.max_depth;
+  a.V = c->cfg.V;
+  DDD_HIP(launch_verify_sample(a, static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
 int ddd_round_enqueue(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
                       void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,
                       float* logits_dbg, float* lse_dbg, void* stream) {

@@ -133,6 +133,19 @@ struct VerifyArgs {
 };
 hipError_t launch_verify_accept(const VerifyArgs& a, hipStream_t stream);
 
+struct VerifySampleArgs {
+  ddd_tree tree;
+  const float* logits;           // fp32 [B,m+1,V]: the target model's logits after every tree node
+  const double* u_accept;        // [B,m+1] uniforms in [0,1): acceptance test of each tree node
+  const double* u_bonus;         // [B,m+1] uniforms in [0,1): bonus draw at each tree node
+  int32_t* accept_len;           // [B]
+  int32_t* accept_path;          // [B,D+1]
+  int32_t* bonus_token;          // [B]
+  float temperature;
+  int B, m, D, V;
+};
+hipError_t launch_verify_sample(const VerifySampleArgs& a, hipStream_t stream);
+
 // Tree attention over the final tree's mask (tree_attn.hip); heads of 128.
 struct TreeAttnArgs {
   const uint16_t* q;          // bf16 [B][T][nh][128]   T = m + 1 tree indices

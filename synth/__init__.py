@@ -15,6 +15,8 @@ from .inputs import (  # noqa: F401
     make_plant_table,
     make_body_weights,
     make_prompt_context,
+    make_random_tree,
+    make_target_logits,
     mix64,
     stream_key,
     node_key,

@@ -213,6 +213,48 @@ def make_prompt_context(L: int, H: int, seed: int = 0) -> dict:
             "f_root": _normal_bits(rng, (1, H), 1.0)[0]}
 
 
+def make_random_tree(m: int, n_sel: int, k: int, V: int, max_depth: int, seed: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """A random draft-tree shape for the acceptance tests: (tree_token[m+1], parent_idx[m+1]) with
+    index 0 the root, parents before children, at most k children per node, no node deeper than
+    max_depth and distinct tokens among the children of one node; entries past n_sel are -1."""
+    rng = np.random.default_rng(3000 + seed)
+    tok = np.full(m + 1, -1, np.int32)
+    par = np.full(m + 1, -1, np.int32)
+    tok[0] = int(rng.integers(0, V))
+    n_kids = np.zeros(m + 1, np.int64)
+    depth = np.zeros(m + 1, np.int64)
+    used = [set() for _ in range(m + 1)]
+    for i in range(1, n_sel + 1):
+        open_nodes = np.nonzero((n_kids[:i] < k) & (depth[:i] < max_depth))[0]
+        if open_nodes.size == 0:
+            raise ValueError("n_sel nodes do not fit a tree of this width and depth")
+        # favour recent nodes a little so that trees get some depth
+        p = int(open_nodes[min(len(open_nodes) - 1, int(len(open_nodes) * rng.random() ** 0.6))])
+        t = int(rng.integers(0, V))
+        while t in used[p]:
+            t = int(rng.integers(0, V))
+        used[p].add(t)
+        n_kids[p] += 1
+        depth[i] = depth[p] + 1
+        par[i], tok[i] = p, t
+    return tok, par
+
+
+def make_target_logits(tree_token: np.ndarray, parent_idx: np.ndarray, n_sel: int, V: int, seed: int = 0,
+                       sigma: float = 2.0, boost: float = 13.0, agree: float = 0.8) -> np.ndarray:
+    """Stand-in target logits fp32 [m+1, V] for sampled acceptance: N(0, sigma) noise, and with
+    probability `agree` a node's row favours the token of one of its children by `boost`, so that
+    accepted paths have a realistic length."""
+    rng = np.random.default_rng(4000 + seed)
+    T = tree_token.shape[0]
+    x = (rng.standard_normal((T, V), dtype=np.float32) * np.float32(sigma)).astype(np.float32)
+    for i in range(n_sel + 1):
+        kids = np.nonzero(parent_idx[1:n_sel + 1] == i)[0] + 1
+        if kids.size and rng.random() < agree:
+            x[i, tree_token[int(rng.choice(kids))]] += np.float32(boost)
+    return x
+
+
 def make_plant_table(W_bits: np.ndarray, wl: Workload) -> Tuple[np.ndarray, np.ndarray]:
     """(plant_tokens int32[n_plant], plant_dir fp32[n_plant,H]) or empty arrays."""
     if wl.n_plant <= 0:

@@ -21,7 +21,7 @@ def D():
 
 def _declared_symbols():
     names = []
-    for hdr in ("ddd.h", "ddd_synth.h"):
+    for hdr in ("ddd.h", "ddd_synth.h", "ddd_body.h"):
         text = open(os.path.join(ROOT, "include", hdr)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names += re.findall(r"^\s*(?:const\s+char\s*\*|int|size_t)\s+(ddd_\w+)\s*\(", text, flags=re.M)
@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(D):
     lib = D.load_library()
     names = _declared_symbols()
     assert len(names) >= 24
-    for n in ("ddd_lmhead_topk", "ddd_beam_select", "ddd_depth_continue", "ddd_tree_finalize", "ddd_verify_accept"):
+    for n in ("ddd_lmhead_topk", "ddd_beam_select", "ddd_depth_continue", "ddd_tree_finalize", "ddd_verify_accept",
+              "ddd_verify_sample", "ddd_tree_attention", "ddd_body_step"):
         assert n in names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
