@@ -79,6 +79,49 @@ def time_tree_attention(torch, D, g, wl, L, side):
             "GBs": alg / us / 1e3, "hbm_frac": alg / us / 1e3 / HBM_PEAK_GBS}
 
 
+def time_verify_sample(torch, D, g, wl, temperature, side):
+    """ddd_verify_sample on the workload's final trees (as left by the last round): target logits N(0, 2) over the
+    vocabulary, most tree nodes favouring the token of one of their children (what synth.make_target_logits does on
+    the host, written here with device tensors because the 7b_b64 shape is 500 MB of logits)."""
+    B, T, V = wl.B, wl.m + 1, wl.V
+    gen = torch.Generator(device="cuda").manual_seed(1234)
+    logits = torch.randn(B, T, V, device="cuda", generator=gen) * 2.0
+    tok, par = g.tree_t["tree_token"].view(B, T).long(), g.tree_t["parent_idx"].view(B, T).long()
+    n_sel = g.tree_t["n_sel"].view(B).long()
+    idx = torch.arange(T, device="cuda")
+    valid = (idx[None, :] >= 1) & (idx[None, :] <= n_sel[:, None])
+    # every valid node proposes itself to its parent with a random priority; the parent's row favours the winner
+    prio = torch.rand(B, T, device="cuda", generator=gen).masked_fill(~valid, -1.0)
+    best = torch.full((B, T), -1.0, device="cuda").scatter_reduce(1, par.clamp(min=0), prio, "amax", include_self=True)
+    win = valid & (prio == best.gather(1, par.clamp(min=0))) & (torch.rand(B, T, device="cuda", generator=gen) < 0.8)
+    bsel, csel = torch.nonzero(win, as_tuple=True)
+    logits[bsel, par[bsel, csel], tok[bsel, csel]] += 13.0
+    ua = torch.rand(B, T, device="cuda", dtype=torch.float64, generator=gen)
+    ub = torch.rand(B, T, device="cuda", dtype=torch.float64, generator=gen)
+    alen = torch.zeros(B, dtype=torch.int32, device="cuda")
+    apath = torch.zeros(B, wl.D + 1, dtype=torch.int32, device="cuda")
+    bonus = torch.zeros(B, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    call = lambda: D.ddd_verify_sample(g.ctx, g.tree, logits, temperature, ua, ub, alen, apath, bonus, stream=side.cuda_stream)
+    n = 50
+    with torch.cuda.stream(side):
+        for _ in range(5):
+            call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        for _ in range(n):
+            call()
+        e1.record(side)
+        side.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / n
+    rows = int((alen.long() + 1).sum())
+    alg = rows * V * 4            # one pass over the logit row of every node on the accepted paths
+    return {"us_per_call": us, "B": B, "tree_nodes": T, "temperature": temperature,
+            "mean_accept_len": float(alen.float().mean()), "rows_read": rows,
+            "rows_longest_path": int(alen.max()) + 1, "algorithmic_bytes": alg,
+            "GBs": alg / us / 1e3, "hbm_frac": alg / us / 1e3 / HBM_PEAK_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +149,9 @@ def main():
     ap.add_argument("--tree-attention", type=int, default=0, metavar="L",
                     help="also time ddd_tree_attention (the consumer of the tree mask) for the workload's B and m, H/128 "
                          "heads and a prompt of L positions; adds a tree_attention object to the JSON line")
+    ap.add_argument("--verify-sample", type=float, default=0.0, metavar="T",
+                    help="also time ddd_verify_sample (sampled acceptance at temperature T > 0) on the workload's final "
+                         "trees with synthetic target logits; adds a verify_sample object to the JSON line")
     ap.add_argument("--pack-weights", choices=["auto", "on", "off"], default="auto",
                     help="tile-major copy of W for the GEMM path (ddd_weights_pack); auto: when the GEMM path is used "
                          "and W is larger than the 256 MB Infinity Cache, i.e. really streams from HBM")
@@ -311,6 +357,9 @@ def main():
     if args.tree_attention > 0:
         out["tree_attention"] = time_tree_attention(torch, D, g, wl, args.tree_attention, side)
         log(f"[bench] tree attention: {out['tree_attention']}")
+    if args.verify_sample > 0:
+        out["verify_sample"] = time_verify_sample(torch, D, g, wl, args.verify_sample, side)
+        log(f"[bench] sampled acceptance: {out['verify_sample']}")
     if args.cpu_budget > 0:
         log(f"[bench] timing the CPU oracle for about {args.cpu_budget:.0f} s ...")
         out["cpu_baseline"] = cpu_baseline(wl, g.W_bits, g.plant_dir_np if wl.n_plant else None, thr, args.cpu_budget)

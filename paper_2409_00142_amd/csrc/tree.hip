@@ -61,11 +61,40 @@ hipError_t launch_verify_accept(const VerifyArgs& a, hipStream_t stream) {
 // accepted the bonus token is the first j whose prefix sum of the remaining weights exceeds
 // u_bonus[node] * rem.  Every decision is taken in fp64.
 //
-// One workgroup of 16 waves per sequence; wave w owns the contiguous token segment
-// [w*seg, (w+1)*seg) of the current node's logit row (coalesced loads, fixed summation order).
+// One workgroup of 16 waves per sequence walks the accepted path.  Per node, one pass for the row
+// maximum and one for the weights: the row is cut into 128 blocks of consecutive tokens (8 per
+// wave, coalesced loads, fixed summation order) whose sums stay in LDS, so the bonus draw only has
+// to look inside the one block in which the prefix sum passes the threshold.
 constexpr int kVsWaves = 16;
 constexpr int kVsThreads = kVsWaves * kWave;
-constexpr int kVsMaxRemoved = 128;     // children of one node <= beam width <= 128
+constexpr int kVsSubPerWave = 8;
+constexpr int kVsSub = kVsWaves * kVsSubPerWave;     // 128 = two per lane of the wave that draws the bonus
+constexpr int kVsMaxRemoved = 128;                   // children of one node <= beam width <= 128
+
+// exp(a) for a <= 0 to about 1e-14 relative: a = n ln2 + r, |r| <= ln2 / 2, Taylor polynomial of
+// degree 11 in r (remainder below 7e-15), scaled by 2^n.  Arguments below -800 give 0.  Every
+// instruction of a 64-wide wave costs four cycles here whatever its precision, and this function
+// is most of what the kernel executes, hence the short polynomial: the decisions need the weights
+// to about 1e-13, not to the last bit.
+__device__ __forceinline__ double exp_nonpos(double a) {
+  a = fmax(a, -800.0);
+  const double n = __builtin_rint(a * 1.4426950408889634074);
+  double r = fma(n, -6.93147180369123816490e-01, a);      // ln2, high part
+  r = fma(n, -1.90821492927058770002e-10, r);             // ln2, low part
+  double p = 1.0 / 39916800.0;
+  p = fma(p, r, 1.0 / 3628800.0);
+  p = fma(p, r, 1.0 / 362880.0);
+  p = fma(p, r, 1.0 / 40320.0);
+  p = fma(p, r, 1.0 / 5040.0);
+  p = fma(p, r, 1.0 / 720.0);
+  p = fma(p, r, 1.0 / 120.0);
+  p = fma(p, r, 1.0 / 24.0);
+  p = fma(p, r, 1.0 / 6.0);
+  p = fma(p, r, 0.5);
+  p = fma(p, r, 1.0);
+  p = fma(p, r, 1.0);
+  return ldexp(p, (int)n);
+}
 
 __device__ __forceinline__ double wave_sum_f64(double x) {
 #pragma unroll
@@ -81,72 +110,127 @@ __device__ __forceinline__ double wave_scan_f64(double x, int lane) {   // inclu
   return x;
 }
 
+// Four consecutive logits starting at token j (a multiple of 4 past the row start); tokens at or
+// beyond lim read as -inf, i.e. weight 0.  vec: the row is 16-byte aligned and V a multiple of 4.
+__device__ __forceinline__ float4 load_logits4(const float* x, int j, int lim, bool vec) {
+  const float ninf = -__builtin_inff();
+  if (vec) return j < lim ? *reinterpret_cast<const float4*>(x + j) : make_float4(ninf, ninf, ninf, ninf);
+  float4 v;
+  v.x = j < lim ? x[j] : ninf;
+  v.y = j + 1 < lim ? x[j + 1] : ninf;
+  v.z = j + 2 < lim ? x[j + 2] : ninf;
+  v.w = j + 3 < lim ? x[j + 3] : ninf;
+  return v;
+}
+
+constexpr int kVsChunk = 4 * kWave;     // tokens one wave loads per instruction
+
 __global__ __launch_bounds__(kVsThreads) void verify_sample_kernel(VerifySampleArgs a) {
-  __shared__ uint64_t s_key[kVsWaves];
-  __shared__ double s_wsum[kVsWaves];
+  __shared__ float s_max[kVsWaves];
+  __shared__ double s_sub[kVsSub];
   __shared__ int s_rm_tok[kVsMaxRemoved];
   __shared__ double s_rm_w[kVsMaxRemoved];
-  __shared__ int s_next, s_nrm, s_found[kVsWaves];
-  __shared__ double s_rem;
+  __shared__ int s_next, s_nrm, s_bonus, s_last[kVsWaves];
+  __shared__ uint64_t s_key[kVsWaves];
+  __shared__ int s_par[DDD_MMAX + 1], s_tok[DDD_MMAX + 1];     // the sequence's tree, read once
+  __shared__ double s_ua[DDD_MMAX + 1], s_ub[DDD_MMAX + 1];
 
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int T = a.m + 1, V = a.V;
+  if (tid < T) {
+    s_par[tid] = a.tree.parent_idx[(size_t)b * T + tid];
+    s_tok[tid] = min(max(a.tree.tree_token[(size_t)b * T + tid], 0), V - 1);
+    s_ua[tid] = a.u_accept[(size_t)b * T + tid];
+    s_ub[tid] = a.u_bonus[(size_t)b * T + tid];
+  }
   const int n = min(a.tree.n_sel[b], a.m) + 1;
-  const int32_t* tok = a.tree.tree_token + (size_t)b * T;
-  const int32_t* par = a.tree.parent_idx + (size_t)b * T;
+  __syncthreads();
   int32_t* path = a.accept_path + (size_t)b * (a.D + 1);
-  const int seg = ((V + kVsThreads - 1) / kVsThreads) * kWave;
-  const int j0 = min(V, wv * seg), j1 = min(V, j0 + seg);
-  const double Tt = (double)a.temperature;
+  const int cpb = (V + kVsSub * kVsChunk - 1) / (kVsSub * kVsChunk);      // chunks per block
+  const int sb = cpb * kVsChunk;                                          // tokens per block
+  const int j0 = wv * kVsSubPerWave * sb;                                 // may lie beyond V
+  const bool vec = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(a.logits) & 15) == 0;
+  const double beta = 1.0 / (double)a.temperature;
 
-  int cur = 0, len = 0, amax = 0;
-  double Md = 0.0;
+  int cur = 0, len = 0, nrm = 0;
+  double Md = 0.0, rem = 0.0;          // nrm, rem: meaningful in wave 0
   const float* x = a.logits;
   if (tid == 0) path[0] = 0;
 
   for (int it = 0; it <= a.D; ++it) {
     x = a.logits + ((size_t)b * T + cur) * V;
-    // row maximum (and the lowest token that attains it)
-    uint64_t key = 0;
-#pragma unroll 4
-    for (int j = j0 + lane; j < j1; j += kWave) key = umax64(key, row_key(x[j], j));
-    key = wave_max_u64(key);
-    if (lane == 0) s_key[wv] = key;
+    // wave 0: what the children tests will need (tree indices 1..64; larger trees fetch the rest
+    // when they get there), requested now so that it arrives behind the two passes
+    bool kid = false;
+    int ktok = 0;
+    float kx = 0.0f;
+    double ku = 0.0;
+    if (wv == 0 && 1 + lane < n) {
+      kid = s_par[1 + lane] == cur;
+      ktok = s_tok[1 + lane];
+      kx = x[ktok];
+      ku = s_ua[1 + lane];
+    }
+    // row maximum
+    float mx = -__builtin_inff();
+#pragma unroll 8
+    for (int c = 0; c < kVsSubPerWave * cpb; ++c) {
+      const float4 v = load_logits4(x, j0 + c * kVsChunk + 4 * lane, V, vec);
+      mx = fmaxf(fmaxf(mx, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+    }
+    mx = wave_max_f32(mx);
+    if (lane == 0) s_max[wv] = mx;
     __syncthreads();
-    uint64_t best = 0;
+    mx = s_max[0];
 #pragma unroll
-    for (int i = 0; i < kVsWaves; ++i) best = umax64(best, s_key[i]);
-    Md = (double)key_value(best);
-    amax = key_token(best);
-    // weights: per-wave sums in a fixed order
-    double acc = 0.0;
-#pragma unroll 4
-    for (int j = j0 + lane; j < j1; j += kWave) acc += exp(((double)x[j] - Md) / Tt);
-    acc = wave_sum_f64(acc);
-    if (lane == 0) s_wsum[wv] = acc;
+    for (int i = 1; i < kVsWaves; ++i) mx = fmaxf(mx, s_max[i]);
+    Md = (double)mx;
+    const double mb = -Md * beta;
+    // weights: one sum per block of sb consecutive tokens, in a fixed order
+#pragma unroll 2
+    for (int i = 0; i < kVsSubPerWave; ++i) {
+      double acc = 0.0;
+      for (int c = 0; c < cpb; ++c) {
+        const int j = j0 + (i * cpb + c) * kVsChunk + 4 * lane;
+        const float4 v = load_logits4(x, j, V, vec);
+        const double e0 = exp_nonpos(fma((double)v.x, beta, mb)), e1 = exp_nonpos(fma((double)v.y, beta, mb));
+        const double e2 = exp_nonpos(fma((double)v.z, beta, mb)), e3 = exp_nonpos(fma((double)v.w, beta, mb));
+        acc += (e0 + e1) + (e2 + e3);
+      }
+      acc = wave_sum_f64(acc);
+      if (lane == 0) s_sub[wv * kVsSubPerWave + i] = acc;
+    }
     __syncthreads();
     if (wv == 0) {
-      double rem = 0.0;
-#pragma unroll
-      for (int i = 0; i < kVsWaves; ++i) rem += s_wsum[i];
-      int nxt = -1, nrm = 0;
+      rem = 0.0;
+      for (int i = 0; i < kVsSub; ++i) rem += s_sub[i];
+      int nxt = -1;
+      nrm = 0;
       if (len < a.D) {
         for (int base = 1; base < n && nxt < 0; base += kWave) {
-          const int c = base + lane;
-          uint64_t kids = __ballot(c < n && par[c] == cur);
+          if (base > 1) {
+            const int c = base + lane;
+            kid = c < n && s_par[c] == cur;
+            ktok = c < n ? s_tok[c] : 0;
+            kx = x[ktok];
+            ku = c < n ? s_ua[c] : 0.0;
+          }
+          const double kw = exp_nonpos(fma((double)kx, beta, mb));       // this lane's tree index: base + lane
+          uint64_t kids = __ballot(kid);
           while (kids) {
-            const int cc = base + __ffsll((unsigned long long)kids) - 1;
+            const int l = __ffsll((unsigned long long)kids) - 1;
             kids &= kids - 1;
-            const int tk = min(max(tok[cc], 0), V - 1);
-            const double w = exp(((double)x[tk] - Md) / Tt);
-            if (a.u_accept[(size_t)b * T + cc] * rem < w) { nxt = cc; break; }
+            const double w = __shfl(kw, l, 64);
+            const int tk = __shfl(ktok, l, 64);
+            if (__shfl(ku, l, 64) * rem < w) { nxt = base + l; break; }
             rem -= w;
             if (lane == 0 && nrm < kVsMaxRemoved) { s_rm_tok[nrm] = tk; s_rm_w[nrm] = w; }
             ++nrm;
           }
         }
       }
-      if (lane == 0) { s_next = nxt; s_rem = rem; s_nrm = min(nrm, kVsMaxRemoved); }
+      nrm = min(nrm, kVsMaxRemoved);
+      if (lane == 0) s_next = nxt;
     }
     __syncthreads();
     const int nxt = s_next;
@@ -156,55 +240,76 @@ __global__ __launch_bounds__(kVsThreads) void verify_sample_kernel(VerifySampleA
     if (tid == 0) path[len] = cur;
   }
 
-  // Bonus token at `cur` (x, Md, amax, s_wsum, s_rm_* describe that node).
-  const int nrm = s_nrm;
-  const double thr = a.u_bonus[(size_t)b * T + cur] * s_rem;
-  double pre = 0.0;               // remaining weight of the waves before this one
-  for (int i = 0; i < wv; ++i) {
-    double v = s_wsum[i];
-    for (int r = 0; r < nrm; ++r)
-      if (s_rm_tok[r] / seg == i) v -= s_rm_w[r];
-    pre += v;
-  }
-  int found = 0x7FFFFFFF;
-  double run = pre;
-  for (int jb = j0; jb < j1; jb += kWave) {
-    const int j = jb + lane;
-    double w = 0.0;
-    if (j < j1) {
-      w = exp(((double)x[j] - Md) / Tt);
-      for (int r = 0; r < nrm; ++r)
-        if (s_rm_tok[r] == j) w = 0.0;
+  // Bonus token at `cur` (x, Md, s_sub, s_rm_* describe that node): wave 0 finds the block in
+  // which the prefix sum of the remaining weights passes the threshold, then the token inside it.
+  if (wv == 0) {
+    const double thr = s_ub[cur] * rem;
+    double v0 = s_sub[2 * lane], v1 = s_sub[2 * lane + 1];
+    for (int r = 0; r < nrm; ++r) {
+      const int blk = s_rm_tok[r] / sb;
+      if (blk == 2 * lane) v0 -= s_rm_w[r];
+      if (blk == 2 * lane + 1) v1 -= s_rm_w[r];
     }
-    const double inc = wave_scan_f64(w, lane);
-    const uint64_t over = __ballot(j < j1 && run + inc > thr);
-    if (over != 0 && found == 0x7FFFFFFF) found = jb + __ffsll((unsigned long long)over) - 1;
-    run += __shfl(inc, 63, 64);
-  }
-  if (lane == 0) s_found[wv] = found;
-  __syncthreads();
-  int bonus = 0x7FFFFFFF;
+    const double inc = wave_scan_f64(v0 + v1, lane);        // prefix up to and including block 2*lane+1
+    const double before = inc - (v0 + v1);
+    const uint64_t hit = __ballot(inc > thr);
+    int bonus = -1;
+    if (hit != 0) {
+      const int hl = __ffsll((unsigned long long)hit) - 1;
+      const double bef = __shfl(before, hl, 64), first = __shfl(v0, hl, 64);
+      const bool in_first = bef + first > thr;
+      double run = in_first ? bef : bef + first;
+      for (int jb = (2 * hl + (in_first ? 0 : 1)) * sb; jb < V; jb += kVsChunk) {   // ends inside the block but for rounding
+        const int j = jb + 4 * lane;
+        const float4 v = load_logits4(x, j, V, vec);
+        const double mb = -Md * beta;
+        double w[4] = {exp_nonpos(fma((double)v.x, beta, mb)), exp_nonpos(fma((double)v.y, beta, mb)),
+                       exp_nonpos(fma((double)v.z, beta, mb)), exp_nonpos(fma((double)v.w, beta, mb))};
+        for (int r = 0; r < nrm; ++r) {
+          const int d = s_rm_tok[r] - j;
 #pragma unroll
-  for (int i = 0; i < kVsWaves; ++i) bonus = min(bonus, s_found[i]);
-  if (bonus == 0x7FFFFFFF) {
+          for (int e = 0; e < 4; ++e)
+            if (d == e) w[e] = 0.0;
+        }
+        const double c0 = w[0], c1 = c0 + w[1], c2 = c1 + w[2], c3 = c2 + w[3];
+        const double pre = run + (wave_scan_f64(c3, lane) - c3);     // remaining weight before this lane's tokens
+        const int e = pre + c0 > thr ? 0 : pre + c1 > thr ? 1 : pre + c2 > thr ? 2 : pre + c3 > thr ? 3 : 4;
+        const uint64_t over = __ballot(e < 4 && j + e < V);
+        if (over != 0) {
+          const int ol = __ffsll((unsigned long long)over) - 1;
+          bonus = jb + 4 * ol + __shfl(e, ol, 64);
+          break;
+        }
+        run = __shfl(pre + c3, 63, 64);
+      }
+    }
+    if (lane == 0) { s_bonus = bonus; s_nrm = nrm; }
+  }
+  __syncthreads();
+  int bonus = s_bonus;
+  if (bonus < 0) {
     // rounding left no prefix above the threshold: the last token that still has weight, and if
-    // the children covered everything the target's most likely token  (uniform branch)
+    // the children covered everything the target's most likely token  (block-uniform branch)
+    const int n_removed = s_nrm;
     int last = -1;
-    for (int j = j0 + lane; j < j1; j += kWave) {
-      bool live = exp(((double)x[j] - Md) / Tt) > 0.0;
-      for (int r = 0; r < nrm; ++r)
+    uint64_t key = 0;
+    for (int j = tid; j < V; j += kVsThreads) {
+      key = umax64(key, row_key(x[j], j));
+      bool live = exp(((double)x[j] - Md) * beta) > 0.0;
+      for (int r = 0; r < n_removed; ++r)
         if (s_rm_tok[r] == j) live = false;
       if (live) last = max(last, j);
     }
+    key = wave_max_u64(key);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) last = max(last, __shfl_xor(last, off, 64));
-    __syncthreads();                 // every thread has read s_found
-    if (lane == 0) s_found[wv] = last;
+    if (lane == 0) { s_last[wv] = last; s_key[wv] = key; }
     __syncthreads();
     last = -1;
+    key = 0;
 #pragma unroll
-    for (int i = 0; i < kVsWaves; ++i) last = max(last, s_found[i]);
-    bonus = last >= 0 ? last : amax;
+    for (int i = 0; i < kVsWaves; ++i) { last = max(last, s_last[i]); key = umax64(key, s_key[i]); }
+    bonus = last >= 0 ? last : key_token(key);
   }
   if (tid == 0) {
     for (int i = len + 1; i <= a.D; ++i) path[i] = -1;
@@ -214,6 +319,7 @@ __global__ __launch_bounds__(kVsThreads) void verify_sample_kernel(VerifySampleA
 }
 
 hipError_t launch_verify_sample(const VerifySampleArgs& a, hipStream_t stream) {
+  if (a.m > DDD_MMAX) return hipErrorInvalidValue;      // the kernel keeps the tree in LDS
   hipLaunchKernelGGL(verify_sample_kernel, dim3(a.B), dim3(kVsThreads), 0, stream, a);
   return hipGetLastError();
 }
