@@ -149,6 +149,9 @@ def main():
     ap.add_argument("--tree-attention", type=int, default=0, metavar="L",
                     help="also time ddd_tree_attention (the consumer of the tree mask) for the workload's B and m, H/128 "
                          "heads and a prompt of L positions; adds a tree_attention object to the JSON line")
+    ap.add_argument("--sweep", choices=["alternate", "forward"], default="alternate",
+                    help="direction in which the weight-stream kernel walks W: alternating between consecutive draft calls "
+                         "(default; a call starts in what the previous one left in the memory-side cache) or always forward")
     ap.add_argument("--verify-sample", type=float, default=0.0, metavar="T",
                     help="also time ddd_verify_sample (sampled acceptance at temperature T > 0) on the workload's final "
                          "trees with synthetic target logits; adds a verify_sample object to the JSON line")
@@ -188,7 +191,8 @@ def main():
     thr = wl.threshold if args.threshold is None else args.threshold
     log(f"[bench] workload {wl.name}: B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} m={wl.m} t={thr} gain={wl.gain}")
     t0 = time.perf_counter()
-    g = SD.GpuWorkload(wl, threshold=thr, debug=False)
+    g = SD.GpuWorkload(wl, threshold=thr, debug=False,
+                       flags=D.DDD_FLAG_FORWARD_SWEEPS if args.sweep == "forward" else 0)
     log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s; "
         f"stream slices={D.ddd_num_slices(g.ctx)}")
 
@@ -336,7 +340,7 @@ def main():
         "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
                    "threshold": thr, "check_mask": int(wl.check_mask), "mode": args.mode, "hidden_gain": wl.gain,
                    "launch": "one hipGraph per round" if args.launch == "graph" else "stream launches",
-                   "packed_weights": bool(pack), "body": args.body,
+                   "packed_weights": bool(pack), "sweep": args.sweep, "body": args.body,
                    "body_weight_bytes_per_call": int(getattr(g, "body_bytes", 0)),
                    "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},
                    "accept_len_hist": {str(d): int(c) for d, c in enumerate(accept_hist) if c},

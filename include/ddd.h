@@ -35,6 +35,11 @@ extern "C" {
 #define DDD_KWIDE_MAX 128    /* largest beam width k at all (wide beams: Appendix, Table 2)       */
 #define DDD_MMAX 128         /* largest final tree size m                                         */
 #define DDD_DMAX 31          /* largest max_depth (check_mask has 32 bits)                        */
+/* ddd_config.flags: every draft call walks W first row to last.  Default (bit clear): calls with
+ * an odd index walk it last to first, so that a call starts in the part of W the previous call
+ * left in the memory-side cache (<= 16 rows per call only; results are the same up to the
+ * rounding order of the fp32 sum of exponentials). */
+#define DDD_FLAG_FORWARD_SWEEPS 1u
 #define DDD_POOL_MAX 4096    /* largest node pool per sequence for k <= DDD_KMAX                  */
 #define DDD_POOL_WIDE_MAX 65536 /* largest node pool per sequence for wider beams                 */
 #define DDD_STREAM_ROWS 16   /* rows handled by one pass of the weight stream                     */
@@ -60,7 +65,7 @@ typedef struct ddd_config {
   int32_t m;           /* final tree size in draft nodes (root not counted), 1..DDD_MMAX  */
   float threshold;     /* t: continue iff sum_i exp(logprobsum[i]) >= t  (Eq. 1, t = exp(x)) */
   uint32_t check_mask; /* bit s set <=> s in S: test after the s-th draft call (s >= 1)   */
-  uint32_t flags;      /* reserved, must be 0                                             */
+  uint32_t flags;      /* DDD_FLAG_* bits, other bits must be 0                           */
 } ddd_config;
 
 /* Per-round beam and node-pool state.  All members are device pointers (caller-owned).

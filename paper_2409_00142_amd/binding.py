@@ -155,8 +155,11 @@ def current_stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def make_config(B, H, V, k, max_depth, m, threshold, check_mask=0xFFFFFFFF) -> ddd_config:
-    return ddd_config(B, H, V, k, max_depth, m, float(threshold), check_mask & 0xFFFFFFFF, 0)
+DDD_FLAG_FORWARD_SWEEPS = 1
+
+
+def make_config(B, H, V, k, max_depth, m, threshold, check_mask=0xFFFFFFFF, flags=0) -> ddd_config:
+    return ddd_config(B, H, V, k, max_depth, m, float(threshold), check_mask & 0xFFFFFFFF, flags)
 
 
 def ddd_config_validate(cfg: ddd_config) -> int:

@@ -126,7 +126,7 @@ int slices_for(const ddd_ctx* c, int n_rows) { return gemm_path(c, n_rows) ? 0 :
 // LM head over n_rows rows, partials into the context scratch: the weight stream for up to
 // DDD_STREAM_ROWS rows, the MFMA GEMM over the compacted active rows otherwise.
 int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const uint8_t* row_active, float* logits_dbg,
-                   hipStream_t s) {
+                   int reverse, hipStream_t s) {
   if (gemm_path(c, n_rows)) {
     float* out = logits_dbg ? logits_dbg : c->logits;
     DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
@@ -160,6 +160,7 @@ int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const
     a.k = c->cfg.k;
     a.ntiles = c->ntiles;
     a.nw = c->nw;
+    a.reverse = (c->cfg.flags & DDD_FLAG_FORWARD_SWEEPS) ? 0 : reverse;
     DDD_HIP(launch_lmhead_stream(a, c->G, c->nslice, s));
   }
   return DDD_OK;
@@ -196,7 +197,7 @@ int ddd_config_validate(const ddd_config* cfg) {
   if (cfg->max_depth < 1 || cfg->max_depth > DDD_DMAX) return DDD_ERR_INVALID_ARG;
   if (cfg->m < 1 || cfg->m > DDD_MMAX) return DDD_ERR_INVALID_ARG;
   if (!(cfg->threshold >= 0.0f)) return DDD_ERR_INVALID_ARG;   // also rejects NaN
-  if (cfg->flags != 0) return DDD_ERR_INVALID_ARG;
+  if ((cfg->flags & ~DDD_FLAG_FORWARD_SWEEPS) != 0) return DDD_ERR_INVALID_ARG;
   int G, nw;
   if (cfg->H < 128 || !pick_split(cfg->H, &G, &nw)) return DDD_ERR_INVALID_ARG;
   const long long nmax = 1LL + cfg->k + (long long)(cfg->max_depth - 1) * cfg->k * cfg->k;
@@ -390,7 +391,7 @@ int ddd_profile_lmhead(ddd_ctx* c, const void* W, const void* hid, int32_t n_row
   for (int i = 0; i < iters && rc == DDD_OK; ++i) {
     if (hipEventRecord(ev[2 * i], s) != hipSuccess) rc = DDD_ERR_HIP;
     if (rc == DDD_OK)
-      rc = gemm ? enqueue_gemm(c, W, hid, n_rows, c->logits, s) : enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, s);
+      rc = gemm ? enqueue_gemm(c, W, hid, n_rows, c->logits, s) : enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, i & 1, s);
     if (rc == DDD_OK && hipEventRecord(ev[2 * i + 1], s) != hipSuccess) rc = DDD_ERR_HIP;
   }
   if (rc == DDD_OK && hipEventSynchronize(ev[2 * (size_t)iters - 1]) != hipSuccess) rc = DDD_ERR_HIP;
@@ -433,7 +434,7 @@ int ddd_lmhead_topk(ddd_ctx* c, const void* W, const void* hid, int32_t n_rows, 
     return DDD_ERR_INVALID_ARG;
   if (n_rows < 1 || n_rows > c->cfg.B * c->cfg.k) return DDD_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  int rc = enqueue_stream(c, W, hid, n_rows, row_active, logits_dbg, s);
+  int rc = enqueue_stream(c, W, hid, n_rows, row_active, logits_dbg, 0, s);
   if (rc != DDD_OK) return rc;
   MergeArgs m;
   m.part_key = c->part_key;
@@ -501,7 +502,7 @@ int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd
     std::memset(&a.tree, 0, sizeof(a.tree));
   a.nslice = slices_for(c, n_rows);
   a.m = c->cfg.m;
-  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, s);
+  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, step & 1, s);
   if (rc != DDD_OK) return rc;
   if (c->cfg.k > DDD_KMAX) {
     WideStepArgs w = wide_args(c, a.beam);

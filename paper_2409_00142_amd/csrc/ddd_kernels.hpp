@@ -85,6 +85,7 @@ struct StreamArgs {
   float* part_sum;            // [R][nslice]
   float* logits_dbg;          // fp32 [R][V] or null
   int H, V, R, k, ntiles, nw;
+  int reverse;                // walk every slice's tiles from the last to the first
 };
 // G = 128-wide K groups per streaming wave (1, 2 or 4); H == 128 * G * nw.
 hipError_t launch_lmhead_stream(const StreamArgs& a, int G, int nslice, hipStream_t stream);

@@ -41,6 +41,9 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
   const int t0 = (int)(((long long)slice * a.ntiles) / nslice);
   const int t1 = (int)(((long long)(slice + 1) * a.ntiles) / nslice);
   const int nt = t1 - t0;
+  // Sweep direction: calls alternate, so that a call starts with the part of W its predecessor read
+  // last, which the memory-side cache still holds.
+  const int tb = a.reverse ? t1 - 1 : t0, td = a.reverse ? -1 : 1;
 
   float* red = reinterpret_cast<float*>(smem);      // [2][NW][256] fp32 partial tiles
   unsigned char* stage = smem + 2 * NW * 1024;      // [NW][kStageBytes]
@@ -68,7 +71,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
 
     u32x4 ring[G][4];
     {
-      const int v0 = t0 * 16;   // in range also when this slice owns no tile: rows are clamped
+      const int v0 = max(tb, 0) * 16;   // in range also when this slice owns no tile: rows are clamped
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
     }
     // every tile but the last refills the ring with the next tile while it is consumed
     for (int t = 0; t + 1 < nt; ++t) {
-      const f32x4 acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, (t0 + t + 1) * 16 + lrow,
+      const f32x4 acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, (tb + td * (t + 1)) * 16 + lrow,
                                              vlast);
       *reinterpret_cast<f32x4*>(red + ((t & 1) * NW + wave) * 256 + lane * 4) = acc;
       __syncthreads();
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
       f32x4 s = {0.f, 0.f, 0.f, 0.f};
       for (int w = 0; w < NW; ++w)   // fixed order: equal W rows give bit-equal logits
         s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + lane * 4);
-      const int v0 = (t0 + t) * 16 + vb * 4;
+      const int v0 = (tb + td * t) * 16 + vb * 4;
       const int nv = min(4, a.V - v0);
       if (row_ok && nv > 0) {
         float x[4];

@@ -25,12 +25,12 @@ class GpuWorkload:
     """One context + caller-owned buffers for a synthetic workload."""
 
     def __init__(self, wl: Workload, W_bits: Optional[np.ndarray] = None, threshold: Optional[float] = None,
-                 debug: bool = False):
+                 debug: bool = False, flags: int = 0):
         self.wl = wl
         self.W_bits = make_lm_head(wl.V, wl.H, wl.sigma_w, wl.seed, wl.dup_pairs) if W_bits is None else W_bits
         self.plant_tokens, self.plant_dir_np = make_plant_table(self.W_bits, wl)
         t = wl.threshold if threshold is None else threshold
-        self.cfg = D.make_config(wl.B, wl.H, wl.V, wl.k, wl.D, wl.m, t, wl.check_mask)
+        self.cfg = D.make_config(wl.B, wl.H, wl.V, wl.k, wl.D, wl.m, t, wl.check_mask, flags)
         self.ctx = D.ddd_create(self.cfg)
         self.W = upload_bits(self.W_bits)
         self.st, self.st_t = D.alloc_state(self.cfg)

@@ -75,7 +75,9 @@ def test_config_validation(D):
         assert D.ddd_config_validate(cfg) == D.DDD_OK, good
         assert D.ddd_pool_capacity(cfg) == 1 + cfg.k + (cfg.max_depth - 1) * cfg.k * cfg.k
     flagged = D.make_config(**base)
-    flagged.flags = 1
+    flagged.flags = D.DDD_FLAG_FORWARD_SWEEPS
+    assert D.ddd_config_validate(flagged) == D.DDD_OK
+    flagged.flags = 2
     assert D.ddd_config_validate(flagged) == D.DDD_ERR_INVALID_ARG
     assert D.load_library().ddd_config_validate(None) == D.DDD_ERR_INVALID_ARG
 
