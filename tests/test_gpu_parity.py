@@ -536,6 +536,38 @@ def test_round_graph_replays_match_eager_and_are_deterministic(gpu):
         g.close()
 
 
+def test_sweep_direction_changes_only_the_rounding_of_lse(gpu):
+    """Odd draft calls walk W backwards unless DDD_FLAG_FORWARD_SWEEPS is set: the same rounds with and without
+    the flag give the same trees; scores agree to the rounding order of the fp32 sum of exponentials."""
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS["7b_b1"]
+    print("[case] sweep direction, 7B-shaped rounds", flush=True)
+    g = SD.GpuWorkload(wl, debug=False)
+    try:
+        g2 = SD.GpuWorkload(wl, W_bits=g.W_bits, debug=False, flags=D.DDD_FLAG_FORWARD_SWEEPS)
+        try:
+            deep = 0
+            for rnd in range(6):
+                snaps = []
+                for w in (g, g2):
+                    w.set_round(rnd)
+                    w.enqueue_round()
+                    snaps.append(w.snapshot())
+                a, b = snaps
+                n = int(a["n_nodes"][0])
+                deep += int(a["steps"][0] >= 3)
+                for name in ("steps", "n_nodes", "n_sel", "tree_token", "parent_idx", "pos", "mask", "accept_len", "bonus"):
+                    assert np.array_equal(a[name], b[name]), (rnd, name)
+                for name in ("pool_token", "pool_parent", "pool_depth"):
+                    assert np.array_equal(a[name][0, :n], b[name][0, :n]), (rnd, name)
+                assert np.allclose(a["pool_score"][0, :n], b["pool_score"][0, :n], rtol=0, atol=1e-5), rnd
+            assert deep >= 2        # some rounds did reach a backward call and a forward call after it
+        finally:
+            g2.close()
+    finally:
+        g.close()
+
+
 def test_7b_shape_round_parity(gpu):
     """Full 7B-shaped sizes in the launch configuration the benchmark times (one captured graph)."""
     torch, D, SD = gpu
