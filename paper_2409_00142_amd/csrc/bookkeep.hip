@@ -6,7 +6,6 @@ namespace ddd {
 
 // ---- standalone merge: one wave per row ------------------------------------------------------
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
-  __shared__ int wl[4][kKM];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + wave;
   if (row >= a.n_rows) return;                                 // wave-uniform
@@ -24,11 +23,10 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   uint64_t key;
   float lse;
   {
-    uint64_t head[kHPL], second[kHPL];
-    float psum[kHPL];
+    RowHeads heads;
     const uint64_t* pk = a.part_key + (size_t)row * a.nslice * a.k;
-    merge_load_heads(pk, a.part_sum + (size_t)row * a.nslice, a.nslice, a.k, lane, head, second, psum);
-    merge_row_dispatch(pk, head, second, psum, a.nslice, a.k, lane, wl[wave], key, lse);
+    merge_load_heads(pk, a.part_sum + (size_t)row * a.nslice, a.nslice, a.k, lane, heads);
+    merge_row_dispatch(pk, heads, a.nslice, a.k, lane, key, lse);
   }
   if (lane < a.k) {
     a.topk_token[(size_t)row * a.k + lane] = key_token(key);

@@ -2,8 +2,8 @@
 // DDD stop test, and the step function that strings them together for one sequence.
 //
 // merge_row      one wave per hidden row: combines the per-slice (max, sum of exponentials)
-//                into lse, and picks the row's top-k tokens: the k slices with the best
-//                heads contain every global top-k element, so only their k*k keys are ranked.
+//                into lse, and picks the row's top-k tokens by a k-way merge of the slices'
+//                sorted lists (three keys per slice in registers).
 // beam_update    one wave per sequence: score = logprobsum[parent] + logprob (one fp32 add),
 //                all k*k candidates go to the node pool, the k best by (score desc, token asc,
 //                flat index asc) become the new beam (Algorithm 1, "postprocess ... to
@@ -19,96 +19,76 @@ namespace ddd {
 
 constexpr int kKM = DDD_KMAX;
 
-// All 64 lanes of the calling wave must be active.  On return lane j < k holds the rank-j key.
-constexpr int kHPL = 8;   // heads per lane: up to 512 slices
+constexpr int kHPL = 4;   // slices per lane: up to 256 slices (one per compute unit of the chip)
 
-// Issue the loads of a row's slice heads, runners-up and sums (lane handles slices lane, lane+64, ...).
+// The three best keys of each of a lane's slices (lane handles slices lane, lane + 64, ...) and the
+// slices' sums of exponentials.
+struct RowHeads {
+  uint64_t q0[kHPL], q1[kHPL], q2[kHPL];
+  float psum[kHPL];
+};
+
+// Issue the loads of a row's slice heads, their two runners-up and the sums.
 __device__ __forceinline__ void merge_load_heads(const uint64_t* __restrict__ pk, const float* __restrict__ ps,
-                                                 int nslice, int k, int lane, uint64_t (&head)[kHPL],
-                                                 uint64_t (&second)[kHPL], float (&psum)[kHPL]) {
+                                                 int nslice, int k, int lane, RowHeads& h) {
 #pragma unroll
   for (int i = 0; i < kHPL; ++i) {
     const int s = lane + 64 * i;
-    head[i] = (s < nslice) ? pk[(size_t)s * k] : 0ull;
-    second[i] = (s < nslice && k > 1) ? pk[(size_t)s * k + 1] : 0ull;
-    psum[i] = (s < nslice) ? ps[s] : 0.f;
+    h.q0[i] = (s < nslice) ? pk[(size_t)s * k] : 0ull;
+    h.q1[i] = (s < nslice && k > 1) ? pk[(size_t)s * k + 1] : 0ull;
+    h.q2[i] = (s < nslice && k > 2) ? pk[(size_t)s * k + 2] : 0ull;
+    h.psum[i] = (s < nslice) ? ps[s] : 0.f;
   }
 }
 
 // All 64 lanes of the calling wave must be active.  On return lane j < k holds the rank-j key.
 //
-// The k slices with the best heads contain every global top-k element.  If none of their
-// runners-up beats the k-th best head, the k best heads are the answer (the common case);
-// otherwise the k*k keys of those slices are fetched and ranked.
+// Every slice's list is sorted, so the next global best is always the front of some slice: k
+// rounds of "wave-wide max of the fronts, the owner moves on to its slice's next key".  The first
+// three keys of every slice are in registers; a slice that places more than three keys among the
+// row's k best (for k = 10 and 256 slices about one row in 500) fetches its further keys one at
+// a time as they are needed.
 template <int HPL>
-__device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, uint64_t (&head)[kHPL],
-                                          const uint64_t (&second)[kHPL], const float (&psum)[kHPL], int k, int lane,
-                                          int* wl, uint64_t& my_key, float& lse) {
+__device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, RowHeads& h, int k, int lane,
+                                          uint64_t& my_key, float& lse) {
   uint64_t loc = 0;
 #pragma unroll
-  for (int i = 0; i < HPL; ++i) loc = umax64(loc, head[i]);
+  for (int i = 0; i < HPL; ++i) loc = umax64(loc, h.q0[i]);
   const float M = unord32(wave_max_u32((uint32_t)(loc >> 32)));
   float acc = 0.f;
 #pragma unroll
   for (int i = 0; i < HPL; ++i)
-    if (head[i] != 0ull) acc += psum[i] * __expf(key_value(head[i]) - M);
+    if (h.q0[i] != 0ull) acc += h.psum[i] * __expf(key_value(h.q0[i]) - M);
   lse = M + __logf(wave_sum_f32(acc));
 
+  constexpr uint64_t kFetch = 1ull;    // "not in registers": no key has this value (its token would be 2^32 - 2)
+  int taken[HPL];
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) taken[i] = 0;
   my_key = 0ull;
-  uint64_t best = 0ull, sec_of_winners = 0ull;
   for (int round = 0; round < k; ++round) {
     loc = 0;
 #pragma unroll
-    for (int i = 0; i < HPL; ++i) loc = umax64(loc, head[i]);
-    best = wave_max_u64(loc);
+    for (int i = 0; i < HPL; ++i) loc = umax64(loc, h.q0[i]);
+    const uint64_t best = wave_max_u64(loc);
     if (lane == round) my_key = best;
-    if (best == 0ull) {
-      if (lane == 0) wl[round] = -1;
-    } else {
+    if (best == 0ull) break;           // uniform: fewer than k keys in the row
 #pragma unroll
-      for (int i = 0; i < HPL; ++i)
-        if (head[i] == best) {
-          wl[round] = lane + 64 * i;
-          head[i] = 0ull;
-          sec_of_winners = umax64(sec_of_winners, second[i]);
-        }
-    }
-  }
-  // `best` is now the k-th best head (0 if there are fewer than k non-empty slices)
-  const uint64_t best_second = wave_max_u64(sec_of_winners);
-  if (best != 0ull && best_second < best) return;   // uniform: the heads are the top-k
-
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  uint64_t cand[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int cidx = lane + 64 * i;
-    cand[i] = 0ull;
-    if (cidx < k * k) {
-      const int s = wl[cidx / k];
-      if (s >= 0) cand[i] = pk[(size_t)s * k + (cidx % k)];
-    }
-  }
-  my_key = 0ull;
-  for (int round = 0; round < k; ++round) {
-    loc = umax64(umax64(cand[0], cand[1]), umax64(cand[2], cand[3]));
-    best = wave_max_u64(loc);
-    if (lane == round) my_key = best;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (cand[i] == best) cand[i] = 0ull;
+    for (int i = 0; i < HPL; ++i)
+      if (h.q0[i] == best) {
+        ++taken[i];
+        h.q0[i] = h.q1[i];
+        h.q1[i] = h.q2[i];
+        h.q2[i] = (taken[i] + 2 < k) ? kFetch : 0ull;
+        if (h.q0[i] == kFetch) h.q0[i] = pk[(size_t)(lane + 64 * i) * k + taken[i]];   // fourth key onwards
+      }
   }
 }
 
-__device__ __forceinline__ void merge_row_dispatch(const uint64_t* pk, uint64_t (&head)[kHPL],
-                                                   const uint64_t (&second)[kHPL], const float (&psum)[kHPL],
-                                                   int nslice, int k, int lane, int* wl, uint64_t& my_key,
-                                                   float& lse) {
-  if (nslice <= 256)   // slices beyond nslice hold empty keys, so a larger HPL is always valid
-    merge_row<4>(pk, head, second, psum, k, lane, wl, my_key, lse);
-  else
-    merge_row<8>(pk, head, second, psum, k, lane, wl, my_key, lse);
+__device__ __forceinline__ void merge_row_dispatch(const uint64_t* pk, RowHeads& h, int nslice, int k, int lane,
+                                                   uint64_t& my_key, float& lse) {
+  (void)nslice;        // slices beyond nslice hold empty keys
+  merge_row<kHPL>(pk, h, k, lane, my_key, lse);
 }
 
 // ---- beam update by one wave (all 64 lanes active) -------------------------------------------
@@ -214,7 +194,6 @@ __device__ __forceinline__ bool stop_test(const BeamArgs& a, int b, int lane, fl
 // call it (nthr a multiple of 64, at least 64); the rows are dealt round-robin to the waves.
 struct StepSmem {
   TreeSmem tsm;
-  int wl[kKM][kKM];
   int tok[kKM][kKM];
   float lp[kKM][kKM];
   int stopped;
@@ -239,15 +218,14 @@ __device__ __forceinline__ void step_bookkeep_block(const StepArgs& a, int b, in
   const bool dense = (a.nslice == 0);             // keys already final (rows came through the GEMM path)
   const size_t row = row0 + min(wave, rows - 1);
   const uint64_t* pk = a.part_key + row * (dense ? 1 : a.nslice) * g.k;
-  uint64_t head[kHPL], second[kHPL];
-  float psum[kHPL];
+  RowHeads heads;
   uint64_t key = 0ull;
   float lse = 0.f;
   if (dense) {
     key = pk[min(lane, g.k - 1)];
     lse = a.part_sum[row];
   } else {
-    merge_load_heads(pk, a.part_sum + row * a.nslice, a.nslice, g.k, lane, head, second, psum);
+    merge_load_heads(pk, a.part_sum + row * a.nslice, a.nslice, g.k, lane, heads);
   }
   const int li = min(lane, g.k - 1);
   const float old_lps = g.st.logprobsum[(size_t)b * g.k + li];
@@ -255,7 +233,7 @@ __device__ __forceinline__ void step_bookkeep_block(const StepArgs& a, int b, in
   if (!active) return;                            // uniform over the workgroup
   if (tid == 0) sm.stopped = 0;
   if (wave < rows) {
-    if (!dense) merge_row_dispatch(pk, head, second, psum, a.nslice, g.k, lane, sm.wl[wave], key, lse);
+    if (!dense) merge_row_dispatch(pk, heads, a.nslice, g.k, lane, key, lse);
     step_publish_row(a, sm, wave, row, lane, key, lse);
   }
   for (int rw = wave + nwaves; rw < rows; rw += nwaves) {   // fewer waves than rows: further passes
@@ -267,10 +245,9 @@ __device__ __forceinline__ void step_bookkeep_block(const StepArgs& a, int b, in
       key2 = pk2[min(lane, g.k - 1)];
       lse2 = a.part_sum[row2];
     } else {
-      uint64_t head2[kHPL], second2[kHPL];
-      float psum2[kHPL];
-      merge_load_heads(pk2, a.part_sum + row2 * a.nslice, a.nslice, g.k, lane, head2, second2, psum2);
-      merge_row_dispatch(pk2, head2, second2, psum2, a.nslice, g.k, lane, sm.wl[rw], key2, lse2);
+      RowHeads heads2;
+      merge_load_heads(pk2, a.part_sum + row2 * a.nslice, a.nslice, g.k, lane, heads2);
+      merge_row_dispatch(pk2, heads2, a.nslice, g.k, lane, key2, lse2);
     }
     step_publish_row(a, sm, rw, row2, lane, key2, lse2);
   }
@@ -281,8 +258,8 @@ __device__ __forceinline__ void step_bookkeep_block(const StepArgs& a, int b, in
     if (lane == 0 && !cont) sm.stopped = 1;
   }
   __syncthreads();                                // also orders wave 0's pool writes before the reads below
-  if (a.tree.mask != nullptr && sm.stopped)
-    tree_finalize_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm.tsm);
+  if (a.tree.mask != nullptr && sm.stopped)   // pool size after this call: 1 + k + step * k^2 (as beam_update just stored it)
+    tree_finalize_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm.tsm, 1 + g.k + g.step * g.k * g.k);
 }
 
 }  // namespace ddd

@@ -241,7 +241,7 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->n_cu = prop.multiProcessorCount;
   pick_split(cfg->H, &c->G, &c->nw);
   c->ntiles = (cfg->V + 15) / 16;
-  c->nslice = c->n_cu < 512 ? c->n_cu : 512;
+  c->nslice = c->n_cu < 256 ? c->n_cu : 256;   // the per-row merge takes four slices per lane
   if (c->nslice > c->ntiles) c->nslice = c->ntiles;
   c->nmax = (int)ddd_pool_capacity(cfg);
   c->graph = nullptr;
