@@ -137,8 +137,10 @@ def main():
                          "test after every call; eagle2: fixed depth 6, no stop test (Section 3.1, Table 1 baselines)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--profile-iters", type=int, default=200)
-    ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
-                    help="one captured hipGraph per round (default) or plain stream launches")
+    ap.add_argument("--launch", choices=["paced", "graph", "eager"], default="paced",
+                    help="paced (default): ddd_round_run, the host queues draft call s once call s-2 has reported that a "
+                         "sequence is still active; graph: one captured hipGraph of all max_depth calls per round; eager: "
+                         "plain stream launches of all max_depth calls")
     ap.add_argument("--body", choices=["hash", "layer"], default="hash",
                     help="draft body between the LM-head calls: the hash-based hidden-state generator of the workload "
                          "(default: the LM head and the bookkeeping are all a round does), or the stand-in draft layer "
@@ -214,6 +216,8 @@ def main():
     if args.launch == "graph":
         g.capture(side)
         launch = lambda: g.launch(side.cuda_stream)
+    elif args.launch == "paced":
+        launch = lambda: g.run_round(side.cuda_stream)
     else:
         launch = lambda: g.enqueue_round(side.cuda_stream)
     torch.cuda.synchronize()
@@ -339,7 +343,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
                    "threshold": thr, "check_mask": int(wl.check_mask), "mode": args.mode, "hidden_gain": wl.gain,
-                   "launch": "one hipGraph per round" if args.launch == "graph" else "stream launches",
+                   "launch": {"graph": "one hipGraph per round", "eager": "stream launches",
+                              "paced": "stream launches paced by the host (ddd_round_run)"}[args.launch],
                    "packed_weights": bool(pack), "sweep": args.sweep, "body": args.body,
                    "body_weight_bytes_per_call": int(getattr(g, "body_bytes", 0)),
                    "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},

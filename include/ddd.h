@@ -241,6 +241,20 @@ int ddd_round_capture(ddd_ctx* ctx, const void* W_bf16, ddd_state* st, ddd_tree*
                       float* logits_dbg, float* lse_dbg, void* stream);
 int ddd_round_launch(ddd_ctx* ctx, void* stream);
 
+/* Algorithm 1 with the host pacing the launches instead of a captured graph: the same kernels as
+ * ddd_round_enqueue, but draft call s (s >= 2) is put into the stream only after call s-2 has reported, through a
+ * word in pinned host memory written by its bookkeeping launch, that some sequence is still active.  The stop test
+ * (Eq. 1) stays on the device and call s-1 is already queued when the report of call s-2 arrives, so the device
+ * never waits for the host (Section 6 of the paper: a check must not cost a synchronisation); what is saved are
+ * the launches a graph of max_depth calls spends on calls that every sequence skips: at most one such call is
+ * queued per round.  Results are those of ddd_round_enqueue.  The host thread polls (at most 20 ms per call, then
+ * it queues the remaining calls unconditionally), so this call returns when the last draft call has been queued,
+ * not when the round has finished.  One round per context at a time.  Beams wider than DDD_KMAX queue every call.
+ * Returns the number of draft calls queued (>= 1), or a negative status. */
+int ddd_round_run(ddd_ctx* ctx, const void* W_bf16, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
+                  void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,
+                  void* stream);
+
 /* Optional tile-major copy of the LM-head weights for the calls that take the MFMA path (more
  * than DDD_STREAM_ROWS rows, or wide beams).  Section 1's projection reads W once per draft call;
  * when W is too large for the chip's caches (a 128k vocabulary: 1 GB) the MFMA path would fetch it

@@ -110,6 +110,7 @@ def load_library() -> C.CDLL:
         "ddd_round_enqueue": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_capture": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_launch": (C.c_int, [vp, vp]),
+        "ddd_round_run": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_synth_draft_body": (C.c_int, [vp, i32, stp, vp, vp]),
         "ddd_synth_target_argmax": (C.c_int, [C.POINTER(ddd_synth_params), stp, trp, vp, vp]),
         "ddd_synth_next_round": (C.c_int, [vp, vp]),
@@ -298,6 +299,16 @@ def ddd_round_capture(ctx, W, st, tree, root_token, hid_buf, body, body_user, po
                                             _fn_ptr(body), body_user, _fn_ptr(post), post_user, _ptr(logits_dbg),
                                             _ptr(lse_dbg), current_stream() if stream is None else stream),
            "ddd_round_capture")
+
+
+def ddd_round_run(ctx, W, st, tree, root_token, hid_buf, body, body_user, post=None, post_user=None, stream=None) -> int:
+    """Host-paced round; returns the number of draft calls queued."""
+    rc = load_library().ddd_round_run(ctx, _ptr(W), C.byref(st), C.byref(tree), _ptr(root_token), _ptr(hid_buf),
+                                      _fn_ptr(body), body_user, _fn_ptr(post), post_user,
+                                      current_stream() if stream is None else stream)
+    if rc < 0:
+        _check(rc, "ddd_round_run")
+    return rc
 
 
 def ddd_round_launch(ctx, stream=None):

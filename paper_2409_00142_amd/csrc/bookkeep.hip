@@ -301,7 +301,19 @@ hipError_t launch_depth_continue(const BeamArgs& a, int steps_done, hipStream_t 
 // the weight stream separately): one workgroup per sequence ---------------------------------------
 __global__ __launch_bounds__(1024) void step_bookkeep_kernel(StepArgs a) {
   __shared__ StepSmem sm;
-  step_bookkeep_block(a, blockIdx.x, threadIdx.x, blockDim.x, sm);
+  const bool active = step_bookkeep_block(a, blockIdx.x, threadIdx.x, blockDim.x, sm);
+  if (a.call_count != nullptr && threadIdx.x == 0) {
+    // One atomic per sequence: arrivals in the low half, active sequences in the high half.  The
+    // last arrival clears the word for the next round and tells the host; nothing but the word
+    // itself is handed over, so no fence is needed.
+    const uint32_t mine = 1u | (active ? 0x10000u : 0u);
+    const uint32_t seen = __hip_atomic_fetch_add(a.call_count, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((seen & 0xFFFFu) + 1u == gridDim.x) {
+      __hip_atomic_store(a.call_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t any = ((seen + mine) >> 16) != 0u ? 1u : 0u;
+      __hip_atomic_store(a.progress, (a.round_tag << 2) | 2u | any, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+  }
 }
 
 hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream) {

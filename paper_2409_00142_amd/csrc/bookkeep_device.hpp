@@ -208,7 +208,8 @@ __device__ __forceinline__ void step_publish_row(const StepArgs& a, StepSmem& sm
   if (a.lse_dbg != nullptr && lane == 0) a.lse_dbg[row] = lse;
 }
 
-__device__ __forceinline__ void step_bookkeep_block(const StepArgs& a, int b, int tid, int nthr, StepSmem& sm) {
+// Returns whether the sequence is still active after this call (the same value in every thread).
+__device__ __forceinline__ bool step_bookkeep_block(const StepArgs& a, int b, int tid, int nthr, StepSmem& sm) {
   const BeamArgs& g = a.beam;
   const int wave = tid >> 6, lane = tid & 63, nwaves = nthr >> 6;
   const int rows = (g.step == 0) ? 1 : g.k;
@@ -230,7 +231,7 @@ __device__ __forceinline__ void step_bookkeep_block(const StepArgs& a, int b, in
   const int li = min(lane, g.k - 1);
   const float old_lps = g.st.logprobsum[(size_t)b * g.k + li];
   const int old_node = g.st.beam_node[(size_t)b * g.k + li];
-  if (!active) return;                            // uniform over the workgroup
+  if (!active) return false;                      // uniform over the workgroup
   if (tid == 0) sm.stopped = 0;
   if (wave < rows) {
     if (!dense) merge_row_dispatch(pk, heads, a.nslice, g.k, lane, key, lse);
@@ -260,6 +261,7 @@ __device__ __forceinline__ void step_bookkeep_block(const StepArgs& a, int b, in
   __syncthreads();                                // also orders wave 0's pool writes before the reads below
   if (a.tree.mask != nullptr && sm.stopped)   // pool size after this call: 1 + k + step * k^2 (as beam_update just stored it)
     tree_finalize_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm.tsm, 1 + g.k + g.step * g.k * g.k);
+  return !sm.stopped;
 }
 
 }  // namespace ddd

@@ -3,6 +3,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <chrono>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -31,6 +32,11 @@ struct ddd_ctx {
   uint16_t* pack;       // [ceil(V/256)*256][H] tile-major copy for the GEMM path, owned
   hipGraph_t graph;
   hipGraphExec_t graph_exec;
+  // ddd_round_run: the kernels of draft call s publish "call s done, some sequence still active" to host memory
+  uint32_t* call_count;          // device [DDD_DMAX + 1]: arrivals (low half) and active sequences (high half) per call
+  volatile uint32_t* progress;   // pinned host [DDD_DMAX + 1]: (round tag << 2) | 2 | any_active
+  uint32_t* progress_dev;        // the same words as the kernels address them
+  uint32_t round_tag;
 };
 
 namespace {
@@ -267,7 +273,25 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
     if (e == hipSuccess && cfg->k > DDD_KMAX) e = prepare_wide();
   }
   if (e == hipSuccess) e = prepare_tree_attention();
+  c->call_count = nullptr;
+  c->progress = nullptr;
+  c->progress_dev = nullptr;
+  c->round_tag = 0;
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->call_count), (DDD_DMAX + 1) * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMemset(c->call_count, 0, (DDD_DMAX + 1) * sizeof(uint32_t));
+  void* host_words = nullptr;
+  if (e == hipSuccess)
+    e = hipHostMalloc(&host_words, (DDD_DMAX + 1) * sizeof(uint32_t), hipHostMallocMapped | hipHostMallocCoherent);
+  if (e == hipSuccess) {
+    std::memset(host_words, 0, (DDD_DMAX + 1) * sizeof(uint32_t));
+    c->progress = static_cast<volatile uint32_t*>(host_words);
+    void* dev_words = nullptr;
+    e = hipHostGetDevicePointer(&dev_words, host_words, 0);
+    c->progress_dev = static_cast<uint32_t*>(dev_words);
+  }
   if (e != hipSuccess) {
+    if (c->call_count) (void)hipFree(c->call_count);
+    if (host_words) (void)hipHostFree(host_words);
     if (c->logits) (void)hipFree(c->logits);
     if (c->grp_max) (void)hipFree(c->grp_max);
     if (c->grp_sum) (void)hipFree(c->grp_sum);
@@ -294,6 +318,8 @@ int ddd_destroy(ddd_ctx* c) {
   if (c->grp_max) (void)hipFree(c->grp_max);
   if (c->grp_sum) (void)hipFree(c->grp_sum);
   if (c->pack) (void)hipFree(c->pack);
+  (void)hipFree(c->call_count);
+  (void)hipHostFree(const_cast<uint32_t*>(c->progress));
   delete c;
   return DDD_OK;
 }
@@ -482,8 +508,13 @@ int ddd_depth_continue(ddd_ctx* c, int32_t steps_done, ddd_state* st, void* stre
   return DDD_OK;
 }
 
-int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_state* st, ddd_tree* tree,
-                   float* logits_dbg, float* lse_dbg, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// One draft call; publish: the bookkeeping launch also reports to c->progress[step] (ddd_round_run).
+int draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_state* st, ddd_tree* tree,
+               float* logits_dbg, float* lse_dbg, bool publish, void* stream) {
   if (c == nullptr || W == nullptr || hid == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
   if (tree != nullptr && !tree_ok(tree)) return DDD_ERR_INVALID_ARG;
   if (step < 0 || step >= c->cfg.max_depth) return DDD_ERR_INVALID_ARG;
@@ -502,6 +533,9 @@ int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd
     std::memset(&a.tree, 0, sizeof(a.tree));
   a.nslice = slices_for(c, n_rows);
   a.m = c->cfg.m;
+  a.call_count = publish ? c->call_count + step : nullptr;
+  a.progress = publish ? c->progress_dev + step : nullptr;
+  a.round_tag = c->round_tag;
   int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, step & 1, s);
   if (rc != DDD_OK) return rc;
   if (c->cfg.k > DDD_KMAX) {
@@ -517,6 +551,15 @@ int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd
   }
   DDD_HIP(launch_step_bookkeep(a, s));
   return DDD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_state* st, ddd_tree* tree,
+                   float* logits_dbg, float* lse_dbg, void* stream) {
+  return draft_step(c, step, W, hid, st, tree, logits_dbg, lse_dbg, false, stream);
 }
 
 int ddd_tree_finalize(ddd_ctx* c, const ddd_state* st, ddd_tree* out, void* stream) {
@@ -594,6 +637,48 @@ int ddd_round_enqueue(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, 
   }
   if (post != nullptr) rc = post(post_user, st, tree, stream);
   return rc;
+}
+
+int ddd_round_run(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, const int32_t* root_token, void* hid_buf,
+                  ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user, void* stream) {
+  if (c == nullptr || W == nullptr || !state_ok(st) || !tree_ok(tree) || hid_buf == nullptr || body == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  const bool publish = c->cfg.k <= DDD_KMAX;     // wide beams: every call is enqueued, as in ddd_round_enqueue
+  c->round_tag = (c->round_tag + 1) & 0x3FFFFFFFu;
+  if (c->round_tag == 0) c->round_tag = 1;
+  int rc = ddd_round_reset(c, st, root_token, stream);
+  if (rc != DDD_OK) return rc;
+  int enqueued = 0;
+  bool wait = publish;
+  for (int step = 0; step < c->cfg.max_depth; ++step) {
+    if (wait && step >= 2) {
+      // Call step-1 is already in the queue; call `step` goes in once call step-2 has reported that
+      // some sequence goes on.  The wait is bounded: after 20 ms the rest is enqueued unconditionally
+      // (the device-side flags skip what is not needed), so a stalled device cannot hang the host.
+      const uint32_t want = c->round_tag << 2;
+      const auto t0 = std::chrono::steady_clock::now();
+      uint32_t v = c->progress[step - 2];
+      for (unsigned spin = 0; (v & ~3u) != want; ++spin) {
+        if ((spin & 1023u) == 1023u &&
+            std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(20)) {
+          wait = false;
+          break;
+        }
+        v = c->progress[step - 2];
+      }
+      if (wait && (v & 1u) == 0u) break;           // every sequence has stopped
+    }
+    rc = body(body_user, step, st, hid_buf, stream);
+    if (rc != DDD_OK) return rc;
+    rc = draft_step(c, step, W, hid_buf, st, tree, nullptr, nullptr, publish, stream);
+    if (rc != DDD_OK) return rc;
+    ++enqueued;
+  }
+  if (post != nullptr) {
+    rc = post(post_user, st, tree, stream);
+    if (rc != DDD_OK) return rc;
+  }
+  return enqueued;
 }
 
 int ddd_round_capture(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, const int32_t* root_token,

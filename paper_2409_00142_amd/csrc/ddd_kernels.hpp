@@ -73,6 +73,9 @@ struct StepArgs {             // merge + beam select + stop test in one launch
   float* lse_dbg;             // [B*k] or null: lse of every merged row
   ddd_tree tree;              // tree.mask == null: do not build the final tree here
   int nslice, m;
+  uint32_t* call_count;       // null, or this call's arrival word (device): the last workgroup to arrive reports
+  uint32_t* progress;         //   (round_tag << 2) | 2 | (some sequence still active) to this word in host memory
+  uint32_t round_tag;
 };
 hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream);
 

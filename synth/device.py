@@ -111,6 +111,10 @@ class GpuWorkload:
         """The whole round (reset, draft calls, tree, stand-in target, accept walk) without a graph."""
         D.ddd_round_enqueue(*self._round_args(), stream=stream)
 
+    def run_round(self, stream: Optional[int] = None) -> int:
+        """The whole round with the host pacing the draft calls (ddd_round_run); returns the calls queued."""
+        return D.ddd_round_run(*self._round_args()[:10], stream=stream)
+
     def capture(self, stream: torch.cuda.Stream) -> None:
         D.ddd_round_capture(*self._round_args(), stream=stream.cuda_stream)
         self.captured = True

@@ -568,6 +568,30 @@ def test_sweep_direction_changes_only_the_rounding_of_lse(gpu):
         g.close()
 
 
+@pytest.mark.parametrize("wname,B", [("tiny", 2), ("7b_b1", 1), ("tiny", 40)])
+def test_host_paced_round_matches_enqueued_round(gpu, wname, B):
+    """ddd_round_run queues draft calls only while some sequence is active: same results as queueing all
+    max_depth calls, and at most one call more than the deepest sequence made."""
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS[wname].with_(B=B)
+    print(f"[case] host-paced rounds {wname} B={B}", flush=True)
+    g = SD.GpuWorkload(wl, debug=False)
+    try:
+        for rnd in range(6):
+            g.set_round(rnd)
+            g.enqueue_round()
+            want = g.snapshot()
+            g.set_round(rnd)
+            torch.cuda.synchronize()
+            n = g.run_round()
+            got = g.snapshot()
+            _same_round(got, want)
+            deepest = int(want["steps"].max())
+            assert deepest <= n <= min(wl.D, deepest + 1), (rnd, n, deepest)
+    finally:
+        g.close()
+
+
 def test_7b_shape_round_parity(gpu):
     """Full 7B-shaped sizes in the launch configuration the benchmark times (one captured graph)."""
     torch, D, SD = gpu
