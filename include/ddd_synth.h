@@ -53,6 +53,24 @@ int ddd_synth_hash_tokens(const int64_t* round_ctr, int32_t* tokens, int32_t n, 
 int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_t* accept_len, int32_t B,
                           int64_t* depth_hist, int64_t* accept_hist, int64_t* batch_depth_hist, void* stream);
 
+/* ddd_post_fn that runs the stand-in target and the accept walk in one host call: ddd_synth_target_argmax,
+ * ddd_verify_accept, ddd_synth_round_stats and, if hash_tokens is not NULL, ddd_synth_hash_tokens on it.
+ * user = const ddd_synth_post_args* (host memory that outlives the call); every pointer inside is device memory
+ * except params and ctx. */
+typedef struct ddd_synth_post_args {
+  const ddd_synth_params* params;
+  ddd_ctx* ctx;
+  int32_t* target_argmax;     /* [B,m+1] */
+  int32_t* accept_len;        /* [B] */
+  int32_t* accept_path;       /* [B,max_depth+1] */
+  int32_t* bonus_token;       /* [B] */
+  int64_t* depth_hist;        /* [32] or NULL */
+  int64_t* accept_hist;       /* [32] or NULL */
+  int64_t* batch_depth_hist;  /* [32] or NULL */
+  int32_t* hash_tokens;       /* [B] or NULL */
+} ddd_synth_post_args;
+int ddd_synth_post(void* user, const ddd_state* st, const ddd_tree* tree, void* stream);
+
 /* Plain coalesced read of n_bytes (multiple of 16) into a 4-byte checksum: the practical
  * HBM read ceiling the weight stream is compared with. */
 int ddd_synth_read_stream(const void* src, size_t n_bytes, uint32_t* sink, int32_t n_blocks, void* stream);

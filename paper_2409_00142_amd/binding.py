@@ -62,6 +62,12 @@ class ddd_synth_params(C.Structure):
                 ("plant_dir", C.c_void_p), ("plant_round_p24", C.c_uint32), ("plant_row_p24", C.c_uint32)]
 
 
+class ddd_synth_post_args(C.Structure):
+    _fields_ = [("params", C.c_void_p), ("ctx", C.c_void_p)] + [(n, C.c_void_p) for n in (
+        "target_argmax", "accept_len", "accept_path", "bonus_token", "depth_hist", "accept_hist", "batch_depth_hist",
+        "hash_tokens")]
+
+
 class ddd_body_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "k", "H", "F", "V", "max_depth", "L")]
 
@@ -114,6 +120,7 @@ def load_library() -> C.CDLL:
         "ddd_synth_draft_body": (C.c_int, [vp, i32, stp, vp, vp]),
         "ddd_synth_target_argmax": (C.c_int, [C.POINTER(ddd_synth_params), stp, trp, vp, vp]),
         "ddd_synth_next_round": (C.c_int, [vp, vp]),
+        "ddd_synth_post": (C.c_int, [vp, stp, trp, vp]),
         "ddd_synth_read_stream": (C.c_int, [vp, sz, vp, i32, vp]),
         "ddd_synth_mfma_rate": (C.c_int, [vp, i32, i32, vp]),
         "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
@@ -316,6 +323,11 @@ def ddd_round_launch(ctx, stream=None):
 
 
 # ---- synthetic workload stand-ins (tests / benchmark) ----------------------------------------
+def synth_post_ptr() -> int:
+    """Address of ddd_synth_post, usable as the `post` argument of the round calls (user = ddd_synth_post_args)."""
+    return C.cast(load_library().ddd_synth_post, C.c_void_p).value
+
+
 def synth_draft_body_ptr() -> int:
     """Address of ddd_synth_draft_body, usable as the `body` argument of the round calls."""
     return C.cast(load_library().ddd_synth_draft_body, C.c_void_p).value

@@ -294,6 +294,24 @@ int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_
   return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
 }
 
+int ddd_synth_post(void* user, const ddd_state* st, const ddd_tree* tree, void* stream) {
+  const ddd_synth_post_args* a = static_cast<const ddd_synth_post_args*>(user);
+  if (a == nullptr || a->params == nullptr || a->ctx == nullptr || st == nullptr || tree == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  int rc = ddd_synth_target_argmax(a->params, st, tree, a->target_argmax, stream);
+  if (rc != DDD_OK) return rc;
+  rc = ddd_verify_accept(a->ctx, tree, a->target_argmax, a->accept_len, a->accept_path, a->bonus_token, stream);
+  if (rc != DDD_OK) return rc;
+  int64_t* ctr = const_cast<int64_t*>(a->params->round_ctr);   // the round's own counter: the statistics step advances it
+  rc = ddd_synth_round_stats(ctr, st->steps, a->accept_len, a->params->cfg.B, a->depth_hist,
+                             a->accept_hist, a->batch_depth_hist, stream);
+  if (rc != DDD_OK) return rc;
+  if (a->hash_tokens != nullptr)
+    rc = ddd_synth_hash_tokens(a->params->round_ctr, a->hash_tokens, a->params->cfg.B, a->params->cfg.V,
+                               a->params->seed, stream);
+  return rc;
+}
+
 int ddd_synth_read_stream(const void* src, size_t n_bytes, uint32_t* sink, int32_t n_blocks, void* stream) {
   if (src == nullptr || sink == nullptr || n_bytes % 16 != 0 || n_blocks < 1) return DDD_ERR_INVALID_ARG;
   hipLaunchKernelGGL(read_stream_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(stream),

@@ -61,22 +61,20 @@ class GpuWorkload:
         p.plant_round_p24 = wl.plant_round_p24()
         p.plant_row_p24 = wl.plant_row_p24()
         self.params = p
-        # post hook: stand-in target model, accept walk, advance the round counter
-        self._post = D.POST_FN(self._post_cb)
+        # post hook: stand-in target model, accept walk, advance the round counter (one C call per round)
+        pa = D.ddd_synth_post_args()
+        pa.params = C.addressof(self.params)
+        pa.ctx = self.ctx
+        pa.target_argmax = self.target.data_ptr()
+        pa.accept_len = self.accept_len.data_ptr()
+        pa.accept_path = self.accept_path.data_ptr()
+        pa.bonus_token = self.bonus.data_ptr()
+        pa.depth_hist = self.depth_hist.data_ptr()
+        pa.accept_hist = self.accept_hist.data_ptr()
+        pa.batch_depth_hist = self.batch_depth_hist.data_ptr()
+        pa.hash_tokens = None
+        self.post_args = pa
         self.captured = False
-
-    def _post_cb(self, user, st_p, tree_p, stream):
-        try:
-            D.ddd_synth_target_argmax(self.params, self.st, self.tree, self.target, stream=stream)
-            D.ddd_verify_accept(self.ctx, self.tree, self.target, self.accept_len, self.accept_path, self.bonus,
-                                stream=stream)
-            D.ddd_synth_round_stats(self.round_ctr, self.st_t["steps"], self.accept_len, self.wl.B, self.depth_hist,
-                                    self.accept_hist, self.batch_depth_hist, stream=stream)
-            if getattr(self, "body", None) is not None:     # the layer's rounds differ by their last prompt token
-                D.ddd_synth_hash_tokens(self.round_ctr, self.root_token, self.wl.B, self.wl.V, self.wl.seed, stream=stream)
-            return 0
-        except D.DDDError as e:
-            return e.code
 
     def set_round(self, rnd: int) -> None:
         self.round_ctr.fill_(rnd)
@@ -96,6 +94,7 @@ class GpuWorkload:
             "f_root": upload_bits(np.stack([p["f_root"] for p in pb])),
             "root_token": self.root_token,
         }
+        self.post_args.hash_tokens = self.root_token.data_ptr()     # the layer's rounds differ by their last prompt token
         self.body = D.ddd_body_create(D.ddd_body_config(wl.B, wl.k, wl.H, F, wl.V, wl.D, L))
         D.ddd_body_bind(self.body, self.body_w, self.body_p)
         self.body_bytes = sum(int(np.prod(wb[n].shape)) * 2 for n in ("Wfc", "Wqkv", "Wo", "Wgu", "Wd"))
@@ -103,9 +102,9 @@ class GpuWorkload:
     def _round_args(self):
         if getattr(self, "body", None) is not None:
             return (self.ctx, self.W, self.st, self.tree, self.root_token, self.hid, D.body_step_ptr(), self.body,
-                    self._post, None, self.logits_dbg, self.lse_dbg)
+                    D.synth_post_ptr(), C.addressof(self.post_args), self.logits_dbg, self.lse_dbg)
         return (self.ctx, self.W, self.st, self.tree, self.root_token, self.hid, D.synth_draft_body_ptr(),
-                C.addressof(self.params), self._post, None, self.logits_dbg, self.lse_dbg)
+                C.addressof(self.params), D.synth_post_ptr(), C.addressof(self.post_args), self.logits_dbg, self.lse_dbg)
 
     def enqueue_round(self, stream: Optional[int] = None) -> None:
         """The whole round (reset, draft calls, tree, stand-in target, accept walk) without a graph."""
