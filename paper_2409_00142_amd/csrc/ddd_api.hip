@@ -620,6 +620,15 @@ int ddd_verify_sample(ddd_ctx* c, const ddd_tree* tree, const float* target_logi
   return DDD_OK;
 }
 
+namespace {
+// Where a round builds the final trees.  Inside the bookkeeping launch of the call in which a sequence stops
+// (no extra launch: right for a few sequences), or in one launch after the last call (with many sequences
+// almost every call has some sequence stopping, and the slowest workgroup sets the time of the launch: the
+// tree building would be on the critical path of every call).  A stopped sequence's pool no longer changes,
+// so both give the same trees.
+bool trees_after_the_calls(const ddd_ctx* c) { return c->cfg.B >= 8; }
+}  // namespace
+
 int ddd_round_enqueue(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
                       void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,
                       float* logits_dbg, float* lse_dbg, void* stream) {
@@ -628,11 +637,17 @@ int ddd_round_enqueue(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, 
   int rc = ddd_round_reset(c, st, root_token, stream);
   if (rc != DDD_OK) return rc;
   const size_t dbg_stride = (size_t)c->cfg.B * c->cfg.k * c->cfg.V;
+  const bool late_trees = trees_after_the_calls(c);
   for (int step = 0; step < c->cfg.max_depth; ++step) {
     rc = body(body_user, step, st, hid_buf, stream);
     if (rc != DDD_OK) return rc;
-    rc = ddd_draft_step(c, step, W, hid_buf, st, tree, logits_dbg ? logits_dbg + dbg_stride * step : nullptr,
+    rc = ddd_draft_step(c, step, W, hid_buf, st, late_trees ? nullptr : tree,
+                        logits_dbg ? logits_dbg + dbg_stride * step : nullptr,
                         lse_dbg ? lse_dbg + (size_t)c->cfg.B * c->cfg.k * step : nullptr, stream);
+    if (rc != DDD_OK) return rc;
+  }
+  if (late_trees) {
+    rc = ddd_tree_finalize(c, st, tree, stream);
     if (rc != DDD_OK) return rc;
   }
   if (post != nullptr) rc = post(post_user, st, tree, stream);
@@ -648,6 +663,7 @@ int ddd_round_run(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, cons
   if (c->round_tag == 0) c->round_tag = 1;
   int rc = ddd_round_reset(c, st, root_token, stream);
   if (rc != DDD_OK) return rc;
+  const bool late_trees = trees_after_the_calls(c);
   int enqueued = 0;
   bool wait = publish;
   for (int step = 0; step < c->cfg.max_depth; ++step) {
@@ -670,9 +686,13 @@ int ddd_round_run(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, cons
     }
     rc = body(body_user, step, st, hid_buf, stream);
     if (rc != DDD_OK) return rc;
-    rc = draft_step(c, step, W, hid_buf, st, tree, nullptr, nullptr, publish, stream);
+    rc = draft_step(c, step, W, hid_buf, st, late_trees ? nullptr : tree, nullptr, nullptr, publish, stream);
     if (rc != DDD_OK) return rc;
     ++enqueued;
+  }
+  if (late_trees) {
+    rc = ddd_tree_finalize(c, st, tree, stream);
+    if (rc != DDD_OK) return rc;
   }
   if (post != nullptr) {
     rc = post(post_user, st, tree, stream);
