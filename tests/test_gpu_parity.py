@@ -568,6 +568,26 @@ def test_sweep_direction_changes_only_the_rounding_of_lse(gpu):
         g.close()
 
 
+@pytest.mark.parametrize("D_max", [1, 2, 3])
+def test_host_paced_round_with_very_few_calls(gpu, D_max):
+    """The pacing loop's first waits: rounds of at most one, two and three draft calls."""
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS["tiny"].with_(D=D_max, threshold=0.0)
+    print(f"[case] host-paced rounds, max_depth={D_max}", flush=True)
+    g = SD.GpuWorkload(wl, debug=False)
+    try:
+        for rnd in range(3):
+            g.set_round(rnd)
+            g.enqueue_round()
+            want = g.snapshot()
+            g.set_round(rnd)
+            torch.cuda.synchronize()
+            assert g.run_round() == D_max          # threshold 0: no early stop
+            _same_round(g.snapshot(), want)
+    finally:
+        g.close()
+
+
 @pytest.mark.parametrize("wname,B", [("tiny", 2), ("7b_b1", 1), ("tiny", 40)])
 def test_host_paced_round_matches_enqueued_round(gpu, wname, B):
     """ddd_round_run queues draft calls only while some sequence is active: same results as queueing all

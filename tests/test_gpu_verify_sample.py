@@ -150,3 +150,24 @@ def test_verify_sample_cold_equals_greedy(gpu):
         assert int(l1.sum()) >= 2
     finally:
         D.ddd_destroy(ctx)
+
+
+def test_verify_sample_rejects_bad_arguments(gpu):
+    torch, D = gpu
+    print("[case] verify_sample argument checks", flush=True)
+    cfg = D.make_config(1, 256, 1000, 4, 4, 8, 0.3)
+    ctx = D.ddd_create(cfg)
+    try:
+        tree, _ = D.alloc_tree(cfg)
+        lg = torch.zeros(1, 9, 1000, device="cuda")
+        u = torch.zeros(1, 9, dtype=torch.float64, device="cuda")
+        i32 = lambda *s: torch.zeros(*s, dtype=torch.int32, device="cuda")
+        for bad_T in (0.0, -1.0, float("nan"), float("inf")):
+            with pytest.raises(D.DDDError):
+                D.ddd_verify_sample(ctx, tree, lg, bad_T, u, u, i32(1), i32(1, 5), i32(1))
+        with pytest.raises(D.DDDError):
+            D.ddd_verify_sample(ctx, tree, None, 1.0, u, u, i32(1), i32(1, 5), i32(1))
+        with pytest.raises(D.DDDError):
+            D.ddd_verify_sample(ctx, tree, lg, 1.0, None, u, i32(1), i32(1, 5), i32(1))
+    finally:
+        D.ddd_destroy(ctx)
