@@ -45,8 +45,11 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
   float* red = reinterpret_cast<float*>(smem);      // [2][NW][256] fp32 partial tiles
   unsigned char* stage = smem + 2 * NW * 1024;      // [NW][kStageBytes]
 
+  const int NR = a.n_ranges;
+  const int total = nt * NR;          // (tile, range) steps of this workgroup, ranges innermost
+
   if (wave < NW) {
-    // streaming wave: K-slice [wave*128*G, +128*G) of this pass, its share of x resident as B operands
+    // streaming wave: K-slice [wave*128*G, +128*G) of every range, its share of x resident as B operands
     const int ks = wave * (128 * G);
     const int n = lane & 15, q = lane >> 4;
     // the first tile of W is requested before anything else: it flies while the input rows are prepared
@@ -54,7 +57,8 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
     unsigned char* mystage = stage + wave * kStageBytes;
     const int wr_off = lrow * kStagePitch + c * 16;
     const int rd_off = n * kStagePitch + q * 16;
-    const uint16_t* wbase = a.W + ks + c * 8;
+    const int woff = ks + c * 8;       // this lane's element offset inside a row of any range
+    const uint16_t* wb0 = a.rg[0].W + woff;
     const int vlast = a.N - 1;
 
     u32x4 ring[G][4];
@@ -65,44 +69,59 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int row = min(v0 + i * 4 + lrow, vlast);
-          ring[g][i] = *reinterpret_cast<const u32x4*>(wbase + (size_t)row * a.ldw + g * 128);
+          ring[g][i] = *reinterpret_cast<const u32x4*>(wb0 + (size_t)row * a.ldw + g * 128);
         }
     }
-    int src = n;                                     // source row of input row n
-    if (n < a.R) {
-      if (a.gather_mode == kGatherIndex) src = a.gather_idx[n];
-      else if (a.gather_mode == kGatherInBlock) src = (n / a.gather_k) * a.gather_k + a.gather_idx[n];
-      else if (a.gather_mode == kGatherBlock) src = n / a.gather_k;
+    // source row of input row n in every range
+    int src[kLinearRanges];
+#pragma unroll
+    for (int r = 0; r < kLinearRanges; ++r) {
+      const LinearRange& rg = a.rg[r < NR ? r : 0];
+      src[r] = n;
+      if (n < a.R) {
+        if (rg.gather_mode == kGatherIndex) src[r] = rg.gather_idx[n];
+        else if (rg.gather_mode == kGatherInBlock) src[r] = (n / a.gather_k) * a.gather_k + rg.gather_idx[n];
+        else if (rg.gather_mode == kGatherBlock) src[r] = n / a.gather_k;
+      }
     }
     bf16x8 bfrag[G][4];
+#pragma unroll 1
+    for (int it = 0; it < total; ++it) {
+      __builtin_amdgcn_sched_barrier(0);   // the previous step's operands are dead before the next ones are requested
+      const int r = it % NR;
+      if (NR > 1 || it == 0) {       // the input rows of this step's range
+        const LinearRange& rg = a.rg[r];
+        const uint16_t* xp = rg.x + (size_t)(r == 0 ? src[0] : r == 1 ? src[1] : src[2]) * rg.ldx + ks + q * 8;
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        u32x4 u = {0u, 0u, 0u, 0u};
-        if (n < a.R) u = *reinterpret_cast<const u32x4*>(a.x + (size_t)src * a.ldx + ks + g * 128 + j * 32 + q * 8);
-        bfrag[g][j] = __builtin_bit_cast(bf16x8, u);
+          for (int j = 0; j < 4; ++j) {
+            u32x4 u = {0u, 0u, 0u, 0u};
+            if (n < a.R) u = *reinterpret_cast<const u32x4*>(xp + g * 128 + j * 32);
+            bfrag[g][j] = __builtin_bit_cast(bf16x8, u);
+          }
       }
-    for (int t = 0; t + 1 < nt; ++t) {
-      const f32x4 acc =
-          stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.ldw, (t0 + t + 1) * 16 + lrow, vlast);
-      *reinterpret_cast<f32x4*>(red + ((t & 1) * NW + wave) * 256 + lane * 4) = acc;
-      __syncthreads();
-    }
-    if (nt > 0) {
-      const int t = nt - 1;
-      const f32x4 acc = stream_tile<G, false>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.ldw, 0, vlast);
-      *reinterpret_cast<f32x4*>(red + ((t & 1) * NW + wave) * 256 + lane * 4) = acc;
+      f32x4 acc;
+      if (it + 1 < total) {          // refill the ring with the next step's tile while this one is consumed
+        const uint16_t* wn = a.rg[(it + 1) % NR].W + woff;
+        acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wn, a.ldw, (t0 + (it + 1) / NR) * 16 + lrow, vlast);
+      } else {
+        acc = stream_tile<G, false>(ring, bfrag, mystage, wr_off, rd_off, wb0, a.ldw, 0, vlast);
+      }
+      *reinterpret_cast<f32x4*>(red + ((it & 1) * NW + wave) * 256 + lane * 4) = acc;
       __syncthreads();
     }
   } else {
     // epilogue wave: lane = (vb, r) owns outputs 4*vb .. 4*vb+3 of the tile for input row r
     const int r = lane & 15, vb = lane >> 4;
     for (int t = 0; t < nt; ++t) {
-      __syncthreads();
       f32x4 s = {0.f, 0.f, 0.f, 0.f};
-      for (int w = 0; w < NW; ++w)   // fixed order
-        s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + lane * 4);
+      for (int rr = 0; rr < NR; ++rr) {
+        const int it = t * NR + rr;
+        __syncthreads();
+        for (int w = 0; w < NW; ++w)   // fixed order
+          s += *reinterpret_cast<const f32x4*>(red + ((it & 1) * NW + w) * 256 + lane * 4);
+      }
       const int v0 = (t0 + t) * 16 + vb * 4;
       if (r < a.R && (a.row_active == nullptr || a.row_active[r] != 0)) {   // rows of stopped sequences stay untouched
         if (a.mode == kLinearSiluPairs) {   // outputs (v0, v0+1) and (v0+2, v0+3) are (gate, up) pairs

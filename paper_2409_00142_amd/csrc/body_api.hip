@@ -47,13 +47,14 @@ bool pick_range(int units, int* G, int* nw) {   // units = remaining K / 128
   return best > 0;
 }
 
-// One product y (+)= x W^T over K = sum of K ranges; `a` carries everything but the per-range fields.
-// a.mode is the LinearMode of the whole product; a.out16 / a.out16b are written by the range that completes it.
+// One product y (+)= x W^T over K, cut into K ranges of 128 * G * nw elements; `a` describes the product: rg[0]
+// holds W, x and the gather of the whole K extent.  Consecutive ranges of the same length go into one launch (at
+// most kLinearRanges of them).  a.mode is the LinearMode of the whole product; a.out16 / a.out16b are written by
+// the launch that completes it.
 int enqueue_linear(const ddd_body* b, LinearArgs a, int K, hipStream_t s) {
   a.ntiles = (a.N + 15) / 16;
   const int nslice = a.ntiles < b->n_cu ? a.ntiles : b->n_cu;
-  const uint16_t* W = a.W;
-  const uint16_t* x = a.x;
+  const LinearRange whole = a.rg[0];
   uint16_t* out16 = a.out16;
   uint16_t* out16b = a.out16b;
   const int mode = a.mode;
@@ -61,24 +62,45 @@ int enqueue_linear(const ddd_body* b, LinearArgs a, int K, hipStream_t s) {
   while (k0 < K) {
     int G = 1, nw = 1;
     pick_range((K - k0) / 128, &G, &nw);
-    const bool last = k0 + 128 * G * nw >= K;
-    // the gate needs complete sums: such a product must fit one K range
+    const int len = 128 * G * nw;
+    int nr = 1;
+    while (nr < kLinearRanges && k0 + (nr + 1) * len <= K) ++nr;
+    const bool last = k0 + nr * len >= K;
+    // the gate needs complete sums: such a product must fit one launch
     if (mode == kLinearSiluPairs && !(k0 == 0 && last)) return DDD_ERR_INVALID_ARG;
-    a.W = W + k0;
-    a.x = x ? x + k0 : nullptr;
+    for (int r = 0; r < nr; ++r) {
+      a.rg[r] = whole;
+      a.rg[r].W = whole.W + k0 + r * len;
+      a.rg[r].x = whole.x + k0 + r * len;
+    }
+    a.n_ranges = nr;
     a.out16 = last ? out16 : nullptr;
     a.out16b = last ? out16b : nullptr;
     a.nw = nw;
     a.mode = (k0 > 0) ? (int)kLinearAccumulate : mode;
     BODY_HIP(launch_linear_stream(a, G, nslice, s));
-    k0 += 128 * G * nw;
+    k0 += nr * len;
   }
+  return DDD_OK;
+}
+
+// One launch of a product whose K ranges come from different places: the ranges in a.rg[0 .. n_ranges) as given, each
+// of K_range elements (one launch: K_range must be a single range length).
+int enqueue_linear_ranges(const ddd_body* b, LinearArgs a, int K_range, hipStream_t s) {
+  int G = 1, nw = 1;
+  if (!pick_range(K_range / 128, &G, &nw) || 128 * G * nw != K_range) return DDD_ERR_INVALID_ARG;
+  a.ntiles = (a.N + 15) / 16;
+  a.nw = nw;
+  const int nslice = a.ntiles < b->n_cu ? a.ntiles : b->n_cu;
+  BODY_HIP(launch_linear_stream(a, G, nslice, s));
   return DDD_OK;
 }
 
 LinearArgs linear_args(const void* W, int ldw, int N, int R, const uint8_t* row_active, float* y, int ldy, int mode) {
   LinearArgs a = {};
-  a.W = static_cast<const uint16_t*>(W);
+  a.rg[0].W = static_cast<const uint16_t*>(W);
+  a.rg[0].gather_mode = kGatherNone;
+  a.n_ranges = 1;
   a.ldw = ldw;
   a.N = N;
   a.R = R;
@@ -86,7 +108,6 @@ LinearArgs linear_args(const void* W, int ldw, int N, int R, const uint8_t* row_
   a.y = y;
   a.ldy = ldy;
   a.mode = mode;
-  a.gather_mode = kGatherNone;
   a.gather_k = 1;
   return a;
 }
@@ -165,8 +186,8 @@ int ddd_body_linear(ddd_body* b, const void* W, int32_t N, int32_t K, const void
   if (b == nullptr || W == nullptr || x == nullptr || y == nullptr) return DDD_ERR_INVALID_ARG;
   if (N < 1 || K < 128 || K % 128 != 0 || R < 1 || R > kBodyRows) return DDD_ERR_INVALID_ARG;
   LinearArgs a = linear_args(W, K, N, R, nullptr, y, N, accumulate ? kLinearAccumulate : kLinearStore);
-  a.x = static_cast<const uint16_t*>(x);
-  a.ldx = K;
+  a.rg[0].x = static_cast<const uint16_t*>(x);
+  a.rg[0].ldx = K;
   return enqueue_linear(b, a, K, static_cast<hipStream_t>(stream));
 }
 
@@ -183,25 +204,26 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   const uint8_t* act = (step == 0) ? nullptr : st->row_active;   // a round starts with every sequence drafting
   const size_t hist = (size_t)step * kBodyRows * H;
 
-  // r0 = [E[token], parent feature] Wfc^T as two K ranges of H, the rows read where they are
+  // r0 = [E[token], parent feature] Wfc^T: one launch over two K ranges of H, the rows read where they are
   const uint16_t* Wfc = static_cast<const uint16_t*>(b->w.Wfc);
-  LinearArgs fe = linear_args(Wfc, 2 * H, H, R, act, b->r, H, kLinearStore);
-  fe.x = static_cast<const uint16_t*>(b->w.E);
-  fe.ldx = H;
-  fe.gather_mode = kGatherIndex;
-  fe.gather_idx = (step == 0) ? b->p.root_token : st->beam_token;
-  int rc = enqueue_linear(b, fe, H, s);
-  if (rc != DDD_OK) return rc;
-  LinearArgs ff = linear_args(Wfc + H, 2 * H, H, R, act, b->r, H, kLinearAccumulate);
-  ff.x = (step == 0) ? static_cast<const uint16_t*>(b->p.f_root) : b->h_hist + hist - (size_t)kBodyRows * H;
-  ff.ldx = H;
-  ff.gather_k = b->cfg.k;
-  if (step == 1) ff.gather_mode = kGatherBlock;            // the prompt call has one row per sequence
+  LinearArgs fc = linear_args(Wfc, 2 * H, H, R, act, b->r, H, kLinearStore);
+  fc.n_ranges = 2;
+  fc.gather_k = b->cfg.k;
+  fc.rg[0].x = static_cast<const uint16_t*>(b->w.E);
+  fc.rg[0].ldx = H;
+  fc.rg[0].gather_mode = kGatherIndex;
+  fc.rg[0].gather_idx = (step == 0) ? b->p.root_token : st->beam_token;
+  fc.rg[1].W = Wfc + H;
+  fc.rg[1].x = (step == 0) ? static_cast<const uint16_t*>(b->p.f_root) : b->h_hist + hist - (size_t)kBodyRows * H;
+  fc.rg[1].ldx = H;
+  fc.rg[1].gather_mode = kGatherNone;
+  fc.rg[1].gather_idx = nullptr;
+  if (step == 1) fc.rg[1].gather_mode = kGatherBlock;      // the prompt call has one row per sequence
   if (step >= 2) {
-    ff.gather_mode = kGatherInBlock;
-    ff.gather_idx = st->beam_parent_slot;
+    fc.rg[1].gather_mode = kGatherInBlock;
+    fc.rg[1].gather_idx = st->beam_parent_slot;
   }
-  rc = enqueue_linear(b, ff, H, s);
+  int rc = enqueue_linear_ranges(b, fc, H, s);
   if (rc != DDD_OK) return rc;
 
   RmsNormArgs n1;
@@ -213,8 +235,8 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   n1.R = R;
   BODY_HIP(launch_rmsnorm(n1, s));
   LinearArgs lq = linear_args(b->w.Wqkv, H, 3 * H, R, act, b->qkv, 3 * H, kLinearStore);
-  lq.x = b->xn;
-  lq.ldx = H;
+  lq.rg[0].x = b->xn;
+  lq.rg[0].ldx = H;
   rc = enqueue_linear(b, lq, H, s);
   if (rc != DDD_OK) return rc;
 
@@ -235,8 +257,8 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   t.R = R;
   BODY_HIP(launch_body_attention(t, s));
   LinearArgs lo = linear_args(b->w.Wo, H, H, R, act, b->r, H, kLinearAccumulate);   // r1 = r0 + o Wo^T
-  lo.x = b->xn;
-  lo.ldx = H;
+  lo.rg[0].x = b->xn;
+  lo.rg[0].ldx = H;
   rc = enqueue_linear(b, lo, H, s);
   if (rc != DDD_OK) return rc;
 
@@ -245,8 +267,8 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   n2.g = b->w.g2;
   BODY_HIP(launch_rmsnorm(n2, s));
   LinearArgs lg = linear_args(b->w.Wgu, H, 2 * F, R, act, nullptr, 0, kLinearSiluPairs);
-  lg.x = b->xn;
-  lg.ldx = H;
+  lg.rg[0].x = b->xn;
+  lg.rg[0].ldx = H;
   lg.out16 = b->act;
   lg.ld16 = F;
   rc = enqueue_linear(b, lg, H, s);
@@ -254,8 +276,8 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
 
   // h = bf16(r1 + a Wd^T): the range that completes the sum also writes the hidden rows and this call's features
   LinearArgs ld = linear_args(b->w.Wd, F, H, R, act, b->r, H, kLinearAccumulate);
-  ld.x = b->act;
-  ld.ldx = F;
+  ld.rg[0].x = b->act;
+  ld.rg[0].ldx = F;
   ld.out16 = static_cast<uint16_t*>(hid_out);
   ld.out16b = b->h_hist + hist;
   ld.ld16 = H;

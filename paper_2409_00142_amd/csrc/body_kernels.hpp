@@ -9,8 +9,8 @@ namespace ddd {
 constexpr int kBodyRows = 16;      // rows per call (B*k): one pass of the weight stream
 constexpr int kHeadDim = 128;
 
-// y[r][n] (+)= sum_k x[r][k] * W[n][k] for one K range of 128*G*nw elements: the LM head's weight
-// stream with a plain store epilogue.  W and x point at the first element of the range.
+// y[r][n] (+)= sum_k x[r][k] * W[n][k] over up to three K ranges of 128*G*nw elements each: the LM
+// head's weight stream with a plain store epilogue.
 enum LinearMode {
   kLinearStore = 0,        // y = sum
   kLinearAccumulate = 1,   // y += sum
@@ -23,16 +23,24 @@ enum GatherMode {
   kGatherInBlock = 2,  // source row (n / gk) * gk + idx[n]              (parent slot inside the sequence's block of gk rows)
   kGatherBlock = 3     // source row n / gk                              (the single row of the sequence's prompt call)
 };
-struct LinearArgs {
-  const uint16_t* W;          // bf16, row pitch ldw
-  const uint16_t* x;          // bf16 source rows, row pitch ldx
+// One K range of a product: where its weights start and where its input rows come from.
+struct LinearRange {
+  const uint16_t* W;          // bf16, first element of the range in row 0 (row pitch LinearArgs::ldw)
+  const uint16_t* x;          // bf16 source rows, first element of the range, row pitch ldx
   const int32_t* gather_idx;  // see GatherMode
-  int gather_mode, gather_k;
+  int gather_mode, ldx;
+};
+constexpr int kLinearRanges = 3;
+// One launch covers n_ranges K ranges of the same length 128*G*nw and adds them up in order before
+// the epilogue runs: y (+)= sum_ranges x_range W_range^T.
+struct LinearArgs {
+  LinearRange rg[kLinearRanges];
+  int n_ranges, gather_k;
   const uint8_t* row_active;  // [R] or null: the launch does nothing if every row is inactive
   float* y;                   // fp32 [R], row pitch ldy
   uint16_t* out16;            // null, or bf16 [R] with row pitch ld16: the rounded result (modes 0/1), the activations (mode 2)
   uint16_t* out16b;           // null, or a second copy of out16 (same pitch)
-  int ldw, ldx, ldy, ld16, N, R, ntiles, nw, mode;
+  int ldw, ldy, ld16, N, R, ntiles, nw, mode;
 };
 hipError_t launch_linear_stream(const LinearArgs& a, int G, int nslice, hipStream_t stream);
 
