@@ -40,6 +40,7 @@ extern "C" {
  * left in the memory-side cache (<= 16 rows per call only; results are the same up to the
  * rounding order of the fp32 sum of exponentials). */
 #define DDD_FLAG_FORWARD_SWEEPS 1u
+#define DDD_BMAX 4096        /* largest number of sequences B                                     */
 #define DDD_POOL_MAX 4096    /* largest node pool per sequence for k <= DDD_KMAX                  */
 #define DDD_POOL_WIDE_MAX 65536 /* largest node pool per sequence for wider beams                 */
 #define DDD_STREAM_ROWS 16   /* rows handled by one pass of the weight stream                     */

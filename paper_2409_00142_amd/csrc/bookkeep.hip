@@ -301,17 +301,59 @@ hipError_t launch_depth_continue(const BeamArgs& a, int steps_done, hipStream_t 
 // the weight stream separately): one workgroup per sequence ---------------------------------------
 __global__ __launch_bounds__(1024) void step_bookkeep_kernel(StepArgs a) {
   __shared__ StepSmem sm;
-  const bool active = step_bookkeep_block(a, blockIdx.x, threadIdx.x, blockDim.x, sm);
-  if (a.call_count != nullptr && threadIdx.x == 0) {
-    // One atomic per sequence: arrivals in the low half, active sequences in the high half.  The
-    // last arrival clears the word for the next round and tells the host; nothing but the word
-    // itself is handed over, so no fence is needed.
-    const uint32_t mine = 1u | (active ? 0x10000u : 0u);
+  __shared__ int s_last;
+  __shared__ int s_word_base[DDD_BMAX / 64 + 1];
+  __shared__ unsigned long long s_words[DDD_BMAX / 64];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const bool active = step_bookkeep_block(a, b, tid, blockDim.x, sm);
+  if (a.call_count == nullptr) return;               // uniform
+  if (tid == 0) {
+    // What the last workgroup needs from this one travels in atomics alone (performed at the device's
+    // coherence point), so no fence is needed: the sequence's bit first, then - once that atomic has returned
+    // its value - one add: arrivals in the low half, active sequences in the high half.
+    uint32_t mine = 1u | (active ? 0x10000u : 0u);
+    if (a.active_mask != nullptr && active) {
+      const uint64_t before = __hip_atomic_fetch_or(a.active_mask + (b >> 6), 1ull << (b & 63), __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+      // the arrival below is made to depend on the value the first atomic returned: it cannot be issued earlier
+      asm volatile("" : "+v"(mine) : "v"((uint32_t)before), "v"((uint32_t)(before >> 32)));
+    }
     const uint32_t seen = __hip_atomic_fetch_add(a.call_count, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if ((seen & 0xFFFFu) + 1u == gridDim.x) {
-      __hip_atomic_store(a.call_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const uint32_t any = ((seen + mine) >> 16) != 0u ? 1u : 0u;
-      __hip_atomic_store(a.progress, (a.round_tag << 2) | 2u | any, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    const bool last = (seen & 0xFFFFu) + 1u == gridDim.x;
+    if (last) {
+      __hip_atomic_store(a.call_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next round
+      if (a.progress != nullptr) {
+        const uint32_t any = ((seen + mine) >> 16) != 0u ? 1u : 0u;
+        __hip_atomic_store(a.progress, (a.round_tag << 2) | 2u | any, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
+    }
+    s_last = (last && a.active_mask != nullptr) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!s_last) return;                               // uniform
+  // The last workgroup to arrive: the next call's active rows, ascending (rows b*k .. b*k+k-1 of every sequence
+  // that goes on), for the GEMM path.  Every other workgroup's bit is in the mask: its arrival came after it.
+  const int B = gridDim.x, k = a.beam.k, nwords = (B + 63) >> 6;
+  for (int w = tid; w < nwords; w += blockDim.x) {
+    s_words[w] = __hip_atomic_load(a.active_mask + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(a.active_mask + w, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next call
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int t = 0;
+    for (int w = 0; w < nwords; ++w) {
+      s_word_base[w] = t;
+      t += __popcll(s_words[w]);
+    }
+    s_word_base[nwords] = t;
+    *a.next_n_act = t * k;
+  }
+  __syncthreads();
+  for (int q = tid; q < B; q += blockDim.x) {
+    const unsigned long long word = s_words[q >> 6];
+    if ((word >> (q & 63)) & 1ull) {
+      const int pos = s_word_base[q >> 6] + __popcll(word & ((1ull << (q & 63)) - 1ull));
+      for (int i = 0; i < k; ++i) a.next_row_list[pos * k + i] = q * k + i;
     }
   }
 }

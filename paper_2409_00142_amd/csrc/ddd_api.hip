@@ -34,6 +34,7 @@ struct ddd_ctx {
   hipGraphExec_t graph_exec;
   // ddd_round_run: the kernels of draft call s publish "call s done, some sequence still active" to host memory
   uint32_t* call_count;          // device [DDD_DMAX + 1]: arrivals (low half) and active sequences (high half) per call
+  uint64_t* active_mask;         // device [DDD_BMAX / 64]: bit b = sequence b goes on after the current call (zero between calls)
   volatile uint32_t* progress;   // pinned host [DDD_DMAX + 1]: (round tag << 2) | 2 | any_active
   uint32_t* progress_dev;        // the same words as the kernels address them
   uint32_t round_tag;
@@ -131,11 +132,12 @@ int slices_for(const ddd_ctx* c, int n_rows) { return gemm_path(c, n_rows) ? 0 :
 
 // LM head over n_rows rows, partials into the context scratch: the weight stream for up to
 // DDD_STREAM_ROWS rows, the MFMA GEMM over the compacted active rows otherwise.
+// list_ready: the previous call's bookkeeping launch has already written the list of active rows (GEMM path).
 int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const uint8_t* row_active, float* logits_dbg,
-                   int reverse, hipStream_t s) {
+                   int reverse, hipStream_t s, bool list_ready = false) {
   if (gemm_path(c, n_rows)) {
     float* out = logits_dbg ? logits_dbg : c->logits;
-    DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
+    if (!list_ready) DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
     int rc = enqueue_gemm(c, W, hid, n_rows, out, s);
     if (rc != DDD_OK) return rc;
     RowTopkArgs t;
@@ -193,7 +195,7 @@ const char* ddd_last_hip_error(void) { return g_hip_err; }
 
 int ddd_config_validate(const ddd_config* cfg) {
   if (cfg == nullptr) return DDD_ERR_INVALID_ARG;
-  if (cfg->B < 1 || cfg->B > 4096) return DDD_ERR_INVALID_ARG;
+  if (cfg->B < 1 || cfg->B > DDD_BMAX) return DDD_ERR_INVALID_ARG;
   if (cfg->k < 1 || cfg->k > DDD_KWIDE_MAX) return DDD_ERR_INVALID_ARG;
   const bool wide = cfg->k > DDD_KMAX;
   if (cfg->V < cfg->k || cfg->V >= (1 << 24)) return DDD_ERR_INVALID_ARG;
@@ -274,11 +276,14 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   }
   if (e == hipSuccess) e = prepare_tree_attention();
   c->call_count = nullptr;
+  c->active_mask = nullptr;
   c->progress = nullptr;
   c->progress_dev = nullptr;
   c->round_tag = 0;
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->call_count), (DDD_DMAX + 1) * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMemset(c->call_count, 0, (DDD_DMAX + 1) * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->active_mask), (DDD_BMAX / 64) * sizeof(uint64_t));
+  if (e == hipSuccess) e = hipMemset(c->active_mask, 0, (DDD_BMAX / 64) * sizeof(uint64_t));
   void* host_words = nullptr;
   if (e == hipSuccess)
     e = hipHostMalloc(&host_words, (DDD_DMAX + 1) * sizeof(uint32_t), hipHostMallocMapped | hipHostMallocCoherent);
@@ -291,6 +296,7 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   }
   if (e != hipSuccess) {
     if (c->call_count) (void)hipFree(c->call_count);
+    if (c->active_mask) (void)hipFree(c->active_mask);
     if (host_words) (void)hipHostFree(host_words);
     if (c->logits) (void)hipFree(c->logits);
     if (c->grp_max) (void)hipFree(c->grp_max);
@@ -319,6 +325,7 @@ int ddd_destroy(ddd_ctx* c) {
   if (c->grp_sum) (void)hipFree(c->grp_sum);
   if (c->pack) (void)hipFree(c->pack);
   (void)hipFree(c->call_count);
+  (void)hipFree(c->active_mask);
   (void)hipHostFree(const_cast<uint32_t*>(c->progress));
   delete c;
   return DDD_OK;
@@ -512,9 +519,11 @@ int ddd_depth_continue(ddd_ctx* c, int32_t steps_done, ddd_state* st, void* stre
 
 namespace {
 
-// One draft call; publish: the bookkeeping launch also reports to c->progress[step] (ddd_round_run).
+// One draft call; publish: the bookkeeping launch also reports to c->progress[step] (ddd_round_run); in_round: the
+// call is one of a round's consecutive calls 0, 1, 2, ... on this context, so on the GEMM path its bookkeeping
+// launch leaves the next call's list of active rows behind and calls after the first do not build their own.
 int draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_state* st, ddd_tree* tree,
-               float* logits_dbg, float* lse_dbg, bool publish, void* stream) {
+               float* logits_dbg, float* lse_dbg, bool publish, bool in_round, void* stream) {
   if (c == nullptr || W == nullptr || hid == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
   if (tree != nullptr && !tree_ok(tree)) return DDD_ERR_INVALID_ARG;
   if (step < 0 || step >= c->cfg.max_depth) return DDD_ERR_INVALID_ARG;
@@ -533,10 +542,15 @@ int draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_sta
     std::memset(&a.tree, 0, sizeof(a.tree));
   a.nslice = slices_for(c, n_rows);
   a.m = c->cfg.m;
-  a.call_count = publish ? c->call_count + step : nullptr;
+  // rows of the calls after the prompt call go through the GEMM path and beams are narrow: the lists chain
+  const bool chain = in_round && c->cfg.k <= DDD_KMAX && gemm_path(c, c->cfg.B * c->cfg.k);
+  a.call_count = (publish || chain) ? c->call_count + step : nullptr;
   a.progress = publish ? c->progress_dev + step : nullptr;
   a.round_tag = c->round_tag;
-  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, step & 1, s);
+  a.active_mask = chain ? c->active_mask : nullptr;
+  a.next_row_list = c->row_list;
+  a.next_n_act = c->n_act;
+  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, step & 1, s, chain && step >= 1);
   if (rc != DDD_OK) return rc;
   if (c->cfg.k > DDD_KMAX) {
     WideStepArgs w = wide_args(c, a.beam);
@@ -559,7 +573,7 @@ extern "C" {
 
 int ddd_draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_state* st, ddd_tree* tree,
                    float* logits_dbg, float* lse_dbg, void* stream) {
-  return draft_step(c, step, W, hid, st, tree, logits_dbg, lse_dbg, false, stream);
+  return draft_step(c, step, W, hid, st, tree, logits_dbg, lse_dbg, false, false, stream);
 }
 
 int ddd_tree_finalize(ddd_ctx* c, const ddd_state* st, ddd_tree* out, void* stream) {
@@ -641,9 +655,9 @@ int ddd_round_enqueue(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, 
   for (int step = 0; step < c->cfg.max_depth; ++step) {
     rc = body(body_user, step, st, hid_buf, stream);
     if (rc != DDD_OK) return rc;
-    rc = ddd_draft_step(c, step, W, hid_buf, st, late_trees ? nullptr : tree,
-                        logits_dbg ? logits_dbg + dbg_stride * step : nullptr,
-                        lse_dbg ? lse_dbg + (size_t)c->cfg.B * c->cfg.k * step : nullptr, stream);
+    rc = draft_step(c, step, W, hid_buf, st, late_trees ? nullptr : tree,
+                    logits_dbg ? logits_dbg + dbg_stride * step : nullptr,
+                    lse_dbg ? lse_dbg + (size_t)c->cfg.B * c->cfg.k * step : nullptr, false, true, stream);
     if (rc != DDD_OK) return rc;
   }
   if (late_trees) {
@@ -686,7 +700,7 @@ int ddd_round_run(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, cons
     }
     rc = body(body_user, step, st, hid_buf, stream);
     if (rc != DDD_OK) return rc;
-    rc = draft_step(c, step, W, hid_buf, st, late_trees ? nullptr : tree, nullptr, nullptr, publish, stream);
+    rc = draft_step(c, step, W, hid_buf, st, late_trees ? nullptr : tree, nullptr, nullptr, publish, true, stream);
     if (rc != DDD_OK) return rc;
     ++enqueued;
   }

@@ -73,9 +73,12 @@ struct StepArgs {             // merge + beam select + stop test in one launch
   float* lse_dbg;             // [B*k] or null: lse of every merged row
   ddd_tree tree;              // tree.mask == null: do not build the final tree here
   int nslice, m;
-  uint32_t* call_count;       // null, or this call's arrival word (device): the last workgroup to arrive reports
-  uint32_t* progress;         //   (round_tag << 2) | 2 | (some sequence still active) to this word in host memory
-  uint32_t round_tag;
+  uint32_t* call_count;       // null, or this call's arrival word (device): the last workgroup to arrive ...
+  uint32_t* progress;         //   ... reports (round_tag << 2) | 2 | (some sequence still active) to this word in host
+  uint32_t round_tag;         //       memory (if progress is not null), and
+  uint64_t* active_mask;      //   ... if not null ([ceil(B/64)] device words, zero between calls: bit b = sequence b goes
+  int32_t* next_row_list;     //       on) writes the next call's list of active rows b*k+i, ascending, and their
+  int32_t* next_n_act;        //       number: what build_row_list_kernel would make of row_active after this launch
 };
 hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream);
 
