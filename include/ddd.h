@@ -37,8 +37,8 @@ extern "C" {
 #define DDD_DMAX 31          /* largest max_depth (check_mask has 32 bits)                        */
 /* ddd_config.flags: every draft call walks W first row to last.  Default (bit clear): calls with
  * an odd index walk it last to first, so that a call starts in the part of W the previous call
- * left in the memory-side cache (<= 16 rows per call only; results are the same up to the
- * rounding order of the fp32 sum of exponentials). */
+ * left in the memory-side cache (on the weight-stream path the results are the same up to the
+ * rounding order of the fp32 sum of exponentials, on the GEMM path they are bit-identical). */
 #define DDD_FLAG_FORWARD_SWEEPS 1u
 #define DDD_BMAX 4096        /* largest number of sequences B                                     */
 #define DDD_POOL_MAX 4096    /* largest node pool per sequence for k <= DDD_KMAX                  */

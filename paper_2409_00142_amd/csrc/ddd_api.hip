@@ -108,7 +108,7 @@ WideStepArgs wide_args(const ddd_ctx* c, const BeamArgs& beam) {
 }
 
 // MFMA GEMM over the rows listed in the context's row list, logits into `out`.
-int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, int max_rows, float* out, hipStream_t s) {
+int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, int max_rows, float* out, int reverse, hipStream_t s) {
   GemmArgs g;
   g.W = static_cast<const uint16_t*>(W);
   g.Wp = (c->pack_src != nullptr && c->pack_src == W) ? c->pack : nullptr;
@@ -121,6 +121,7 @@ int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, int max_rows, float
   g.H = c->cfg.H;
   g.V = c->cfg.V;
   g.ngrp = c->ngrp;
+  g.reverse = (c->cfg.flags & DDD_FLAG_FORWARD_SWEEPS) ? 0 : reverse;
   DDD_HIP(launch_lmhead_gemm(g, max_rows, c->g_grid, s));
   return DDD_OK;
 }
@@ -138,7 +139,7 @@ int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const
   if (gemm_path(c, n_rows)) {
     float* out = logits_dbg ? logits_dbg : c->logits;
     if (!list_ready) DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
-    int rc = enqueue_gemm(c, W, hid, n_rows, out, s);
+    int rc = enqueue_gemm(c, W, hid, n_rows, out, reverse, s);
     if (rc != DDD_OK) return rc;
     RowTopkArgs t;
     t.logits = out;
@@ -424,7 +425,7 @@ int ddd_profile_lmhead(ddd_ctx* c, const void* W, const void* hid, int32_t n_row
   for (int i = 0; i < iters && rc == DDD_OK; ++i) {
     if (hipEventRecord(ev[2 * i], s) != hipSuccess) rc = DDD_ERR_HIP;
     if (rc == DDD_OK)
-      rc = gemm ? enqueue_gemm(c, W, hid, n_rows, c->logits, s) : enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, i & 1, s);
+      rc = gemm ? enqueue_gemm(c, W, hid, n_rows, c->logits, i & 1, s) : enqueue_stream(c, W, hid, n_rows, nullptr, nullptr, i & 1, s);
     if (rc == DDD_OK && hipEventRecord(ev[2 * i + 1], s) != hipSuccess) rc = DDD_ERR_HIP;
   }
   if (rc == DDD_OK && hipEventSynchronize(ev[2 * (size_t)iters - 1]) != hipSuccess) rc = DDD_ERR_HIP;

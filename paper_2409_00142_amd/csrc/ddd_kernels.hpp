@@ -18,6 +18,7 @@ struct GemmArgs {
   float* grp_max;             // fp32 [rows][ngrp]: max of each group of 64 consecutive vocabulary rows ...
   float* grp_sum;             // fp32 [rows][ngrp]: ... and sum of exp(logit - that max); ngrp = ceil(V/64) rounded up to 4
   int H, V, ngrp;
+  int reverse;                // hand the row tiles of W out from the last to the first
 };
 hipError_t prepare_lmhead_gemm();   // once per process: enables the kernels' LDS sizes
 // max_rows: the largest number of rows this call can have (picks the tile shape)

@@ -288,7 +288,8 @@ __device__ __forceinline__ void gemm_units(const GemmArgs& a, unsigned char* lds
   const int vg = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);   // neighbours on one XCD get neighbouring units
 
   for (int u = vg; u < nunits; u += G) {
-    const int mt = u / NT, nt = u - mt * NT;
+    const int mu = u / NT, nt = u - mu * NT;
+    const int mt = a.reverse ? nmt - 1 - mu : mu;   // consecutive calls walk W in opposite directions (memory-side cache)
     const int nblk = min(bpt, nblk_all - nt * bpt);  // >= 1
     const int h0 = (nblk + 1) >> 1;
     const int wblk0 = wn ? h0 : 0, nb = wn ? nblk - h0 : h0;   // wave-uniform
