@@ -617,7 +617,9 @@ def test_host_paced_round_matches_enqueued_round(gpu, wname, B):
 
 
 def test_7b_shape_round_parity(gpu):
-    """Full 7B-shaped sizes in the launch configuration the benchmark times (one captured graph)."""
+    """Full 7B-shaped sizes: rounds launched as one captured graph with the debug buffers are replayed by the
+    oracle; the same rounds launched the way the benchmark times them (host-paced, no debug buffers) leave
+    byte-identical state."""
     torch, D, SD = gpu
     wl = synth.WORKLOADS["7b_b1"]
     print("[case] 7B-shaped rounds, graph launch", flush=True)
@@ -635,6 +637,11 @@ def test_7b_shape_round_parity(gpu):
             snap = g.snapshot()
             depths += _compare_round(g, snap, wl, rnd, wl.threshold, g.logits_dbg.cpu().numpy(),
                                      g.lse_dbg.cpu().numpy(), check_own_logits_steps=2 if rnd == 0 else 0)
+            g.set_round(rnd)
+            torch.cuda.synchronize()
+            g.run_round(side.cuda_stream)
+            side.synchronize()
+            _same_round(g.snapshot(), snap)
         print(f"[info] 7b depths {depths}", flush=True)
     finally:
         g.close()
@@ -650,10 +657,10 @@ FULL_CASES = [
 
 @pytest.mark.parametrize("case", FULL_CASES, ids=[c[0] for c in FULL_CASES])
 def test_full_size_round_parity(gpu, case):
-    """The other workloads at their full sizes, launched as the captured graph the benchmark times: every
-    sequence's round is replayed by the oracle from the GPU's dumped logits (bit-exact integers and scores), the
-    oracle's own fp64 projection is compared on sampled sequences, and the same rounds launched without the
-    debug buffers (exactly the benchmark's configuration) leave byte-identical state."""
+    """The other workloads at their full sizes, launched as a captured graph: every sequence's round is replayed
+    by the oracle from the GPU's dumped logits (bit-exact integers and scores), the oracle's own fp64 projection
+    is compared on sampled sequences, and the same rounds launched without the debug buffers, as a graph and
+    host-paced (exactly the benchmark's configuration), leave byte-identical state."""
     torch, D, SD = gpu
     name, wl, n_rounds, seqs, own_seqs = case
     print(f"[case] full-size {name} B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D}", flush=True)
@@ -676,6 +683,11 @@ def test_full_size_round_parity(gpu, case):
             depths = _compare_round(g, snap, wl, rnd, wl.threshold, g.logits_dbg.cpu().numpy(),
                                     g.lse_dbg.cpu().numpy(), check_own_logits_steps=2 if rnd == 0 else 0,
                                     seqs=seqs, own_seqs=own_seqs)
+            _same_round(g2.snapshot(), snap)
+            g2.set_round(rnd)
+            torch.cuda.synchronize()
+            g2.run_round(side.cuda_stream)
+            side.synchronize()
             _same_round(g2.snapshot(), snap)
             print(f"[info] {name} round {rnd} depths {depths}", flush=True)
     finally:
