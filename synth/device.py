@@ -95,6 +95,7 @@ class GpuWorkload:
             "root_token": self.root_token,
         }
         self.post_args.hash_tokens = self.root_token.data_ptr()     # the layer's rounds differ by their last prompt token
+        self._run_args = None
         self.body = D.ddd_body_create(D.ddd_body_config(wl.B, wl.k, wl.H, F, wl.V, wl.D, L))
         D.ddd_body_bind(self.body, self.body_w, self.body_p)
         self.body_bytes = sum(int(np.prod(wb[n].shape)) * 2 for n in ("Wfc", "Wqkv", "Wo", "Wgu", "Wd"))
@@ -112,7 +113,16 @@ class GpuWorkload:
 
     def run_round(self, stream: Optional[int] = None) -> int:
         """The whole round with the host pacing the draft calls (ddd_round_run); returns the calls queued."""
-        return D.ddd_round_run(*self._round_args()[:10], stream=stream)
+        a = getattr(self, "_run_args", None)
+        if a is None:       # none of these pointers changes while the workload lives: marshal them once
+            r = self._round_args()
+            a = self._run_args = (r[0], r[1].data_ptr(), C.byref(r[2]), C.byref(r[3]), r[4].data_ptr(), r[5].data_ptr(),
+                                  r[6], r[7], r[8], r[9])
+            self._run_fn = D.load_library().ddd_round_run
+        rc = self._run_fn(*a, D.current_stream() if stream is None else stream)
+        if rc < 0:
+            raise D.DDDError(rc, "ddd_round_run")
+        return rc
 
     def capture(self, stream: torch.cuda.Stream) -> None:
         D.ddd_round_capture(*self._round_args(), stream=stream.cuda_stream)
