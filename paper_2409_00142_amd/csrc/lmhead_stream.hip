@@ -38,12 +38,16 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
   }
 
   const int nslice = gridDim.x, slice = blockIdx.x;
-  const int t0 = (int)(((long long)slice * a.ntiles) / nslice);
-  const int t1 = (int)(((long long)(slice + 1) * a.ntiles) / nslice);
-  const int nt = t1 - t0;
+  // The vocabulary rows are dealt to the slices row by row, not tile by tile, so that every workgroup
+  // fetches the same amount from memory (32000 rows over 256 slices: 125 rows each instead of 7 or 8
+  // tiles of 16); a slice's last tile is ragged: its missing rows repeat the slice's last row (cache
+  // hits) and are masked in the epilogue.
+  const int r0 = (int)(((long long)slice * a.V) / nslice);
+  const int r1 = (int)(((long long)(slice + 1) * a.V) / nslice);
+  const int nt = (r1 - r0 + 15) >> 4;
   // Sweep direction: calls alternate, so that a call starts with the part of W its predecessor read
   // last, which the memory-side cache still holds.
-  const int tb = a.reverse ? t1 - 1 : t0, td = a.reverse ? -1 : 1;
+  const int tb = a.reverse ? nt - 1 : 0, td = a.reverse ? -1 : 1;     // tile index inside the slice
 
   float* red = reinterpret_cast<float*>(smem);      // [2][NW][256] fp32 partial tiles
   unsigned char* stage = smem + 2 * NW * 1024;      // [NW][kStageBytes]
@@ -67,11 +71,11 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
     const int wr_off = lrow * kStagePitch + c * 16;
     const int rd_off = n * kStagePitch + q * 16;
     const uint16_t* wbase = a.W + ks + c * 8;
-    const int vlast = a.V - 1;
+    const int vlast = max(r1 - 1, 0);                // rows are clamped to the slice
 
     u32x4 ring[G][4];
     {
-      const int v0 = max(tb, 0) * 16;   // in range also when this slice owns no tile: rows are clamped
+      const int v0 = r0 + max(tb, 0) * 16;   // in range also when this slice owns no tile: rows are clamped
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
     }
     // every tile but the last refills the ring with the next tile while it is consumed
     for (int t = 0; t + 1 < nt; ++t) {
-      const f32x4 acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, (tb + td * (t + 1)) * 16 + lrow,
+      const f32x4 acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, r0 + (tb + td * (t + 1)) * 16 + lrow,
                                              vlast);
       *reinterpret_cast<f32x4*>(red + ((t & 1) * NW + wave) * 256 + lane * 4) = acc;
       __syncthreads();
@@ -108,8 +112,8 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
       f32x4 s = {0.f, 0.f, 0.f, 0.f};
       for (int w = 0; w < NW; ++w)   // fixed order: equal W rows give bit-equal logits
         s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + lane * 4);
-      const int v0 = (tb + td * t) * 16 + vb * 4;
-      const int nv = min(4, a.V - v0);
+      const int v0 = r0 + (tb + td * t) * 16 + vb * 4;
+      const int nv = min(4, r1 - v0);
       if (row_ok && nv > 0) {
         float x[4];
 #pragma unroll
