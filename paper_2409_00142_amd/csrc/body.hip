@@ -38,9 +38,13 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
     if (__ballot(on != 0) == 0ull) return;
   }
   const int nslice = gridDim.x, slice = blockIdx.x;
-  const int t0 = (int)(((long long)slice * a.ntiles) / nslice);
-  const int t1 = (int)(((long long)(slice + 1) * a.ntiles) / nslice);
-  const int nt = t1 - t0;
+  // Output rows are dealt to the workgroups in units of 4 (an epilogue lane's outputs, and whole gate/up
+  // pairs), not in tiles of 16: every workgroup streams the same number of weight rows; a slice's last tile
+  // is ragged, its missing rows repeat the slice's last row and are not written.
+  const int nq = (a.N + 3) >> 2;
+  const int n0 = (int)(((long long)slice * nq) / nslice) * 4;
+  const int n1 = min((int)(((long long)(slice + 1) * nq) / nslice) * 4, a.N);
+  const int nt = (n1 - n0 + 15) >> 4;
 
   float* red = reinterpret_cast<float*>(smem);      // [2][NW][256] fp32 partial tiles
   unsigned char* stage = smem + 2 * NW * 1024;      // [NW][kStageBytes]
@@ -59,11 +63,11 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
     const int rd_off = n * kStagePitch + q * 16;
     const int woff = ks + c * 8;       // this lane's element offset inside a row of any range
     const uint16_t* wb0 = a.rg[0].W + woff;
-    const int vlast = a.N - 1;
+    const int vlast = max(n1 - 1, 0);
 
     u32x4 ring[G][4];
     {
-      const int v0 = t0 * 16;
+      const int v0 = n0;
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
       f32x4 acc;
       if (it + 1 < total) {          // refill the ring with the next step's tile while this one is consumed
         const uint16_t* wn = a.rg[(it + 1) % NR].W + woff;
-        acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wn, a.ldw, (t0 + (it + 1) / NR) * 16 + lrow, vlast);
+        acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wn, a.ldw, n0 + ((it + 1) / NR) * 16 + lrow, vlast);
       } else {
         acc = stream_tile<G, false>(ring, bfrag, mystage, wr_off, rd_off, wb0, a.ldw, 0, vlast);
       }
@@ -122,12 +126,12 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
         for (int w = 0; w < NW; ++w)   // fixed order
           s += *reinterpret_cast<const f32x4*>(red + ((it & 1) * NW + w) * 256 + lane * 4);
       }
-      const int v0 = (t0 + t) * 16 + vb * 4;
+      const int v0 = n0 + t * 16 + vb * 4;
       if (r < a.R && (a.row_active == nullptr || a.row_active[r] != 0)) {   // rows of stopped sequences stay untouched
         if (a.mode == kLinearSiluPairs) {   // outputs (v0, v0+1) and (v0+2, v0+3) are (gate, up) pairs
 #pragma unroll
           for (int e = 0; e < 4; e += 2)
-            if (v0 + e + 1 < a.N) {
+            if (v0 + e + 1 < n1) {
               const float g = s[e], u = s[e + 1];
               a.out16[(size_t)r * a.ld16 + ((v0 + e) >> 1)] = f32_to_bf16_rne(g / (1.0f + __expf(-g)) * u);
             }
@@ -135,7 +139,7 @@ __global__ __launch_bounds__(704) void linear_stream_kernel(LinearArgs a) {
           float* yp = a.y + (size_t)r * a.ldy + v0;
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            if (v0 + e < a.N) {
+            if (v0 + e < n1) {
               const float y = (a.mode == kLinearAccumulate) ? yp[e] + s[e] : s[e];
               yp[e] = y;
               if (a.out16 != nullptr) {
