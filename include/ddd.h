@@ -115,7 +115,7 @@ size_t ddd_scratch_bytes(const ddd_config* cfg);      /* device scratch a contex
 int ddd_create(const ddd_config* cfg, ddd_ctx** out);
 int ddd_destroy(ddd_ctx* ctx);
 
-/* Start of a round (Algorithm 1, before line 1): pool := {root}, steps := 0, active := 1.
+/* Start of a round (Algorithm 1, its state before the first draft call): pool := {root}, steps := 0, active := 1.
  * root_token: device int32[B] or NULL (root token recorded as -1). */
 int ddd_round_reset(ddd_ctx* ctx, ddd_state* st, const int32_t* root_token, void* stream);
 
@@ -132,8 +132,8 @@ int ddd_lmhead_topk(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, int3
                     const uint8_t* row_active, int32_t* topk_token, float* topk_logprob, float* lse,
                     float* logits_dbg, void* stream);
 
-/* Beam update after draft call number step+1 (Algorithm 1 lines 2-3 for step 0, lines 11-12
- * otherwise): adds logprobsum of the parents, appends all candidates to the pool, keeps the
+/* Beam update after draft call number step+1 (Algorithm 1: the first beam and its logprobsum after the
+ * prompt call for step 0, the post-processing of the draft outputs inside the loop otherwise): adds logprobsum of the parents, appends all candidates to the pool, keeps the
  * k best by (score desc, token asc, flat index asc) as the new beam; steps[b] += 1.
  *   topk_token / topk_logprob: as written by ddd_lmhead_topk; rows [B] for step 0 (row b),
  *   rows [B*k] for step >= 1 (row b*k+i is beam slot i of sequence b).
@@ -141,7 +141,7 @@ int ddd_lmhead_topk(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, int3
 int ddd_beam_select(ddd_ctx* ctx, int32_t step, const int32_t* topk_token, const float* topk_logprob,
                     ddd_state* st, void* stream);
 
-/* DDD stop test (Eq. 1, Algorithm 1 lines 5-9) taken after `steps_done` draft calls:
+/* DDD stop test (Eq. 1; Algorithm 1: the check on H at the loop indices in S) taken after `steps_done` draft calls:
  * conf[b] = sum_i exp(logprobsum[b,i]) (fp64); active[b] stays 1 iff steps_done < max_depth and
  * (bit steps_done of check_mask is clear or conf[b] >= threshold).  Written on the device; the
  * host never needs to read it inside a round. */

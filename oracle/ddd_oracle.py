@@ -366,7 +366,7 @@ def run_round(W_bits: Optional[np.ndarray], k: int, D: int, m: int, t: float, ch
             return logits_fn(s, hid)
         return lmhead_logits(W_bits, hid), None
 
-    # Algorithm 1, lines 1-3: prompt call, first beam, logprobsum
+    # Algorithm 1, before the loop: prompt call, first beam, logprobsum
     hid = draft_body(0, None, pool)
     logits, lse_in = project(0, hid)
     tok, lp, lse = lmhead_topk(logits, k, lse_in)

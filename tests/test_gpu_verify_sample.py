@@ -19,7 +19,7 @@ MIN_MARGIN = 1e-10
 def gpu():
     import torch
     if not torch.cuda.is_available():
-        pytest.fail("GPU tests need a HIP device (run them with gpurun)")
+        pytest.fail("GPU tests need a HIP device (an MI355X)")
     import paper_2409_00142_amd as D
     return torch, D
 
