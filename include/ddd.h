@@ -55,7 +55,7 @@ typedef enum ddd_status {
   DDD_ERR_STATE = -6          /* e.g. ddd_round_launch before ddd_round_capture      */
 } ddd_status;
 
-/* Parameters of Algorithm 1 ("Require" line) plus the problem shape. */
+/* Parameters of Algorithm 1 (its Require clause) plus the problem shape. */
 typedef struct ddd_config {
   int32_t B;           /* independent sequences, each with its own beam and stop decision */
   int32_t H;           /* hidden size: H = 128*G*nw with G in {1,2,4} and 1 <= nw <= 10 (so H <= 5120)    */

@@ -200,7 +200,7 @@ class Beam:
 
 
 def beam_first(pool: Pool, root_token: int, tok: np.ndarray, lp: np.ndarray) -> Beam:
-    """Algorithm 1, first three lines: the prompt call's top-k tokens become nodes 1..k and the beam."""
+    """Algorithm 1, before the loop: the prompt call's top-k tokens become nodes 1..k and the beam."""
     k = pool.k
     pool.token[0] = root_token
     pool.parent[0] = -1
