@@ -166,7 +166,7 @@ def depth_continue(logprobsum_f32: Sequence[float], steps_done: int, D: int, t: 
 
 
 # --------------------------------------------------------------------------
-# node pool and beam  (Section 1, EAGLE-2 paragraph; Algorithm 1 "postprocess";
+# node pool and beam  (Section 1, EAGLE-2 paragraph; Algorithm 1, the beam update;
 #                      readings R5, R7)
 # --------------------------------------------------------------------------
 @dataclass

@@ -6,8 +6,8 @@
 //                sorted lists (three keys per slice in registers).
 // beam_update    one wave per sequence: score = logprobsum[parent] + logprob (one fp32 add),
 //                all k*k candidates go to the node pool, the k best by (score desc, token asc,
-//                flat index asc) become the new beam (Algorithm 1, "postprocess ... to
-//                produce the new beam", "calculate logprobsum").
+//                flat index asc) become the new beam (Algorithm 1: the step that turns the draft
+//                outputs into the next beam and its summed log-probabilities).
 // stop_test      Eq. 1 in the probability domain: P = sum_i exp(logprobsum[i]) in fp64, index
 //                order; continue iff another call is allowed and (step not in S or P >= t).
 #pragma once
