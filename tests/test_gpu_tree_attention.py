@@ -91,3 +91,48 @@ def test_tree_attention_against_oracle(gpu, case):
         want = OT.tree_attention(f(q[b]), f(kt[b]), f(vt[b]), f(kp[b]), f(vp[b]), masks[b], n_sels[b])
         assert np.max(np.abs(got[b] - want)) <= ATTN_TOL, float(np.max(np.abs(got[b] - want)))
         assert np.all(got[b, n_sels[b] + 1:] == 0.0)
+
+
+def test_tree_attention_full_size_sampled(gpu):
+    """The verification-pass shape the benchmark times (B = 64, 61 tree nodes, 32 heads, prompt 2048, one key
+    split per head): the oracle recomputes sampled (sequence, head) pairs."""
+    torch, D, SD = gpu
+    B, m, nh, L, d = 64, 60, 32, 2048, 128
+    T, Tp = m + 1, 64
+    print(f"[case] tree attention full size B={B} m={m} heads={nh} L={L}, sampled heads", flush=True)
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    rnd = lambda *s: torch.randn(*s, device="cuda", generator=gen).to(torch.bfloat16)
+    q, kt, vt = rnd(B, T, nh, d), rnd(B, T, nh, d), rnd(B, T, nh, d)
+    vtt = torch.zeros(B, nh, d, Tp, device="cuda", dtype=torch.bfloat16)
+    vtt[..., :T] = vt.permute(0, 2, 3, 1)
+    kp, vp = rnd(B, L, nh, d), rnd(B, L, nh, d)
+    rng = np.random.default_rng(78)
+    n_sels = [int(x) for x in rng.integers(20, m + 1, size=B)]
+    parents = [_random_tree(rng, T, n_sels[b]) for b in range(B)]
+    masks = np.zeros((B, T, T), dtype=np.uint8)
+    for b in range(B):
+        n = n_sels[b] + 1
+        masks[b, :n, :n] = np.array(BF.closure_mask(parents[b][:n], n), dtype=np.uint8)
+    cfg = D.make_config(B, 256, 1000, 4, 4, m, 0.3)
+    ctx = D.ddd_create(cfg)
+    try:
+        tree, tree_t = D.alloc_tree(cfg)
+        tree_t["mask"].copy_(torch.from_numpy(masks).view_as(tree_t["mask"]))
+        tree_t["n_sel"].copy_(torch.tensor(n_sels, dtype=torch.int32))
+        ws = torch.empty(max(1, D.ddd_tree_attention_workspace(ctx, nh, L) // 4), dtype=torch.float32, device="cuda")
+        out = torch.full((B, T, nh, d), float("nan"), dtype=torch.float32, device="cuda")
+        kpk = torch.empty(B * nh * (L // 32) * 4096, dtype=torch.bfloat16, device="cuda")
+        vpk = torch.empty_like(kpk)
+        D.ddd_kv_pack(ctx, kp, vp, L, nh, kpk, vpk)
+        D.ddd_tree_attention(ctx, tree, q, kt, vtt, kpk, vpk, L, nh, ws, out)
+        torch.cuda.synchronize()
+        assert not torch.isnan(out).any()
+        f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+        for b, h in [(0, 0), (63, 31), (17, 5), (40, 20), (5, 30), (29, 11)]:
+            want = OT.tree_attention(f64(q[b, :, h:h + 1]), f64(kt[b, :, h:h + 1]), f64(vt[b, :, h:h + 1]),
+                                     f64(kp[b, :, h:h + 1]), f64(vp[b, :, h:h + 1]), masks[b], n_sels[b])
+            got = out[b, :, h:h + 1].cpu().numpy().astype(np.float64)
+            assert np.max(np.abs(got - want)) <= ATTN_TOL, (b, h, float(np.max(np.abs(got - want))))
+            assert np.all(got[n_sels[b] + 1:] == 0.0)
+    finally:
+        D.ddd_destroy(ctx)

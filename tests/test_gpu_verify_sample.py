@@ -58,6 +58,7 @@ CASES = [
     ("large_vocab", 2, 128256, 10, 10, 60, [60, 45], 1.0),
     ("wide_beam_many_children", 1, 5003, 100, 2, 127, [127], 1.5),
     ("cold", 2, 32000, 10, 10, 60, [60, 60], 0.05),
+    ("7b_b64_shape", 64, 32000, 10, 10, 60, [60] * 40 + [37] * 24, 0.9),      # the batch the benchmark times
 ]
 
 
