@@ -251,7 +251,7 @@ int ddd_round_launch(ddd_ctx* ctx, void* stream);
  * queued per round.  Results are those of ddd_round_enqueue.  The host thread polls (at most 20 ms per call, then
  * it queues the remaining calls unconditionally), so this call returns when the last draft call has been queued,
  * not when the round has finished.  One round per context at a time; not for use under stream capture (nothing
- * would run while the host waits).  Beams wider than DDD_KMAX queue every call.  Arguments as for ddd_round_enqueue,
+ * would run while the host waits).  Arguments as for ddd_round_enqueue,
  * without the debug buffers.  Returns the number of draft calls queued (>= 1), or a negative status. */
 int ddd_round_run(ddd_ctx* ctx, const void* W_bf16, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
                   void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,

@@ -104,6 +104,9 @@ WideStepArgs wide_args(const ddd_ctx* c, const BeamArgs& beam) {
   w.do_select = 0;
   w.do_stop = 0;
   w.steps_done = 0;
+  w.call_count = nullptr;
+  w.progress = nullptr;
+  w.round_tag = 0;
   return w;
 }
 
@@ -561,6 +564,9 @@ int draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_sta
     w.tree = a.tree;
     w.do_select = 1;
     w.do_stop = 1;
+    w.call_count = publish ? c->call_count + step : nullptr;
+    w.progress = publish ? c->progress_dev + step : nullptr;
+    w.round_tag = c->round_tag;
     DDD_HIP(launch_step_wide(w, s));
     return DDD_OK;
   }
@@ -673,7 +679,7 @@ int ddd_round_run(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, cons
                   ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user, void* stream) {
   if (c == nullptr || W == nullptr || !state_ok(st) || !tree_ok(tree) || hid_buf == nullptr || body == nullptr)
     return DDD_ERR_INVALID_ARG;
-  const bool publish = c->cfg.k <= DDD_KMAX;     // wide beams: every call is enqueued, as in ddd_round_enqueue
+  const bool publish = true;
   c->round_tag = (c->round_tag + 1) & 0x3FFFFFFFu;
   if (c->round_tag == 0) c->round_tag = 1;
   int rc = ddd_round_reset(c, st, root_token, stream);

@@ -111,6 +111,9 @@ struct WideStepArgs {
   int do_select;              // run the beam update
   int do_stop;                // run the stop test (steps_done = beam.step + 1 after a beam update)
   int steps_done;             // draft calls made so far, for a stop test without a beam update
+  uint32_t* call_count;       // null, or this call's arrival word: the last workgroup to arrive reports
+  uint32_t* progress;         //   (round_tag << 2) | 2 | (some sequence still active) to this word in host memory
+  uint32_t round_tag;
 };
 hipError_t prepare_wide();    // once per process: enables the kernels' LDS sizes
 hipError_t launch_step_wide(const WideStepArgs& a, hipStream_t stream);

@@ -217,14 +217,15 @@ __device__ __forceinline__ void tree_finalize_wide_block(const ddd_state& st, co
   tree_emit_block(st, tree, b, m, m_eff, nmax, tid, nthr, sm.te);
 }
 
-__global__ __launch_bounds__(kWideThreads) void step_wide_kernel(WideStepArgs a) {
-  extern __shared__ __align__(16) unsigned char wsm_raw[];
+// One draft call of one sequence by one workgroup; returns whether the sequence is still active after it
+// (the same value in every thread; true when no stop test is asked for).
+__device__ __forceinline__ bool step_wide_block(const WideStepArgs& a, unsigned char* wsm_raw) {
   const BeamArgs& g = a.beam;
   const int b = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
   const int k = g.k, step = g.step;
   uint64_t* keys = reinterpret_cast<uint64_t*>(wsm_raw);                       // [k*k]
   WideSmem& sm = *reinterpret_cast<WideSmem*>(wsm_raw + (((size_t)k * k * 8 + 15) & ~(size_t)15));
-  if (!g.st.active[b]) return;               // uniform over the workgroup
+  if (!g.st.active[b]) return false;         // uniform over the workgroup
 
   float* lps = g.st.logprobsum + (size_t)b * k;
   int32_t* bnode = g.st.beam_node + (size_t)b * k;
@@ -357,7 +358,25 @@ __global__ __launch_bounds__(kWideThreads) void step_wide_kernel(WideStepArgs a)
     for (int i = tid; i < k; i += nthr) g.st.row_active[(size_t)b * k + i] = on;
   }
   __syncthreads();   // also orders the pool writes before the reads below
-  if (a.tree.mask != nullptr && sm.stopped) tree_finalize_wide_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm);
+  const bool stopped = sm.stopped != 0;
+  if (a.tree.mask != nullptr && stopped) tree_finalize_wide_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm);
+  return !stopped;
+}
+
+__global__ __launch_bounds__(kWideThreads) void step_wide_kernel(WideStepArgs a) {
+  extern __shared__ __align__(16) unsigned char wsm_raw[];
+  const bool active = step_wide_block(a, wsm_raw);
+  if (a.call_count != nullptr && threadIdx.x == 0) {
+    // report to the host that paces the round (see step_bookkeep_kernel): one atomic per sequence, arrivals in
+    // the low half, active sequences in the high half; the last arrival clears the word and writes the host word
+    const uint32_t mine = 1u | (active ? 0x10000u : 0u);
+    const uint32_t seen = __hip_atomic_fetch_add(a.call_count, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((seen & 0xFFFFu) + 1u == gridDim.x) {
+      __hip_atomic_store(a.call_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t any = ((seen + mine) >> 16) != 0u ? 1u : 0u;
+      __hip_atomic_store(a.progress, (a.round_tag << 2) | 2u | any, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+  }
 }
 
 __global__ __launch_bounds__(kWideThreads) void tree_finalize_wide_kernel(FinalizeArgs a) {

@@ -588,12 +588,14 @@ def test_host_paced_round_with_very_few_calls(gpu, D_max):
         g.close()
 
 
-@pytest.mark.parametrize("wname,B", [("tiny", 2), ("7b_b1", 1), ("tiny", 40)])
+@pytest.mark.parametrize("wname,B", [("tiny", 2), ("7b_b1", 1), ("tiny", 40), ("wide_k20", 3), ("wide_k50", 1)])
 def test_host_paced_round_matches_enqueued_round(gpu, wname, B):
     """ddd_round_run queues draft calls only while some sequence is active: same results as queueing all
     max_depth calls, and at most one call more than the deepest sequence made."""
     torch, D, SD = gpu
-    wl = synth.WORKLOADS[wname].with_(B=B)
+    wl = (WIDE[wname] if wname in WIDE else synth.WORKLOADS[wname]).with_(B=B)
+    if wname in WIDE:
+        wl = wl.with_(D=6, threshold=0.4)          # rounds that stop before the last call
     print(f"[case] host-paced rounds {wname} B={B}", flush=True)
     g = SD.GpuWorkload(wl, debug=False)
     try:
