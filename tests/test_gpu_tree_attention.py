@@ -44,11 +44,35 @@ CASES = [
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_tree_attention_against_oracle(gpu, case):
-    torch, D, SD = gpu
     name, B, m, nh, L, n_sels = case
+    _check_case(gpu, name, B, m, nh, L, n_sels, seed=sum(map(ord, name)))
+
+
+def _random_cases(n=24, seed=9):
+    """Seeded random shapes: trees of 1..128 rows, 0..2100 prompt positions (ragged against the 32-key chunks and the
+    split sizes), 1..8 heads, 1..5 sequences with trees of different sizes (empty ones included)."""
+    import random
+    rnd = random.Random(seed)
+    out = []
+    while len(out) < n:
+        B, m, nh = rnd.choice([1, 1, 2, 3, 5]), rnd.choice([1, 2, 20, 31, 32, 60, 63, 64, 100, 127]), rnd.choice([1, 2, 3, 8])
+        L = rnd.choice([0, 1, 31, 32, 33, 100, 255, 256, 1000, 2100])
+        if B * nh * (L + m) > 12000:
+            continue
+        out.append(("random%d" % len(out), B, m, nh, L, [rnd.randint(0, m) for _ in range(B)]))
+    return out
+
+
+def test_tree_attention_random_shapes(gpu):
+    for i, (name, B, m, nh, L, n_sels) in enumerate(_random_cases()):
+        _check_case(gpu, name, B, m, nh, L, n_sels, seed=500 + i)
+
+
+def _check_case(gpu, name, B, m, nh, L, n_sels, seed):
+    torch, D, SD = gpu
     T, d = m + 1, 128
     print(f"[case] tree attention {name} B={B} m={m} heads={nh} L={L} n_sel={n_sels}", flush=True)
-    rng = np.random.default_rng(abs(hash(name)) % (1 << 31))
+    rng = np.random.default_rng(seed)
     bits = lambda shape: synth.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
     q, kt, vt = bits((B, T, nh, d)), bits((B, T, nh, d)), bits((B, T, nh, d))
     kp, vp = bits((B, L, nh, d)), bits((B, L, nh, d))
