@@ -716,6 +716,48 @@ def test_random_configurations_against_oracle_and_host_paced(gpu):
             g.close()
 
 
+LARGE_B = [(4096, 2, 3, 64, 128, 7, 0.3), (4096, 1, 2, 64, 128, 1, 0.0), (1000, 10, 4, 257, 256, 60, 0.3),
+           (700, 20, 3, 300, 128, 128, 0.2)]
+
+
+@pytest.mark.parametrize("cfg", LARGE_B, ids=lambda c: "B%d-k%d-D%d-V%d-H%d-m%d-t%s" % c)
+def test_large_batches_up_to_the_limit(gpu, cfg):
+    """Thousands of sequences (DDD_BMAX = 4096; up to 14 000 hidden rows per call, many column tiles of the GEMM,
+    64 words of the active mask): two rounds replayed by the oracle, and the host-paced and the graph launch
+    leave the same bytes."""
+    torch, D, SD = gpu
+    B, k, Dm, V, H, m, t = cfg
+    wl = synth.WORKLOADS["tiny"].with_(B=B, k=k, D=Dm, V=V, H=H, m=m, threshold=t)
+    print(f"[case] large batch B={B} k={k} D={Dm} V={V} H={H} m={m} t={t}", flush=True)
+    side = torch.cuda.Stream()
+    g = SD.GpuWorkload(wl, debug=True)
+    try:
+        for rnd in range(2):
+            g.set_round(rnd)
+            g.enqueue_round()
+            torch.cuda.synchronize()
+            snap = g.snapshot()
+            try:
+                _compare_round(g, snap, wl, rnd, t, g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy())
+            except AssertionError as e:
+                if "too close to the threshold" not in str(e):
+                    raise
+            g.set_round(rnd)
+            torch.cuda.synchronize()
+            g.run_round(side.cuda_stream)
+            side.synchronize()
+            _same_round(g.snapshot(), snap)
+            if rnd == 0:
+                g.capture(side)
+            g.set_round(rnd)
+            torch.cuda.synchronize()
+            g.launch(side.cuda_stream)
+            side.synchronize()
+            _same_round(g.snapshot(), snap)
+    finally:
+        g.close()
+
+
 def test_7b_shape_round_parity(gpu):
     """Full 7B-shaped sizes: rounds launched as one captured graph with the debug buffers are replayed by the
     oracle; the same rounds launched the way the benchmark times them (host-paced, no debug buffers) leave
