@@ -34,9 +34,9 @@ __device__ __forceinline__ void merge_load_heads(const uint64_t* __restrict__ pk
 #pragma unroll
   for (int i = 0; i < kHPL; ++i) {
     const int s = lane + 64 * i;
-    h.q0[i] = (s < nslice) ? pk[(size_t)s * k] : 0ull;
-    h.q1[i] = (s < nslice && k > 1) ? pk[(size_t)s * k + 1] : 0ull;
-    h.q2[i] = (s < nslice && k > 2) ? pk[(size_t)s * k + 2] : 0ull;
+    h.q0[i] = (s < nslice) ? pk[s] : 0ull;
+    h.q1[i] = (s < nslice && k > 1) ? pk[nslice + s] : 0ull;
+    h.q2[i] = (s < nslice && k > 2) ? pk[2 * nslice + s] : 0ull;
     h.psum[i] = (s < nslice) ? ps[s] : 0.f;
   }
 }
@@ -49,7 +49,7 @@ __device__ __forceinline__ void merge_load_heads(const uint64_t* __restrict__ pk
 // row's k best (for k = 10 and 256 slices about one row in 500) fetches its further keys one at
 // a time as they are needed.
 template <int HPL>
-__device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, RowHeads& h, int k, int lane,
+__device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, RowHeads& h, int nslice, int k, int lane,
                                           uint64_t& my_key, float& lse) {
   uint64_t loc = 0;
 #pragma unroll
@@ -73,22 +73,32 @@ __device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, RowHe
     const uint64_t best = wave_max_u64(loc);
     if (lane == round) my_key = best;
     if (best == 0ull) break;           // uniform: fewer than k keys in the row
+    // Keys are distinct (every token sits in one slice), so exactly one slot of one lane holds the best:
+    // its index is made uniform and only that slot's update is issued (the wave would otherwise execute
+    // the update of every slot for the sake of one lane).
+    int which = -1;
 #pragma unroll
     for (int i = 0; i < HPL; ++i)
-      if (h.q0[i] == best) {
-        ++taken[i];
-        h.q0[i] = h.q1[i];
-        h.q1[i] = h.q2[i];
-        h.q2[i] = (taken[i] + 2 < k) ? kFetch : 0ull;
-        if (h.q0[i] == kFetch) h.q0[i] = pk[(size_t)(lane + 64 * i) * k + taken[i]];   // fourth key onwards
+      if (h.q0[i] == best) which = i;
+    const int owner = __ffsll((unsigned long long)__ballot(which >= 0)) - 1;
+    const int iu = __builtin_amdgcn_readlane(which, owner);
+#pragma unroll
+    for (int i = 0; i < HPL; ++i)
+      if (iu == i) {                     // uniform
+        if (which == i) {
+          ++taken[i];
+          h.q0[i] = h.q1[i];
+          h.q1[i] = h.q2[i];
+          h.q2[i] = (taken[i] + 2 < k) ? kFetch : 0ull;
+          if (h.q0[i] == kFetch) h.q0[i] = pk[(size_t)taken[i] * nslice + lane + 64 * i];   // fourth key onwards
+        }
       }
   }
 }
 
 __device__ __forceinline__ void merge_row_dispatch(const uint64_t* pk, RowHeads& h, int nslice, int k, int lane,
                                                    uint64_t& my_key, float& lse) {
-  (void)nslice;        // slices beyond nslice hold empty keys
-  merge_row<kHPL>(pk, h, k, lane, my_key, lse);
+  merge_row<kHPL>(pk, h, nslice, k, lane, my_key, lse);
 }
 
 // ---- beam update by one wave (all 64 lanes active) -------------------------------------------

@@ -20,7 +20,7 @@ struct ddd_ctx {
   int ntiles, nslice;   // 16-row tiles of W, workgroups of the weight stream (<= 16 rows)
   int g_grid;           // GEMM path (> 16 rows): one workgroup per CU
   int nmax;
-  uint64_t* part_key;   // [B*k][nslice][k] (weight stream) or [B*k][k] (GEMM path, dense)
+  uint64_t* part_key;   // [B*k][k][nslice] (weight stream: rank-major, the slices' j-th keys together) or [B*k][k] (GEMM path, dense)
   float* part_sum;      // [B*k][nslice] or [B*k]
   int32_t* row_list;    // [B*k] active rows of the current call (GEMM path)
   int32_t* n_act;       // [1]

@@ -46,7 +46,7 @@ hipError_t launch_row_topk(const RowTopkArgs& a, hipStream_t stream);
 // ---- per-row merge, beam select, stop test (bookkeep.hip) -------------------------------------
 // nslice == 0 selects the dense format above (nothing to merge).
 struct MergeArgs {
-  const uint64_t* part_key;   // [n_rows][nslice][k]
+  const uint64_t* part_key;   // [n_rows][k][nslice]: rank j of every slice together (the merge reads ranks 0..2)
   const float* part_sum;      // [n_rows][nslice]
   const uint8_t* row_active;  // [n_rows] or null
   int32_t* topk_token;        // [n_rows,k]
@@ -69,7 +69,7 @@ hipError_t launch_depth_continue(const BeamArgs& a, int steps_done, hipStream_t 
 
 struct StepArgs {             // merge + beam select + stop test in one launch
   BeamArgs beam;              // topk_* unused
-  const uint64_t* part_key;   // [B*k][nslice][k]
+  const uint64_t* part_key;   // [B*k][k][nslice]
   const float* part_sum;
   float* lse_dbg;             // [B*k] or null: lse of every merged row
   ddd_tree tree;              // tree.mask == null: do not build the final tree here
@@ -88,7 +88,7 @@ struct StreamArgs {
   const uint16_t* W;          // bf16 [V,H]
   const uint16_t* hid;        // bf16 [R,H], first row of this pass
   const uint8_t* row_active;  // [R] or null
-  uint64_t* part_key;         // [R][nslice][k], first row of this pass
+  uint64_t* part_key;         // [R][k][nslice], first row of this pass
   float* part_sum;            // [R][nslice]
   float* logits_dbg;          // fp32 [R][V] or null
   int H, V, R, k, ntiles, nw;

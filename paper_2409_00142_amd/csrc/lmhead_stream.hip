@@ -168,14 +168,14 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
     float s_q = (s_l == 0.f) ? 0.f : s_l * __expf(m_l - m_q);
     s_q += dpp_move_f32<0xB1>(s_q);
     s_q += dpp_move_f32<0x4E>(s_q);
-    uint64_t* pk = a.part_key + ((size_t)(ok2 ? r2 : 0) * nslice + slice) * a.k;
+    uint64_t* pk = a.part_key + (size_t)(ok2 ? r2 : 0) * nslice * a.k + slice;   // [row][rank][slice]
     int cur = 0;
     for (int round = 0; round < a.k; ++round) {
       const uint64_t head = (cur < KL) ? elist[lane * KL + cur] : 0ull;
       uint64_t q = umax64(head, dpp_move_u64<0xB1>(head));
       q = umax64(q, dpp_move_u64<0x4E>(q));
       if (head == q && q != 0ull) ++cur;
-      if (ok2 && (lane & 3) == 0) pk[round] = q;
+      if (ok2 && (lane & 3) == 0) pk[(size_t)round * nslice] = q;
     }
     if (ok2 && (lane & 3) == 0) a.part_sum[(size_t)r2 * nslice + slice] = s_q;
   }
