@@ -2,12 +2,17 @@
 """Benchmark of the DDD draft round on one MI355X.
 
 A "step" is one whole draft round (Algorithm 1 of the paper end to end: reset, up to D draft
-calls each = stand-in draft body + LM-head weight stream + merge/beam/stop kernel, final tree,
-stand-in target, accept walk) launched as one captured HIP graph.  Inputs are seeded and
-synthetic (7B-shaped by default) and resident in HBM before the timed region starts.
+calls each = stand-in draft body + LM-head kernel + merge/beam/stop kernel, final tree,
+stand-in target, accept walk).  By default the host paces the draft calls (ddd_round_run);
+`--launch graph` replays one captured HIP graph per round instead, and the default run times
+that form too, beside the headline.  Inputs are seeded and synthetic (7B-shaped by default)
+and resident in HBM before the timed region starts.
 
-Prints ONE JSON line: draft rounds/s plus us per executed depth step, the HBM roofline of the
-dominant kernel (the LM-head weight stream) and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: draft rounds/s plus us per executed depth step, the roofline of the
+dominant kernel (the LM-head weight stream at B = 1: HBM; the MFMA GEMM at B = 64), the
+round-level HBM fraction, the CPU oracle timed on a bounded sample, and - in the default
+run - a `secondary` list with the other workloads of the metric (7B shape at B = 64, 13B
+shape, large vocabulary), each measured the same way on fewer rounds.
 """
 import argparse
 import json
@@ -21,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X published HBM3E peak
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 MFMA peak
+CACHE_BYTES = 256 * 2**20   # memory-side cache (Infinity Cache)
 
 
 def log(*a):
@@ -28,7 +34,8 @@ def log(*a):
 
 
 def cpu_baseline(wl, W_bits, plant_dir, threshold, budget_s):
-    """The CPU oracle, as it stands, on a bounded sample of the same rounds."""
+    """The CPU oracle, as it stands, on a bounded sample of the same rounds: sequence after sequence of round 0,
+    then of round 1, ... until the time budget is used."""
     from oracle import synth_round as SR
     try:
         from threadpoolctl import threadpool_info
@@ -36,16 +43,18 @@ def cpu_baseline(wl, W_bits, plant_dir, threshold, budget_s):
     except Exception:
         threads = os.cpu_count() or 1
     t0 = time.perf_counter()
-    rounds = steps = 0
+    n = steps = 0
     while True:
-        res, _, _ = SR.oracle_round(wl, W_bits, plant_dir, 0, rounds, threshold=threshold)
-        rounds += 1
+        res, _, _ = SR.oracle_round(wl, W_bits, plant_dir, n % wl.B, n // wl.B, threshold=threshold)
+        n += 1
         steps += res.steps
         el = time.perf_counter() - t0
-        if el > budget_s or rounds >= 64:
+        if el > budget_s or n >= 64:
             break
-    return {"value": rounds / el, "unit": "rounds/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{rounds} rounds ({steps} depth steps) of sequence 0, rounds 0..{rounds - 1}, {el:.1f} s",
+    what = (f"{n} rounds of sequence 0, rounds 0..{n - 1}" if wl.B == 1 else
+            f"{n} sequence-rounds (sequences 0..{min(n, wl.B) - 1} of round 0" + (", then round 1 ..." if n > wl.B else "") + ")")
+    return {"value": n / el, "unit": "rounds/s" if wl.B == 1 else "sequence-rounds/s", "cores": int(threads),
+            "kind": "oracle", "sample": f"{what}, {steps} depth steps, {el:.1f} s",
             "us_per_depth_step": 1e6 * el / steps}
 
 
@@ -122,6 +131,232 @@ def time_verify_sample(torch, D, g, wl, temperature, side):
             "GBs": alg / us / 1e3, "hbm_frac": alg / us / 1e3 / HBM_PEAK_GBS}
 
 
+def time_rounds(torch, g, launch, steps, warmup, side):
+    """`warmup` untimed rounds, then exactly `steps` timed ones between synchronisations; returns wall seconds,
+    the event time and the histograms the rounds' post hook kept on the device."""
+    torch.cuda.synchronize()
+    g.set_round(0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(warmup):
+            launch()
+        side.synchronize()
+        g.depth_hist.zero_()
+        g.accept_hist.zero_()
+        g.batch_depth_hist.zero_()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        e0.record(side)
+        for _ in range(steps):
+            launch()
+        e1.record(side)
+        side.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - w0
+    depth_hist = g.depth_hist.cpu().numpy()
+    return {"wall": wall, "ev_ms": e0.elapsed_time(e1), "depth_hist": depth_hist,
+            "accept_hist": g.accept_hist.cpu().numpy(),
+            "exec_steps": int(sum(d * int(c) for d, c in enumerate(depth_hist))),
+            # a depth step of the batch = one LM-head pass: a round executes as many as its deepest sequence
+            "batch_steps": int(sum(d * int(c) for d, c in enumerate(g.batch_depth_hist.cpu().numpy())))}
+
+
+def kernel_roofline(torch, D, SD, g, wl, iters, side, traffic_path):
+    """The LM-head kernel alone: HIP events around stand-alone launches on the stream they run on (all B*k rows
+    active; <= 16 rows: the weight stream, HBM-bound; more: the MFMA GEMM), in three settings - as consecutive
+    draft calls run it (alternating sweep direction: a launch starts in what its predecessor left in the memory-side
+    cache), every launch sweeping forward, and every launch after a 1 GB read of other memory (nothing of W
+    cached) - plus a plain read-stream kernel and, for MFMA-bound shapes, a register-resident MFMA loop as the
+    practical ceilings."""
+    n_rows = wl.B * wl.k
+    w_bytes = wl.V * wl.H * 2
+    mean_ms, min_ms = D.ddd_profile_lmhead(g.ctx, g.W, g.hid, n_rows, iters, stream=side.cuda_stream)
+    if n_rows <= 16 and wl.k <= 16:
+        kernel_name = "lmhead_stream_kernel"
+        alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * D.ddd_num_slices(g.ctx) * (wl.k * 8 + 4)
+    else:
+        kernel_name = "lmhead_gemm_kernel"
+        alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * (wl.k * 8 + 4)   # W, hidden rows, k keys + lse per row
+    alg_flops = 2.0 * wl.V * wl.H * n_rows
+    achieved = alg_bytes / (mean_ms * 1e-3) / 1e9
+    achieved_tflops = alg_flops / (mean_ms * 1e-3) / 1e12
+    mfma_bound = alg_flops / (MFMA_PEAK_TFLOPS * 1e12) > alg_bytes / (HBM_PEAK_GBS * 1e9)
+
+    # the same launch with every call sweeping forward, and with the memory-side cache emptied before each launch
+    cfg_fwd = D.make_config(wl.B, wl.H, wl.V, wl.k, wl.D, wl.m, wl.threshold, wl.check_mask, D.DDD_FLAG_FORWARD_SWEEPS)
+    ctx_fwd = D.ddd_create(cfg_fwd)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    try:
+        if g.packed:
+            D.ddd_weights_pack(ctx_fwd, g.W, stream=side.cuda_stream)
+        fwd_ms, _ = D.ddd_profile_lmhead(ctx_fwd, g.W, g.hid, n_rows, iters, stream=side.cuda_stream)
+        other = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        other.zero_()
+        cold = []
+        for _ in range(24):
+            D.ddd_synth_read_stream(other, other.numel(), sink, 4096, stream=side.cuda_stream)
+            cold.append(D.ddd_profile_lmhead(ctx_fwd, g.W, g.hid, n_rows, 1, stream=side.cuda_stream)[0])
+        cold_ms = sum(cold[4:]) / len(cold[4:])
+        del other
+    finally:
+        D.ddd_destroy(ctx_fwd)
+
+    # plain read stream over the same bytes: the practical ceiling of an HBM-bound kernel
+    with torch.cuda.stream(side):
+        best = None
+        for blocks in (2048, 4096, 8192):
+            for _ in range(3):
+                D.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
+            r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            r0.record(side)
+            for _ in range(20):
+                D.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
+            r1.record(side)
+            side.synchronize()
+            gbs = 20 * w_bytes / (r0.elapsed_time(r1) * 1e-3) / 1e9
+            best = gbs if best is None else max(best, gbs)
+    # register-resident MFMA loop on random operands: the practical matrix-core ceiling
+    mfma_ceiling = None
+    if mfma_bound:
+        fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        with torch.cuda.stream(side):
+            it, blocks = 4000, 512             # 2 waves per SIMD; 512*4*4000*8 MFMAs of 32768 flop
+            D.ddd_synth_mfma_rate(fsink, 200, blocks, stream=side.cuda_stream)
+            m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            m0.record(side)
+            D.ddd_synth_mfma_rate(fsink, it, blocks, stream=side.cuda_stream)
+            m1.record(side)
+            side.synchronize()
+        mfma_ceiling = blocks * 4 * it * 8 * 32768.0 / (m0.elapsed_time(m1) * 1e-3) / 1e12
+
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload (null if none)
+    traffic, source = None, None
+    if os.path.exists(traffic_path):
+        with open(traffic_path) as f:
+            tj = json.load(f)
+        traffic = tj.get("bytes")
+        source = (f"{os.path.relpath(traffic_path, ROOT)}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                  f"scaled by a copy of known size (committed; not measured in this run; see {tj.get('source')})")
+    if mfma_bound:
+        roof = {"bound": "mfma", "achieved": achieved_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved_tflops / MFMA_PEAK_TFLOPS, "hbm_GBs": achieved, "hbm_frac": achieved / HBM_PEAK_GBS,
+                "frac_forward_sweep": alg_flops / (fwd_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                "frac_cache_flushed": alg_flops / (cold_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS}
+    else:
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS,
+                "frac_forward_sweep": alg_bytes / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "frac_cache_flushed": alg_bytes / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "mfma_TFLOPs": achieved_tflops}
+    roof.update({"traffic": traffic, "traffic_source": source, "kernel": kernel_name, "rows": n_rows,
+                 "sweep_of_frac": "alternating (memory-side cache included when W is within its reach: "
+                                  f"W = {w_bytes / 2**20:.0f} MiB, cache = 256 MiB)",
+                 "us_per_launch": mean_ms * 1e3, "us_per_launch_min": min_ms * 1e3,
+                 "us_per_launch_forward_sweep": fwd_ms * 1e3, "us_per_launch_cache_flushed": cold_ms * 1e3,
+                 "algorithmic_bytes_per_launch": alg_bytes, "algorithmic_flops_per_launch": alg_flops,
+                 "launches_timed": iters, "read_stream_ceiling_GBs": best, "mfma_loop_ceiling_TFLOPs": mfma_ceiling})
+    log(f"[bench] {wl.name}: {kernel_name} ({n_rows} rows): {mean_ms * 1e3:.2f} us per launch (min {min_ms * 1e3:.2f}; "
+        f"forward sweeps {fwd_ms * 1e3:.2f}; cache flushed {cold_ms * 1e3:.2f}); {alg_bytes / 1e6:.2f} MB -> {achieved:.0f} GB/s "
+        f"({100 * achieved / HBM_PEAK_GBS:.1f}% of 8 TB/s); {alg_flops / 1e9:.1f} GFLOP -> {achieved_tflops:.0f} TFLOP/s "
+        f"({100 * achieved_tflops / MFMA_PEAK_TFLOPS:.1f}% of {MFMA_PEAK_TFLOPS:.0f}); read stream {best:.0f} GB/s"
+        + (f"; MFMA loop {mfma_ceiling:.0f} TFLOP/s" if mfma_ceiling else ""))
+    return roof
+
+
+def run_workload(torch, D, synth, SD, wl, thr, args, steps, warmup, launch_mode, also_graph, cpu_budget, W_cache):
+    """One workload measured end to end; returns the fields of its JSON object."""
+    log(f"[bench] workload {wl.name}: B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} m={wl.m} t={thr} gain={wl.gain}")
+    t0 = time.perf_counter()
+    key = (wl.V, wl.H, wl.sigma_w, wl.seed, wl.dup_pairs)
+    g = SD.GpuWorkload(wl, W_bits=W_cache.get(key), threshold=thr, debug=False,
+                       flags=D.DDD_FLAG_FORWARD_SWEEPS if args.sweep == "forward" else 0)
+    W_cache.clear()                 # keep one matrix at most (the 7B head serves both 7B workloads)
+    W_cache[key] = g.W_bits
+    log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s; "
+        f"stream slices={D.ddd_num_slices(g.ctx)}")
+    if args.body == "layer":
+        if wl.B * wl.k > 16:
+            sys.exit("--body layer handles at most 16 rows per call (B*k <= 16)")
+        F = args.ffn if args.ffn is not None else (13824 if wl.H == 5120 else 11008)
+        t1 = time.perf_counter()
+        g.use_layer_body(F, args.prompt_len)
+        log(f"[bench] draft layer: F={F}, prompt length {args.prompt_len}, {g.body_bytes / 1e6:.1f} MB of layer weights "
+            f"streamed per call ({time.perf_counter() - t1:.1f} s to generate and upload)")
+    uses_gemm = wl.B * wl.k > 16 or wl.k > 16
+    g.packed = args.pack_weights == "on" or (args.pack_weights == "auto" and uses_gemm and wl.V * wl.H * 2 > CACHE_BYTES)
+    if g.packed:
+        D.ddd_weights_pack(g.ctx, g.W)
+        torch.cuda.synchronize()
+        log("[bench] GEMM path reads W from its tile-major copy (ddd_weights_pack)")
+    side = torch.cuda.Stream()
+    launchers = {"paced": lambda: g.run_round(side.cuda_stream), "eager": lambda: g.enqueue_round(side.cuda_stream),
+                 "graph": lambda: g.launch(side.cuda_stream)}
+    if launch_mode == "graph" or also_graph:
+        g.capture(side)
+    r = time_rounds(torch, g, launchers[launch_mode], steps, warmup, side)
+    n_round_seq = int(r["depth_hist"].sum())
+    assert n_round_seq == steps * wl.B, (n_round_seq, steps, wl.B)
+    wall = r["wall"]
+    rounds_per_s = steps * wl.B / wall
+    w_bytes = wl.V * wl.H * 2
+    log(f"[bench] {steps} rounds ({launch_mode}) in {wall * 1e3:.2f} ms wall ({r['ev_ms']:.2f} ms by events): "
+        f"{rounds_per_s:.1f} {'rounds' if wl.B == 1 else 'sequence-rounds'}/s, {1e6 * wall / steps:.1f} us/round, "
+        f"{1e6 * wall / max(1, r['batch_steps']):.1f} us per executed depth step")
+    log(f"[bench] depth histogram (steps -> sequences): { {d: int(c) for d, c in enumerate(r['depth_hist']) if c} }")
+    log(f"[bench] accept-length histogram: { {d: int(c) for d, c in enumerate(r['accept_hist']) if c} }")
+    launch_names = {"graph": "one hipGraph per round", "eager": "stream launches",
+                    "paced": "stream launches paced by the host (ddd_round_run)"}
+    modes = {launch_mode: {"rounds_per_s": rounds_per_s, "us_per_round": 1e6 * wall / steps, "rounds_timed": steps}}
+    if launch_mode == "paced":
+        modes["paced"]["host_waits"] = D.ddd_round_run_stats(g.ctx)
+    if also_graph and launch_mode != "graph":
+        n2 = max(steps, 200)
+        r2 = time_rounds(torch, g, launchers["graph"], n2, warmup, side)
+        modes["graph"] = {"rounds_per_s": n2 * wl.B / r2["wall"], "us_per_round": 1e6 * r2["wall"] / n2, "rounds_timed": n2}
+        log(f"[bench] the same rounds as one hipGraph each: {modes['graph']['rounds_per_s']:.1f}/s, "
+            f"{modes['graph']['us_per_round']:.1f} us/round")
+
+    traffic_path = args.traffic or os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
+    roof = kernel_roofline(torch, D, SD, g, wl, args.profile_iters, side, traffic_path)
+    # round level: one pass over W per executed depth step of the batch is what the method has to move
+    roof["round_frac"] = r["batch_steps"] * w_bytes / wall / 1e9 / HBM_PEAK_GBS
+    roof["round_GBs"] = r["batch_steps"] * w_bytes / wall / 1e9
+    out = {
+        "value": rounds_per_s,
+        "unit": "rounds/s" if wl.B == 1 else "sequence-rounds/s",
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": 1e3 * wall / steps,
+        "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
+                   "threshold": thr, "check_mask": int(wl.check_mask), "mode": args.mode, "hidden_gain": wl.gain,
+                   "launch": launch_names[launch_mode], "launch_modes": modes,
+                   "paced_timeouts": modes.get("paced", {}).get("host_waits", {}).get("timeouts"),
+                   "packed_weights": bool(g.packed), "sweep": args.sweep, "body": args.body,
+                   "body_weight_bytes_per_call": int(getattr(g, "body_bytes", 0)),
+                   "depth_hist": {str(d): int(c) for d, c in enumerate(r["depth_hist"]) if c},
+                   "accept_len_hist": {str(d): int(c) for d, c in enumerate(r["accept_hist"]) if c},
+                   "executed_depth_steps": r["exec_steps"], "executed_batch_steps": r["batch_steps"],
+                   "us_per_depth_step": 1e6 * wall / max(1, r["batch_steps"]),
+                   "mean_depth": r["exec_steps"] / max(1, n_round_seq)},
+        "roofline": roof,
+    }
+    if args.tree_attention > 0:
+        out["tree_attention"] = time_tree_attention(torch, D, g, wl, args.tree_attention, side)
+        log(f"[bench] tree attention: {out['tree_attention']}")
+    if args.verify_sample > 0:
+        out["verify_sample"] = time_verify_sample(torch, D, g, wl, args.verify_sample, side)
+        log(f"[bench] sampled acceptance: {out['verify_sample']}")
+    if cpu_budget > 0:
+        log(f"[bench] timing the CPU oracle for about {cpu_budget:.0f} s ...")
+        out["cpu_baseline"] = cpu_baseline(wl, g.W_bits, g.plant_dir_np if wl.n_plant else None, thr, cpu_budget)
+        log(f"[bench] oracle: {out['cpu_baseline']}")
+    g.close()
+    del g
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,8 +368,9 @@ def main():
     ap.add_argument("--max-depth", type=int, default=None, help="maximum number of draft calls override")
     ap.add_argument("--m", type=int, default=None, help="final tree size override")
     ap.add_argument("--mode", choices=["default", "paper", "strict", "eagle2"], default="default",
-                    help="paper: the paper's setting n=11, S={5,7,9}, x=-0.3 (t=exp(x)); strict: the same with the "
-                         "test after every call; eagle2: fixed depth 6, no stop test (Section 3.1, Table 1 baselines)")
+                    help="paper: the paper's setting n=11, S={5,7,9}, x=-0.3 (t=exp(x)) of Section 3.2; strict: the same "
+                         "with the test after every call (Table 1's DDD + Strict row, Section 3.3); eagle2: fixed depth "
+                         "6, no stop test (Section 3.2)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--profile-iters", type=int, default=200)
     ap.add_argument("--launch", choices=["paced", "graph", "eager"], default="paced",
@@ -163,11 +399,14 @@ def main():
     ap.add_argument("--traffic", default=None,
                     help="JSON file with the HBM bytes per launch from rocprofv3 --pmc runs "
                          "(default: profiles/traffic_<workload>.json)")
+    ap.add_argument("--secondary", choices=["auto", "on", "off"], default="auto",
+                    help="also measure the other workloads of the metric (7b_b64, 13b_b1, large_vocab; 200 rounds each) "
+                         "into a `secondary` list; auto: in the plain default run only (no workload, mode, shape or body option)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
 
-    import numpy as np
+    import numpy as np  # noqa: F401
     import torch
     import paper_2409_00142_amd as D
     import synth
@@ -177,12 +416,8 @@ def main():
         sys.exit("bench.py needs a gfx950 GPU (the HIP path has no CPU fallback)")
     D.load_library()
     wl = synth.WORKLOADS[args.workload]
-    if args.mode == "paper":      # Section 3.1: n = 11 draft calls at most, checks after calls 5, 7, 9, x = -0.3
-        wl = wl.with_(D=11, check_mask=(1 << 5) | (1 << 7) | (1 << 9), threshold=float(np.float32(np.exp(-0.3))))
-    elif args.mode == "strict":   # Section 3.3 ablation: the same, checked after every call
-        wl = wl.with_(D=11, check_mask=0xFFFFFFFF, threshold=float(np.float32(np.exp(-0.3))))
-    elif args.mode == "eagle2":   # EAGLE-2's fixed depth: 6 calls, never stops early
-        wl = wl.with_(D=6, threshold=0.0)
+    if args.mode != "default":    # Section 3.2's parameters / Table 1's strict variant / EAGLE-2's fixed depth
+        wl = synth.paper_mode(wl, args.mode)
     over = {n: v for n, v in (("k", args.k), ("D", args.max_depth), ("m", args.m)) if v is not None}
     if over:
         wl = wl.with_(**over)
@@ -191,189 +426,37 @@ def main():
         # gives the logits the same spread (std about 4.5), so that rounds again stop at mixed depths
         wl = wl.with_(sigma_w=args.lm_sigma if args.lm_sigma is not None else 0.07)
     thr = wl.threshold if args.threshold is None else args.threshold
-    log(f"[bench] workload {wl.name}: B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} m={wl.m} t={thr} gain={wl.gain}")
-    t0 = time.perf_counter()
-    g = SD.GpuWorkload(wl, threshold=thr, debug=False,
-                       flags=D.DDD_FLAG_FORWARD_SWEEPS if args.sweep == "forward" else 0)
-    log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s; "
-        f"stream slices={D.ddd_num_slices(g.ctx)}")
+    plain = (args.workload == "7b_b1" and args.mode == "default" and not over and args.body == "hash"
+             and args.threshold is None and args.launch == "paced" and args.sweep == "alternate")
+    secondary = args.secondary == "on" or (args.secondary == "auto" and plain)
 
-    if args.body == "layer":
-        if wl.B * wl.k > 16:
-            sys.exit("--body layer handles at most 16 rows per call (B*k <= 16)")
-        F = args.ffn if args.ffn is not None else (13824 if wl.H == 5120 else 11008)
-        t1 = time.perf_counter()
-        g.use_layer_body(F, args.prompt_len)
-        log(f"[bench] draft layer: F={F}, prompt length {args.prompt_len}, {g.body_bytes / 1e6:.1f} MB of layer weights "
-            f"streamed per call ({time.perf_counter() - t1:.1f} s to generate and upload)")
-    uses_gemm = wl.B * wl.k > 16 or wl.k > 16
-    pack = args.pack_weights == "on" or (args.pack_weights == "auto" and uses_gemm and wl.V * wl.H * 2 > 256 * 2**20)
-    if pack:
-        D.ddd_weights_pack(g.ctx, g.W)
-        torch.cuda.synchronize()
-        log("[bench] GEMM path reads W from its tile-major copy (ddd_weights_pack)")
-    side = torch.cuda.Stream()
-    if args.launch == "graph":
-        g.capture(side)
-        launch = lambda: g.launch(side.cuda_stream)
-    elif args.launch == "paced":
-        launch = lambda: g.run_round(side.cuda_stream)
-    else:
-        launch = lambda: g.enqueue_round(side.cuda_stream)
-    torch.cuda.synchronize()
-    g.set_round(0)
-    torch.cuda.synchronize()
-    with torch.cuda.stream(side):
-        for _ in range(args.warmup):
-            launch()
-        side.synchronize()
-        g.depth_hist.zero_()
-        g.accept_hist.zero_()
-        g.batch_depth_hist.zero_()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        w0 = time.perf_counter()
-        e0.record(side)
-        for _ in range(args.steps):
-            launch()
-        e1.record(side)
-        side.synchronize()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - w0
-    ev_ms = e0.elapsed_time(e1)
-    depth_hist = g.depth_hist.cpu().numpy()
-    accept_hist = g.accept_hist.cpu().numpy()
-    exec_steps = int(sum(d * int(c) for d, c in enumerate(depth_hist)))
-    n_round_seq = int(depth_hist.sum())
-    assert n_round_seq == args.steps * wl.B, (n_round_seq, args.steps, wl.B)
-    rounds_per_s = args.steps * wl.B / wall
-    ms_per_round = 1e3 * wall / args.steps
-    # an executed depth step of the batch = one LM-head pass; count passes, not sequences
-    # (for B=1 the two are the same)
-    log(f"[bench] {args.steps} rounds in {wall * 1e3:.2f} ms wall ({ev_ms:.2f} ms by events): "
-        f"{rounds_per_s:.1f} rounds/s, {ms_per_round * 1e3:.1f} us/round")
-    log(f"[bench] depth histogram (steps -> sequences): "
-        f"{ {d: int(c) for d, c in enumerate(depth_hist) if c} }")
-    log(f"[bench] accept-length histogram: { {d: int(c) for d, c in enumerate(accept_hist) if c} }")
-
-    # ---- dominant kernel: the LM head, alone, per-launch HIP events --------------------------------
-    # <= 16 rows: the weight stream (HBM-bound); more rows: the MFMA GEMM (all B*k rows active)
-    n_rows = wl.B * wl.k
-    mean_ms, min_ms = D.ddd_profile_lmhead(g.ctx, g.W, g.hid, n_rows, args.profile_iters, stream=side.cuda_stream)
-    w_bytes = wl.V * wl.H * 2
-    if n_rows <= 16:
-        kernel_name = "lmhead_stream_kernel"
-        alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * D.ddd_num_slices(g.ctx) * (wl.k * 8 + 4)
-    else:
-        kernel_name = "lmhead_gemm_kernel"
-        alg_bytes = w_bytes + n_rows * wl.H * 2 + n_rows * (wl.k * 8 + 4)   # W, hidden rows, k keys + lse per row
-    alg_flops = 2.0 * wl.V * wl.H * n_rows
-    achieved = alg_bytes / (mean_ms * 1e-3) / 1e9
-    achieved_tflops = alg_flops / (mean_ms * 1e-3) / 1e12
-    log(f"[bench] {kernel_name} ({n_rows} rows): mean {mean_ms * 1e3:.2f} us, min {min_ms * 1e3:.2f} us per launch; "
-        f"{alg_bytes / 1e6:.2f} MB algorithmic -> {achieved:.0f} GB/s ({100 * achieved / HBM_PEAK_GBS:.1f}% of 8 TB/s); "
-        f"{alg_flops / 1e9:.1f} GFLOP -> {achieved_tflops:.0f} TFLOP/s ({100 * achieved_tflops / MFMA_PEAK_TFLOPS:.1f}% of "
-        f"{MFMA_PEAK_TFLOPS:.0f} TFLOP/s bf16)")
-    # which roofline binds: time at peak for the bytes vs for the flops
-    mfma_bound = alg_flops / (MFMA_PEAK_TFLOPS * 1e12) > alg_bytes / (HBM_PEAK_GBS * 1e9)
-
-    # ---- plain read stream over the same bytes: the practical ceiling --------------------------
-    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-    with torch.cuda.stream(side):
-        best = None
-        for blocks in (2048, 4096, 8192):
-            for _ in range(3):
-                D.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
-            r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            r0.record(side)
-            for _ in range(20):
-                D.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
-            r1.record(side)
-            side.synchronize()
-            gbs = 20 * w_bytes / (r0.elapsed_time(r1) * 1e-3) / 1e9
-            best = gbs if best is None else max(best, gbs)
-    log(f"[bench] plain read-stream kernel over W: {best:.0f} GB/s ({100 * best / HBM_PEAK_GBS:.1f}% of 8 TB/s)")
-    # ---- register-resident MFMA loop on random operands: the practical matrix-core ceiling -------
-    mfma_ceiling = None
-    if mfma_bound:
-        fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
-        with torch.cuda.stream(side):
-            iters, blocks = 4000, 512          # 2 waves per SIMD; 512*4*4000*8 MFMAs of 32768 flop
-            D.ddd_synth_mfma_rate(fsink, 200, blocks, stream=side.cuda_stream)
-            m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            m0.record(side)
-            D.ddd_synth_mfma_rate(fsink, iters, blocks, stream=side.cuda_stream)
-            m1.record(side)
-            side.synchronize()
-        mfma_ceiling = blocks * 4 * iters * 8 * 32768.0 / (m0.elapsed_time(m1) * 1e-3) / 1e12
-        log(f"[bench] register-resident MFMA loop on random bf16 operands: {mfma_ceiling:.0f} TFLOP/s "
-            f"({100 * mfma_ceiling / MFMA_PEAK_TFLOPS:.1f}% of {MFMA_PEAK_TFLOPS:.0f})")
-
-    # a plain device-to-device copy of W (known size: reads and writes V*H*2 bytes): the reference the
-    # rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by
-    with torch.cuda.stream(side):
-        wcopy = torch.empty_like(g.W)
-        for _ in range(3):
-            wcopy.copy_(g.W)
-        side.synchronize()
-        del wcopy
-
-    # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload (null if none)
-    traffic = None
-    tpath = args.traffic or os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get("bytes")
-
-    # a depth step of the batch = one LM-head pass: a round executes as many as its deepest sequence
-    batch_steps = int(sum(d * int(c) for d, c in enumerate(g.batch_depth_hist.cpu().numpy())))
-    us_per_depth_step = 1e6 * wall / max(1, batch_steps)
+    W_cache = {}
+    res = run_workload(torch, D, synth, SD, wl, thr, args, args.steps, args.warmup, args.launch,
+                       also_graph=True, cpu_budget=args.cpu_budget, W_cache=W_cache)
     out = {
         "metric": "DDD draft rounds/sec (7B-shaped synthetic draft round, whole hot path per round)",
-        "value": rounds_per_s,
-        "unit": "rounds/s",
+        "value": res["value"],
+        "unit": res["unit"],
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_round,
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "V": wl.V, "k": wl.k, "max_depth": wl.D, "m": wl.m,
-                   "threshold": thr, "check_mask": int(wl.check_mask), "mode": args.mode, "hidden_gain": wl.gain,
-                   "launch": {"graph": "one hipGraph per round", "eager": "stream launches",
-                              "paced": "stream launches paced by the host (ddd_round_run)"}[args.launch],
-                   "packed_weights": bool(pack), "sweep": args.sweep, "body": args.body,
-                   "body_weight_bytes_per_call": int(getattr(g, "body_bytes", 0)),
-                   "depth_hist": {str(d): int(c) for d, c in enumerate(depth_hist) if c},
-                   "accept_len_hist": {str(d): int(c) for d, c in enumerate(accept_hist) if c},
-                   "executed_depth_steps": exec_steps, "executed_batch_steps": batch_steps,
-                   "us_per_depth_step": us_per_depth_step,
-                   "mean_depth": exec_steps / max(1, n_round_seq)},
-        "roofline": ({"bound": "mfma", "achieved": achieved_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                      "frac": achieved_tflops / MFMA_PEAK_TFLOPS, "hbm_GBs": achieved,
-                      "hbm_frac": achieved / HBM_PEAK_GBS} if mfma_bound else
-                     {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                      "frac": achieved / HBM_PEAK_GBS}),
     }
-    out["roofline"].update({"traffic": traffic, "kernel": kernel_name, "rows": n_rows,
-                            "us_per_launch": mean_ms * 1e3, "us_per_launch_min": min_ms * 1e3,
-                            "algorithmic_bytes_per_launch": alg_bytes, "algorithmic_flops_per_launch": alg_flops,
-                            "launches_timed": args.profile_iters, "read_stream_ceiling_GBs": best,
-                            "mfma_loop_ceiling_TFLOPs": mfma_ceiling})
-    if args.tree_attention > 0:
-        out["tree_attention"] = time_tree_attention(torch, D, g, wl, args.tree_attention, side)
-        log(f"[bench] tree attention: {out['tree_attention']}")
-    if args.verify_sample > 0:
-        out["verify_sample"] = time_verify_sample(torch, D, g, wl, args.verify_sample, side)
-        log(f"[bench] sampled acceptance: {out['verify_sample']}")
-    if args.cpu_budget > 0:
-        log(f"[bench] timing the CPU oracle for about {args.cpu_budget:.0f} s ...")
-        out["cpu_baseline"] = cpu_baseline(wl, g.W_bits, g.plant_dir_np if wl.n_plant else None, thr, args.cpu_budget)
-        log(f"[bench] oracle: {out['cpu_baseline']}")
-    g.close()
+    out.update({k: v for k, v in res.items() if k not in out})
+    if secondary:
+        out["secondary"] = []
+        for name in ("7b_b64", "13b_b1", "large_vocab"):
+            if name == args.workload:
+                continue
+            w2 = synth.WORKLOADS[name]
+            sec = run_workload(torch, D, synth, SD, w2, w2.threshold, args, 200, 10, "paced", also_graph=True,
+                               cpu_budget=min(args.cpu_budget, 5.0), W_cache=W_cache)
+            out["secondary"].append(sec)
     print(json.dumps(out), flush=True)
 
 

@@ -148,7 +148,8 @@ int ddd_beam_select(ddd_ctx* ctx, int32_t step, const int32_t* topk_token, const
 int ddd_depth_continue(ddd_ctx* ctx, int32_t steps_done, ddd_state* st, void* stream);
 
 /* One whole draft call for every active sequence: ddd_lmhead_topk + ddd_beam_select +
- * ddd_depth_continue with the per-row results kept on chip (two kernel launches).
+ * ddd_depth_continue with the per-row results kept on chip (two kernel launches for up to DDD_STREAM_ROWS rows:
+ * weight stream, bookkeeping; with more rows: list of active rows, MFMA GEMM, row reduction, bookkeeping).
  * hid_bf16: [B,H] for step 0, [B*k,H] for step >= 1.
  * tree: NULL, or the output of ddd_tree_finalize: a sequence whose stop test fails in this call
  * (or that has made max_depth calls) gets its final tree written by the same launch.
@@ -246,16 +247,26 @@ int ddd_round_launch(ddd_ctx* ctx, void* stream);
  * ddd_round_enqueue, but draft call s (s >= 2) is put into the stream only after call s-2 has reported, through a
  * word in pinned host memory written by its bookkeeping launch, that some sequence is still active.  The stop test
  * (Eq. 1) stays on the device and call s-1 is already queued when the report of call s-2 arrives, so the device
- * never waits for the host (Section 6 of the paper: a check must not cost a synchronisation); what is saved are
- * the launches a graph of max_depth calls spends on calls that every sequence skips: at most one such call is
- * queued per round.  Results are those of ddd_round_enqueue.  The host thread polls (at most 20 ms per call, then
- * it queues the remaining calls unconditionally), so this call returns when the last draft call has been queued,
- * not when the round has finished.  One round per context at a time; not for use under stream capture (nothing
- * would run while the host waits).  Arguments as for ddd_round_enqueue,
- * without the debug buffers.  Returns the number of draft calls queued (>= 1), or a negative status. */
+ * never waits for the host (Section 2 and the Limitations section of the paper: on its runtime every check forces
+ * evaluation, which is why it checks only at the steps in S); what is saved are the launches a graph of max_depth
+ * calls spends on calls that every sequence skips: at most one such call is queued per round.  Results are those
+ * of ddd_round_enqueue.
+ * The host thread polls, occupying a core until the last draft call has been queued (the call returns then, not
+ * when the round has finished).  A wait is bounded: 20 ms for the report of a call, 1 s for the first report of a
+ * round (the stream may still hold earlier work, e.g. the target model's forward of the previous round, which has
+ * to finish before call 0 runs; with more than a second of backlog drain the stream first).  When a limit passes
+ * the remaining calls are queued unconditionally - the results are the same, the pacing is lost for that round -
+ * and the expiry is counted, see ddd_round_run_stats.  One round per context at a time; not for use under stream
+ * capture (nothing would run while the host waits).  Arguments as for ddd_round_enqueue, without the debug
+ * buffers.  Returns the number of draft calls queued (>= 1), or a negative status. */
 int ddd_round_run(ddd_ctx* ctx, const void* W_bf16, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
                   void* hid_buf, ddd_draft_body_fn body, void* body_user, ddd_post_fn post, void* post_user,
                   void* stream);
+
+/* Counters of ddd_round_run's host waits since the context was created (any pointer may be NULL): rounds run,
+ * waits for a call's report, waits that ran into their limit (the round then lost its pacing, see above), and the
+ * longest wait in microseconds. */
+int ddd_round_run_stats(const ddd_ctx* ctx, uint64_t* rounds, uint64_t* waits, uint64_t* timeouts, double* max_wait_us);
 
 /* Optional tile-major copy of the LM-head weights for the calls that take the MFMA path (more
  * than DDD_STREAM_ROWS rows, or wide beams).  Section 1's projection reads W once per draft call;

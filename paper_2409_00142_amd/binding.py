@@ -116,6 +116,8 @@ def load_library() -> C.CDLL:
         "ddd_round_enqueue": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_capture": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_launch": (C.c_int, [vp, vp]),
+        "ddd_round_run_stats": (C.c_int, [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
+                                          C.POINTER(C.c_double)]),
         "ddd_round_run": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_synth_draft_body": (C.c_int, [vp, i32, stp, vp, vp]),
         "ddd_synth_target_argmax": (C.c_int, [C.POINTER(ddd_synth_params), stp, trp, vp, vp]),
@@ -316,6 +318,13 @@ def ddd_round_run(ctx, W, st, tree, root_token, hid_buf, body, body_user, post=N
     if rc < 0:
         _check(rc, "ddd_round_run")
     return rc
+
+
+def ddd_round_run_stats(ctx) -> Dict[str, float]:
+    """Counters of ddd_round_run's host waits: rounds, waits, timeouts (waits that ran into their limit), max_wait_us."""
+    r, w, t, m = C.c_uint64(), C.c_uint64(), C.c_uint64(), C.c_double()
+    _check(load_library().ddd_round_run_stats(ctx, C.byref(r), C.byref(w), C.byref(t), C.byref(m)), "ddd_round_run_stats")
+    return {"rounds": r.value, "waits": w.value, "timeouts": t.value, "max_wait_us": m.value}
 
 
 def ddd_round_launch(ctx, stream=None):

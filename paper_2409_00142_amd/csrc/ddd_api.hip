@@ -38,6 +38,9 @@ struct ddd_ctx {
   volatile uint32_t* progress;   // pinned host [DDD_DMAX + 1]: (round tag << 2) | 2 | any_active
   uint32_t* progress_dev;        // the same words as the kernels address them
   uint32_t round_tag;
+  // ddd_round_run's host waits, since the context was created (ddd_round_run_stats)
+  uint64_t run_rounds, run_waits, run_timeouts;
+  double run_max_wait_us;
 };
 
 namespace {
@@ -284,6 +287,8 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->progress = nullptr;
   c->progress_dev = nullptr;
   c->round_tag = 0;
+  c->run_rounds = c->run_waits = c->run_timeouts = 0;
+  c->run_max_wait_us = 0.0;
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->call_count), (DDD_DMAX + 1) * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMemset(c->call_count, 0, (DDD_DMAX + 1) * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->active_mask), (DDD_BMAX / 64) * sizeof(uint64_t));
@@ -648,6 +653,8 @@ namespace {
 // tree building would be on the critical path of every call).  A stopped sequence's pool no longer changes,
 // so both give the same trees.
 bool trees_after_the_calls(const ddd_ctx* c) { return c->cfg.B >= 8; }
+// Limits of ddd_round_run's host waits for a draft call's report.
+constexpr int kWaitMs = 20, kFirstWaitMs = 1000;
 }  // namespace
 
 int ddd_round_enqueue(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, const int32_t* root_token,
@@ -687,22 +694,32 @@ int ddd_round_run(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, cons
   const bool late_trees = trees_after_the_calls(c);
   int enqueued = 0;
   bool wait = publish;
+  ++c->run_rounds;
   for (int step = 0; step < c->cfg.max_depth; ++step) {
     if (wait && step >= 2) {
       // Call step-1 is already in the queue; call `step` goes in once call step-2 has reported that
-      // some sequence goes on.  The wait is bounded: after 20 ms the rest is enqueued unconditionally
-      // (the device-side flags skip what is not needed), so a stalled device cannot hang the host.
+      // some sequence goes on.  The wait is bounded, so a stalled device cannot hang the host: when the
+      // limit passes the rest is enqueued unconditionally (the device-side flags skip what is not needed)
+      // and the expiry is counted (ddd_round_run_stats).  The first wait of a round also covers whatever
+      // the stream still held when the round was queued, so its limit is the long one.
       const uint32_t want = c->round_tag << 2;
+      const auto limit = std::chrono::milliseconds(step == 2 ? kFirstWaitMs : kWaitMs);
       const auto t0 = std::chrono::steady_clock::now();
       uint32_t v = c->progress[step - 2];
       for (unsigned spin = 0; (v & ~3u) != want; ++spin) {
-        if ((spin & 1023u) == 1023u &&
-            std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(20)) {
-          wait = false;
+        if ((spin & 1023u) == 1023u && std::chrono::steady_clock::now() - t0 > limit) {
+          // the thread may have been off the CPU for most of that time: look once more before giving up
+          v = c->progress[step - 2];
+          if ((v & ~3u) != want) wait = false;
           break;
         }
         v = c->progress[step - 2];
       }
+      const double waited_us =
+          std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+      ++c->run_waits;
+      if (waited_us > c->run_max_wait_us) c->run_max_wait_us = waited_us;
+      if (!wait) ++c->run_timeouts;
       if (wait && (v & 1u) == 0u) break;           // every sequence has stopped
     }
     rc = body(body_user, step, st, hid_buf, stream);
@@ -720,6 +737,15 @@ int ddd_round_run(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, cons
     if (rc != DDD_OK) return rc;
   }
   return enqueued;
+}
+
+int ddd_round_run_stats(const ddd_ctx* c, uint64_t* rounds, uint64_t* waits, uint64_t* timeouts, double* max_wait_us) {
+  if (c == nullptr) return DDD_ERR_INVALID_ARG;
+  if (rounds) *rounds = c->run_rounds;
+  if (waits) *waits = c->run_waits;
+  if (timeouts) *timeouts = c->run_timeouts;
+  if (max_wait_us) *max_wait_us = c->run_max_wait_us;
+  return DDD_OK;
 }
 
 int ddd_round_capture(ddd_ctx* c, const void* W, ddd_state* st, ddd_tree* tree, const int32_t* root_token,

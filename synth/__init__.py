@@ -9,6 +9,8 @@ identical bits.
 from .inputs import (  # noqa: F401
     Workload,
     WORKLOADS,
+    PAPER_MODES,
+    paper_mode,
     f32_to_bf16_bits,
     bf16_bits_to_f32,
     make_lm_head,

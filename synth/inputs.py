@@ -156,6 +156,27 @@ WORKLOADS = {
 }
 
 
+# The paper's own parameter settings as variants of a workload (configuration only).  The values are also
+# kept, with their citations, in tests/golden/paper_parameters.json.
+PAPER_MODES = ("paper", "strict", "eagle2")
+PAPER_X = -0.3               # Section 3.2: threshold in the log domain
+
+
+def paper_mode(wl: Workload, mode: str) -> Workload:
+    """`paper`: Section 3.2's DDD setting, n = 11 draft calls at most, checks after calls 5, 7 and 9,
+    x = -0.3, i.e. t = fl32(exp(x)) in the probability domain; `strict`: the same with the check after every
+    call (the "DDD + Strict" row of Table 1, S = {1..10}); `eagle2`: EAGLE-2's fixed depth of 6 calls and no
+    check (Section 3.2).  The beam width of all three is the paper's w = 10, which the 7B / 13B workloads have."""
+    t = float(np.float32(math.exp(PAPER_X)))
+    if mode == "paper":
+        return wl.with_(D=11, check_mask=(1 << 5) | (1 << 7) | (1 << 9), threshold=t)
+    if mode == "strict":
+        return wl.with_(D=11, check_mask=0x7FE, threshold=t)
+    if mode == "eagle2":
+        return wl.with_(D=6, check_mask=0, threshold=0.0)
+    raise ValueError(f"unknown mode {mode!r}")
+
+
 # --------------------------------------------------------------------------
 # LM head
 # --------------------------------------------------------------------------

@@ -92,6 +92,7 @@ def test_error_strings_and_null_arguments(D):
     assert lib.ddd_round_launch(None, None) == D.DDD_ERR_INVALID_ARG
     assert lib.ddd_lmhead_topk(None, None, None, 1, None, None, None, None, None, None) == D.DDD_ERR_INVALID_ARG
     assert lib.ddd_synth_next_round(None, None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_round_run_stats(None, None, None, None, None) == D.DDD_ERR_INVALID_ARG
 
 
 def test_create_without_a_device_fails_with_a_status():

@@ -146,7 +146,9 @@ def test_body_steps_with_scripted_beams(gpu):
         D.ddd_body_destroy(body)
 
 
-@pytest.mark.parametrize("shape", [("tiny", 1, 4, 256, 384, 500, 9, 5), ("k10_h1024", 1, 10, 1024, 2816, 3000, 33, 6)],
+@pytest.mark.parametrize("shape", [("tiny", 1, 4, 256, 384, 500, 9, 5), ("k10_h1024", 1, 10, 1024, 2816, 3000, 33, 6),
+                                   # the shape the benchmark's --body layer times: 7B sizes, 32 heads, 256 prompt positions
+                                   ("7b_full_shape", 1, 10, 4096, 11008, 32000, 256, 3)],
                          ids=lambda s: s[0])
 def test_round_with_body_matches_oracle(gpu, shape):
     """Whole rounds with the layer as the draft body: eager calls (rows inspected after every body call), then the

@@ -383,21 +383,61 @@ def test_synth_draft_body_matches_numpy_generator(gpu):
 # ------------------------------------------------------------------------------------------------
 # L2: whole rounds, the oracle replaying the GPU's logits and lse
 # ------------------------------------------------------------------------------------------------
+STOP_MARGIN = 1e-9      # a stop test closer than this to the threshold is not comparable (fp64 exp may differ by an ulp)
+AMBIGUOUS = {"tests": 0, "forced": 0}      # ambiguous stop tests seen / of those, decisions taken over from the GPU
+
+
+def _replay(g, wl, b, rnd, thr, check_mask, logits_dbg, lse_dbg):
+    k = wl.k
+
+    def logits_fn(s, hid):
+        rows = slice(b, b + 1) if s == 0 else slice(b * k, (b + 1) * k)
+        return logits_dbg[s, rows], lse_dbg[s, rows].astype(np.float64)
+
+    return SR.oracle_round(wl.with_(check_mask=check_mask), g.W_bits, g.plant_dir_np, b, rnd, threshold=thr,
+                           logits_fn=logits_fn)
+
+
 def _compare_round(g, snap, wl, rnd, thr, logits_dbg, lse_dbg, check_own_logits_steps=0, seqs=None, own_seqs=None):
     """Replay sequence by sequence (all, or those in `seqs`); returns the list of oracle step counts.
-    The oracle's own projection is compared for the sequences in `own_seqs` (default: all replayed)."""
+    The oracle's own projection is compared for the sequences in `own_seqs` (default: all replayed).
+
+    Every stop test of the replay is looked at: one whose P lies within STOP_MARGIN of the threshold is
+    ambiguous (counted in AMBIGUOUS).  Only if the oracle and the GPU decided such a test differently is that one
+    decision taken over from the GPU (the replay runs again with it forced: a forced "continue" clears the test's
+    bit in S, a forced "stop" makes it the only test, against a threshold above 1); every other field of the
+    sequence, and every other sequence, is compared as usual."""
     k = wl.k
+    t32 = float(np.float32(thr))
     steps_out = []
     for b in (range(wl.B) if seqs is None else seqs):
-        def logits_fn(s, hid, b=b):
-            rows = slice(b, b + 1) if s == 0 else slice(b * k, (b + 1) * k)
-            return logits_dbg[s, rows], lse_dbg[s, rows].astype(np.float64)
-
-        res, tgt, (o_len, o_path, o_bonus) = SR.oracle_round(wl, g.W_bits, g.plant_dir_np, b, rnd, threshold=thr,
-                                                            logits_fn=logits_fn)
-        steps_out.append(res.steps)
         ctx_msg = f"round {rnd} seq {b}"
-        assert int(snap["steps"][b]) == res.steps, ctx_msg
+        gpu_steps = int(snap["steps"][b])
+        mask, t_run, seen = wl.check_mask, thr, set()
+        for _ in range(wl.D + 1):
+            res, tgt, (o_len, o_path, o_bonus) = _replay(g, wl, b, rnd, t_run, mask, logits_dbg, lse_dbg)
+            fix = None
+            for s, rec in enumerate(res.records):
+                done = s + 1
+                if done >= wl.D or not (wl.check_mask >> done) & 1 or abs(rec.P - t32) > STOP_MARGIN:
+                    continue
+                if done not in seen:
+                    seen.add(done)
+                    AMBIGUOUS["tests"] += 1
+                if rec.cont != (gpu_steps > done):
+                    fix = (done, gpu_steps > done)
+                    break
+            if fix is None:
+                break
+            AMBIGUOUS["forced"] += 1
+            print(f"[info] {ctx_msg}: stop test after call {fix[0]} within {STOP_MARGIN} of the threshold, "
+                  f"the GPU's decision ({'continue' if fix[1] else 'stop'}) taken over", flush=True)
+            if fix[1]:
+                mask &= ~(1 << fix[0])
+            else:
+                mask, t_run = 1 << fix[0], 2.0
+        steps_out.append(res.steps)
+        assert gpu_steps == res.steps, ctx_msg
         assert int(snap["active"][b]) == 0, ctx_msg
         n = res.pool.n_nodes
         assert int(snap["n_nodes"][b]) == n, ctx_msg
@@ -409,7 +449,6 @@ def _compare_round(g, snap, wl, rnd, thr, logits_dbg, lse_dbg, check_own_logits_
         assert np.array_equal(snap["beam_node"][b], last.beam.node), ctx_msg
         assert np.array_equal(snap["logprobsum"][b], last.beam.logprobsum), ctx_msg
         assert abs(float(snap["conf"][b]) - last.P) <= 1e-12, ctx_msg
-        assert abs(last.P - float(np.float32(thr))) > 1e-9, "stop test too close to the threshold to compare"
         tr = res.tree
         assert int(snap["n_sel"][b]) == tr.n_sel, ctx_msg
         assert np.array_equal(snap["sel_node"][b], tr.sel_node), ctx_msg
@@ -434,6 +473,11 @@ def _compare_round(g, snap, wl, rnd, thr, logits_dbg, lse_dbg, check_own_logits_
             for i in range(own.shape[0]):
                 assert abs(O.logsumexp_row(logits_dbg[s, rows][i]) - float(lse_dbg[s, rows][i])) <= LOGPROB_TOL
     return steps_out
+
+
+def _ambiguous_since(before):
+    return f"ambiguous stop tests: {AMBIGUOUS['tests'] - before[0]}, decisions taken over from the GPU: " \
+           f"{AMBIGUOUS['forced'] - before[1]}"
 
 
 ROUND_CASES = [
@@ -599,7 +643,6 @@ def test_host_paced_round_matches_enqueued_round(gpu, wname, B):
     print(f"[case] host-paced rounds {wname} B={B}", flush=True)
     g = SD.GpuWorkload(wl, debug=False)
     try:
-        paced = 0
         for rnd in range(6):
             g.set_round(rnd)
             g.enqueue_round()
@@ -610,10 +653,11 @@ def test_host_paced_round_matches_enqueued_round(gpu, wname, B):
             got = g.snapshot()
             _same_round(got, want)
             deepest = int(want["steps"].max())
-            assert deepest <= n <= wl.D, (rnd, n, deepest)
-            paced += int(n <= deepest + 1)
-        # a host wait that runs into its time limit queues the remaining calls (same results, no pacing): rare
-        assert paced >= 4
+            stats = D.ddd_round_run_stats(g.ctx)
+            # no wait ran into its limit, so pacing held: one call at most that every sequence skips
+            assert stats["timeouts"] == 0 and deepest <= n <= min(wl.D, deepest + 1), (rnd, n, deepest, stats)
+        print(f"[info] host waits of the paced rounds: {stats}", flush=True)
+        assert stats["rounds"] == 6
     finally:
         g.close()
 
@@ -624,8 +668,11 @@ def _edge_configs():
     import random
     rnd = random.Random(11)
     out = [(1, 1, 1, 64, 1, 0.0), (2, 1, 5, 64, 3, 0.0), (3, 2, 1, 100, 60, 0.3), (1, 16, 2, 64, 128, 0.0),
-           (17, 3, 4, 257, 7, 0.2), (9, 16, 3, 1000, 16, 0.1), (2, 20, 2, 300, 128, 0.3), (1, 128, 2, 700, 128, 0.0)]
-    while len(out) < 20:
+           (17, 3, 4, 257, 7, 0.2), (9, 16, 3, 1000, 16, 0.1), (2, 20, 2, 300, 128, 0.3), (1, 128, 2, 700, 128, 0.0),
+           # the whole vocabulary is in the beam, so P = 1 up to rounding, against t = 1: stop tests that fall within
+           # 1e-9 of the threshold (the comparison takes such a decision over from the GPU and checks the rest)
+           (3, 4, 3, 4, 7, 1.0), (2, 8, 4, 8, 16, 1.0)]
+    while len(out) < 22:
         B, k = rnd.choice([1, 2, 3, 8, 17, 33]), rnd.choice([1, 2, 3, 5, 10, 16, 20, 50])
         D, V = rnd.choice([1, 2, 3, 6, 9]), rnd.choice([64, 257, 1000, 3001])
         m, t = rnd.choice([1, 7, 16, 60, 128]), rnd.choice([0.0, 0.1, 0.3, 0.6])
@@ -648,11 +695,9 @@ def test_edge_configurations_against_oracle_and_across_launch_modes(gpu, cfg):
         g.set_round(0)
         g.enqueue_round()
         snap = g.snapshot()
-        try:
-            _compare_round(g, snap, wl, 0, t, g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy())
-        except AssertionError as e:
-            if "too close to the threshold" not in str(e):
-                raise
+        before = (AMBIGUOUS["tests"], AMBIGUOUS["forced"])
+        _compare_round(g, snap, wl, 0, t, g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy())
+        print(f"[info] edge configuration: {_ambiguous_since(before)}", flush=True)
         side = torch.cuda.Stream()
         g.capture(side)
         g.set_round(0)
@@ -692,6 +737,7 @@ def test_random_configurations_against_oracle_and_host_paced(gpu):
     logits (bit-exact state) and the host-paced launch leaves the same bytes as the eager one."""
     torch, D, SD = gpu
     side = torch.cuda.Stream()
+    before = (AMBIGUOUS["tests"], AMBIGUOUS["forced"])
     for B, k, Dm, V, H, m, t in _random_configs():
         wl = synth.WORKLOADS["tiny"].with_(B=B, k=k, D=Dm, V=V, H=H, m=m, threshold=t)
         print(f"[case] random configuration B={B} k={k} D={Dm} V={V} H={H} m={m} t={t}", flush=True)
@@ -702,11 +748,7 @@ def test_random_configurations_against_oracle_and_host_paced(gpu):
                 g.enqueue_round()
                 torch.cuda.synchronize()
                 snap = g.snapshot()
-                try:
-                    _compare_round(g, snap, wl, rnd, t, g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy())
-                except AssertionError as e:
-                    if "too close to the threshold" not in str(e):
-                        raise
+                _compare_round(g, snap, wl, rnd, t, g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy())
                 g.set_round(rnd)
                 torch.cuda.synchronize()
                 g.run_round(side.cuda_stream)
@@ -714,6 +756,7 @@ def test_random_configurations_against_oracle_and_host_paced(gpu):
                 _same_round(g.snapshot(), snap)
         finally:
             g.close()
+    print(f"[info] random configurations: {_ambiguous_since(before)}", flush=True)
 
 
 LARGE_B = [(4096, 2, 3, 64, 128, 7, 0.3), (4096, 1, 2, 64, 128, 1, 0.0), (1000, 10, 4, 257, 256, 60, 0.3),
@@ -737,11 +780,9 @@ def test_large_batches_up_to_the_limit(gpu, cfg):
             g.enqueue_round()
             torch.cuda.synchronize()
             snap = g.snapshot()
-            try:
-                _compare_round(g, snap, wl, rnd, t, g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy())
-            except AssertionError as e:
-                if "too close to the threshold" not in str(e):
-                    raise
+            before = (AMBIGUOUS["tests"], AMBIGUOUS["forced"])
+            _compare_round(g, snap, wl, rnd, t, g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy())
+            print(f"[info] large batch round {rnd}: {_ambiguous_since(before)}", flush=True)
             g.set_round(rnd)
             torch.cuda.synchronize()
             g.run_round(side.cuda_stream)
@@ -785,6 +826,54 @@ def test_7b_shape_round_parity(gpu):
             side.synchronize()
             _same_round(g.snapshot(), snap)
         print(f"[info] 7b depths {depths}", flush=True)
+    finally:
+        g.close()
+
+
+MODE_CASES = [
+    # mode, hidden gain (None = the workload's 3.5, whose rounds all stop at the first check of S = {5,7,9}), rounds
+    ("paper", None, 3), ("paper", 6.0, 4), ("paper", 9.0, 3), ("strict", None, 3), ("strict", 6.0, 3), ("eagle2", None, 2),
+]
+
+
+@pytest.mark.parametrize("mode,gain,n_rounds", MODE_CASES, ids=[f"{c[0]}-gain{c[1]}" for c in MODE_CASES])
+def test_paper_parameter_modes_at_7b_shape(gpu, mode, gain, n_rounds):
+    """Section 3.2's own parameters at the full 7B shape - n = 11, S = {5,7,9}, x = -0.3 (t = fl32(e^-0.3)) - the
+    strict variant of Table 1 (S = {1..10}) and EAGLE-2's fixed depth 6: exactly the configurations
+    `bench.py --mode` times.  Rounds are launched as a captured graph with debug buffers and replayed by the
+    oracle (bit-exact state); the host-paced launch leaves the same bytes.  Larger hidden gains give confident
+    beams, so that rounds also pass the checks after calls 5, 7 and 9 and reach the 11th call."""
+    torch, D, SD = gpu
+    wl = synth.paper_mode(synth.WORKLOADS["7b_b1"], mode)
+    if gain is not None:
+        wl = wl.with_(gain=gain)
+    print(f"[case] 7B shape, mode {mode}: D={wl.D} check_mask={wl.check_mask:#x} t={wl.threshold} gain={wl.gain}", flush=True)
+    assert wl.k == 10 and wl.D == (6 if mode == "eagle2" else 11)
+    g = SD.GpuWorkload(wl, debug=True)
+    try:
+        side = torch.cuda.Stream()
+        g.capture(side)
+        torch.cuda.synchronize()
+        before = (AMBIGUOUS["tests"], AMBIGUOUS["forced"])
+        depths = []
+        for rnd in range(n_rounds):
+            g.set_round(rnd)
+            torch.cuda.synchronize()
+            g.launch(side.cuda_stream)
+            side.synchronize()
+            snap = g.snapshot()
+            depths += _compare_round(g, snap, wl, rnd, wl.threshold, g.logits_dbg.cpu().numpy(),
+                                     g.lse_dbg.cpu().numpy(), check_own_logits_steps=1 if rnd == 0 else 0)
+            g.set_round(rnd)
+            torch.cuda.synchronize()
+            g.run_round(side.cuda_stream)
+            side.synchronize()
+            _same_round(g.snapshot(), snap)
+        print(f"[info] mode {mode} gain {wl.gain}: depths {depths}; {_ambiguous_since(before)}", flush=True)
+        if mode == "paper":
+            assert set(depths) <= {5, 7, 9, 11}          # a round can only end at a check in S or at n
+        if mode == "eagle2":
+            assert set(depths) == {6}
     finally:
         g.close()
 
@@ -838,43 +927,97 @@ def test_full_size_round_parity(gpu, case):
             g2.close()
 
 
-def test_free_running_rounds_agree_with_oracle(gpu):
+def _first_divergence(free, repl, wl, thr):
+    """Walks the free-running oracle round `free` (its own fp64 logits) and `repl` (the oracle replaying the
+    GPU's logits and lse, i.e. the GPU's round, verified bit for bit against the device state) in the order the
+    method takes its decisions.  Returns None if every decision agrees, else (kind, call, margin, tolerance):
+    the first decision that differs, how far the free-running oracle's own values are from deciding it the other
+    way, and the tolerance of the arithmetic feeding that decision (2e-2 per logit for row top-k; 1e-4 per
+    logprob and draft call for score-keyed choices; for the stop test the same score tolerance carried through
+    Eq. 1 plus 1e-9)."""
+    k, t32 = wl.k, float(np.float32(thr))
+    for s in range(min(len(free.records), len(repl.records))):
+        a, b = free.records[s], repl.records[s]
+        depth = s + 1
+        for r in range(a.tok.shape[0]):
+            if not np.array_equal(a.tok[r], b.tok[r]):
+                # tokens the two sides rank differently: gap of their logits in the free-running oracle's own row
+                j = int(np.nonzero(a.tok[r] != b.tok[r])[0][0])
+                x = a.logits[r].astype(np.float64)
+                return ("row top-k", s, abs(x[a.tok[r][j]] - x[b.tok[r][j]]), 2 * LOGIT_TOL)
+        if not np.array_equal(a.beam.node, b.beam.node):
+            j = int(np.nonzero(a.beam.node != b.beam.node)[0][0])
+            sc = free.pool.score
+            return ("beam", s, abs(float(sc[a.beam.node[j]]) - float(sc[b.beam.node[j]])), 2 * LOGPROB_TOL * depth)
+        if a.cont != b.cont:
+            return ("stop test", s, abs(a.P - t32), STOP_MARGIN + LOGPROB_TOL * depth * a.P)
+    if not np.array_equal(free.tree.sel_node, repl.tree.sel_node):
+        only_a = sorted(set(free.tree.sel_node.tolist()) - set(repl.tree.sel_node.tolist()))
+        only_b = sorted(set(repl.tree.sel_node.tolist()) - set(free.tree.sel_node.tolist()))
+        sc = free.pool.score
+        gap = min(abs(float(sc[x]) - float(sc[y])) for x in only_a for y in only_b)
+        return ("final tree", len(free.records) - 1, gap, 2 * LOGPROB_TOL * wl.D)
+    return None
+
+
+L3_CASES = [("7b_b1_full", synth.WORKLOADS["7b_b1"], 12),
+            # a quarter of the hidden size: twice the gain for the same spread of the logits, so that rounds go as deep
+            ("small_b2", synth.WORKLOADS["7b_b1"].with_(B=2, H=1024, V=8000, D=8, m=40, gain=7.0), 16)]
+
+
+@pytest.mark.parametrize("name,wl,n_rounds", L3_CASES, ids=[c[0] for c in L3_CASES])
+def test_free_running_rounds_agree_with_oracle(gpu, name, wl, n_rounds):
     """Free-running comparison: the GPU round uses its own fp32-accumulated logits and fast lse, the oracle its
-    own fp64 ones, with no values passed between them.  Outputs can legitimately differ only where a decision
-    falls inside the arithmetic tolerance (two candidates closer than the logit / logprob error); such rounds
-    are counted, not failed, and must be rare.  Every other round must agree in depth, tree and accept walk."""
+    own fp64 ones, with no values passed between them.  A round may differ only where a decision falls inside
+    the arithmetic tolerance that feeds it: for every differing round the first differing decision is located and
+    the free-running oracle's margin there must lie inside that tolerance (such rounds are counted and reported
+    as ambiguous); any other difference fails.  Rounds that agree must also agree in scores, tree and walk."""
     torch, D, SD = gpu
-    wl = synth.WORKLOADS["7b_b1"].with_(B=2, H=1024, V=8000, D=8, m=40)
-    print(f"[case] free-running B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D}", flush=True)
-    g = SD.GpuWorkload(wl, debug=False)
-    n_rounds, exact, differ = 24, 0, []
+    print(f"[case] free-running {name} B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D}", flush=True)
+    g = SD.GpuWorkload(wl, debug=True)
+    exact, ambiguous, depth_g, depth_o = 0, [], [], []
     try:
         for rnd in range(n_rounds):
             g.set_round(rnd)
             g.enqueue_round()
             snap = g.snapshot()
+            logits_dbg, lse_dbg = g.logits_dbg.cpu().numpy(), g.lse_dbg.cpu().numpy()
+            _compare_round(g, snap, wl, rnd, wl.threshold, logits_dbg, lse_dbg)      # the replay below is the GPU's round
             for b in range(wl.B):
-                res, tgt, (o_len, o_path, o_bonus) = SR.oracle_round(wl, g.W_bits, g.plant_dir_np, b, rnd,
-                                                                    threshold=wl.threshold)
-                same = (int(snap["steps"][b]) == res.steps
-                        and int(snap["n_sel"][b]) == res.tree.n_sel
-                        and np.array_equal(snap["sel_node"][b], res.tree.sel_node)
-                        and np.array_equal(snap["tree_token"][b], res.tree.tree_token)
-                        and np.array_equal(snap["mask"][b], res.tree.mask)
-                        and int(snap["accept_len"][b]) == o_len and int(snap["bonus"][b]) == o_bonus)
-                if same:
+                repl = _replay(g, wl, b, rnd, wl.threshold, wl.check_mask, logits_dbg, lse_dbg)[0]
+                free, tgt, (o_len, o_path, o_bonus) = SR.oracle_round(wl, g.W_bits, g.plant_dir_np, b, rnd,
+                                                                      threshold=wl.threshold, keep_logits=True)
+                depth_g.append(int(snap["steps"][b]))
+                depth_o.append(free.steps)
+                # logits and lse of the executed calls agree within the north star's tolerances
+                for s in range(min(free.steps, repl.steps)):
+                    rows = slice(b, b + 1) if s == 0 else slice(b * wl.k, (b + 1) * wl.k)
+                    if np.array_equal(free.records[s].hid_bits, repl.records[s].hid_bits):
+                        assert np.max(np.abs(free.records[s].logits.astype(np.float64) - logits_dbg[s, rows])) <= LOGIT_TOL
+                div = _first_divergence(free, repl, wl, wl.threshold)
+                if div is None:
                     exact += 1
-                    n = res.pool.n_nodes                 # then the scores agree to the logprob tolerance as well
-                    err = np.max(np.abs(snap["pool_score"][b, 1:n].astype(np.float64) - res.pool.score[1:n]))
+                    assert int(snap["steps"][b]) == free.steps and int(snap["n_sel"][b]) == free.tree.n_sel
+                    for nme, want in (("sel_node", free.tree.sel_node), ("tree_token", free.tree.tree_token),
+                                      ("mask", free.tree.mask), ("parent_idx", free.tree.parent_idx)):
+                        assert np.array_equal(snap[nme][b], want), (rnd, b, nme)
+                    assert int(snap["accept_len"][b]) == o_len and int(snap["bonus"][b]) == o_bonus
+                    n = free.pool.n_nodes                # the scores agree to the logprob tolerance as well
+                    err = np.max(np.abs(snap["pool_score"][b, 1:n].astype(np.float64) - free.pool.score[1:n]))
                     assert err <= LOGPROB_TOL * wl.D, (rnd, b, err)
                 else:
-                    differ.append((rnd, b, int(snap["steps"][b]), res.steps))
+                    kind, call, margin, tol = div
+                    print(f"[info] round {rnd} seq {b}: first differing decision: {kind} in call {call}, oracle margin "
+                          f"{margin:.3e}, tolerance {tol:.3e}", flush=True)
+                    assert margin <= tol, (rnd, b, div)
+                    ambiguous.append((rnd, b, kind, call, margin))
     finally:
         g.close()
     total = n_rounds * wl.B
-    print(f"[info] free-running: {exact}/{total} rounds identical; differing (round, seq, gpu steps, oracle steps): "
-          f"{differ}", flush=True)
-    assert exact >= total - 2, differ
+    print(f"[info] free-running {name}: {exact}/{total} rounds identical, {len(ambiguous)} ambiguous {ambiguous}; "
+          f"depth histogram GPU {np.bincount(depth_g, minlength=wl.D + 1).tolist()} oracle "
+          f"{np.bincount(depth_o, minlength=wl.D + 1).tolist()}", flush=True)
+    assert exact >= total - max(2, total // 8), ambiguous
 
 
 def test_context_lifecycle_and_recapture(gpu):

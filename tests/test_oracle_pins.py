@@ -146,6 +146,28 @@ def test_log_domain_form_agrees_with_probability_domain():
     assert n_checked > 400
 
 
+def test_workload_modes_carry_the_papers_parameters():
+    """The configurations the benchmark's --mode and the GPU mode tests run are Section 3.2's numbers."""
+    with open(os.path.join(GOLD, "paper_parameters.json")) as f:
+        pp = json.load(f)
+    base = synth.WORKLOADS["7b_b1"]
+    assert base.k == pp["w"]
+    paper, strict, eagle2 = (synth.paper_mode(base, m) for m in synth.PAPER_MODES)
+    assert paper.D == strict.D == pp["n"] and eagle2.D == pp["eagle2_depth"]
+    assert [s for s in range(32) if (paper.check_mask >> s) & 1] == pp["S"]
+    assert [s for s in range(32) if (strict.check_mask >> s) & 1] == pp["strict_S"]
+    assert paper.threshold == strict.threshold == float(np.float32(pp["t_equiv"]))
+    assert eagle2.threshold == 0.0
+    # and the oracle's stop test under them: stops only at a step of S, and never when no step is checked
+    lps = np.full(pp["w"], -6.0, np.float32)                   # P = 10 e^-6, far below t
+    for done in range(1, pp["n"]):
+        assert O.depth_continue(lps, done, paper.D, paper.threshold, paper.check_mask)[0] == (done not in pp["S"])
+        assert O.depth_continue(lps, done, strict.D, strict.threshold, strict.check_mask)[0] is False
+    for done in range(1, eagle2.D):
+        assert O.depth_continue(lps, done, eagle2.D, eagle2.threshold, eagle2.check_mask)[0] is True
+    assert O.depth_continue(lps, eagle2.D, eagle2.D, eagle2.threshold, eagle2.check_mask)[0] is False
+
+
 # ----------------------------------------------------------------------------------------------
 # the hand-worked round
 # ----------------------------------------------------------------------------------------------
