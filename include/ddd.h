@@ -44,6 +44,8 @@ extern "C" {
 #define DDD_POOL_MAX 4096    /* largest node pool per sequence for k <= DDD_KMAX                  */
 #define DDD_POOL_WIDE_MAX 65536 /* largest node pool per sequence for wider beams                 */
 #define DDD_STREAM_ROWS 16   /* rows handled by one pass of the weight stream                     */
+#define DDD_STATIC_ROWS 16   /* most rows per call of ddd_lmhead_topk_static                      */
+#define DDD_STATIC_SLICES 256 /* most weight-stream workgroups its static scratch has room for    */
 
 typedef enum ddd_status {
   DDD_OK = 0,
@@ -52,7 +54,8 @@ typedef enum ddd_status {
   DDD_ERR_WRONG_ARCH = -3,    /* the current device is not gfx950                    */
   DDD_ERR_HIP = -4,           /* a HIP runtime call failed (see ddd_last_hip_error)  */
   DDD_ERR_UNIMPLEMENTED = -5,
-  DDD_ERR_STATE = -6          /* e.g. ddd_round_launch before ddd_round_capture      */
+  DDD_ERR_STATE = -6,         /* e.g. ddd_round_launch before ddd_round_capture      */
+  DDD_ERR_STATIC_LIMIT = -7   /* ddd_lmhead_topk_static: more rows or a wider beam than its static scratch holds */
 } ddd_status;
 
 /* Parameters of Algorithm 1 (its Require clause) plus the problem shape. */
@@ -131,6 +134,23 @@ int ddd_round_reset(ddd_ctx* ctx, ddd_state* st, const int32_t* root_token, void
 int ddd_lmhead_topk(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, int32_t n_rows,
                     const uint8_t* row_active, int32_t* topk_token, float* topk_logprob, float* lse,
                     float* logits_dbg, void* stream);
+
+/* ddd_lmhead_topk for callers that cannot allocate device memory or create a context: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and the same results, bit for
+ * bit, as ddd_lmhead_topk on a context of this configuration, with the per-slice partial results in a static
+ * device array of ddd_static_scratch_bytes() bytes (540 672) that every GPU the library runs on holds until
+ * the process ends; the call allocates and frees nothing.
+ *   cfg      only H, V and k are used; the whole configuration must be valid
+ *   n_rows   1..DDD_STATIC_ROWS hidden rows, and k <= DDD_KMAX: anything larger returns DDD_ERR_STATIC_LIMIT
+ *            (those sizes take the MFMA path, whose scratch is hundreds of megabytes: use a context)
+ *   other arguments as for ddd_lmhead_topk (no debug buffer)
+ * The first call on a device looks the array's address up (make that call outside stream capture).  All calls
+ * on one GPU share the one array: calls that overlap on a GPU, on different streams or from different threads,
+ * race; calls on one stream are ordered and safe.  Nothing in the array carries over between calls. */
+int ddd_lmhead_topk_static(const ddd_config* cfg, const void* W_bf16, const void* hid_bf16, int32_t n_rows,
+                           const uint8_t* row_active, int32_t* topk_token, float* topk_logprob, float* lse,
+                           void* stream);
+size_t ddd_static_scratch_bytes(void);
 
 /* Beam update after draft call number step+1 (Algorithm 1: the first beam and its logprobsum after the
  * prompt call for step 0, the post-processing of the draft outputs inside the loop otherwise): adds logprobsum of the parents, appends all candidates to the pool, keeps the

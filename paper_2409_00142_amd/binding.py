@@ -19,6 +19,7 @@ DDD_ERR_WRONG_ARCH = -3
 DDD_ERR_HIP = -4
 DDD_ERR_UNIMPLEMENTED = -5
 DDD_ERR_STATE = -6
+DDD_ERR_STATIC_LIMIT = -7
 
 DDD_KMAX = 16
 DDD_KWIDE_MAX = 128
@@ -26,6 +27,7 @@ DDD_MMAX = 128
 DDD_DMAX = 31
 DDD_POOL_MAX = 4096
 DDD_POOL_WIDE_MAX = 65536
+DDD_STATIC_ROWS = 16
 
 
 class DDDError(RuntimeError):
@@ -107,6 +109,8 @@ def load_library() -> C.CDLL:
         "ddd_num_slices": (C.c_int, [vp]),
         "ddd_round_reset": (C.c_int, [vp, stp, vp, vp]),
         "ddd_lmhead_topk": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]),
+        "ddd_lmhead_topk_static": (C.c_int, [cfgp, vp, vp, i32, vp, vp, vp, vp, vp]),
+        "ddd_static_scratch_bytes": (sz, []),
         "ddd_beam_select": (C.c_int, [vp, i32, vp, vp, stp, vp]),
         "ddd_depth_continue": (C.c_int, [vp, i32, stp, vp]),
         "ddd_draft_step": (C.c_int, [vp, i32, vp, vp, stp, trp, vp, vp, vp]),
@@ -249,6 +253,18 @@ def ddd_lmhead_topk(ctx, W, hid, n_rows, row_active, topk_token, topk_logprob, l
     _check(load_library().ddd_lmhead_topk(ctx, _ptr(W), _ptr(hid), n_rows, _ptr(row_active), _ptr(topk_token),
                                           _ptr(topk_logprob), _ptr(lse), _ptr(logits_dbg),
                                           current_stream() if stream is None else stream), "ddd_lmhead_topk")
+
+
+def ddd_lmhead_topk_static(cfg: ddd_config, W, hid, n_rows, row_active, topk_token, topk_logprob, lse, stream=None):
+    """ddd_lmhead_topk without a context and without any allocation (static device scratch)."""
+    _check(load_library().ddd_lmhead_topk_static(C.byref(cfg), _ptr(W), _ptr(hid), n_rows, _ptr(row_active),
+                                                 _ptr(topk_token), _ptr(topk_logprob), _ptr(lse),
+                                                 current_stream() if stream is None else stream),
+           "ddd_lmhead_topk_static")
+
+
+def ddd_static_scratch_bytes() -> int:
+    return int(load_library().ddd_static_scratch_bytes())
 
 
 def ddd_beam_select(ctx, step, topk_token, topk_logprob, st: ddd_state, stream=None):

@@ -5,6 +5,7 @@
 #include <cstdlib>
 #include <chrono>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -194,6 +195,7 @@ const char* ddd_strerror(int code) {
     case DDD_ERR_HIP: return "HIP runtime error";
     case DDD_ERR_UNIMPLEMENTED: return "not implemented";
     case DDD_ERR_STATE: return "call not valid in the current state";
+    case DDD_ERR_STATIC_LIMIT: return "size beyond the static scratch of the allocation-free entry point";
     default: return "unknown status";
   }
 }
@@ -782,6 +784,117 @@ int ddd_round_launch(ddd_ctx* c, void* stream) {
   if (c == nullptr) return DDD_ERR_INVALID_ARG;
   if (c->graph_exec == nullptr) return DDD_ERR_STATE;
   DDD_HIP(hipGraphLaunch(c->graph_exec, static_cast<hipStream_t>(stream)));
+  return DDD_OK;
+}
+
+}  // extern "C"
+
+// ---- allocation-free entry point ------------------------------------------------------------------
+// The per-slice partial results of the weight stream (what a context keeps in memory it allocated) in a
+// file-scope device array instead: DDD_STATIC_ROWS rows x DDD_KMAX ranks x DDD_STATIC_SLICES slices of
+// 64-bit keys, then the slices' sums of exponentials.  Every device the library runs on holds its own copy
+// until the process ends.
+#define DDD_STATIC_KEY_BYTES ((size_t)DDD_STATIC_ROWS * DDD_KMAX * DDD_STATIC_SLICES * sizeof(uint64_t))
+#define DDD_STATIC_SUM_BYTES ((size_t)DDD_STATIC_ROWS * DDD_STATIC_SLICES * sizeof(float))
+
+static __device__ __align__(256) unsigned char scratch[DDD_STATIC_KEY_BYTES + DDD_STATIC_SUM_BYTES];
+
+namespace {
+
+constexpr size_t kStaticKeyBytes = DDD_STATIC_KEY_BYTES;
+constexpr size_t kStaticBytes = DDD_STATIC_KEY_BYTES + DDD_STATIC_SUM_BYTES;
+
+// In host code `scratch` is only a handle for the runtime: the array's device address is looked up once per
+// device (with that device current) and host code uses nothing but that address.
+constexpr int kMaxDevices = 64;
+struct StaticDevice {
+  bool ready;
+  unsigned char* ptr;   // device address of `scratch` on this device
+  int n_cu;
+};
+StaticDevice g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+// The current device's entry, set up on first use.  DDD_OK, or why the device cannot be used.
+int static_device(StaticDevice* out) {
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+    (void)hipGetLastError();
+    return DDD_ERR_NO_DEVICE;
+  }
+  int dev = 0;
+  DDD_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return DDD_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticDevice& d = g_static[dev];
+  if (!d.ready) {
+    hipDeviceProp_t prop;
+    DDD_HIP(hipGetDeviceProperties(&prop, dev));
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return DDD_ERR_WRONG_ARCH;
+    void* p = nullptr;
+    DDD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return DDD_ERR_HIP;
+    d.ptr = static_cast<unsigned char*>(p);
+    d.n_cu = prop.multiProcessorCount;
+    d.ready = true;
+  }
+  *out = d;
+  return DDD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ddd_static_scratch_bytes(void) { return kStaticBytes; }
+
+int ddd_lmhead_topk_static(const ddd_config* cfg, const void* W, const void* hid, int32_t n_rows,
+                           const uint8_t* row_active, int32_t* topk_token, float* topk_logprob, float* lse,
+                           void* stream) {
+  if (ddd_config_validate(cfg) != DDD_OK) return DDD_ERR_INVALID_ARG;
+  if (W == nullptr || hid == nullptr || topk_token == nullptr || topk_logprob == nullptr || lse == nullptr)
+    return DDD_ERR_INVALID_ARG;
+  if (n_rows < 1) return DDD_ERR_INVALID_ARG;
+  if (n_rows > DDD_STATIC_ROWS || cfg->k > DDD_KMAX) return DDD_ERR_STATIC_LIMIT;
+  StaticDevice d;
+  int rc = static_device(&d);
+  if (rc != DDD_OK) return rc;
+  int G = 0, nw = 0;
+  pick_split(cfg->H, &G, &nw);
+  const int ntiles = (cfg->V + 15) / 16;
+  int nslice = d.n_cu < DDD_STATIC_SLICES ? d.n_cu : DDD_STATIC_SLICES;   // as a context picks it: same bits
+  if (nslice > ntiles) nslice = ntiles;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // Nothing here has to start at zero: the stream kernel writes all k ranks and the sum of every
+  // (row < n_rows, slice < nslice), which is exactly what the merge reads; leftovers of earlier calls lie outside.
+  uint64_t* part_key = reinterpret_cast<uint64_t*>(d.ptr);
+  float* part_sum = reinterpret_cast<float*>(d.ptr + kStaticKeyBytes);
+  StreamArgs a;
+  a.W = static_cast<const uint16_t*>(W);
+  a.hid = static_cast<const uint16_t*>(hid);
+  a.row_active = row_active;
+  a.part_key = part_key;
+  a.part_sum = part_sum;
+  a.logits_dbg = nullptr;
+  a.H = cfg->H;
+  a.V = cfg->V;
+  a.R = n_rows;
+  a.k = cfg->k;
+  a.ntiles = ntiles;
+  a.nw = nw;
+  a.reverse = 0;
+  DDD_HIP(launch_lmhead_stream(a, G, nslice, s));
+  MergeArgs m;
+  m.part_key = part_key;
+  m.part_sum = part_sum;
+  m.row_active = row_active;
+  m.topk_token = topk_token;
+  m.topk_logprob = topk_logprob;
+  m.lse = lse;
+  m.n_rows = n_rows;
+  m.nslice = nslice;
+  m.k = cfg->k;
+  DDD_HIP(launch_merge(m, s));
   return DDD_OK;
 }
 

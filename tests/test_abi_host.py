@@ -84,7 +84,7 @@ def test_config_validation(D):
 
 def test_error_strings_and_null_arguments(D):
     lib = D.load_library()
-    for code in (0, -1, -2, -3, -4, -5, -6):
+    for code in (0, -1, -2, -3, -4, -5, -6, -7):
         assert D.ddd_strerror(code) not in ("", "unknown status")
     assert D.ddd_strerror(-99) == "unknown status"
     assert lib.ddd_create(None, None) == D.DDD_ERR_INVALID_ARG
@@ -93,6 +93,16 @@ def test_error_strings_and_null_arguments(D):
     assert lib.ddd_lmhead_topk(None, None, None, 1, None, None, None, None, None, None) == D.DDD_ERR_INVALID_ARG
     assert lib.ddd_synth_next_round(None, None) == D.DDD_ERR_INVALID_ARG
     assert lib.ddd_round_run_stats(None, None, None, None, None) == D.DDD_ERR_INVALID_ARG
+    # the allocation-free entry point validates before it touches a device
+    assert lib.ddd_static_scratch_bytes() == 16 * 16 * 256 * 8 + 16 * 256 * 4
+    cfg = D.make_config(1, 256, 1000, 4, 6, 16, 0.35)
+    one = C.c_void_p(8)       # any non-null address: rejected calls never look at it
+    assert lib.ddd_lmhead_topk_static(None, one, one, 1, None, one, one, one, None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_lmhead_topk_static(C.byref(cfg), None, one, 1, None, one, one, one, None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_lmhead_topk_static(C.byref(cfg), one, one, 0, None, one, one, one, None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_lmhead_topk_static(C.byref(cfg), one, one, 17, None, one, one, one, None) == D.DDD_ERR_STATIC_LIMIT
+    wide = D.make_config(1, 256, 1000, 17, 3, 16, 0.35)
+    assert lib.ddd_lmhead_topk_static(C.byref(wide), one, one, 1, None, one, one, one, None) == D.DDD_ERR_STATIC_LIMIT
 
 
 def test_create_without_a_device_fails_with_a_status():
