@@ -195,7 +195,7 @@ def kernel_roofline(torch, D, SD, g, wl, iters, side, traffic_path):
         other.zero_()
         cold = []
         for _ in range(24):
-            D.ddd_synth_read_stream(other, other.numel(), sink, 4096, stream=side.cuda_stream)
+            SD.N.ddd_synth_read_stream(other, other.numel(), sink, 4096, stream=side.cuda_stream)
             cold.append(D.ddd_profile_lmhead(ctx_fwd, g.W, g.hid, n_rows, 1, stream=side.cuda_stream)[0])
         cold_ms = sum(cold[4:]) / len(cold[4:])
         del other
@@ -207,11 +207,11 @@ def kernel_roofline(torch, D, SD, g, wl, iters, side, traffic_path):
         best = None
         for blocks in (2048, 4096, 8192):
             for _ in range(3):
-                D.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
+                SD.N.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
             r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             r0.record(side)
             for _ in range(20):
-                D.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
+                SD.N.ddd_synth_read_stream(g.W, w_bytes, sink, blocks, stream=side.cuda_stream)
             r1.record(side)
             side.synchronize()
             gbs = 20 * w_bytes / (r0.elapsed_time(r1) * 1e-3) / 1e9
@@ -222,10 +222,10 @@ def kernel_roofline(torch, D, SD, g, wl, iters, side, traffic_path):
         fsink = torch.zeros(1, dtype=torch.float32, device="cuda")
         with torch.cuda.stream(side):
             it, blocks = 4000, 512             # 2 waves per SIMD; 512*4*4000*8 MFMAs of 32768 flop
-            D.ddd_synth_mfma_rate(fsink, 200, blocks, stream=side.cuda_stream)
+            SD.N.ddd_synth_mfma_rate(fsink, 200, blocks, stream=side.cuda_stream)
             m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             m0.record(side)
-            D.ddd_synth_mfma_rate(fsink, it, blocks, stream=side.cuda_stream)
+            SD.N.ddd_synth_mfma_rate(fsink, it, blocks, stream=side.cuda_stream)
             m1.record(side)
             side.synchronize()
         mfma_ceiling = blocks * 4 * it * 8 * 32768.0 / (m0.elapsed_time(m1) * 1e-3) / 1e12
@@ -369,7 +369,7 @@ def main():
     ap.add_argument("--m", type=int, default=None, help="final tree size override")
     ap.add_argument("--mode", choices=["default", "paper", "strict", "eagle2"], default="default",
                     help="paper: the paper's setting n=11, S={5,7,9}, x=-0.3 (t=exp(x)) of Section 3.2; strict: the same "
-                         "with the test after every call (Table 1's DDD + Strict row, Section 3.3); eagle2: fixed depth "
+                         "with the test after every call (Table 1's DDD + Strict row, Section 3.4); eagle2: fixed depth "
                          "6, no stop test (Section 3.2)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     ap.add_argument("--profile-iters", type=int, default=200)

@@ -60,7 +60,8 @@ typedef enum ddd_status {
 
 /* Parameters of Algorithm 1 (its Require clause) plus the problem shape. */
 typedef struct ddd_config {
-  int32_t B;           /* independent sequences, each with its own beam and stop decision */
+  int32_t B;           /* independent sequences, each with its own beam and stop decision; B*k*H < 2^31 when
+                          B*k > DDD_STREAM_ROWS or k > DDD_KMAX (hidden rows of the MFMA path: 32-bit byte offsets) */
   int32_t H;           /* hidden size: H = 128*G*nw with G in {1,2,4} and 1 <= nw <= 10 (so H <= 5120)    */
   int32_t V;           /* vocabulary size, k <= V < 2^24; V <= 2^17 if B*k > DDD_STREAM_ROWS or k > DDD_KMAX */
   int32_t k;           /* beam width w, 1..DDD_KWIDE_MAX; the node pool 1 + k + (max_depth-1)*k*k must

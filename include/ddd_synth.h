@@ -1,7 +1,8 @@
 /*
  * ddd_synth.h - synthetic stand-ins for the two models the draft round talks to.
  *
- * These are workload generators for tests and the benchmark, not part of the method:
+ * These are workload generators for tests and the benchmark, not part of the method, and they
+ * are built into a shared object of their own (libddd_synth.so, linked against libddd.so):
  * the paper's draft body is EAGLE's trained layer and its target is a Vicuna / LLaMA2
  * model (Section 3.1); neither is available, so a counter-based pseudo-Gaussian hidden
  * state and a hashed target argmax take their place on the device.  The recipe is the

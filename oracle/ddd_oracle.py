@@ -106,7 +106,7 @@ def lmhead_logits_loops(W_bits: np.ndarray, hid_bits: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# logsoftmax  (Section 2: "processes the draft model output with a logsoftmax")
+# logsoftmax  (Section 2: the draft output is turned into logprobs by a logsoftmax)
 # --------------------------------------------------------------------------
 def logsumexp_row(logits_f32: np.ndarray) -> float:
     """lse = M + log(sum_v exp(logit[v] - M)), M = max, in fp64."""

@@ -58,18 +58,6 @@ class ddd_tree(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _TREE_FIELDS]
 
 
-class ddd_synth_params(C.Structure):
-    _fields_ = [("cfg", ddd_config), ("seed", C.c_uint64), ("round_ctr", C.c_void_p),
-                ("root_token", C.c_int32), ("n_plant", C.c_int32), ("scale_depth", C.c_float * 32),
-                ("plant_dir", C.c_void_p), ("plant_round_p24", C.c_uint32), ("plant_row_p24", C.c_uint32)]
-
-
-class ddd_synth_post_args(C.Structure):
-    _fields_ = [("params", C.c_void_p), ("ctx", C.c_void_p)] + [(n, C.c_void_p) for n in (
-        "target_argmax", "accept_len", "accept_path", "bonus_token", "depth_hist", "accept_hist", "batch_depth_hist",
-        "hash_tokens")]
-
-
 class ddd_body_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "k", "H", "F", "V", "max_depth", "L")]
 
@@ -123,18 +111,10 @@ def load_library() -> C.CDLL:
         "ddd_round_run_stats": (C.c_int, [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
                                           C.POINTER(C.c_double)]),
         "ddd_round_run": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp]),
-        "ddd_synth_draft_body": (C.c_int, [vp, i32, stp, vp, vp]),
-        "ddd_synth_target_argmax": (C.c_int, [C.POINTER(ddd_synth_params), stp, trp, vp, vp]),
-        "ddd_synth_next_round": (C.c_int, [vp, vp]),
-        "ddd_synth_post": (C.c_int, [vp, stp, trp, vp]),
-        "ddd_synth_read_stream": (C.c_int, [vp, sz, vp, i32, vp]),
-        "ddd_synth_mfma_rate": (C.c_int, [vp, i32, i32, vp]),
-        "ddd_synth_round_stats": (C.c_int, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "ddd_weights_pack": (C.c_int, [vp, vp, vp]),
         "ddd_tree_attention_workspace": (sz, [vp, i32, i32]),
         "ddd_kv_pack": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp]),
         "ddd_tree_attention": (C.c_int, [vp, trp, vp, vp, vp, vp, vp, i32, i32, vp, sz, vp, vp]),
-        "ddd_synth_hash_tokens": (C.c_int, [vp, vp, i32, i32, C.c_uint64, vp]),
         "ddd_body_create": (C.c_int, [C.POINTER(ddd_body_config), C.POINTER(vp)]),
         "ddd_body_destroy": (C.c_int, [vp]),
         "ddd_body_bind": (C.c_int, [vp, C.POINTER(ddd_body_weights), C.POINTER(ddd_body_prompt)]),
@@ -347,45 +327,6 @@ def ddd_round_launch(ctx, stream=None):
     _check(load_library().ddd_round_launch(ctx, current_stream() if stream is None else stream), "ddd_round_launch")
 
 
-# ---- synthetic workload stand-ins (tests / benchmark) ----------------------------------------
-def synth_post_ptr() -> int:
-    """Address of ddd_synth_post, usable as the `post` argument of the round calls (user = ddd_synth_post_args)."""
-    return C.cast(load_library().ddd_synth_post, C.c_void_p).value
-
-
-def synth_draft_body_ptr() -> int:
-    """Address of ddd_synth_draft_body, usable as the `body` argument of the round calls."""
-    return C.cast(load_library().ddd_synth_draft_body, C.c_void_p).value
-
-
-def ddd_synth_draft_body(params: ddd_synth_params, step, st: ddd_state, hid_out, stream=None):
-    _check(load_library().ddd_synth_draft_body(C.addressof(params), step, C.byref(st), _ptr(hid_out),
-                                               current_stream() if stream is None else stream), "ddd_synth_draft_body")
-
-
-def ddd_synth_target_argmax(params: ddd_synth_params, st: ddd_state, tree: ddd_tree, target_argmax, stream=None):
-    _check(load_library().ddd_synth_target_argmax(C.byref(params), C.byref(st), C.byref(tree), _ptr(target_argmax),
-                                                  current_stream() if stream is None else stream),
-           "ddd_synth_target_argmax")
-
-
-def ddd_synth_next_round(round_ctr, stream=None):
-    _check(load_library().ddd_synth_next_round(_ptr(round_ctr), current_stream() if stream is None else stream),
-           "ddd_synth_next_round")
-
-
-def ddd_synth_round_stats(round_ctr, steps, accept_len, B, depth_hist, accept_hist, batch_depth_hist=None, stream=None):
-    _check(load_library().ddd_synth_round_stats(_ptr(round_ctr), _ptr(steps), _ptr(accept_len), B, _ptr(depth_hist),
-                                                _ptr(accept_hist), _ptr(batch_depth_hist),
-                                                current_stream() if stream is None else stream),
-           "ddd_synth_round_stats")
-
-
-def ddd_synth_hash_tokens(round_ctr, tokens, n, V, seed, stream=None):
-    _check(load_library().ddd_synth_hash_tokens(_ptr(round_ctr), _ptr(tokens), n, V, seed,
-                                                current_stream() if stream is None else stream), "ddd_synth_hash_tokens")
-
-
 def ddd_tree_attention_workspace(ctx, n_heads, L) -> int:
     return int(load_library().ddd_tree_attention_workspace(ctx, n_heads, L))
 
@@ -449,14 +390,3 @@ def ddd_profile_lmhead(ctx, W, hid, n_rows, iters, stream=None):
                                                     current_stream() if stream is None else stream),
            "ddd_profile_lmhead")
     return mean.value, mn.value
-
-
-def ddd_synth_mfma_rate(sink, iters, n_blocks, stream=None):
-    _check(load_library().ddd_synth_mfma_rate(_ptr(sink), iters, n_blocks, current_stream() if stream is None else stream),
-           "ddd_synth_mfma_rate")
-
-
-def ddd_synth_read_stream(src, n_bytes, sink, n_blocks, stream=None):
-    _check(load_library().ddd_synth_read_stream(_ptr(src), n_bytes, _ptr(sink), n_blocks,
-                                                current_stream() if stream is None else stream),
-           "ddd_synth_read_stream")

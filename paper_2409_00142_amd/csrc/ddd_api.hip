@@ -211,6 +211,9 @@ int ddd_config_validate(const ddd_config* cfg) {
   // the GEMM path (more than DDD_STREAM_ROWS rows, or wide beams) keeps per-row statistics of at most
   // 2048 groups of 64 vocabulary rows; wide beam keys hold the token in 18 bits
   if ((wide || (long long)cfg->B * cfg->k > DDD_STREAM_ROWS) && cfg->V > (1 << 17)) return DDD_ERR_INVALID_ARG;
+  // the MFMA path addresses the hidden rows by 32-bit byte offsets
+  if ((wide || (long long)cfg->B * cfg->k > DDD_STREAM_ROWS) && (long long)cfg->B * cfg->k * cfg->H * 2 >= (1LL << 32))
+    return DDD_ERR_INVALID_ARG;
   if (cfg->max_depth < 1 || cfg->max_depth > DDD_DMAX) return DDD_ERR_INVALID_ARG;
   if (cfg->m < 1 || cfg->m > DDD_MMAX) return DDD_ERR_INVALID_ARG;
   if (!(cfg->threshold >= 0.0f)) return DDD_ERR_INVALID_ARG;   // also rejects NaN

@@ -14,8 +14,9 @@
 // rows per register quad: the output is stored as float4 along V.  Both operands reach LDS by
 // LDS-direct loads (16 bytes per lane straight from global memory into LDS: no staging registers,
 // no LDS write instructions, nothing returned through the VGPR write path the fragment reads
-// use), three stages of 32 k, loads two tiles ahead, one barrier per tile.  Rows are not padded;
-// the four 16-byte chunks of a row are XOR-swizzled with bits 2-3 of the row, which keeps both the
+// use), in tiles of 64 k (one whole 128-byte line per row) that sit in two rings - W tiles four deep,
+// hidden-row tiles two to three deep - with one barrier per tile.  Rows are not padded; the eight
+// 16-byte chunks of a row are XOR-swizzled with bits 1-3 of the row, which keeps both the
 // 1 KB-per-wave copy destinations contiguous and the fragment reads conflict-free.  Only active
 // rows are multiplied: the B rows are gathered through the compacted row list and column blocks
 // past the last active row are skipped per wave.  Work units are (row tile of W, column tile),

@@ -2,7 +2,8 @@
 
 Uploads the seeded inputs, fills the parameter block of the on-device stand-in draft body /
 target model, and drives whole rounds through the C ABI binding.  Contains no method
-arithmetic: every step of a round runs inside libddd.so.
+arithmetic: every step of a round runs inside libddd.so; the stand-ins for
+the draft body and the target model come from libddd_synth.so (native.py).
 """
 from __future__ import annotations
 
@@ -13,6 +14,7 @@ import numpy as np
 import torch
 
 import paper_2409_00142_amd as D
+from . import native as N
 from .inputs import Workload, make_lm_head, make_plant_table
 
 
@@ -49,7 +51,7 @@ class GpuWorkload:
         self.batch_depth_hist = torch.zeros(32, dtype=torch.int64, device="cuda")
         self.logits_dbg = torch.zeros(Dm, B * k, V, dtype=torch.float32, device="cuda") if debug else None
         self.lse_dbg = torch.zeros(Dm, B * k, dtype=torch.float32, device="cuda") if debug else None
-        p = D.ddd_synth_params()
+        p = N.ddd_synth_params()
         p.cfg = self.cfg
         p.seed = wl.seed
         p.round_ctr = self.round_ctr.data_ptr()
@@ -62,7 +64,7 @@ class GpuWorkload:
         p.plant_row_p24 = wl.plant_row_p24()
         self.params = p
         # post hook: stand-in target model, accept walk, advance the round counter (one C call per round)
-        pa = D.ddd_synth_post_args()
+        pa = N.ddd_synth_post_args()
         pa.params = C.addressof(self.params)
         pa.ctx = self.ctx
         pa.target_argmax = self.target.data_ptr()
@@ -103,9 +105,9 @@ class GpuWorkload:
     def _round_args(self):
         if getattr(self, "body", None) is not None:
             return (self.ctx, self.W, self.st, self.tree, self.root_token, self.hid, D.body_step_ptr(), self.body,
-                    D.synth_post_ptr(), C.addressof(self.post_args), self.logits_dbg, self.lse_dbg)
-        return (self.ctx, self.W, self.st, self.tree, self.root_token, self.hid, D.synth_draft_body_ptr(),
-                C.addressof(self.params), D.synth_post_ptr(), C.addressof(self.post_args), self.logits_dbg, self.lse_dbg)
+                    N.synth_post_ptr(), C.addressof(self.post_args), self.logits_dbg, self.lse_dbg)
+        return (self.ctx, self.W, self.st, self.tree, self.root_token, self.hid, N.synth_draft_body_ptr(),
+                C.addressof(self.params), N.synth_post_ptr(), C.addressof(self.post_args), self.logits_dbg, self.lse_dbg)
 
     def enqueue_round(self, stream: Optional[int] = None) -> None:
         """The whole round (reset, draft calls, tree, stand-in target, accept walk) without a graph."""

@@ -19,18 +19,25 @@ def D():
     return D
 
 
-def _declared_symbols():
+def _declared_symbols(headers):
     names = []
-    for hdr in ("ddd.h", "ddd_synth.h", "ddd_body.h"):
+    for hdr in headers:
         text = open(os.path.join(ROOT, "include", hdr)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names += re.findall(r"^\s*(?:const\s+char\s*\*|int|size_t)\s+(ddd_\w+)\s*\(", text, flags=re.M)
     return sorted(set(names))
 
 
+def _exported_symbols(path):
+    """Dynamic symbols a shared object defines (nm -D --defined-only)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], check=True, capture_output=True, text=True).stdout
+    return {line.split()[-1] for line in out.splitlines() if line.strip()}
+
+
 def test_every_declared_symbol_is_exported(D):
     lib = D.load_library()
-    names = _declared_symbols()
+    names = _declared_symbols(("ddd.h", "ddd_body.h"))
     assert len(names) >= 24
     for n in ("ddd_lmhead_topk", "ddd_beam_select", "ddd_depth_continue", "ddd_tree_finalize", "ddd_verify_accept",
               "ddd_verify_sample", "ddd_tree_attention", "ddd_body_step"):
@@ -39,12 +46,29 @@ def test_every_declared_symbol_is_exported(D):
         assert hasattr(lib, n), f"{n} declared in include/ but not exported"
 
 
+def test_harness_lives_in_its_own_shared_object(D):
+    """The workload generators and measurement kernels of the tests and the benchmark (include/ddd_synth.h) are
+    exported by synth/libddd_synth.so; the product library exports none of them."""
+    from synth import native
+    slib = native.load_library()
+    names = _declared_symbols(("ddd_synth.h",))
+    assert len(names) >= 8 and all(n.startswith("ddd_synth_") for n in names)
+    for n in names:
+        assert hasattr(slib, n), f"{n} declared in include/ddd_synth.h but not exported by libddd_synth.so"
+    product = _exported_symbols(D.LIB_PATH)
+    assert "ddd_lmhead_topk" in product
+    assert not [n for n in product if "synth" in n]
+    harness = _exported_symbols(native.LIB_PATH)
+    assert not [n for n in harness if n.startswith("ddd_") and not n.startswith("ddd_synth_")]
+
+
 def test_struct_layouts_match_the_header(D):
     assert C.sizeof(D.ddd_config) == 36
     assert C.sizeof(D.ddd_state) == 13 * 8
     assert C.sizeof(D.ddd_tree) == 6 * 8
-    assert D.ddd_synth_params.seed.offset == 40 and D.ddd_synth_params.scale_depth.offset == 64
-    assert C.sizeof(D.ddd_synth_params) == 208
+    from synth import native
+    assert native.ddd_synth_params.seed.offset == 40 and native.ddd_synth_params.scale_depth.offset == 64
+    assert C.sizeof(native.ddd_synth_params) == 208
 
 
 def test_config_validation(D):
@@ -74,6 +98,11 @@ def test_config_validation(D):
         cfg = D.make_config(**dict(base, **good))
         assert D.ddd_config_validate(cfg) == D.DDD_OK, good
         assert D.ddd_pool_capacity(cfg) == 1 + cfg.k + (cfg.max_depth - 1) * cfg.k * cfg.k
+    # hidden rows of the MFMA path are addressed by 32-bit byte offsets: B*k*H*2 must stay below 2^32
+    big = dict(base, B=4096, k=128, H=5120, V=1000, max_depth=4)
+    assert D.ddd_config_validate(D.make_config(**big)) == D.DDD_ERR_INVALID_ARG
+    assert D.ddd_config_validate(D.make_config(**dict(big, H=4096))) == D.DDD_ERR_INVALID_ARG      # exactly 2^32 bytes
+    assert D.ddd_config_validate(D.make_config(**dict(big, H=4096, B=4095))) == D.DDD_OK
     flagged = D.make_config(**base)
     flagged.flags = D.DDD_FLAG_FORWARD_SWEEPS
     assert D.ddd_config_validate(flagged) == D.DDD_OK
@@ -91,7 +120,8 @@ def test_error_strings_and_null_arguments(D):
     assert lib.ddd_destroy(None) == D.DDD_ERR_INVALID_ARG
     assert lib.ddd_round_launch(None, None) == D.DDD_ERR_INVALID_ARG
     assert lib.ddd_lmhead_topk(None, None, None, 1, None, None, None, None, None, None) == D.DDD_ERR_INVALID_ARG
-    assert lib.ddd_synth_next_round(None, None) == D.DDD_ERR_INVALID_ARG
+    from synth import native
+    assert native.load_library().ddd_synth_next_round(None, None) == D.DDD_ERR_INVALID_ARG
     assert lib.ddd_round_run_stats(None, None, None, None, None) == D.DDD_ERR_INVALID_ARG
     # the allocation-free entry point validates before it touches a device
     assert lib.ddd_static_scratch_bytes() == 16 * 16 * 256 * 8 + 16 * 256 * 4

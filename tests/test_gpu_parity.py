@@ -357,7 +357,7 @@ def test_synth_draft_body_matches_numpy_generator(gpu):
             g.set_round(rnd)
             D.ddd_round_reset(g.ctx, g.st, g.root_token)
             for step in range(wl.D):
-                D.ddd_synth_draft_body(g.params, step, g.st, g.hid)
+                SD.N.ddd_synth_draft_body(g.params, step, g.st, g.hid)
                 torch.cuda.synchronize()
                 hid = g.hid.view(torch.int16).cpu().numpy().view(np.uint16)
                 st = {n: t.cpu().numpy() for n, t in g.st_t.items()}
