@@ -162,6 +162,77 @@ def time_rounds(torch, g, launch, steps, warmup, side):
             "batch_steps": int(sum(d * int(c) for d, c in enumerate(g.batch_depth_hist.cpu().numpy())))}
 
 
+def trace_rounds(torch, D, g, wl, n_rounds, launch, side):
+    """Device-timestamp breakdown of the draft calls (B = 1 weight-stream workloads): `n_rounds` rounds with the
+    context's trace on, read back after every round.  Times in microseconds (100 MHz wall clock, 10 ns steps):
+    where a call's time goes inside the weight-stream launch (workgroup start skew, first tile, steady stream,
+    last workgroup's lag), between the launches, and inside the bookkeeping launch."""
+    import numpy as np
+    D.ddd_trace_enable(g.ctx, True)
+    acc = {}
+
+    def add(name, v):
+        acc.setdefault(name, []).append(float(v) / 100.0)
+
+    nsl = D.ddd_num_slices(g.ctx)
+    per_slice = []
+    try:
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            for _ in range(n_rounds):
+                launch()
+                side.synchronize()
+                steps = int(g.st_t["steps"][0])
+                tr = D.ddd_trace_read(g.ctx).astype(np.int64)
+                prev_end = None
+                for s in range(steps):
+                    st = tr[s, :nsl * 8].reshape(nsl, 8)
+                    bk = tr[s, 256 * 8:256 * 8 + 8]
+                    if (st[:, :6] == 0).any() or (bk[:6] == 0).any():
+                        continue
+                    t0, t1, t2, t3 = st[:, 0], st[:, 1], st[:, 2], st[:, 5]
+                    add("stream: last tile multiplied -> folded into the row statistics, median", np.median(st[:, 3] - t2))
+                    add("stream: -> the lanes' lists exchanged through LDS, median", np.median(st[:, 4] - st[:, 3]))
+                    add("stream: -> k merge rounds, partials written, median", np.median(st[:, 5] - st[:, 4]))
+                    per_slice.append((t3 - t0.min()) / 100.0)
+                    add("stream: launch span (first workgroup in -> last out)", t3.max() - t0.min())
+                    add("stream: workgroup start skew (last in - first in)", t0.max() - t0.min())
+                    add("stream: entry -> first tile multiplied, median", np.median(t1 - t0))
+                    add("stream: first -> last tile, median", np.median(t2 - t1))
+                    add("stream: last tile -> partials written, median", np.median(t3 - t2))
+                    add("stream: median workgroup in -> out", np.median(t3 - t0))
+                    add("stream: last workgroup out - median out", t3.max() - np.median(t3))
+                    add("gap: stream out -> bookkeeping in", bk[0] - t3.max())
+                    add("bookkeeping: entry -> slice keys arrived", bk[1] - bk[0])
+                    add("bookkeeping: merge of the rows", bk[2] - bk[1])
+                    add("bookkeeping: beam update + stop test", bk[3] - bk[2])
+                    if bk[4] - bk[3] > 20:                      # a tree was built in this call (more than 0.2 us)
+                        add("bookkeeping: final tree (stopping call)", bk[4] - bk[3])
+                    add("bookkeeping: entry -> exit", bk[5] - bk[0])
+                    if prev_end is not None:
+                        add("gap: bookkeeping out -> next stream in (draft body between)", t0.min() - prev_end[0])
+                        add("call period (stream in -> next stream in)", t0.min() - prev_end[1])
+                    prev_end = (bk[5], t0.min())
+    finally:
+        D.ddd_trace_enable(g.ctx, False)
+    out = {k: {"mean_us": float(np.mean(v)), "min_us": float(np.min(v)), "max_us": float(np.max(v)), "n": len(v)}
+           for k, v in acc.items()}
+    for k, v in out.items():
+        log(f"[trace] {k:78s} mean {v['mean_us']:7.2f}  min {v['min_us']:7.2f}  max {v['max_us']:7.2f}  (n={v['n']})")
+    if per_slice:
+        # is the lag of the last workgroups a property of where they run?  mean finish time per workgroup index
+        ps = np.mean(np.stack(per_slice), axis=0)
+        by8 = [float(np.mean(ps[i::8])) for i in range(8)]
+        out["finish_us_by_workgroup_mod_8"] = by8
+        order = np.argsort(ps)
+        log(f"[trace] mean finish time after the first entry, by workgroup index mod 8: {[round(x, 2) for x in by8]}")
+        log(f"[trace] earliest workgroups {order[:8].tolist()} ({ps[order[:8]].round(2).tolist()}), latest "
+            f"{order[-8:].tolist()} ({ps[order[-8:]].round(2).tolist()}); spread of the per-workgroup means "
+            f"{float(ps.max() - ps.min()):.2f} us")
+        out["finish_us_spread_of_workgroup_means"] = float(ps.max() - ps.min())
+    return out
+
+
 def kernel_roofline(torch, D, SD, g, wl, iters, side, traffic_path):
     """The LM-head kernel alone: HIP events around stand-alone launches on the stream they run on (all B*k rows
     active; <= 16 rows: the weight stream, HBM-bound; more: the MFMA GEMM), in three settings - as consecutive
@@ -341,6 +412,9 @@ def run_workload(torch, D, synth, SD, wl, thr, args, steps, warmup, launch_mode,
                    "mean_depth": r["exec_steps"] / max(1, n_round_seq)},
         "roofline": roof,
     }
+    if args.trace > 0 and not uses_gemm:
+        g.set_round(0)
+        out["trace"] = trace_rounds(torch, D, g, wl, args.trace, launchers["paced" if launch_mode == "graph" else launch_mode], side)
     if args.tree_attention > 0:
         out["tree_attention"] = time_tree_attention(torch, D, g, wl, args.tree_attention, side)
         log(f"[bench] tree attention: {out['tree_attention']}")
@@ -399,6 +473,10 @@ def main():
     ap.add_argument("--traffic", default=None,
                     help="JSON file with the HBM bytes per launch from rocprofv3 --pmc runs "
                          "(default: profiles/traffic_<workload>.json)")
+    ap.add_argument("--trace", type=int, default=0, metavar="N",
+                    help="also run N rounds with the context's device-timestamp trace on (B*k <= 16 workloads) and add the "
+                         "breakdown of a draft call - inside the weight-stream launch, between launches, inside the "
+                         "bookkeeping launch - as a trace object to the JSON line")
     ap.add_argument("--secondary", choices=["auto", "on", "off"], default="auto",
                     help="also measure the other workloads of the metric (7b_b64, 13b_b1, large_vocab; 200 rounds each) "
                          "into a `secondary` list; auto: in the plain default run only (no workload, mode, shape or body option)")

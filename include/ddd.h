@@ -313,6 +313,22 @@ int ddd_num_slices(const ddd_ctx* ctx);
 int ddd_profile_lmhead(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, int32_t n_rows, int32_t iters,
                        float* mean_ms, float* min_ms, void* stream);
 
+/* Device-timestamp trace of the draft calls' kernels (measurement aid; the second call that synchronises).
+ * While enabled, every draft call of the context (ddd_draft_step and the round calls) leaves 100 MHz wall-clock
+ * stamps in a device buffer the context allocates on enabling: for call number s, at word s * DDD_TRACE_CALL_WORDS,
+ * first DDD_STATIC_SLICES * 8 words of the weight stream (per workgroup: entry, first tile multiplied, last tile
+ * multiplied, last tile folded into the row statistics, the lanes' lists exchanged, partial results written, two
+ * unused; zero on the MFMA path), then 8 words of the bookkeeping launch's workgroup 0
+ * (entry, slice keys arrived, rows merged, beam update and stop test done, final tree done - equal to the previous
+ * stamp if none was built -, exit; two unused).  Kernels of a later round overwrite the stamps of an earlier one.
+ * ddd_trace_enable waits for the device, then allocates / clears (on != 0) or frees (on == 0) the buffer: do not
+ * call it between the capture and the last launch of a graph.  ddd_trace_read waits for the device, copies all
+ * ddd_trace_words() words to host memory `out` (n_words must be that number) and clears the buffer. */
+#define DDD_TRACE_CALL_WORDS (DDD_STATIC_SLICES * 8 + 8)
+int ddd_trace_enable(ddd_ctx* ctx, int32_t on);
+int ddd_trace_read(ddd_ctx* ctx, uint64_t* out, size_t n_words);
+size_t ddd_trace_words(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,8 @@
  * h is the hidden row handed to the LM head and the feature f of this node.  rmsnorm uses eps 1e-6.
  *
  * Conventions are those of ddd.h (device buffers are caller-owned, calls only enqueue, status
- * codes, `stream`).  This body handles calls of at most DDD_STREAM_ROWS rows (B*k <= 16).
+ * codes, `stream`).  Calls of up to DDD_STREAM_ROWS rows run every linear as a weight stream (each matrix
+ * read once, HBM-bound); calls of more rows (batched rounds) run them on the matrix cores over the active rows.
  */
 #ifndef DDD_BODY_H_
 #define DDD_BODY_H_
@@ -31,9 +32,10 @@ extern "C" {
 #endif
 
 #define DDD_BODY_LMAX 2048   /* largest prompt length */
+#define DDD_BODY_ROWS_MAX 4096 /* largest B*k */
 
 typedef struct ddd_body_config {
-  int32_t B, k;        /* as in ddd_config; B*k <= DDD_STREAM_ROWS                       */
+  int32_t B, k;        /* as in ddd_config; B*k <= DDD_BODY_ROWS_MAX                     */
   int32_t H;           /* hidden size: H = 128*G*nw as in ddd_config (heads of 128)      */
   int32_t F;           /* MLP width, a multiple of 128                                   */
   int32_t V;           /* rows of the embedding                                          */
@@ -49,7 +51,8 @@ typedef struct ddd_body_weights {
   const void* Wqkv;   /* [3H,H]  rows: q, then k, then v            */
   const void* Wo;     /* [H,H]                                      */
   const float* g2;    /* [H] fp32                                   */
-  const void* Wgu;    /* [2F,H]  row 2i: gate i, row 2i+1: up i     */
+  const void* Wgu;    /* [2F,H]  row 2i: gate i, row 2i+1: up i (this interleaving is the ABI's: it lets the
+                                 product's epilogue form silu(gate)*up from neighbouring sums) */
   const void* Wd;     /* [H,F]                                      */
 } ddd_body_weights;
 
@@ -63,7 +66,7 @@ typedef struct ddd_body_prompt {
 typedef struct ddd_body ddd_body;
 
 /* Allocates the body's scratch and per-call history (features, keys, values and parent slots of
- * every row of every call of the current round: 3 * max_depth * 16 * H bf16). */
+ * every row of every call of the current round: 3 * max_depth * max(B*k, 16) * H bf16). */
 int ddd_body_create(const ddd_body_config* cfg, ddd_body** out);
 int ddd_body_destroy(ddd_body* body);
 
@@ -76,8 +79,9 @@ int ddd_body_bind(ddd_body* body, const ddd_body_weights* w, const ddd_body_prom
  * one round must come in order step = 0, 1, ... (each reads the history of the earlier ones). */
 int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out_bf16, void* stream);
 
-/* y[r,n] = sum_k x[r,k] W[n,k]: the layer's weight stream on its own (R <= 16 rows, K a multiple
- * of 128, N >= 1; W bf16 [N,K], x bf16 [R,K], y fp32 [R,N], all device).  accumulate != 0 adds to y. */
+/* y[r,n] = sum_k x[r,k] W[n,k]: one linear of the layer on its own (K a multiple of 128, N >= 1; W bf16 [N,K],
+ * x bf16 [R,K], y fp32 [R,N], all device): the weight stream for R <= 16 rows, the MFMA path for
+ * 16 < R <= B*k rows (N a multiple of 4 there).  accumulate != 0 adds to y. */
 int ddd_body_linear(ddd_body* body, const void* W, int32_t N, int32_t K, const void* x, int32_t R, float* y,
                     int32_t accumulate, void* stream);
 

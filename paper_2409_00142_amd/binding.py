@@ -108,6 +108,9 @@ def load_library() -> C.CDLL:
         "ddd_round_enqueue": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_capture": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_launch": (C.c_int, [vp, vp]),
+        "ddd_trace_enable": (C.c_int, [vp, i32]),
+        "ddd_trace_read": (C.c_int, [vp, vp, sz]),
+        "ddd_trace_words": (sz, []),
         "ddd_round_run_stats": (C.c_int, [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
                                           C.POINTER(C.c_double)]),
         "ddd_round_run": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp]),
@@ -390,3 +393,17 @@ def ddd_profile_lmhead(ctx, W, hid, n_rows, iters, stream=None):
                                                     current_stream() if stream is None else stream),
            "ddd_profile_lmhead")
     return mean.value, mn.value
+
+
+def ddd_trace_enable(ctx, on: bool = True) -> None:
+    _check(load_library().ddd_trace_enable(ctx, 1 if on else 0), "ddd_trace_enable")
+
+
+def ddd_trace_read(ctx):
+    """The context's device-timestamp trace as a numpy uint64 array [DDD_DMAX + 1, DDD_TRACE_CALL_WORDS]
+    (100 MHz ticks, 0 = not written); synchronises and clears the device buffer."""
+    import numpy as np
+    n = int(load_library().ddd_trace_words())
+    out = np.zeros(n, dtype=np.uint64)
+    _check(load_library().ddd_trace_read(ctx, out.ctypes.data, n), "ddd_trace_read")
+    return out.reshape(DDD_DMAX + 1, -1)

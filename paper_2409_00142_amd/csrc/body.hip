@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kAttnThreads) void body_attention_kernel(BodyAttnAr
     qs[tid + 64] = q1 * cs + q0 * sn;
     const uint16_t kb0 = f32_to_bf16_rne(k0 * cs - k1 * sn), kb1 = f32_to_bf16_rne(k1 * cs + k0 * sn);
     const uint16_t vb0 = f32_to_bf16_rne(v0), vb1 = f32_to_bf16_rne(v1);
-    const size_t slot = ((size_t)a.step * kBodyRows + r) * a.H + h * kHeadDim;
+    const size_t slot = ((size_t)a.step * a.hist_rows + r) * a.H + h * kHeadDim;
     a.k_hist[slot + tid] = kb0;
     a.k_hist[slot + tid + 64] = kb1;
     a.v_hist[slot + tid] = vb0;
@@ -273,12 +273,12 @@ __global__ __launch_bounds__(kAttnThreads) void body_attention_kernel(BodyAttnAr
     int cur = r;
     for (int s = a.step; s > c; --s) {
       // this call's slots are still in the beam (and are recorded below); earlier calls' were recorded then
-      const int pslot = (s == a.step) ? a.beam_parent_slot[cur] : a.par_hist[s * kBodyRows + cur];
+      const int pslot = (s == a.step) ? a.beam_parent_slot[cur] : a.par_hist[s * a.hist_rows + cur];
       cur = (s - 1 == 0) ? b : b * a.k + pslot;
     }
     anc[c] = cur;
   } else if (tid == 128 && h == 0 && a.step >= 1) {
-    a.par_hist[a.step * kBodyRows + r] = a.beam_parent_slot[r];
+    a.par_hist[a.step * a.hist_rows + r] = a.beam_parent_slot[r];
   }
   __syncthreads();
 
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kAttnThreads) void body_attention_kernel(BodyAttnAr
       for (int i = 0; i < kHeadDim; ++i) dot += qs[i] * ks[i];
     } else {
       const uint16_t* kp = (j < a.L) ? a.Kp + ((size_t)(b * a.L + j) * a.H + h * kHeadDim)
-                                     : a.k_hist + (((size_t)(j - a.L) * kBodyRows + anc[j - a.L]) * a.H + h * kHeadDim);
+                                     : a.k_hist + (((size_t)(j - a.L) * a.hist_rows + anc[j - a.L]) * a.H + h * kHeadDim);
       u32x4 u[kHeadDim / 8];
 #pragma unroll
       for (int c = 0; c < kHeadDim / 8; ++c) u[c] = *reinterpret_cast<const u32x4*>(kp + c * 8);
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(kAttnThreads) void body_attention_kernel(BodyAttnAr
     }
     for (; j < a.L; j += 8) o += sc[j] * bf16_to_f32(vbase[(size_t)j * a.H]);
     for (int c = grp; c < a.step; c += 8)
-      o += sc[a.L + c] * bf16_to_f32(a.v_hist[((size_t)c * kBodyRows + anc[c]) * a.H + h * kHeadDim + d]);
+      o += sc[a.L + c] * bf16_to_f32(a.v_hist[((size_t)c * a.hist_rows + anc[c]) * a.H + h * kHeadDim + d]);
     if (grp == 0) o += sc[n_vis - 1] * vs[d];
   }
   part[grp * kHeadDim + d] = o;
@@ -342,6 +342,28 @@ __global__ __launch_bounds__(kAttnThreads) void body_attention_kernel(BodyAttnAr
     for (int g = 0; g < 8; ++g) t += part[g * kHeadDim + tid];   // fixed order
     a.o[(size_t)r * a.H + h * kHeadDim + tid] = f32_to_bf16_rne(t / sum);
   }
+}
+
+// ---- rows of [E[token], parent feature] for the GEMM path: one workgroup per row ------------------------------
+__global__ __launch_bounds__(256) void pack_x0_kernel(PackX0Args a) {
+  const int r = blockIdx.x, tid = threadIdx.x;
+  if (a.row_active != nullptr && a.row_active[r] == 0) return;   // uniform
+  int fr = r;
+  if (a.feat_mode == kGatherBlock) fr = r / a.k;
+  else if (a.feat_mode == kGatherInBlock) fr = (r / a.k) * a.k + a.parent_slot[r];
+  const u32x4* e = reinterpret_cast<const u32x4*>(a.E + (size_t)a.token[r] * a.H);
+  const u32x4* f = reinterpret_cast<const u32x4*>(a.feat + (size_t)fr * a.H);
+  u32x4* out = reinterpret_cast<u32x4*>(a.x0 + (size_t)r * 2 * a.H);
+  const int n = a.H / 8;                                         // 16-byte pieces of a half
+  for (int i = tid; i < n; i += 256) {
+    out[i] = e[i];
+    out[n + i] = f[i];
+  }
+}
+
+hipError_t launch_pack_x0(const PackX0Args& a, hipStream_t stream) {
+  hipLaunchKernelGGL(pack_x0_kernel, dim3(a.R), dim3(256), 0, stream, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_body_attention(const BodyAttnArgs& a, hipStream_t stream) {

@@ -5,6 +5,7 @@
 #include <new>
 
 #include "body_kernels.hpp"
+#include "ddd_kernels.hpp"
 #include "../../include/ddd_body.h"
 
 using namespace ddd;
@@ -12,17 +13,22 @@ using namespace ddd;
 struct ddd_body {
   ddd_body_config cfg;
   int n_cu;
+  int rows;          // B*k: rows of a call after the prompt call, and rows per call in the histories
   ddd_body_weights w;
   ddd_body_prompt p;
   bool bound;
-  float* r;          // fp32 [16][H]   residual stream
-  uint16_t* xn;      // bf16 [16][H]   normalised rows / attention output
-  float* qkv;        // fp32 [16][3H]
-  uint16_t* act;     // bf16 [16][F]
-  uint16_t* h_hist;  // bf16 [D][16][H]
+  float* r;          // fp32 [rows][H]   residual stream
+  uint16_t* xn;      // bf16 [rows][H]   normalised rows / attention output
+  float* qkv;        // fp32 [rows][3H]
+  uint16_t* act;     // bf16 [rows][F]
+  uint16_t* h_hist;  // bf16 [D][rows][H]
   uint16_t* k_hist;
   uint16_t* v_hist;
-  int32_t* par_hist; // [D][16]
+  int32_t* par_hist; // [D][rows]
+  // calls of more than kBodyRows rows go through the MFMA GEMM:
+  uint16_t* x0;      // bf16 [rows][2H]  FC input rows, assembled (null if rows <= kBodyRows)
+  int32_t* row_list; // [rows] ids of the active rows of the current call
+  int32_t* n_act;    // [1]
 };
 
 namespace {
@@ -96,6 +102,30 @@ int enqueue_linear_ranges(const ddd_body* b, LinearArgs a, int K_range, hipStrea
   return DDD_OK;
 }
 
+// y (+)= x W^T over the rows in b->row_list through the MFMA GEMM (calls of more than kBodyRows rows).
+int enqueue_gemm_linear(const ddd_body* b, const void* W, int N, int K, const uint16_t* x, float* y, int epi,
+                        uint16_t* out16, uint16_t* out16b, int ld16, hipStream_t s) {
+  GemmArgs g;
+  g.W = static_cast<const uint16_t*>(W);
+  g.Wp = nullptr;
+  g.hid = x;
+  g.row_list = b->row_list;
+  g.n_act_ptr = b->n_act;
+  g.logits = y;
+  g.grp_max = nullptr;
+  g.grp_sum = nullptr;
+  g.H = K;
+  g.V = N;
+  g.ngrp = 0;
+  g.reverse = 0;
+  g.epi = epi;
+  g.out16 = out16;
+  g.out16b = out16b;
+  g.ld16 = ld16;
+  BODY_HIP(launch_gemm_linear(g, b->rows, ((b->n_cu + 7) / 8) * 8, s));
+  return DDD_OK;
+}
+
 LinearArgs linear_args(const void* W, int ldw, int N, int R, const uint8_t* row_active, float* y, int ldy, int mode) {
   LinearArgs a = {};
   a.rg[0].W = static_cast<const uint16_t*>(W);
@@ -119,7 +149,7 @@ extern "C" {
 int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
   if (cfg == nullptr || out == nullptr) return DDD_ERR_INVALID_ARG;
   *out = nullptr;
-  if (cfg->B < 1 || cfg->k < 1 || cfg->B * cfg->k > kBodyRows) return DDD_ERR_INVALID_ARG;
+  if (cfg->B < 1 || cfg->k < 1 || (long long)cfg->B * cfg->k > DDD_BODY_ROWS_MAX) return DDD_ERR_INVALID_ARG;
   if (cfg->H < 128 || cfg->H > 5120 || cfg->H % 128 != 0 || cfg->F < 128 || cfg->F % 128 != 0 || cfg->V < 1) return DDD_ERR_INVALID_ARG;
   {
     int G = 0, nw = 0;   // H must fit one K range of the weight stream (the gated linear needs complete sums)
@@ -136,7 +166,9 @@ int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
   b->cfg = *cfg;
   b->n_cu = prop.multiProcessorCount;
   b->bound = false;
-  const size_t H = cfg->H, F = cfg->F, D = cfg->max_depth, R = kBodyRows;
+  b->rows = cfg->B * cfg->k;
+  // the stand-alone linear (ddd_body_linear) may be called with up to kBodyRows rows whatever B*k is
+  const size_t H = cfg->H, F = cfg->F, D = cfg->max_depth, R = b->rows > kBodyRows ? b->rows : kBodyRows;
   hipError_t e = hipMalloc(&b->r, R * H * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(&b->xn, R * H * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMalloc(&b->qkv, R * 3 * H * sizeof(float));
@@ -149,6 +181,12 @@ int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
   if (e == hipSuccess) e = hipMemset(b->xn, 0, R * H * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMemset(b->act, 0, R * F * sizeof(uint16_t));
   if (e == hipSuccess) e = hipMemset(b->par_hist, 0, D * R * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc(&b->row_list, R * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc(&b->n_act, sizeof(int32_t));
+  if (e == hipSuccess && b->rows > kBodyRows) {
+    e = hipMalloc(&b->x0, R * 2 * H * sizeof(uint16_t));
+    if (e == hipSuccess) e = prepare_lmhead_gemm();
+  }
   if (e != hipSuccess) {
     ddd_body_destroy(b);
     return DDD_ERR_HIP;
@@ -167,6 +205,9 @@ int ddd_body_destroy(ddd_body* b) {
   (void)hipFree(b->k_hist);
   (void)hipFree(b->v_hist);
   (void)hipFree(b->par_hist);
+  (void)hipFree(b->x0);
+  (void)hipFree(b->row_list);
+  (void)hipFree(b->n_act);
   delete b;
   return DDD_OK;
 }
@@ -184,7 +225,14 @@ int ddd_body_bind(ddd_body* b, const ddd_body_weights* w, const ddd_body_prompt*
 int ddd_body_linear(ddd_body* b, const void* W, int32_t N, int32_t K, const void* x, int32_t R, float* y,
                     int32_t accumulate, void* stream) {
   if (b == nullptr || W == nullptr || x == nullptr || y == nullptr) return DDD_ERR_INVALID_ARG;
-  if (N < 1 || K < 128 || K % 128 != 0 || R < 1 || R > kBodyRows) return DDD_ERR_INVALID_ARG;
+  if (N < 1 || K < 128 || K % 128 != 0 || R < 1) return DDD_ERR_INVALID_ARG;
+  if (R > kBodyRows) {   // the MFMA path of calls with more rows, all R rows taken as active
+    if (R > b->rows || N % 4 != 0) return DDD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    BODY_HIP(launch_build_row_list(nullptr, R, b->row_list, b->n_act, s));
+    return enqueue_gemm_linear(b, W, N, K, static_cast<const uint16_t*>(x), y, accumulate ? kGemmAccumulate : kGemmStore,
+                               nullptr, nullptr, 0, s);
+  }
   LinearArgs a = linear_args(W, K, N, R, nullptr, y, N, accumulate ? kLinearAccumulate : kLinearStore);
   a.rg[0].x = static_cast<const uint16_t*>(x);
   a.rg[0].ldx = K;
@@ -202,29 +250,10 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   const int H = b->cfg.H, F = b->cfg.F;
   const int R = (step == 0) ? b->cfg.B : b->cfg.B * b->cfg.k;
   const uint8_t* act = (step == 0) ? nullptr : st->row_active;   // a round starts with every sequence drafting
-  const size_t hist = (size_t)step * kBodyRows * H;
-
-  // r0 = [E[token], parent feature] Wfc^T: one launch over two K ranges of H, the rows read where they are
-  const uint16_t* Wfc = static_cast<const uint16_t*>(b->w.Wfc);
-  LinearArgs fc = linear_args(Wfc, 2 * H, H, R, act, b->r, H, kLinearStore);
-  fc.n_ranges = 2;
-  fc.gather_k = b->cfg.k;
-  fc.rg[0].x = static_cast<const uint16_t*>(b->w.E);
-  fc.rg[0].ldx = H;
-  fc.rg[0].gather_mode = kGatherIndex;
-  fc.rg[0].gather_idx = (step == 0) ? b->p.root_token : st->beam_token;
-  fc.rg[1].W = Wfc + H;
-  fc.rg[1].x = (step == 0) ? static_cast<const uint16_t*>(b->p.f_root) : b->h_hist + hist - (size_t)kBodyRows * H;
-  fc.rg[1].ldx = H;
-  fc.rg[1].gather_mode = kGatherNone;
-  fc.rg[1].gather_idx = nullptr;
-  if (step == 1) fc.rg[1].gather_mode = kGatherBlock;      // the prompt call has one row per sequence
-  if (step >= 2) {
-    fc.rg[1].gather_mode = kGatherInBlock;
-    fc.rg[1].gather_idx = st->beam_parent_slot;
-  }
-  int rc = enqueue_linear_ranges(b, fc, H, s);
-  if (rc != DDD_OK) return rc;
+  const size_t hist_rows = b->rows > kBodyRows ? b->rows : kBodyRows;
+  const size_t hist = (size_t)step * hist_rows * H;
+  const bool gemm = R > kBodyRows;
+  int rc = DDD_OK;
 
   RmsNormArgs n1;
   n1.x = b->r;
@@ -233,13 +262,6 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   n1.out = b->xn;
   n1.H = H;
   n1.R = R;
-  BODY_HIP(launch_rmsnorm(n1, s));
-  LinearArgs lq = linear_args(b->w.Wqkv, H, 3 * H, R, act, b->qkv, 3 * H, kLinearStore);
-  lq.rg[0].x = b->xn;
-  lq.rg[0].ldx = H;
-  rc = enqueue_linear(b, lq, H, s);
-  if (rc != DDD_OK) return rc;
-
   BodyAttnArgs t;
   t.qkv = b->qkv;
   t.Kp = static_cast<const uint16_t*>(b->p.K);
@@ -255,6 +277,71 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   t.k = b->cfg.k;
   t.step = step;
   t.R = R;
+  t.hist_rows = (int)hist_rows;
+  RmsNormArgs n2 = n1;
+  n2.g = b->w.g2;
+
+  if (gemm) {
+    // More than kBodyRows rows: the same sequence of operations with every linear on the matrix cores, over the
+    // compacted list of active rows; the FC's input rows are assembled first (the GEMM gathers whole rows).
+    BODY_HIP(launch_build_row_list(act, R, b->row_list, b->n_act, s));
+    PackX0Args px;
+    px.E = static_cast<const uint16_t*>(b->w.E);
+    px.token = (step == 0) ? b->p.root_token : st->beam_token;
+    px.feat = (step == 0) ? static_cast<const uint16_t*>(b->p.f_root) : b->h_hist + hist - hist_rows * H;
+    px.parent_slot = st->beam_parent_slot;
+    px.row_active = act;
+    px.x0 = b->x0;
+    px.H = H;
+    px.k = b->cfg.k;
+    px.R = R;
+    px.feat_mode = (step == 0) ? kGatherNone : (step == 1) ? kGatherBlock : kGatherInBlock;
+    BODY_HIP(launch_pack_x0(px, s));
+    rc = enqueue_gemm_linear(b, b->w.Wfc, H, 2 * H, b->x0, b->r, kGemmStore, nullptr, nullptr, 0, s);
+    if (rc != DDD_OK) return rc;
+    BODY_HIP(launch_rmsnorm(n1, s));
+    rc = enqueue_gemm_linear(b, b->w.Wqkv, 3 * H, H, b->xn, b->qkv, kGemmStore, nullptr, nullptr, 0, s);
+    if (rc != DDD_OK) return rc;
+    BODY_HIP(launch_body_attention(t, s));
+    rc = enqueue_gemm_linear(b, b->w.Wo, H, H, b->xn, b->r, kGemmAccumulate, nullptr, nullptr, 0, s);   // r1 = r0 + o Wo^T
+    if (rc != DDD_OK) return rc;
+    BODY_HIP(launch_rmsnorm(n2, s));
+    rc = enqueue_gemm_linear(b, b->w.Wgu, 2 * F, H, b->xn, nullptr, kGemmSiluPairs, b->act, nullptr, F, s);
+    if (rc != DDD_OK) return rc;
+    // h = bf16(r1 + a Wd^T), written to the hidden rows and to this call's features
+    return enqueue_gemm_linear(b, b->w.Wd, H, F, b->act, b->r, kGemmAccumulate, static_cast<uint16_t*>(hid_out),
+                               b->h_hist + hist, H, s);
+  }
+
+  // r0 = [E[token], parent feature] Wfc^T: one launch over two K ranges of H, the rows read where they are
+  const uint16_t* Wfc = static_cast<const uint16_t*>(b->w.Wfc);
+  LinearArgs fc = linear_args(Wfc, 2 * H, H, R, act, b->r, H, kLinearStore);
+  fc.n_ranges = 2;
+  fc.gather_k = b->cfg.k;
+  fc.rg[0].x = static_cast<const uint16_t*>(b->w.E);
+  fc.rg[0].ldx = H;
+  fc.rg[0].gather_mode = kGatherIndex;
+  fc.rg[0].gather_idx = (step == 0) ? b->p.root_token : st->beam_token;
+  fc.rg[1].W = Wfc + H;
+  fc.rg[1].x = (step == 0) ? static_cast<const uint16_t*>(b->p.f_root) : b->h_hist + hist - hist_rows * H;
+  fc.rg[1].ldx = H;
+  fc.rg[1].gather_mode = kGatherNone;
+  fc.rg[1].gather_idx = nullptr;
+  if (step == 1) fc.rg[1].gather_mode = kGatherBlock;      // the prompt call has one row per sequence
+  if (step >= 2) {
+    fc.rg[1].gather_mode = kGatherInBlock;
+    fc.rg[1].gather_idx = st->beam_parent_slot;
+  }
+  rc = enqueue_linear_ranges(b, fc, H, s);
+  if (rc != DDD_OK) return rc;
+
+  BODY_HIP(launch_rmsnorm(n1, s));
+  LinearArgs lq = linear_args(b->w.Wqkv, H, 3 * H, R, act, b->qkv, 3 * H, kLinearStore);
+  lq.rg[0].x = b->xn;
+  lq.rg[0].ldx = H;
+  rc = enqueue_linear(b, lq, H, s);
+  if (rc != DDD_OK) return rc;
+
   BODY_HIP(launch_body_attention(t, s));
   LinearArgs lo = linear_args(b->w.Wo, H, H, R, act, b->r, H, kLinearAccumulate);   // r1 = r0 + o Wo^T
   lo.rg[0].x = b->xn;
@@ -263,8 +350,6 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   if (rc != DDD_OK) return rc;
 
   // gate and up rows of Wgu alternate, so the epilogue of their linear forms a = bf16(silu(gate) * up) itself
-  RmsNormArgs n2 = n1;
-  n2.g = b->w.g2;
   BODY_HIP(launch_rmsnorm(n2, s));
   LinearArgs lg = linear_args(b->w.Wgu, H, 2 * F, R, act, nullptr, 0, kLinearSiluPairs);
   lg.rg[0].x = b->xn;

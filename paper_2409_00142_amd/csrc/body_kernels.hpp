@@ -6,7 +6,7 @@
 
 namespace ddd {
 
-constexpr int kBodyRows = 16;      // rows per call (B*k): one pass of the weight stream
+constexpr int kBodyRows = 16;      // most rows of a call that go through the weight stream (one pass); more: MFMA GEMM
 constexpr int kHeadDim = 128;
 
 // y[r][n] (+)= sum_k x[r][k] * W[n][k] over up to three K ranges of 128*G*nw elements each: the LM
@@ -60,14 +60,29 @@ struct BodyAttnArgs {
   const float* qkv;           // fp32 [R][3H]
   const uint16_t* Kp;         // bf16 [B][L][H] keys of the prompt (as cached)
   const uint16_t* Vp;
-  uint16_t* k_hist;           // bf16 [D][kBodyRows][H]
+  uint16_t* k_hist;           // bf16 [D][hist_rows][H]
   uint16_t* v_hist;
-  int32_t* par_hist;          // [D][kBodyRows] parent slot of every row of every call; this call's row is written here
+  int32_t* par_hist;          // [D][hist_rows] parent slot of every row of every call; this call's row is written here
   const int32_t* beam_parent_slot;   // [B*k] of the current beam (read for step >= 1)
   const uint8_t* row_active;
   uint16_t* o;                // bf16 [R][H]
   int H, L, k, step, R;
+  int hist_rows;              // rows per call in the histories (B*k)
 };
 hipError_t launch_body_attention(const BodyAttnArgs& a, hipStream_t stream);
+
+// Input rows of the FC for calls that go through the MFMA GEMM: x0[r] = [E[token of r], feature of r's parent],
+// assembled once (the GEMM gathers whole rows of one matrix).
+struct PackX0Args {
+  const uint16_t* E;          // bf16 [V][H]
+  const int32_t* token;       // [R] token of every row (root tokens for the prompt call)
+  const uint16_t* feat;       // bf16 feature rows of the previous call (f_root for the prompt call), row pitch H
+  const int32_t* parent_slot; // [R] or null
+  const uint8_t* row_active;  // [R] or null
+  uint16_t* x0;               // bf16 [R][2H]
+  int H, k, R;
+  int feat_mode;              // GatherMode of the feature row: kGatherNone (prompt call), kGatherBlock, kGatherInBlock
+};
+hipError_t launch_pack_x0(const PackX0Args& a, hipStream_t stream);
 
 }  // namespace ddd

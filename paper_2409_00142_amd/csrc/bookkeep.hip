@@ -305,7 +305,9 @@ __global__ __launch_bounds__(1024) void step_bookkeep_kernel(StepArgs a) {
   __shared__ int s_word_base[DDD_BMAX / 64 + 1];
   __shared__ unsigned long long s_words[DDD_BMAX / 64];
   const int b = blockIdx.x, tid = threadIdx.x;
+  if (a.trace != nullptr && b == 0 && tid == 0) a.trace[0] = (uint64_t)wall_clock64();
   const bool active = step_bookkeep_block(a, b, tid, blockDim.x, sm);
+  if (a.trace != nullptr && b == 0 && tid == 0) a.trace[5] = (uint64_t)wall_clock64();
   if (a.call_count == nullptr) return;               // uniform
   if (tid == 0) {
     // What the last workgroup needs from this one travels in atomics alone (performed at the device's

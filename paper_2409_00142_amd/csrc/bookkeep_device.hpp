@@ -243,10 +243,16 @@ __device__ __forceinline__ bool step_bookkeep_block(const StepArgs& a, int b, in
   const int old_node = g.st.beam_node[(size_t)b * g.k + li];
   if (!active) return false;                      // uniform over the workgroup
   if (tid == 0) sm.stopped = 0;
+  uint64_t* const trace = (a.trace != nullptr && b == 0 && tid == 0) ? a.trace : nullptr;
+  if (trace != nullptr) {   // the stamp must follow the arrival of this wave's keys: use one
+    if (!dense && heads.q2[kHPL - 1] == 1ull) trace[7] = 1;       // (never true: keys are never 1)
+    trace[1] = (uint64_t)wall_clock64();
+  }
   if (wave < rows) {
     if (!dense) merge_row_dispatch(pk, heads, a.nslice, g.k, lane, key, lse);
     step_publish_row(a, sm, wave, row, lane, key, lse);
   }
+  if (trace != nullptr) trace[2] = (uint64_t)wall_clock64();
   for (int rw = wave + nwaves; rw < rows; rw += nwaves) {   // fewer waves than rows: further passes
     const size_t row2 = row0 + rw;
     const uint64_t* pk2 = a.part_key + row2 * (dense ? 1 : a.nslice) * g.k;
@@ -269,8 +275,10 @@ __device__ __forceinline__ bool step_bookkeep_block(const StepArgs& a, int b, in
     if (lane == 0 && !cont) sm.stopped = 1;
   }
   __syncthreads();                                // also orders wave 0's pool writes before the reads below
+  if (trace != nullptr) trace[3] = (uint64_t)wall_clock64();
   if (a.tree.mask != nullptr && sm.stopped)   // pool size after this call: 1 + k + step * k^2 (as beam_update just stored it)
     tree_finalize_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm.tsm, 1 + g.k + g.step * g.k * g.k);
+  if (trace != nullptr) trace[4] = (uint64_t)wall_clock64();
   return !sm.stopped;
 }
 

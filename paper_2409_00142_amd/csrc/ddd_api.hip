@@ -42,6 +42,7 @@ struct ddd_ctx {
   // ddd_round_run's host waits, since the context was created (ddd_round_run_stats)
   uint64_t run_rounds, run_waits, run_timeouts;
   double run_max_wait_us;
+  uint64_t* trace;               // null, or device [DDD_DMAX + 1][kTraceCallWords]: stamps of every draft call's kernels
 };
 
 namespace {
@@ -129,6 +130,10 @@ int enqueue_gemm(ddd_ctx* c, const void* W, const void* hid, int max_rows, float
   g.V = c->cfg.V;
   g.ngrp = c->ngrp;
   g.reverse = (c->cfg.flags & DDD_FLAG_FORWARD_SWEEPS) ? 0 : reverse;
+  g.epi = kGemmLogits;
+  g.out16 = nullptr;
+  g.out16b = nullptr;
+  g.ld16 = 0;
   DDD_HIP(launch_lmhead_gemm(g, max_rows, c->g_grid, s));
   return DDD_OK;
 }
@@ -142,7 +147,7 @@ int slices_for(const ddd_ctx* c, int n_rows) { return gemm_path(c, n_rows) ? 0 :
 // DDD_STREAM_ROWS rows, the MFMA GEMM over the compacted active rows otherwise.
 // list_ready: the previous call's bookkeeping launch has already written the list of active rows (GEMM path).
 int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const uint8_t* row_active, float* logits_dbg,
-                   int reverse, hipStream_t s, bool list_ready = false) {
+                   int reverse, hipStream_t s, bool list_ready = false, int trace_step = -1) {
   if (gemm_path(c, n_rows)) {
     float* out = logits_dbg ? logits_dbg : c->logits;
     if (!list_ready) DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
@@ -177,6 +182,7 @@ int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const
     a.ntiles = c->ntiles;
     a.nw = c->nw;
     a.reverse = (c->cfg.flags & DDD_FLAG_FORWARD_SWEEPS) ? 0 : reverse;
+    a.trace = (c->trace != nullptr && trace_step >= 0 && r0 == 0) ? c->trace + (size_t)trace_step * kTraceCallWords : nullptr;
     DDD_HIP(launch_lmhead_stream(a, c->G, c->nslice, s));
   }
   return DDD_OK;
@@ -294,6 +300,7 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->round_tag = 0;
   c->run_rounds = c->run_waits = c->run_timeouts = 0;
   c->run_max_wait_us = 0.0;
+  c->trace = nullptr;
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->call_count), (DDD_DMAX + 1) * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMemset(c->call_count, 0, (DDD_DMAX + 1) * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->active_mask), (DDD_BMAX / 64) * sizeof(uint64_t));
@@ -338,6 +345,7 @@ int ddd_destroy(ddd_ctx* c) {
   if (c->grp_max) (void)hipFree(c->grp_max);
   if (c->grp_sum) (void)hipFree(c->grp_sum);
   if (c->pack) (void)hipFree(c->pack);
+  if (c->trace) (void)hipFree(c->trace);
   (void)hipFree(c->call_count);
   (void)hipFree(c->active_mask);
   (void)hipHostFree(const_cast<uint32_t*>(c->progress));
@@ -462,6 +470,33 @@ int ddd_profile_lmhead(ddd_ctx* c, const void* W, const void* hid, int32_t n_row
   return rc;
 }
 
+int ddd_trace_enable(ddd_ctx* c, int32_t on) {
+  if (c == nullptr) return DDD_ERR_INVALID_ARG;
+  DDD_HIP(hipDeviceSynchronize());   // no kernel in flight holds the old pointer
+  const size_t bytes = (size_t)(DDD_DMAX + 1) * kTraceCallWords * sizeof(uint64_t);
+  if (on) {
+    if (c->trace == nullptr) DDD_HIP(hipMalloc(reinterpret_cast<void**>(&c->trace), bytes));
+    DDD_HIP(hipMemset(c->trace, 0, bytes));
+  } else if (c->trace != nullptr) {
+    DDD_HIP(hipFree(c->trace));
+    c->trace = nullptr;
+  }
+  return DDD_OK;
+}
+
+int ddd_trace_read(ddd_ctx* c, uint64_t* out, size_t n_words) {
+  if (c == nullptr || out == nullptr) return DDD_ERR_INVALID_ARG;
+  if (c->trace == nullptr) return DDD_ERR_STATE;
+  const size_t total = (size_t)(DDD_DMAX + 1) * kTraceCallWords;
+  if (n_words != total) return DDD_ERR_INVALID_ARG;
+  DDD_HIP(hipDeviceSynchronize());
+  DDD_HIP(hipMemcpy(out, c->trace, total * sizeof(uint64_t), hipMemcpyDeviceToHost));
+  DDD_HIP(hipMemset(c->trace, 0, total * sizeof(uint64_t)));
+  return DDD_OK;
+}
+
+size_t ddd_trace_words(void) { return (size_t)(DDD_DMAX + 1) * kTraceCallWords; }
+
 int ddd_round_reset(ddd_ctx* c, ddd_state* st, const int32_t* root_token, void* stream) {
   if (c == nullptr || !state_ok(st)) return DDD_ERR_INVALID_ARG;
   ResetArgs a;
@@ -564,7 +599,8 @@ int draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_sta
   a.active_mask = chain ? c->active_mask : nullptr;
   a.next_row_list = c->row_list;
   a.next_n_act = c->n_act;
-  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, step & 1, s, chain && step >= 1);
+  a.trace = c->trace ? c->trace + (size_t)step * kTraceCallWords + DDD_STATIC_SLICES * kTraceStreamWords : nullptr;
+  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, step & 1, s, chain && step >= 1, step);
   if (rc != DDD_OK) return rc;
   if (c->cfg.k > DDD_KMAX) {
     WideStepArgs w = wide_args(c, a.beam);
@@ -886,6 +922,7 @@ int ddd_lmhead_topk_static(const ddd_config* cfg, const void* W, const void* hid
   a.ntiles = ntiles;
   a.nw = nw;
   a.reverse = 0;
+  a.trace = nullptr;
   DDD_HIP(launch_lmhead_stream(a, G, nslice, s));
   MergeArgs m;
   m.part_key = part_key;

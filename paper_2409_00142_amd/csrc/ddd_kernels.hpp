@@ -7,6 +7,14 @@
 
 namespace ddd {
 
+// Device-timestamp trace (measurement aid, off unless the context enables it): 100 MHz wall-clock stamps.
+// Weight stream, per workgroup: entry, first tile multiplied, last tile multiplied, last tile folded into the
+// row statistics, the lanes' lists exchanged, partial results written; two unused.
+// Bookkeeping, workgroup 0: entry, slice keys arrived, rows merged, beam and stop test done, tree done, exit.
+constexpr int kTraceStreamWords = 8;
+constexpr int kTraceStepWords = 8;
+constexpr int kTraceCallWords = DDD_STATIC_SLICES * kTraceStreamWords + kTraceStepWords;   // one draft call
+
 // ---- LM-head MFMA GEMM for more than 16 rows (lmhead_gemm.hip) --------------------------------
 struct GemmArgs {
   const uint16_t* W;          // bf16 [V,H]
@@ -19,10 +27,25 @@ struct GemmArgs {
   float* grp_sum;             // fp32 [rows][ngrp]: ... and sum of exp(logit - that max); ngrp = ceil(V/64) rounded up to 4
   int H, V, ngrp;
   int reverse;                // hand the row tiles of W out from the last to the first
+  // What happens to the sums (the same product serves the draft layer's linears: W = a weight matrix [N = V][K = H],
+  // hid = the input rows, logits = y).  kGemmLogits needs grp_max / grp_sum; the other modes ignore them.
+  int epi;                    // GemmEpilogue
+  uint16_t* out16;            // bf16 [rows][ld16]: the activations (kGemmSiluPairs), or null / the rounded result (kGemmAccumulate)
+  uint16_t* out16b;           // null, or a second copy of out16 (kGemmAccumulate)
+  int ld16;
+};
+enum GemmEpilogue {
+  kGemmLogits = 0,       // logits = sum, plus max and sum of exponentials of every group of 64 vocabulary rows
+  kGemmStore = 1,        // y = sum
+  kGemmAccumulate = 2,   // y += sum; out16 / out16b (if not null) = bf16(y)
+  kGemmSiluPairs = 3     // rows of W come in (gate_i, up_i) pairs: out16[r][i] = bf16(silu(gate) * up); y unused
 };
 hipError_t prepare_lmhead_gemm();   // once per process: enables the kernels' LDS sizes
 // max_rows: the largest number of rows this call can have (picks the tile shape)
 hipError_t launch_lmhead_gemm(const GemmArgs& a, int max_rows, int grid, hipStream_t stream);
+// The same kernel for a linear of the draft layer: the tile shape is picked so that the launch has about as many
+// work units as workgroups (N = a.V is a few thousand rows, not a vocabulary).
+hipError_t launch_gemm_linear(const GemmArgs& a, int max_rows, int grid, hipStream_t stream);
 // Tile-major copy of W for the GEMM: blocks of 256 vocabulary rows x 64 k, each 32 KB contiguous
 // ([row in block][64 bf16]), blocks ordered (row block, k block); rows past V repeat row V-1.
 // Wp holds ceil(V/256)*256*H elements.
@@ -80,6 +103,7 @@ struct StepArgs {             // merge + beam select + stop test in one launch
   uint64_t* active_mask;      //   ... if not null ([ceil(B/64)] device words, zero between calls: bit b = sequence b goes
   int32_t* next_row_list;     //       on) writes the next call's list of active rows b*k+i, ascending, and their
   int32_t* next_n_act;        //       number: what build_row_list_kernel would make of row_active after this launch
+  uint64_t* trace;            // null, or [kTraceStepWords] device words: wall-clock stamps of workgroup 0's phases
 };
 hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream);
 
@@ -93,6 +117,7 @@ struct StreamArgs {
   float* logits_dbg;          // fp32 [R][V] or null
   int H, V, R, k, ntiles, nw;
   int reverse;                // walk every slice's tiles from the last to the first
+  uint64_t* trace;            // null, or [nslice][kTraceStreamWords] device words: wall-clock stamps of every workgroup
 };
 // G = 128-wide K groups per streaming wave (1, 2 or 4); H == 128 * G * nw.
 hipError_t launch_lmhead_stream(const StreamArgs& a, int G, int nslice, hipStream_t stream);

@@ -36,6 +36,12 @@ constexpr int kGK = 64;        // k per LDS tile: 128 bytes per row = one cache 
 constexpr int kRowB = 2 * kGK; // bytes of a tile row in LDS
 constexpr int kWM = 2;         // waves along the vocabulary rows; 2 more along the hidden rows
 
+__device__ __forceinline__ uint32_t bf16_rne(float x) {   // finite inputs; the bf16 bits in the low half
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
 // AB x BB blocks of 32 x 32 per wave, 2 x 2 waves per workgroup.  The W tiles (from HBM: long
 // latency) and the hidden-row tiles (shared by every workgroup: L2 hits) sit in rings of their own
 // depth, as deep as the 160 KB of LDS allow.
@@ -213,6 +219,40 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, unsigned char* ldsb
   static_assert(AB % 2 == 0, "a wave covers whole groups of 64 vocabulary rows");
   constexpr int NGW = AB / 2;                                  // groups per wave
   const int grp0 = (mt * C::BM + wm * 32 * AB) >> 6;
+  if (a.epi != kGemmLogits) {
+    // ---- a linear of the draft layer: store, accumulate, or gate (V is a multiple of 4 there) ------------
+#pragma unroll
+    for (int bn = 0; bn < NBR; ++bn) {
+      const int n = col0 + bn * 32 + l32;
+      if (n >= n_act) continue;
+      const int orow_id = a.row_list[n];
+      float* orow = a.logits + (size_t)orow_id * a.V;
+      uint16_t* o16 = a.out16 ? a.out16 + (size_t)orow_id * a.ld16 : nullptr;
+      uint16_t* o16b = a.out16b ? a.out16b + (size_t)orow_id * a.ld16 : nullptr;
+#pragma unroll
+      for (int bm = 0; bm < AB; ++bm)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int v = vb + bm * 32 + q * 8;
+          if (v + 3 >= a.V) continue;
+          f32x4 o = {acc[bm][bn][q * 4], acc[bm][bn][q * 4 + 1], acc[bm][bn][q * 4 + 2], acc[bm][bn][q * 4 + 3]};
+          if (a.epi == kGemmSiluPairs) {   // (v, v+1) and (v+2, v+3) are (gate, up) pairs
+            const uint32_t lo = bf16_rne(o[0] / (1.0f + __expf(-o[0])) * o[1]);
+            const uint32_t hi = bf16_rne(o[2] / (1.0f + __expf(-o[2])) * o[3]);
+            *reinterpret_cast<uint32_t*>(o16 + (v >> 1)) = lo | (hi << 16);
+          } else {
+            if (a.epi == kGemmAccumulate) o += *reinterpret_cast<const f32x4*>(orow + v);
+            *reinterpret_cast<f32x4*>(orow + v) = o;
+            if (o16 != nullptr) {
+              const uint32_t p0 = bf16_rne(o[0]) | (bf16_rne(o[1]) << 16), p1 = bf16_rne(o[2]) | (bf16_rne(o[3]) << 16);
+              *reinterpret_cast<uint2*>(o16 + v) = make_uint2(p0, p1);
+              if (o16b != nullptr) *reinterpret_cast<uint2*>(o16b + v) = make_uint2(p0, p1);
+            }
+          }
+        }
+    }
+    return;
+  }
 #pragma unroll
   for (int bn = 0; bn < NBR; ++bn) {
     const int n = col0 + bn * 32 + l32;
@@ -415,6 +455,15 @@ template <int AB, int BB>
 static void launch_shape(const GemmArgs& a, int grid, hipStream_t stream) {
   constexpr int lds_bytes = GemmCfg<AB, BB>::kLdsBytes;
   hipLaunchKernelGGL((lmhead_gemm_kernel<AB, BB>), dim3(grid), dim3(256), lds_bytes, stream, a);
+}
+
+hipError_t launch_gemm_linear(const GemmArgs& a, int max_rows, int grid, hipStream_t stream) {
+  // work units of the widest tile that holds the rows; fewer than workgroups: take 128 x 128 tiles instead
+  const int mt = (a.V + 127) / 128;
+  const int wide = max_rows > 192 ? 320 : max_rows > 128 ? 192 : 128;
+  if (mt * ((max_rows + wide - 1) / wide) >= grid) return launch_lmhead_gemm(a, max_rows, grid, stream);
+  launch_shape<2, 2>(a, grid, stream);
+  return hipGetLastError();
 }
 
 hipError_t launch_lmhead_gemm(const GemmArgs& a, int max_rows, int grid, hipStream_t stream) {

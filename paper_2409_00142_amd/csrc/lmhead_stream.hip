@@ -3,8 +3,8 @@
 // Computes, for R <= 16 hidden rows, logits[r,v] = sum_h hid[r,h] * W[v,h] (bf16 in, fp32
 // accumulate) for every vocabulary row v, reading W exactly once, and leaves per
 // (row, slice) partial results: the slice's k best (logit, token) keys in order and
-// sum_v exp(logit - slice max).  A slice is the contiguous range of 16-row tiles owned by
-// one workgroup.  The full logits are never written unless a debug buffer is given.
+// sum_v exp(logit - slice max).  A slice is the set of tiles (of at most 16 rows) owned by one
+// workgroup: every nslice-th tile of the vocabulary.  The full logits are never written unless a debug buffer is given.
 //
 // Workgroup = NW streaming waves + 1 epilogue wave.
 //  * Streaming wave w owns the K-slice [w*KS, (w+1)*KS) of the hidden dimension, KS = 128*G.
@@ -38,16 +38,29 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
   }
 
   const int nslice = gridDim.x, slice = blockIdx.x;
-  // The vocabulary rows are dealt to the slices row by row, not tile by tile, so that every workgroup
-  // fetches the same amount from memory (32000 rows over 256 slices: 125 rows each instead of 7 or 8
-  // tiles of 16); a slice's last tile is ragged: its missing rows repeat the slice's last row (cache
-  // hits) and are masked in the epilogue.
-  const int r0 = (int)(((long long)slice * a.V) / nslice);
-  const int r1 = (int)(((long long)(slice + 1) * a.V) / nslice);
-  const int nt = (r1 - r0 + 15) >> 4;
+  uint64_t* const trace = a.trace ? a.trace + (size_t)slice * kTraceStreamWords : nullptr;
+  if (trace != nullptr && tid == 0) trace[0] = (uint64_t)wall_clock64();
+  // The vocabulary is cut into nslice * nt tiles of equal height (V / (nslice * nt) <= 16 rows, i.e. 15 or 16
+  // rows each at 32000 rows over 256 slices) and slice i owns tiles i, i + nslice, i + 2 nslice, ...: every
+  // workgroup fetches the same amount, and at any time the workgroups together read one contiguous window of W
+  // that moves through the matrix.  (With one contiguous range of rows per workgroup the workgroups that owned
+  // the odd megabytes of W finished 3 us after the others, launch after launch: which addresses are served faster
+  // is a property of the memory system, so every workgroup gets its share of all of them.)  A tile's missing
+  // rows repeat its last row (the same cache lines) and are masked in the epilogue.
+  const int nt = (a.V + 16 * nslice - 1) / (16 * nslice);
+  const long long NT = (long long)nslice * nt;
   // Sweep direction: calls alternate, so that a call starts with the part of W its predecessor read
   // last, which the memory-side cache still holds.
-  const int tb = a.reverse ? nt - 1 : 0, td = a.reverse ? -1 : 1;     // tile index inside the slice
+  auto tile_lo = [&](int t) -> int {     // first row of this slice's t-th tile in walk order
+    const int u = a.reverse ? nt - 1 - t : t;
+    const long long j = (long long)u * nslice + (slice + u) % nslice;
+    return (int)((j * a.V) / NT);
+  };
+  auto tile_hi = [&](int t) -> int {
+    const int u = a.reverse ? nt - 1 - t : t;
+    const long long j = (long long)u * nslice + (slice + u) % nslice + 1;
+    return (int)((j * a.V) / NT);
+  };
 
   float* red = reinterpret_cast<float*>(smem);      // [2][NW][256] fp32 partial tiles
   unsigned char* stage = smem + 2 * NW * 1024;      // [NW][kStageBytes]
@@ -71,30 +84,34 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
     const int wr_off = lrow * kStagePitch + c * 16;
     const int rd_off = n * kStagePitch + q * 16;
     const uint16_t* wbase = a.W + ks + c * 8;
-    const int vlast = max(r1 - 1, 0);                // rows are clamped to the slice
 
     u32x4 ring[G][4];
     {
-      const int v0 = r0 + max(tb, 0) * 16;   // in range also when this slice owns no tile: rows are clamped
+      const int lo = tile_lo(0), last = tile_hi(0) - 1;   // rows are clamped to the tile
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          int row = min(v0 + i * 4 + lrow, vlast);
+          const int row = min(lo + i * 4 + lrow, last);
           ring[g][i] = *reinterpret_cast<const u32x4*>(wbase + (size_t)row * a.H + g * 128);
         }
     }
     // every tile but the last refills the ring with the next tile while it is consumed
     for (int t = 0; t + 1 < nt; ++t) {
-      const f32x4 acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, r0 + (tb + td * (t + 1)) * 16 + lrow,
-                                             vlast);
+      const f32x4 acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, tile_lo(t + 1) + lrow,
+                                             tile_hi(t + 1) - 1);
       *reinterpret_cast<f32x4*>(red + ((t & 1) * NW + wave) * 256 + lane * 4) = acc;
+      if (trace != nullptr && t == 0 && tid == 0) trace[1] = (uint64_t)wall_clock64();
       __syncthreads();
     }
-    if (nt > 0) {
+    {
       const int t = nt - 1;
-      const f32x4 acc = stream_tile<G, false>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, 0, vlast);
+      const f32x4 acc = stream_tile<G, false>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, 0, 0);
       *reinterpret_cast<f32x4*>(red + ((t & 1) * NW + wave) * 256 + lane * 4) = acc;
+      if (trace != nullptr && tid == 0) {
+        if (t == 0) trace[1] = (uint64_t)wall_clock64();
+        trace[2] = (uint64_t)wall_clock64();
+      }
       __syncthreads();
     }
   } else {
@@ -112,8 +129,8 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
       f32x4 s = {0.f, 0.f, 0.f, 0.f};
       for (int w = 0; w < NW; ++w)   // fixed order: equal W rows give bit-equal logits
         s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + lane * 4);
-      const int v0 = r0 + (tb + td * t) * 16 + vb * 4;
-      const int nv = min(4, r1 - v0);
+      const int v0 = tile_lo(t) + vb * 4;
+      const int nv = min(4, tile_hi(t) - v0);
       if (row_ok && nv > 0) {
         float x[4];
 #pragma unroll
@@ -150,6 +167,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
       }
     }
 
+    if (trace != nullptr && lane == 0) trace[3] = (uint64_t)wall_clock64();
     // The four lanes of a hidden row merge their lists: through LDS into quads (lane' = 4*r + vb).
     // Every streaming wave has passed its last barrier, so the stage area is free.
     uint64_t* elist = reinterpret_cast<uint64_t*>(stage);            // [64][KL]
@@ -168,6 +186,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
     float s_q = (s_l == 0.f) ? 0.f : s_l * __expf(m_l - m_q);
     s_q += dpp_move_f32<0xB1>(s_q);
     s_q += dpp_move_f32<0x4E>(s_q);
+    if (trace != nullptr && lane == 0) trace[4] = (uint64_t)wall_clock64();
     uint64_t* pk = a.part_key + (size_t)(ok2 ? r2 : 0) * nslice * a.k + slice;   // [row][rank][slice]
     int cur = 0;
     for (int round = 0; round < a.k; ++round) {
@@ -178,6 +197,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
       if (ok2 && (lane & 3) == 0) pk[(size_t)round * nslice] = q;
     }
     if (ok2 && (lane & 3) == 0) a.part_sum[(size_t)r2 * nslice + slice] = s_q;
+    if (trace != nullptr && lane == 0) trace[5] = (uint64_t)wall_clock64();
   }
 }
 

@@ -66,6 +66,11 @@ LINEAR_CASES = [
     ("two_ranges_1408", 1000, 1408, 16),          # 128*11 = 1280 + 128
     ("k8192", 520, 8192, 10),                      # 5120 + 3072
     ("k11008_ragged_N", 1037, 11008, 3),           # 5120 + 5120 + 768; N not a multiple of 16
+    # more than 16 rows: the MFMA path (128 x 128 tiles when the product has few of them, wider ones otherwise)
+    ("gemm_rows40", 512, 1024, 40),
+    ("gemm_rows130_k8192", 520, 8192, 130),
+    ("gemm_rows24_k11008_ragged_N", 1036, 11008, 24),
+    ("gemm_rows330_wide_tiles", 33000, 256, 330),
 ]
 
 
@@ -77,7 +82,7 @@ def test_body_linear_against_oracle(gpu, case):
     rng = np.random.default_rng(sum(map(ord, name)))
     W_bits = synth.f32_to_bf16_bits((rng.standard_normal((N, K)) * K ** -0.5).astype(np.float32))
     x_bits = synth.f32_to_bf16_bits(rng.standard_normal((R, K)).astype(np.float32))
-    body = D.ddd_body_create(D.ddd_body_config(1, 4, 256, 256, 10, 2, 0))
+    body = D.ddd_body_create(D.ddd_body_config(max(1, (R + 3) // 4), 4, 256, 256, 10, 2, 0))
     try:
         W, x = SD.upload_bits(W_bits), SD.upload_bits(x_bits)
         y = torch.full((R, N), float("nan"), dtype=torch.float32, device="cuda")
@@ -100,22 +105,22 @@ class _Beam:
         self.token, self.parent_slot = np.asarray(token), np.asarray(parent_slot)
 
 
-def test_body_steps_with_scripted_beams(gpu):
-    """Four calls of two sequences with hand-written beams; the second sequence stops after call 1, so its rows
-    must be left untouched from call 2 on."""
+@pytest.mark.parametrize("B,k", [(2, 3), (6, 3), (20, 2)], ids=lambda v: str(v))
+def test_body_steps_with_scripted_beams(gpu, B, k):
+    """Four calls with scripted beams (seeded tokens and parent slots); some sequences stop after call 1 or 2, and
+    their rows must be left untouched from then on.  B*k <= 16: every linear is a weight stream; more rows: the
+    MFMA path (B = 6: from the second call on; B = 20: for the prompt call as well)."""
     torch, D, SD = gpu
-    B, k, H, F, V, L, Dm = 2, 3, 256, 384, 60, 7, 4
+    H, F, V, L, Dm = 256, 384, 60, 7, 4
     print(f"[case] body scripted beams B={B} k={k} H={H} F={F} L={L}", flush=True)
     dev_w, dev_p, ow, op = _body_inputs(torch, SD, V, H, F, L, B)
     cfg = D.make_config(B, H, V, k, Dm, 8, 0.3)
     st, st_t = D.alloc_state(cfg)
-    beams = [  # per call s >= 1: per sequence (tokens, parent slots)
-        None,
-        [([1, 2, 3], [0, 0, 0]), ([4, 5, 6], [0, 0, 0])],
-        [([7, 8, 9], [2, 0, 2]), ([10, 11, 12], [1, 1, 0])],
-        [([13, 14, 15], [1, 1, 0]), ([16, 17, 18], [0, 2, 2])],
-    ]
-    active = [None, [1, 1], [1, 0], [1, 0]]
+    rng = np.random.default_rng(100 * B + k)
+    beams = [None] + [[(rng.integers(0, V, k).tolist(), [0] * k if s == 1 else rng.integers(0, k, k).tolist())
+                       for b in range(B)] for s in range(1, Dm)]
+    stop_after = [int(rng.integers(1, Dm + 1)) if b % 2 == 1 else Dm for b in range(B)]      # calls a sequence makes
+    active = [None] + [[1 if s < stop_after[b] else 0 for b in range(B)] for s in range(1, Dm)]
     body = D.ddd_body_create(D.ddd_body_config(B, k, H, F, V, Dm, L))
     obodies = [OB.StandInBody(ow, op[b], root_token=3) for b in range(B)]
     try:
@@ -148,7 +153,9 @@ def test_body_steps_with_scripted_beams(gpu):
 
 @pytest.mark.parametrize("shape", [("tiny", 1, 4, 256, 384, 500, 9, 5), ("k10_h1024", 1, 10, 1024, 2816, 3000, 33, 6),
                                    # the shape the benchmark's --body layer times: 7B sizes, 32 heads, 256 prompt positions
-                                   ("7b_full_shape", 1, 10, 4096, 11008, 32000, 256, 3)],
+                                   ("7b_full_shape", 1, 10, 4096, 11008, 32000, 256, 3),
+                                   # several sequences, more than 16 rows per call: the MFMA path of the layer and of the LM head
+                                   ("b5_k6_gemm_rows", 5, 6, 512, 1024, 2000, 17, 4)],
                          ids=lambda s: s[0])
 def test_round_with_body_matches_oracle(gpu, shape):
     """Whole rounds with the layer as the draft body: eager calls (rows inspected after every body call), then the
@@ -179,29 +186,29 @@ def test_round_with_body_matches_oracle(gpu, shape):
             hid_rows.append(_bits(hid).copy())
             D.ddd_draft_step(ctx, s, W, hid, st, tree, logits[s], None)
         torch.cuda.synchronize()
-        steps = int(st_t["steps"].cpu()[0])
         g_logits = logits.cpu().numpy()
         eager_tree = {n: t.cpu().numpy().copy() for n, t in tree_t.items()}
-        # oracle round on the GPU's logits, with its own layer producing the rows
-        obody = OB.StandInBody(ow, op[0], root_token=root)
-        o_rows = []
+        for b in range(B):
+            steps = int(st_t["steps"].cpu()[b])
+            # oracle round of this sequence on the GPU's logits, with its own layer producing the rows
+            obody = OB.StandInBody(ow, op[b], root_token=root)
+            o_rows = []
 
-        def body_fn(s, beam, pool):
-            rows = obody(s, beam, pool)
-            o_rows.append(rows)
-            return rows
+            def body_fn(s, beam, pool):
+                rows = obody(s, beam, pool)
+                o_rows.append(rows)
+                return rows
 
-        def logits_fn(s, hid_bits):
-            n = 1 if s == 0 else k
-            return g_logits[s, :n], None
+            def logits_fn(s, hid_bits, b=b):
+                return (g_logits[s, b:b + 1] if s == 0 else g_logits[s, b * k:(b + 1) * k]), None
 
-        res = O.run_round(None, k, Dm, m, thr, 0xFFFFFFFF, body_fn, root_token=root, logits_fn=logits_fn)
-        assert res.steps == steps and steps >= 2
-        for s in range(steps):
-            n = 1 if s == 0 else k
-            _rows_close(hid_rows[s][:n], o_rows[s])
-        assert np.array_equal(eager_tree["tree_token"][0], res.tree.tree_token)
-        assert np.array_equal(eager_tree["parent_idx"][0], res.tree.parent_idx)
+            res = O.run_round(None, k, Dm, m, thr, 0xFFFFFFFF, body_fn, root_token=root, logits_fn=logits_fn)
+            assert res.steps == steps and steps >= 2
+            for s in range(steps):
+                rows = hid_rows[s][b:b + 1] if s == 0 else hid_rows[s][b * k:(b + 1) * k]
+                _rows_close(rows, o_rows[s])
+            assert np.array_equal(eager_tree["tree_token"][b], res.tree.tree_token)
+            assert np.array_equal(eager_tree["parent_idx"][b], res.tree.parent_idx)
         # the same round from a captured graph gives the same bits
         side = torch.cuda.Stream()
         for t in tree_t.values():
