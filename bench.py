@@ -347,8 +347,6 @@ def run_workload(torch, D, synth, SD, wl, thr, args, steps, warmup, launch_mode,
     log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s; "
         f"stream slices={D.ddd_num_slices(g.ctx)}")
     if args.body == "layer":
-        if wl.B * wl.k > 16:
-            sys.exit("--body layer handles at most 16 rows per call (B*k <= 16)")
         F = args.ffn if args.ffn is not None else (13824 if wl.H == 5120 else 11008)
         t1 = time.perf_counter()
         g.use_layer_body(F, args.prompt_len)
@@ -454,7 +452,8 @@ def main():
     ap.add_argument("--body", choices=["hash", "layer"], default="hash",
                     help="draft body between the LM-head calls: the hash-based hidden-state generator of the workload "
                          "(default: the LM head and the bookkeeping are all a round does), or the stand-in draft layer "
-                         "(embedding + FC + one decoder layer with tree attention, synthetic weights; <= 16 rows per call)")
+                         "(embedding + FC + one decoder layer with tree attention, synthetic weights; weight streams for up "
+                         "to 16 rows per call, the MFMA path for batched rounds)")
     ap.add_argument("--ffn", type=int, default=None, help="MLP width of the draft layer (default 11008, 13824 for H=5120)")
     ap.add_argument("--lm-sigma", type=float, default=None, help="std of the LM-head weights with --body layer (default 0.07)")
     ap.add_argument("--prompt-len", type=int, default=256, help="prompt positions every draft row attends to")

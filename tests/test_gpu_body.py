@@ -155,16 +155,20 @@ def test_body_steps_with_scripted_beams(gpu, B, k):
                                    # the shape the benchmark's --body layer times: 7B sizes, 32 heads, 256 prompt positions
                                    ("7b_full_shape", 1, 10, 4096, 11008, 32000, 256, 3),
                                    # several sequences, more than 16 rows per call: the MFMA path of the layer and of the LM head
-                                   ("b5_k6_gemm_rows", 5, 6, 512, 1024, 2000, 17, 4)],
+                                   ("b5_k6_gemm_rows", 5, 6, 512, 1024, 2000, 17, 4),
+                                   # the same with a stop threshold: the sequences stop after different calls, the later
+                                   # calls run the layer on the rows that are left
+                                   ("b7_k6_gemm_ragged_stops", 7, 6, 512, 1024, 2000, 17, 5, 0.03)],
                          ids=lambda s: s[0])
 def test_round_with_body_matches_oracle(gpu, shape):
     """Whole rounds with the layer as the draft body: eager calls (rows inspected after every body call), then the
     same round from one captured graph.  The oracle replays the GPU's logits, so beams and trees must agree
     bit for bit, and its own layer must reproduce every hidden row within the tolerance."""
     torch, D, SD = gpu
-    name, B, k, H, F, V, L, Dm = shape
-    print(f"[case] round with body {name} B={B} k={k} H={H} F={F} V={V} L={L} D={Dm}", flush=True)
-    m, thr, root = 12, 0.0, 3     # t = 0: every call is made, the tree is built in the last one
+    name, B, k, H, F, V, L, Dm = shape[:8]
+    thr = shape[8] if len(shape) > 8 else 0.0     # t = 0: every call is made, the tree is built in the last one
+    print(f"[case] round with body {name} B={B} k={k} H={H} F={F} V={V} L={L} D={Dm} t={thr}", flush=True)
+    m, root = 12, 3
     dev_w, dev_p, ow, op = _body_inputs(torch, SD, V, H, F, L, B, seed=4, root_token=root)
     W_bits = synth.make_lm_head(V, H, 0.08, seed=11)
     W = SD.upload_bits(W_bits)
@@ -188,6 +192,7 @@ def test_round_with_body_matches_oracle(gpu, shape):
         torch.cuda.synchronize()
         g_logits = logits.cpu().numpy()
         eager_tree = {n: t.cpu().numpy().copy() for n, t in tree_t.items()}
+        depths = []
         for b in range(B):
             steps = int(st_t["steps"].cpu()[b])
             # oracle round of this sequence on the GPU's logits, with its own layer producing the rows
@@ -203,12 +208,18 @@ def test_round_with_body_matches_oracle(gpu, shape):
                 return (g_logits[s, b:b + 1] if s == 0 else g_logits[s, b * k:(b + 1) * k]), None
 
             res = O.run_round(None, k, Dm, m, thr, 0xFFFFFFFF, body_fn, root_token=root, logits_fn=logits_fn)
-            assert res.steps == steps and steps >= 2
+            assert res.steps == steps and (steps >= 2 or thr > 0.0)
+            depths.append(steps)
+            if thr > 0.0:
+                print(f"[info] {name} seq {b}: P after each call {[round(rec.P, 4) for rec in res.records]}", flush=True)
             for s in range(steps):
                 rows = hid_rows[s][b:b + 1] if s == 0 else hid_rows[s][b * k:(b + 1) * k]
                 _rows_close(rows, o_rows[s])
             assert np.array_equal(eager_tree["tree_token"][b], res.tree.tree_token)
             assert np.array_equal(eager_tree["parent_idx"][b], res.tree.parent_idx)
+        print(f"[info] {name}: calls made per sequence {depths}", flush=True)
+        if thr > 0.0:
+            assert len(set(depths)) >= 2          # ragged: the sequences did stop at different depths
         # the same round from a captured graph gives the same bits
         side = torch.cuda.Stream()
         for t in tree_t.values():
