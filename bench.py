@@ -335,8 +335,10 @@ def kernel_roofline(torch, D, SD, g, wl, iters, side, traffic_path):
     return roof
 
 
-def run_workload(torch, D, synth, SD, wl, thr, args, steps, warmup, launch_mode, also_graph, cpu_budget, W_cache):
-    """One workload measured end to end; returns the fields of its JSON object."""
+def run_workload(torch, D, synth, SD, wl, thr, args, steps, warmup, launch_mode, also_graph, cpu_budget, W_cache,
+                 with_kernel=True):
+    """One workload measured end to end; returns the fields of its JSON object.  with_kernel=False skips the
+    stand-alone timing of the LM-head kernel (variants of a workload whose kernel launch is the same)."""
     log(f"[bench] workload {wl.name}: B={wl.B} H={wl.H} V={wl.V} k={wl.k} D={wl.D} m={wl.m} t={thr} gain={wl.gain}")
     t0 = time.perf_counter()
     key = (wl.V, wl.H, wl.sigma_w, wl.seed, wl.dup_pairs)
@@ -387,7 +389,7 @@ def run_workload(torch, D, synth, SD, wl, thr, args, steps, warmup, launch_mode,
             f"{modes['graph']['us_per_round']:.1f} us/round")
 
     traffic_path = args.traffic or os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
-    roof = kernel_roofline(torch, D, SD, g, wl, args.profile_iters, side, traffic_path)
+    roof = kernel_roofline(torch, D, SD, g, wl, args.profile_iters, side, traffic_path) if with_kernel else {}
     # round level: one pass over W per executed depth step of the batch is what the method has to move
     roof["round_frac"] = r["batch_steps"] * w_bytes / wall / 1e9 / HBM_PEAK_GBS
     roof["round_GBs"] = r["batch_steps"] * w_bytes / wall / 1e9
@@ -477,8 +479,10 @@ def main():
                          "breakdown of a draft call - inside the weight-stream launch, between launches, inside the "
                          "bookkeeping launch - as a trace object to the JSON line")
     ap.add_argument("--secondary", choices=["auto", "on", "off"], default="auto",
-                    help="also measure the other workloads of the metric (7b_b64, 13b_b1, large_vocab; 200 rounds each) "
-                         "into a `secondary` list; auto: in the plain default run only (no workload, mode, shape or body option)")
+                    help="also measure, into a `secondary` list, the other thresholds and the paper's parameter modes at the "
+                         "7B shape, the other workloads of the metric (7b_b64, 13b_b1, large_vocab; 200 rounds each) and "
+                         "the rounds with the stand-in draft layer; auto: in the plain default run only (no workload, "
+                         "mode, shape or body option)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -526,14 +530,39 @@ def main():
     }
     out.update({k: v for k, v in res.items() if k not in out})
     if secondary:
+        import copy
         out["secondary"] = []
-        for name in ("7b_b64", "13b_b1", "large_vocab"):
-            if name == args.workload:
-                continue
+
+        def variant(label, name, steps, full, **over):
+            a2 = copy.copy(args)
+            a2.tree_attention, a2.verify_sample, a2.trace = 0, 0.0, 0
             w2 = synth.WORKLOADS[name]
-            sec = run_workload(torch, D, synth, SD, w2, w2.threshold, args, 200, 10, "paced", also_graph=True,
-                               cpu_budget=min(args.cpu_budget, 5.0), W_cache=W_cache)
+            thr2 = over.pop("threshold", None)
+            for key, val in over.items():
+                setattr(a2, key, val)
+            if a2.mode != "default":
+                w2 = synth.paper_mode(w2, a2.mode)
+            if a2.body == "layer":
+                w2 = w2.with_(sigma_w=0.07)
+            sec = run_workload(torch, D, synth, SD, w2, w2.threshold if thr2 is None else thr2, a2, steps, 10, "paced",
+                               also_graph=True, cpu_budget=min(args.cpu_budget, 5.0) if full else 0.0, W_cache=W_cache,
+                               with_kernel=full)
+            sec["label"] = label
             out["secondary"].append(sec)
+
+        # the other thresholds of the 7B B = 1 configuration, and the paper's own parameter settings (same kernel launch)
+        variant("7b_b1, t = 0.1", "7b_b1", 1000, False, threshold=0.1)
+        variant("7b_b1, t = 0.5", "7b_b1", 1000, False, threshold=0.5)
+        variant("7b_b1, Section 3.2's parameters (n = 11, S = {5,7,9}, x = -0.3)", "7b_b1", 300, False, mode="paper")
+        variant("7b_b1, the same checked after every call (Table 1: DDD + Strict)", "7b_b1", 300, False, mode="strict")
+        variant("7b_b1, EAGLE-2's fixed depth 6", "7b_b1", 300, False, mode="eagle2")
+        # the batched half of the metric, with the consumers of the tree on its trees
+        variant("7b_b64", "7b_b64", 200, True, tree_attention=2048, verify_sample=1.0)
+        variant("13b_b1", "13b_b1", 200, True)
+        variant("large_vocab", "large_vocab", 200, True)
+        # the stand-in draft layer between the LM-head calls (472 MB of layer weights per call)
+        variant("7b_b1 with the stand-in draft layer", "7b_b1", 200, False, body="layer")
+        variant("7b_b64 with the stand-in draft layer", "7b_b64", 30, False, body="layer")
     print(json.dumps(out), flush=True)
 
 
