@@ -40,6 +40,11 @@ extern "C" {
  * left in the memory-side cache (on the weight-stream path the results are the same up to the
  * rounding order of the fp32 sum of exponentials, on the GEMM path they are bit-identical). */
 #define DDD_FLAG_FORWARD_SWEEPS 1u
+/* ddd_config.flags, debugging aid: ddd_round_reset (and so every round) first fills the context's scratch - per-slice
+ * partial results, materialised logits and group statistics, list of active rows - with 0xFF bytes, so that a kernel
+ * that read something an earlier round or call left there would give visibly wrong results.  Costs a fill of the
+ * scratch per round (up to 82 MB at the B = 64 shape). */
+#define DDD_FLAG_POISON_SCRATCH 2u
 #define DDD_BMAX 4096        /* largest number of sequences B                                     */
 #define DDD_POOL_MAX 4096    /* largest node pool per sequence for k <= DDD_KMAX                  */
 #define DDD_POOL_WIDE_MAX 65536 /* largest node pool per sequence for wider beams                 */

@@ -153,6 +153,7 @@ def current_stream() -> int:
 
 
 DDD_FLAG_FORWARD_SWEEPS = 1
+DDD_FLAG_POISON_SCRATCH = 2
 
 
 def make_config(B, H, V, k, max_depth, m, threshold, check_mask=0xFFFFFFFF, flags=0) -> ddd_config:

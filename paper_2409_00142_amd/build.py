@@ -45,3 +45,35 @@ def build_library(verbose: bool = True) -> str:
 if __name__ == "__main__":
     build_library()
     print("built", LIB_PATH)
+
+
+def build_sanitized_check(out_dir: str, verbose: bool = False) -> str:
+    """Builds the library once more with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST code (device
+    code is compiled as usual: sanitizers are for the validation and dispatch layer) and links it with
+    tests/sanitize/abi_check.cpp into one executable in `out_dir`; returns its path.  Needs no GPU."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(out_dir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    flags = ["--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+    srcs = [os.path.join(CSRC, s) for s in SOURCES] + [os.path.join(os.path.dirname(PKG_DIR), "tests", "sanitize", "abi_check.cpp")]
+    procs, objs = [], []
+    for src in srcs:
+        obj = os.path.join(out_dir, os.path.basename(src).rsplit(".", 1)[0] + ".o")
+        cmd = [hipcc] + flags + san + ["-x", "hip", "-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    for src, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError(f"sanitized build failed on {src}:\n{out}")
+    exe = os.path.join(out_dir, "abi_check")
+    cmd = [hipcc, "--offload-arch=gfx950", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined", "-o", exe] + objs
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"sanitized link failed:\n{r.stdout}")
+    return exe

@@ -365,6 +365,21 @@ hipError_t launch_step_bookkeep(const StepArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// ---- poison fill of the scratch (debugging aid) -------------------------------------------------
+__global__ __launch_bounds__(256) void poison_kernel(uint32_t* p, size_t n_words) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = 0xFFFFFFFFu;
+}
+
+hipError_t launch_poison(void* p, size_t bytes, hipStream_t stream) {
+  const size_t n = bytes / 4;
+  if (n == 0) return hipSuccess;
+  const size_t want = (n + 255) / 256;
+  hipLaunchKernelGGL(poison_kernel, dim3((unsigned)(want < 2048 ? want : 2048)), dim3(256), 0, stream,
+                     static_cast<uint32_t*>(p), n);
+  return hipGetLastError();
+}
+
 // ---- start of a round ------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void round_reset_kernel(ResetArgs a) {
   const int b = blockIdx.x, lane = threadIdx.x;

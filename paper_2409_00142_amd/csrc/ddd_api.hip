@@ -43,6 +43,7 @@ struct ddd_ctx {
   uint64_t run_rounds, run_waits, run_timeouts;
   double run_max_wait_us;
   uint64_t* trace;               // null, or device [DDD_DMAX + 1][kTraceCallWords]: stamps of every draft call's kernels
+  size_t part_key_bytes, part_sum_bytes, logits_bytes, grp_bytes;   // sizes of the scratch arrays (DDD_FLAG_POISON_SCRATCH)
 };
 
 namespace {
@@ -223,7 +224,7 @@ int ddd_config_validate(const ddd_config* cfg) {
   if (cfg->max_depth < 1 || cfg->max_depth > DDD_DMAX) return DDD_ERR_INVALID_ARG;
   if (cfg->m < 1 || cfg->m > DDD_MMAX) return DDD_ERR_INVALID_ARG;
   if (!(cfg->threshold >= 0.0f)) return DDD_ERR_INVALID_ARG;   // also rejects NaN
-  if ((cfg->flags & ~DDD_FLAG_FORWARD_SWEEPS) != 0) return DDD_ERR_INVALID_ARG;
+  if ((cfg->flags & ~(DDD_FLAG_FORWARD_SWEEPS | DDD_FLAG_POISON_SCRATCH)) != 0) return DDD_ERR_INVALID_ARG;
   int G, nw;
   if (cfg->H < 128 || !pick_split(cfg->H, &G, &nw)) return DDD_ERR_INVALID_ARG;
   const long long nmax = 1LL + cfg->k + (long long)(cfg->max_depth - 1) * cfg->k * cfg->k;
@@ -281,14 +282,19 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->ngrp = ((cfg->V + 63) / 64 + 3) & ~3;
   const size_t rows = (size_t)cfg->B * cfg->k;
   const size_t ns = (cfg->k > DDD_KMAX) ? 1 : (size_t)c->nslice;   // wide beams only use the dense format
-  hipError_t e = hipMalloc(&c->part_key, rows * ns * cfg->k * sizeof(uint64_t));
-  if (e == hipSuccess) e = hipMalloc(&c->part_sum, rows * ns * sizeof(float));
+  c->part_key_bytes = rows * ns * cfg->k * sizeof(uint64_t);
+  c->part_sum_bytes = rows * ns * sizeof(float);
+  c->logits_bytes = c->grp_bytes = 0;
+  hipError_t e = hipMalloc(&c->part_key, c->part_key_bytes);
+  if (e == hipSuccess) e = hipMalloc(&c->part_sum, c->part_sum_bytes);
   if (e == hipSuccess) e = hipMalloc(&c->row_list, rows * sizeof(int32_t));
   if (e == hipSuccess) e = hipMalloc(&c->n_act, sizeof(int32_t));
   if (e == hipSuccess && (rows > DDD_STREAM_ROWS || cfg->k > DDD_KMAX)) {
-    e = hipMalloc(&c->logits, rows * (size_t)cfg->V * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(&c->grp_max, rows * (size_t)c->ngrp * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(&c->grp_sum, rows * (size_t)c->ngrp * sizeof(float));
+    c->logits_bytes = rows * (size_t)cfg->V * sizeof(float);
+    c->grp_bytes = rows * (size_t)c->ngrp * sizeof(float);
+    e = hipMalloc(&c->logits, c->logits_bytes);
+    if (e == hipSuccess) e = hipMalloc(&c->grp_max, c->grp_bytes);
+    if (e == hipSuccess) e = hipMalloc(&c->grp_sum, c->grp_bytes);
     if (e == hipSuccess) e = prepare_lmhead_gemm();
     if (e == hipSuccess && cfg->k > DDD_KMAX) e = prepare_wide();
   }
@@ -506,6 +512,18 @@ int ddd_round_reset(ddd_ctx* c, ddd_state* st, const int32_t* root_token, void* 
   a.k = c->cfg.k;
   a.nmax = c->nmax;
   DDD_HIP(launch_round_reset(a, static_cast<hipStream_t>(stream)));
+  if (c->cfg.flags & DDD_FLAG_POISON_SCRATCH) {
+    // debugging aid: nothing a round reads from the context's scratch may predate the round
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    DDD_HIP(launch_poison(c->part_key, c->part_key_bytes, s));
+    DDD_HIP(launch_poison(c->part_sum, c->part_sum_bytes, s));
+    if (c->logits != nullptr) {
+      DDD_HIP(launch_poison(c->logits, c->logits_bytes, s));
+      DDD_HIP(launch_poison(c->grp_max, c->grp_bytes, s));
+      DDD_HIP(launch_poison(c->grp_sum, c->grp_bytes, s));
+    }
+    DDD_HIP(launch_poison(c->row_list, (size_t)c->cfg.B * c->cfg.k * sizeof(int32_t), s));
+  }
   return DDD_OK;
 }
 

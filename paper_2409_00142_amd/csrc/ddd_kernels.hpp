@@ -143,6 +143,10 @@ struct WideStepArgs {
 hipError_t prepare_wide();    // once per process: enables the kernels' LDS sizes
 hipError_t launch_step_wide(const WideStepArgs& a, hipStream_t stream);
 
+// Fills `bytes` (a multiple of 4) bytes with 0xFF: the context's scratch before a round when
+// DDD_FLAG_POISON_SCRATCH is set (a kernel, not a memset node, so that it can be captured into a graph).
+hipError_t launch_poison(void* p, size_t bytes, hipStream_t stream);
+
 struct ResetArgs {
   ddd_state st;
   const int32_t* root_token;  // [B] or null

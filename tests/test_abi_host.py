@@ -106,7 +106,9 @@ def test_config_validation(D):
     flagged = D.make_config(**base)
     flagged.flags = D.DDD_FLAG_FORWARD_SWEEPS
     assert D.ddd_config_validate(flagged) == D.DDD_OK
-    flagged.flags = 2
+    flagged.flags = D.DDD_FLAG_FORWARD_SWEEPS | D.DDD_FLAG_POISON_SCRATCH
+    assert D.ddd_config_validate(flagged) == D.DDD_OK
+    flagged.flags = 4
     assert D.ddd_config_validate(flagged) == D.DDD_ERR_INVALID_ARG
     assert D.load_library().ddd_config_validate(None) == D.DDD_ERR_INVALID_ARG
 
@@ -143,6 +145,20 @@ def test_create_without_a_device_fails_with_a_status():
     with pytest.raises(D.DDDError) as e:
         D.ddd_create(D.make_config(1, 256, 1000, 4, 6, 16, 0.35))
     assert e.value.code == D.DDD_ERR_NO_DEVICE
+
+
+def test_sanitized_host_build_of_the_abi_checks(tmp_path):
+    """The library's host code (argument validation, size arithmetic, dispatch) compiled with AddressSanitizer and
+    UndefinedBehaviorSanitizer and driven through every entry point's rejection paths by tests/sanitize/abi_check.cpp:
+    extreme field values, null pointers, sizes beyond the limits.  Device code is compiled as usual and nothing is
+    launched, so this runs without a GPU."""
+    import subprocess
+    from paper_2409_00142_amd.build import build_sanitized_check
+    exe = build_sanitized_check(str(tmp_path / "san"))
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0 and "ABI_SANITIZE_OK" in r.stdout, (r.stdout[-2000:], r.stderr[-4000:])
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr, r.stderr[-4000:]
 
 
 def test_product_package_does_not_import_the_oracle():

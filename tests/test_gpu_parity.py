@@ -580,6 +580,41 @@ def test_round_graph_replays_match_eager_and_are_deterministic(gpu):
         g.close()
 
 
+@pytest.mark.parametrize("wname,B", [("tiny", 2), ("tiny", 5), ("7b_b1", 1), ("wide_k20", 2)])
+def test_poisoned_scratch_changes_nothing(gpu, wname, B):
+    """DDD_FLAG_POISON_SCRATCH fills the context's scratch with 0xFF bytes before every round: a round that read
+    anything an earlier round or call left there would differ.  Eager, graph and host-paced rounds leave the same
+    bytes as a context without the flag (weight-stream path, MFMA path with chained row lists, wide beams)."""
+    torch, D, SD = gpu
+    wl = (WIDE[wname] if wname in WIDE else synth.WORKLOADS[wname]).with_(B=B)
+    print(f"[case] poisoned scratch {wname} B={B}", flush=True)
+    g = SD.GpuWorkload(wl, debug=False)
+    try:
+        gp = SD.GpuWorkload(wl, W_bits=g.W_bits, debug=False, flags=D.DDD_FLAG_POISON_SCRATCH)
+        try:
+            side = torch.cuda.Stream()
+            gp.capture(side)
+            for rnd in range(4):
+                g.set_round(rnd)
+                g.enqueue_round()
+                want = g.snapshot()
+                for how in ("eager", "graph", "paced"):
+                    gp.set_round(rnd)
+                    torch.cuda.synchronize()
+                    if how == "eager":
+                        gp.enqueue_round(side.cuda_stream)
+                    elif how == "graph":
+                        gp.launch(side.cuda_stream)
+                    else:
+                        gp.run_round(side.cuda_stream)
+                    side.synchronize()
+                    _same_round(gp.snapshot(), want)
+        finally:
+            gp.close()
+    finally:
+        g.close()
+
+
 def test_sweep_direction_changes_only_the_rounding_of_lse(gpu):
     """Odd draft calls walk W backwards unless DDD_FLAG_FORWARD_SWEEPS is set: the same rounds with and without
     the flag give the same trees; scores agree to the rounding order of the fp32 sum of exponentials."""
