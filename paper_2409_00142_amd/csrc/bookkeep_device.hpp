@@ -70,17 +70,30 @@ __device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, RowHe
     loc = 0;
 #pragma unroll
     for (int i = 0; i < HPL; ++i) loc = umax64(loc, h.q0[i]);
-    const uint64_t best = wave_max_u64(loc);
+    // The high words (the logits) decide unless two slices' fronts tie in them: one 32-bit wave maximum and the
+    // ballot of its holders; only a tie needs the second reduction over the low words (the tokens).
+    const uint32_t hi = (uint32_t)(loc >> 32);
+    const uint32_t M = wave_max_u32(hi);
+    const unsigned long long holders = __ballot(hi == M);
+    uint64_t best;
+    int owner;
+    if (__popcll(holders) == 1) {      // uniform
+      owner = __ffsll(holders) - 1;
+      best = ((uint64_t)M << 32) | (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)loc, owner);
+    } else {
+      const uint32_t L = wave_max_u32(hi == M ? (uint32_t)loc : 0u);
+      best = ((uint64_t)M << 32) | L;
+      owner = __ffsll((unsigned long long)__ballot(loc == best)) - 1;
+    }
     if (lane == round) my_key = best;
     if (best == 0ull) break;           // uniform: fewer than k keys in the row
-    // Keys are distinct (every token sits in one slice), so exactly one slot of one lane holds the best:
+    // Keys are distinct (every token sits in one slice), so exactly one slot of the owner lane holds the best:
     // its index is made uniform and only that slot's update is issued (the wave would otherwise execute
     // the update of every slot for the sake of one lane).
     int which = -1;
 #pragma unroll
     for (int i = 0; i < HPL; ++i)
       if (h.q0[i] == best) which = i;
-    const int owner = __ffsll((unsigned long long)__ballot(which >= 0)) - 1;
     const int iu = __builtin_amdgcn_readlane(which, owner);
 #pragma unroll
     for (int i = 0; i < HPL; ++i)
@@ -206,6 +219,9 @@ struct StepSmem {
   TreeSmem tsm;
   int tok[kKM][kKM];
   float lp[kKM][kKM];
+  uint64_t cand[kKM * kKM];   // beam keys of the k*k candidates (beam update by the whole block)
+  int rank[kKM * kKM];        // number of candidates with a larger key
+  float newlps[kKM];          // logprobsum of the new beam
   int stopped;
 };
 
@@ -248,11 +264,75 @@ __device__ __forceinline__ bool step_bookkeep_block(const StepArgs& a, int b, in
     if (!dense && heads.q2[kHPL - 1] == 1ull) trace[7] = 1;       // (never true: keys are never 1)
     trace[1] = (uint64_t)wall_clock64();
   }
+  // One wave per row (every call after the prompt call, launched with 64 * k threads): the whole block takes
+  // part in the beam update.  Otherwise (the prompt call's single row; fewer waves than rows) wave 0 does it
+  // from the rows' results in LDS.
+  const bool by_block = g.step >= 1 && nwaves >= rows;
   if (wave < rows) {
     if (!dense) merge_row_dispatch(pk, heads, a.nslice, g.k, lane, key, lse);
-    step_publish_row(a, sm, wave, row, lane, key, lse);
+    if (!by_block) step_publish_row(a, sm, wave, row, lane, key, lse);
   }
   if (trace != nullptr) trace[2] = (uint64_t)wall_clock64();
+  if (by_block) {
+    // ---- Algorithm 1's beam update by all k waves: wave i holds row i's k candidates in its lanes j < k ------
+    const int k = g.k, kk = k * k;
+    const int base = 1 + k + (g.step - 1) * kk;
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const bool owner = wave < rows && lane < k;
+    const int f = wv * k + lane;                       // flat index of this lane's candidate
+    float sc = 0.f;
+    int tkn = 0;
+    if (wave < rows) {
+      // the parent's logprobsum and pool id: lane i of every wave loaded slot i's
+      const float plps = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(old_lps), wv));
+      const int pnode = __builtin_amdgcn_readlane(old_node, wv);
+      if (a.lse_dbg != nullptr && lane == 0) a.lse_dbg[row] = lse;
+      if (owner) {
+        tkn = key_token(key);
+        sc = __fadd_rn(plps, key_value(key) - lse);    // logprob = logit - lse, then one fp32 add
+        const size_t pn = (size_t)b * g.nmax + base + f;
+        g.st.pool_token[pn] = tkn;
+        g.st.pool_parent[pn] = pnode;
+        g.st.pool_depth[pn] = g.step + 1;
+        g.st.pool_score[pn] = sc;
+        sm.cand[f] = beam_key(sc, tkn, f);
+        sm.rank[f] = 0;
+      }
+    }
+    __syncthreads();
+    // rank = number of larger keys (keys are distinct: the flat index is part of them); the k*k comparisons of a
+    // candidate are shared by the 64 / k lane groups of its wave
+    if (wave < rows) {
+      const int P = 64 / k, part = lane / k, j = lane - part * k;
+      if (part < P) {
+        const uint64_t mine = sm.cand[wv * k + j];
+        const int chunk = (kk + P - 1) / P, lo = part * chunk, hi = min(kk, lo + chunk);
+        int cnt = 0;
+        for (int x = lo; x < hi; ++x) cnt += (sm.cand[x] > mine) ? 1 : 0;
+        if (cnt != 0) atomicAdd(&sm.rank[wv * k + j], cnt);
+      }
+    }
+    __syncthreads();
+    if (owner) {
+      const int rk = sm.rank[f];
+      if (rk < k) {                                    // this candidate is slot rk of the new beam
+        g.st.beam_node[(size_t)b * k + rk] = base + f;
+        g.st.beam_token[(size_t)b * k + rk] = tkn;
+        g.st.beam_parent_slot[(size_t)b * k + rk] = wv;
+        g.st.logprobsum[(size_t)b * k + rk] = sc;
+        sm.newlps[rk] = sc;
+      }
+    }
+    if (tid == 0) {
+      g.st.n_nodes[b] = base + kk;
+      g.st.steps[b] = g.step + 1;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      const bool cont = stop_test(g, b, lane, lane < k ? sm.newlps[lane] : 0.f, g.step + 1);
+      if (lane == 0 && !cont) sm.stopped = 1;
+    }
+  } else {
   for (int rw = wave + nwaves; rw < rows; rw += nwaves) {   // fewer waves than rows: further passes
     const size_t row2 = row0 + rw;
     const uint64_t* pk2 = a.part_key + row2 * (dense ? 1 : a.nslice) * g.k;
@@ -273,6 +353,7 @@ __device__ __forceinline__ bool step_bookkeep_block(const StepArgs& a, int b, in
     const float v = beam_update(g, b, lane, &sm.tok[0][0], &sm.lp[0][0], kKM, old_lps, old_node);
     const bool cont = stop_test(g, b, lane, v, g.step + 1);
     if (lane == 0 && !cont) sm.stopped = 1;
+  }
   }
   __syncthreads();                                // also orders wave 0's pool writes before the reads below
   if (trace != nullptr) trace[3] = (uint64_t)wall_clock64();

@@ -148,7 +148,7 @@ int slices_for(const ddd_ctx* c, int n_rows) { return gemm_path(c, n_rows) ? 0 :
 // DDD_STREAM_ROWS rows, the MFMA GEMM over the compacted active rows otherwise.
 // list_ready: the previous call's bookkeeping launch has already written the list of active rows (GEMM path).
 int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const uint8_t* row_active, float* logits_dbg,
-                   int reverse, hipStream_t s, bool list_ready = false, int trace_step = -1) {
+                   int reverse, hipStream_t s, bool list_ready = false, int trace_step = -1, bool eager_loads = false) {
   if (gemm_path(c, n_rows)) {
     float* out = logits_dbg ? logits_dbg : c->logits;
     if (!list_ready) DDD_HIP(launch_build_row_list(row_active, n_rows, c->row_list, c->n_act, s));
@@ -183,6 +183,7 @@ int enqueue_stream(ddd_ctx* c, const void* W, const void* hid, int n_rows, const
     a.ntiles = c->ntiles;
     a.nw = c->nw;
     a.reverse = (c->cfg.flags & DDD_FLAG_FORWARD_SWEEPS) ? 0 : reverse;
+    a.eager_loads = eager_loads ? 1 : 0;
     a.trace = (c->trace != nullptr && trace_step >= 0 && r0 == 0) ? c->trace + (size_t)trace_step * kTraceCallWords : nullptr;
     DDD_HIP(launch_lmhead_stream(a, c->G, c->nslice, s));
   }
@@ -618,7 +619,8 @@ int draft_step(ddd_ctx* c, int32_t step, const void* W, const void* hid, ddd_sta
   a.next_row_list = c->row_list;
   a.next_n_act = c->n_act;
   a.trace = c->trace ? c->trace + (size_t)step * kTraceCallWords + DDD_STATIC_SLICES * kTraceStreamWords : nullptr;
-  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, step & 1, s, chain && step >= 1, step);
+  // publish = the host-paced round: it queues at most one call per round that every sequence skips
+  int rc = enqueue_stream(c, W, hid, n_rows, flags, logits_dbg, step & 1, s, chain && step >= 1, step, publish);
   if (rc != DDD_OK) return rc;
   if (c->cfg.k > DDD_KMAX) {
     WideStepArgs w = wide_args(c, a.beam);
@@ -940,6 +942,7 @@ int ddd_lmhead_topk_static(const ddd_config* cfg, const void* W, const void* hid
   a.ntiles = ntiles;
   a.nw = nw;
   a.reverse = 0;
+  a.eager_loads = 0;
   a.trace = nullptr;
   DDD_HIP(launch_lmhead_stream(a, G, nslice, s));
   MergeArgs m;

@@ -117,6 +117,7 @@ struct StreamArgs {
   float* logits_dbg;          // fp32 [R][V] or null
   int H, V, R, k, ntiles, nw;
   int reverse;                // walk every slice's tiles from the last to the first
+  int eager_loads;            // request the first tile of W before the row flags are known (skipped calls are rare)
   uint64_t* trace;            // null, or [nslice][kTraceStreamWords] device words: wall-clock stamps of every workgroup
 };
 // G = 128-wide K groups per streaming wave (1, 2 or 4); H == 128 * G * nw.

@@ -31,22 +31,28 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
   const int NW = a.nw;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
-  if (a.row_active != nullptr) {  // nothing to do if every row of this pass is inactive (uniform)
-    // one load per lane and a ballot: a single memory round trip before the launch can retire
+  // Nothing to do if every row of this pass is inactive (uniform): one load per lane and a ballot.  Normally that
+  // round trip comes first, so that a skipped call retires at once.  A caller that knows skipped calls to be rare
+  // (the host-paced round queues at most one per round) sets eager_loads: the first tile of W and the hidden rows
+  // are requested before the flags are looked at, and the check costs an executed call nothing.
+  const bool check_late = a.row_active != nullptr && a.eager_loads != 0;
+  if (a.row_active != nullptr && !a.eager_loads) {
     const int on = (lane < a.R) ? a.row_active[lane] : 0;
     if (__ballot(on != 0) == 0ull) return;
   }
+  int on_late = 1;     // requested now, looked at once the first tile's requests are out
+  if (check_late) on_late = (lane < a.R) ? a.row_active[lane] : 0;
 
   const int nslice = gridDim.x, slice = blockIdx.x;
   uint64_t* const trace = a.trace ? a.trace + (size_t)slice * kTraceStreamWords : nullptr;
   if (trace != nullptr && tid == 0) trace[0] = (uint64_t)wall_clock64();
   // The vocabulary is cut into nslice * nt tiles of equal height (V / (nslice * nt) <= 16 rows, i.e. 15 or 16
-  // rows each at 32000 rows over 256 slices) and slice i owns tiles i, i + nslice, i + 2 nslice, ...: every
-  // workgroup fetches the same amount, and at any time the workgroups together read one contiguous window of W
-  // that moves through the matrix.  (With one contiguous range of rows per workgroup the workgroups that owned
-  // the odd megabytes of W finished 3 us after the others, launch after launch: which addresses are served faster
-  // is a property of the memory system, so every workgroup gets its share of all of them.)  A tile's missing
-  // rows repeat its last row (the same cache lines) and are masked in the epilogue.
+  // rows each at 32000 rows over 256 slices) and slice i owns every nslice-th tile (the column rotated by one per
+  // step): every workgroup fetches the same amount, and at any time the workgroups together read one contiguous
+  // window of W that moves through the matrix (against one contiguous range of rows per workgroup: 53 -> 50 us per
+  // launch at the 7B shape when W comes from HBM, 64 -> 60 us at the 13B shape).  A tile's missing rows repeat its
+  // last row (the same cache lines) and are masked in the epilogue.  (Workgroups with an odd index - the odd XCDs -
+  // finish about 3 us after the even ones whatever they read; the timestamps of ddd_trace_read show it.)
   const int nt = (a.V + 16 * nslice - 1) / (16 * nslice);
   const long long NT = (long long)nslice * nt;
   // Sweep direction: calls alternate, so that a call starts with the part of W its predecessor read
@@ -96,6 +102,10 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
           ring[g][i] = *reinterpret_cast<const u32x4*>(wbase + (size_t)row * a.H + g * 128);
         }
     }
+    if (check_late) {   // the requests above are simply dropped if nothing is active
+      asm volatile("" : "+v"(on_late));   // keeps the compiler from waiting for the flags before the requests are out
+      if (__ballot(on_late != 0) == 0ull) return;
+    }
     // every tile but the last refills the ring with the next tile while it is consumed
     for (int t = 0; t + 1 < nt; ++t) {
       const f32x4 acc = stream_tile<G, true>(ring, bfrag, mystage, wr_off, rd_off, wbase, a.H, tile_lo(t + 1) + lrow,
@@ -117,6 +127,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
   } else {
     // ------------------------------ epilogue wave ------------------------------
     // lane = (vb, r): rows 4*vb .. 4*vb+3 of the tile for hidden row r, exactly the MFMA C layout
+    if (check_late && __ballot(on_late != 0) == 0ull) return;
     const int r = lane & 15, vb = lane >> 4;
     const bool row_ok = r < a.R;
     float m_run = -INFINITY, s_run = 0.f;
