@@ -301,6 +301,15 @@ def kernel_roofline(torch, D, SD, g, wl, iters, side, traffic_path):
             side.synchronize()
         mfma_ceiling = blocks * 4 * it * 8 * 32768.0 / (m0.elapsed_time(m1) * 1e-3) / 1e12
 
+    # a plain device-to-device copy of W (known size: reads and writes V*H*2 bytes): the reference the
+    # rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled by
+    with torch.cuda.stream(side):
+        wcopy = torch.empty_like(g.W)
+        for _ in range(3):
+            wcopy.copy_(g.W)
+        side.synchronize()
+        del wcopy
+
     # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload (null if none)
     traffic, source = None, None
     if os.path.exists(traffic_path):
@@ -363,6 +372,7 @@ def run_workload(torch, D, synth, SD, wl, thr, args, steps, warmup, launch_mode,
     side = torch.cuda.Stream()
     launchers = {"paced": lambda: g.run_round(side.cuda_stream), "eager": lambda: g.enqueue_round(side.cuda_stream),
                  "graph": lambda: g.launch(side.cuda_stream)}
+    also_graph = also_graph and args.graph_rounds > 0
     if launch_mode == "graph" or also_graph:
         g.capture(side)
     r = time_rounds(torch, g, launchers[launch_mode], steps, warmup, side)
@@ -382,7 +392,7 @@ def run_workload(torch, D, synth, SD, wl, thr, args, steps, warmup, launch_mode,
     if launch_mode == "paced":
         modes["paced"]["host_waits"] = D.ddd_round_run_stats(g.ctx)
     if also_graph and launch_mode != "graph":
-        n2 = max(steps, 200)
+        n2 = max(steps, args.graph_rounds)
         r2 = time_rounds(torch, g, launchers["graph"], n2, warmup, side)
         modes["graph"] = {"rounds_per_s": n2 * wl.B / r2["wall"], "us_per_round": 1e6 * r2["wall"] / n2, "rounds_timed": n2}
         log(f"[bench] the same rounds as one hipGraph each: {modes['graph']['rounds_per_s']:.1f}/s, "
@@ -474,6 +484,8 @@ def main():
     ap.add_argument("--traffic", default=None,
                     help="JSON file with the HBM bytes per launch from rocprofv3 --pmc runs "
                          "(default: profiles/traffic_<workload>.json)")
+    ap.add_argument("--graph-rounds", type=int, default=200,
+                    help="rounds (at least) of the second timing leg, the same rounds launched as one hipGraph each; 0 skips it")
     ap.add_argument("--trace", type=int, default=0, metavar="N",
                     help="also run N rounds with the context's device-timestamp trace on (B*k <= 16 workloads) and add the "
                          "breakdown of a draft call - inside the weight-stream launch, between launches, inside the "
