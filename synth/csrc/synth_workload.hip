@@ -43,14 +43,20 @@ struct BodyArgs {
   int step;
 };
 
-// grid: (rows, ceil(H / 256)); block 256: one element per thread
+// grid: (rows, parts of a row); block 256: a thread makes pairs of neighbouring elements (one 4-byte store each).
+// With hundreds of rows a row is one workgroup: the chain of dependent loads that identifies the row's node (flag,
+// beam entry, its parent) is walked once per row; a few rows are cut into parts so that the chip is still used.
+__device__ inline float synth_element(uint64_t nk, int e, float scale) {
+  const uint64_t z = mix64(nk + (uint64_t)(e + 1) * kGold);
+  const int s = (int)((z & 0xFFFFu) + ((z >> 16) & 0xFFFFu) + ((z >> 32) & 0xFFFFu) + (z >> 48)) - 131070;
+  return __fmul_rn((float)s, scale);
+}
+
 __global__ __launch_bounds__(256) void synth_body_kernel(BodyArgs a) {
   const int k = a.p.cfg.k, H = a.p.cfg.H;
   const int row = blockIdx.x;
   const int b = (a.step == 0) ? row : row / k;
   if (!a.st.active[b]) return;
-  const int e = blockIdx.y * 256 + threadIdx.x;
-  if (e >= H) return;
   const uint64_t skey = stream_key(a.p.seed, b, *a.p.round_ctr);
   uint32_t parent, token;
   if (a.step == 0) {
@@ -64,11 +70,8 @@ __global__ __launch_bounds__(256) void synth_body_kernel(BodyArgs a) {
     token = (uint32_t)a.st.beam_token[(size_t)b * k + i];
   }
   const uint64_t nk = node_key(skey, parent, token);
-  const uint64_t z = mix64(nk + (uint64_t)(e + 1) * kGold);
-  const int s = (int)((z & 0xFFFFu) + ((z >> 16) & 0xFFFFu) + ((z >> 32) & 0xFFFFu) + (z >> 48)) - 131070;
-  float val = __fmul_rn((float)s, a.p.scale_depth[a.step]);
+  int pi = -1;
   if (a.p.n_plant > 0) {
-    int pi = -1;
     const uint64_t ur = mix64(skey ^ kRoundPlant);
     if ((uint32_t)(ur >> 40) < a.p.plant_round_p24) {
       pi = (int)((ur & 0xFFFFu) % (uint32_t)a.p.n_plant);
@@ -76,9 +79,17 @@ __global__ __launch_bounds__(256) void synth_body_kernel(BodyArgs a) {
       const uint64_t un = mix64(nk ^ kRowPlant);
       if ((uint32_t)(un >> 40) < a.p.plant_row_p24) pi = (int)((un & 0xFFFFu) % (uint32_t)a.p.n_plant);
     }
-    if (pi >= 0) val = __fadd_rn(val, a.p.plant_dir[(size_t)pi * H + e]);
   }
-  a.hid[(size_t)row * H + e] = f32_to_bf16_rne(val);
+  const float scale = a.p.scale_depth[a.step];
+  uint32_t* out = reinterpret_cast<uint32_t*>(a.hid + (size_t)row * H);   // H is even (a multiple of 128)
+  for (int e = 512 * blockIdx.y + 2 * threadIdx.x; e < H; e += 512 * gridDim.y) {
+    float v0 = synth_element(nk, e, scale), v1 = synth_element(nk, e + 1, scale);
+    if (pi >= 0) {
+      v0 = __fadd_rn(v0, a.p.plant_dir[(size_t)pi * H + e]);
+      v1 = __fadd_rn(v1, a.p.plant_dir[(size_t)pi * H + e + 1]);
+    }
+    out[e >> 1] = (uint32_t)f32_to_bf16_rne(v0) | ((uint32_t)f32_to_bf16_rne(v1) << 16);
+  }
 }
 
 struct TargetArgs {
@@ -254,8 +265,11 @@ int ddd_synth_draft_body(void* user, int32_t step, const ddd_state* st, void* hi
   a.hid = static_cast<uint16_t*>(hid_out_bf16);
   a.step = step;
   const int rows = (step == 0) ? p->cfg.B : p->cfg.B * p->cfg.k;
-  hipLaunchKernelGGL(synth_body_kernel, dim3(rows, (p->cfg.H + 255) / 256), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), a);
+  if (p->cfg.H % 2 != 0) return DDD_ERR_INVALID_ARG;
+  int parts = 512 / rows;                                   // about 512 workgroups
+  const int max_parts = (p->cfg.H + 511) / 512;
+  parts = parts < 1 ? 1 : (parts > max_parts ? max_parts : parts);
+  hipLaunchKernelGGL(synth_body_kernel, dim3(rows, parts), dim3(256), 0, static_cast<hipStream_t>(stream), a);
   return hipGetLastError() == hipSuccess ? DDD_OK : DDD_ERR_HIP;
 }
 
