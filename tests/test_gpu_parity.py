@@ -7,6 +7,7 @@ import pytest
 import synth
 from oracle import ddd_oracle as O
 from oracle import synth_round as SR
+from replay_util import take_over_stop_decision
 
 pytestmark = pytest.mark.gpu
 
@@ -432,10 +433,7 @@ def _compare_round(g, snap, wl, rnd, thr, logits_dbg, lse_dbg, check_own_logits_
             AMBIGUOUS["forced"] += 1
             print(f"[info] {ctx_msg}: stop test after call {fix[0]} within {STOP_MARGIN} of the threshold, "
                   f"the GPU's decision ({'continue' if fix[1] else 'stop'}) taken over", flush=True)
-            if fix[1]:
-                mask &= ~(1 << fix[0])
-            else:
-                mask, t_run = 1 << fix[0], 2.0
+            mask, t_run = take_over_stop_decision(mask, t_run, fix[0], fix[1])
         steps_out.append(res.steps)
         assert gpu_steps == res.steps, ctx_msg
         assert int(snap["active"][b]) == 0, ctx_msg
@@ -704,8 +702,8 @@ def _edge_configs():
     rnd = random.Random(11)
     out = [(1, 1, 1, 64, 1, 0.0), (2, 1, 5, 64, 3, 0.0), (3, 2, 1, 100, 60, 0.3), (1, 16, 2, 64, 128, 0.0),
            (17, 3, 4, 257, 7, 0.2), (9, 16, 3, 1000, 16, 0.1), (2, 20, 2, 300, 128, 0.3), (1, 128, 2, 700, 128, 0.0),
-           # the whole vocabulary is in the beam, so P = 1 up to rounding, against t = 1: stop tests that fall within
-           # 1e-9 of the threshold (the comparison takes such a decision over from the GPU and checks the rest)
+           # the whole vocabulary is in the beam after the prompt call, so P = 1 up to the rounding of the fp32
+           # logprobs (about 1e-7), against t = 1: the closest a stop test comes to its threshold here
            (3, 4, 3, 4, 7, 1.0), (2, 8, 4, 8, 16, 1.0)]
     while len(out) < 22:
         B, k = rnd.choice([1, 2, 3, 8, 17, 33]), rnd.choice([1, 2, 3, 5, 10, 16, 20, 50])

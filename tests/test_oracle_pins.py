@@ -346,6 +346,32 @@ def test_threshold_extremes_and_empty_S(tiny):
         assert a.P == b.P
 
 
+def test_taking_over_one_stop_decision_leaves_the_earlier_calls_alone(tiny):
+    """The replay comparisons may take one borderline stop decision over from the other side; the parameters they
+    use for that must change nothing before the call in question and decide that call as asked."""
+    from replay_util import take_over_stop_decision
+    wl, W = tiny
+    seen = 0
+    for rnd in range(12):
+        base, _, _ = SR.oracle_round(wl, W, None, 0, rnd)
+        s = base.steps
+        if s < wl.D:                                         # stopped after call s: force it to go on
+            mask, t = take_over_stop_decision(wl.check_mask, wl.threshold, s, True)
+            r, _, _ = SR.oracle_round(wl.with_(check_mask=mask), W, None, 0, rnd, threshold=t)
+            assert r.steps > s
+            for a, b in zip(base.records, r.records):
+                assert list(a.beam.node) == list(b.beam.node) and a.P == b.P
+            seen += 1
+        if s >= 2:                                           # went on after call s - 1: force it to stop there
+            mask, t = take_over_stop_decision(wl.check_mask, wl.threshold, s - 1, False)
+            r, _, _ = SR.oracle_round(wl.with_(check_mask=mask), W, None, 0, rnd, threshold=t)
+            assert r.steps == s - 1
+            for a, b in zip(r.records, base.records):
+                assert list(a.beam.node) == list(b.beam.node) and a.P == b.P
+            seen += 1
+    assert seen >= 8
+
+
 def test_m_at_least_N_selects_everything(tiny):
     wl, W = tiny
     res, _, _ = SR.oracle_round(wl.with_(m=200), W, None, 0, 1)
