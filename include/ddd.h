@@ -196,6 +196,30 @@ int ddd_tree_finalize(ddd_ctx* ctx, const ddd_state* st, ddd_tree* out, void* st
 int ddd_verify_accept(ddd_ctx* ctx, const ddd_tree* tree, const int32_t* target_argmax, int32_t* accept_len,
                       int32_t* accept_path, int32_t* bonus_token, void* stream);
 
+/* Running statistics of the rounds a context verifies, kept on the device (Section 3.3 and Table 1 report the
+ * mean accepted length per round; the number of draft calls a round makes is the quantity Section 2 makes
+ * dynamic).  All arrays are device memory owned by the caller, int64, any of them may be NULL:
+ *   rounds            [1]   rounds verified (every sequence of the batch has been walked)
+ *   depth_hist        [32]  sequences by their number of draft calls (ddd_state.steps; needs `steps`)
+ *   accept_hist       [32]  sequences by accepted length
+ *   batch_depth_hist  [32]  rounds by the number of draft calls of their deepest sequence (needs `steps`)
+ *   steps             device int32[B]: the ddd_state.steps of the rounds being verified, or NULL
+ * Values above 31 are counted in entry 31.  While a set is bound, ddd_verify_accept and ddd_verify_sample add
+ * their round to it inside their own launch (integer atomics: the totals do not depend on the order; `rounds` and
+ * `batch_depth_hist` are written once per launch, by the sequence that finishes last).  The caller zeroes the
+ * arrays and reads them, ordered on the stream like any other output.  ddd_stats_bind(ctx, NULL) unbinds.  The
+ * pointers are read when a verify call is enqueued (or captured): bind before capturing a graph that verifies.
+ * Two verify launches of one context that overlap in time would share the round's arrival counter: keep them on
+ * one stream. */
+typedef struct ddd_round_stats {
+  int64_t* rounds;
+  int64_t* depth_hist;
+  int64_t* accept_hist;
+  int64_t* batch_depth_hist;
+  const int32_t* steps;
+} ddd_round_stats;
+int ddd_stats_bind(ddd_ctx* ctx, const ddd_round_stats* stats);
+
 /* Sampled accept walk at temperature T > 0.  The paper evaluates temperature 0 only (Section 3.1); what it
  * fixes is that the emitted tokens follow the target model's distribution (Section 1).  A drafted child is a
  * deterministic proposal, so it is accepted with the probability the target gives its token, and after a

@@ -55,7 +55,9 @@ int ddd_synth_round_stats(int64_t* round_ctr, const int32_t* steps, const int32_
                           int64_t* depth_hist, int64_t* accept_hist, int64_t* batch_depth_hist, void* stream);
 
 /* ddd_post_fn that runs the stand-in target and the accept walk in one host call: ddd_synth_target_argmax,
- * ddd_verify_accept, ddd_synth_round_stats and, if hash_tokens is not NULL, ddd_synth_hash_tokens on it.
+ * ddd_verify_accept, ddd_synth_round_stats (left out if its three histograms are all NULL: the round counter must
+ * then advance by other means, e.g. as the `rounds` word of statistics bound to the context with ddd_stats_bind,
+ * which the accept walk's own launch keeps) and, if hash_tokens is not NULL, ddd_synth_hash_tokens on it.
  * user = const ddd_synth_post_args* (host memory that outlives the call); every pointer inside is device memory
  * except params and ctx. */
 typedef struct ddd_synth_post_args {

@@ -58,6 +58,10 @@ class ddd_tree(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _TREE_FIELDS]
 
 
+class ddd_round_stats(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("rounds", "depth_hist", "accept_hist", "batch_depth_hist", "steps")]
+
+
 class ddd_body_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "k", "H", "F", "V", "max_depth", "L")]
 
@@ -108,6 +112,7 @@ def load_library() -> C.CDLL:
         "ddd_round_enqueue": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_capture": (C.c_int, [vp, vp, stp, trp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ddd_round_launch": (C.c_int, [vp, vp]),
+        "ddd_stats_bind": (C.c_int, [vp, vp]),
         "ddd_trace_enable": (C.c_int, [vp, i32]),
         "ddd_trace_read": (C.c_int, [vp, vp, sz]),
         "ddd_trace_words": (sz, []),
@@ -394,6 +399,16 @@ def ddd_profile_lmhead(ctx, W, hid, n_rows, iters, stream=None):
                                                     current_stream() if stream is None else stream),
            "ddd_profile_lmhead")
     return mean.value, mn.value
+
+
+def ddd_stats_bind(ctx, rounds=None, depth_hist=None, accept_hist=None, batch_depth_hist=None, steps=None) -> None:
+    """Binds device statistics arrays (int64; `steps` int32) that the context's verify calls add their rounds to;
+    all None unbinds.  The tensors must outlive the binding."""
+    if rounds is None and depth_hist is None and accept_hist is None and batch_depth_hist is None:
+        _check(load_library().ddd_stats_bind(ctx, None), "ddd_stats_bind")
+        return
+    s = ddd_round_stats(_ptr(rounds), _ptr(depth_hist), _ptr(accept_hist), _ptr(batch_depth_hist), _ptr(steps))
+    _check(load_library().ddd_stats_bind(ctx, C.byref(s)), "ddd_stats_bind")
 
 
 def ddd_trace_enable(ctx, on: bool = True) -> None:

@@ -42,6 +42,9 @@ struct ddd_ctx {
   // ddd_round_run's host waits, since the context was created (ddd_round_run_stats)
   uint64_t run_rounds, run_waits, run_timeouts;
   double run_max_wait_us;
+  ddd_round_stats stats;         // caller's statistics arrays (all null: none bound)
+  bool stats_on;
+  uint32_t* stats_sync;          // device [2]: arrivals and deepest sequence of the verify launch in flight (zero between)
   uint64_t* trace;               // null, or device [DDD_DMAX + 1][kTraceCallWords]: stamps of every draft call's kernels
   size_t part_key_bytes, part_sum_bytes, logits_bytes, grp_bytes;   // sizes of the scratch arrays (DDD_FLAG_POISON_SCRATCH)
 };
@@ -302,6 +305,9 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   if (e == hipSuccess) e = prepare_tree_attention();
   c->call_count = nullptr;
   c->active_mask = nullptr;
+  c->stats_sync = nullptr;
+  c->stats_on = false;
+  c->stats = ddd_round_stats{nullptr, nullptr, nullptr, nullptr, nullptr};
   c->progress = nullptr;
   c->progress_dev = nullptr;
   c->round_tag = 0;
@@ -310,6 +316,8 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   c->trace = nullptr;
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->call_count), (DDD_DMAX + 1) * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMemset(c->call_count, 0, (DDD_DMAX + 1) * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->stats_sync), 2 * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMemset(c->stats_sync, 0, 2 * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->active_mask), (DDD_BMAX / 64) * sizeof(uint64_t));
   if (e == hipSuccess) e = hipMemset(c->active_mask, 0, (DDD_BMAX / 64) * sizeof(uint64_t));
   void* host_words = nullptr;
@@ -325,6 +333,7 @@ int ddd_create(const ddd_config* cfg, ddd_ctx** out) {
   if (e != hipSuccess) {
     if (c->call_count) (void)hipFree(c->call_count);
     if (c->active_mask) (void)hipFree(c->active_mask);
+    if (c->stats_sync) (void)hipFree(c->stats_sync);
     if (host_words) (void)hipHostFree(host_words);
     if (c->logits) (void)hipFree(c->logits);
     if (c->grp_max) (void)hipFree(c->grp_max);
@@ -355,6 +364,7 @@ int ddd_destroy(ddd_ctx* c) {
   if (c->trace) (void)hipFree(c->trace);
   (void)hipFree(c->call_count);
   (void)hipFree(c->active_mask);
+  (void)hipFree(c->stats_sync);
   (void)hipHostFree(const_cast<uint32_t*>(c->progress));
   delete c;
   return DDD_OK;
@@ -665,6 +675,33 @@ int ddd_tree_finalize(ddd_ctx* c, const ddd_state* st, ddd_tree* out, void* stre
   return DDD_OK;
 }
 
+namespace {
+StatsArgs stats_args(const ddd_ctx* c) {
+  StatsArgs s{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  if (c->stats_on) {
+    s.rounds = c->stats.rounds;
+    s.depth_hist = c->stats.depth_hist;
+    s.accept_hist = c->stats.accept_hist;
+    s.batch_depth_hist = c->stats.batch_depth_hist;
+    s.steps = c->stats.steps;
+    s.sync = c->stats_sync;
+  }
+  return s;
+}
+}  // namespace
+
+int ddd_stats_bind(ddd_ctx* c, const ddd_round_stats* stats) {
+  if (c == nullptr) return DDD_ERR_INVALID_ARG;
+  if (stats == nullptr) {
+    c->stats_on = false;
+    return DDD_OK;
+  }
+  c->stats = *stats;
+  c->stats_on = stats->rounds != nullptr || stats->depth_hist != nullptr || stats->accept_hist != nullptr ||
+                stats->batch_depth_hist != nullptr;
+  return DDD_OK;
+}
+
 int ddd_verify_accept(ddd_ctx* c, const ddd_tree* tree, const int32_t* target_argmax, int32_t* accept_len,
                       int32_t* accept_path, int32_t* bonus_token, void* stream) {
   if (c == nullptr || !tree_ok(tree) || target_argmax == nullptr || accept_len == nullptr || accept_path == nullptr ||
@@ -672,6 +709,7 @@ int ddd_verify_accept(ddd_ctx* c, const ddd_tree* tree, const int32_t* target_ar
     return DDD_ERR_INVALID_ARG;
   VerifyArgs a;
   a.tree = *tree;
+  a.stats = stats_args(c);
   a.target_argmax = target_argmax;
   a.accept_len = accept_len;
   a.accept_path = accept_path;
@@ -692,6 +730,7 @@ int ddd_verify_sample(ddd_ctx* c, const ddd_tree* tree, const float* target_logi
   if (!(temperature > 0.0f) || !(temperature < 3.0e38f)) return DDD_ERR_INVALID_ARG;
   VerifySampleArgs a;
   a.tree = *tree;
+  a.stats = stats_args(c);
   a.logits = target_logits;
   a.u_accept = u_accept;
   a.u_bonus = u_bonus;

@@ -164,8 +164,19 @@ struct FinalizeArgs {
 hipError_t launch_tree_finalize(const FinalizeArgs& a, hipStream_t stream);
 hipError_t launch_tree_finalize_wide(const FinalizeArgs& a, hipStream_t stream);   // pools beyond DDD_POOL_MAX
 
+// Round statistics a verify launch adds to (all null: none kept).
+struct StatsArgs {
+  int64_t* rounds;
+  int64_t* depth_hist;        // [32]
+  int64_t* accept_hist;       // [32]
+  int64_t* batch_depth_hist;  // [32]
+  const int32_t* steps;       // [B] or null
+  uint32_t* sync;             // device [2], zero between launches: arrivals, deepest sequence so far
+};
+
 struct VerifyArgs {
   ddd_tree tree;
+  StatsArgs stats;
   const int32_t* target_argmax;  // [B,m+1]
   int32_t* accept_len;           // [B]
   int32_t* accept_path;          // [B,D+1]
@@ -176,6 +187,7 @@ hipError_t launch_verify_accept(const VerifyArgs& a, hipStream_t stream);
 
 struct VerifySampleArgs {
   ddd_tree tree;
+  StatsArgs stats;
   const float* logits;           // fp32 [B,m+1,V]: the target model's logits after every tree node
   const double* u_accept;        // [B,m+1] uniforms in [0,1): acceptance test of each tree node
   const double* u_bonus;         // [B,m+1] uniforms in [0,1): bonus draw at each tree node

@@ -15,6 +15,41 @@ hipError_t launch_tree_finalize(const FinalizeArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// Round statistics (Section 3.3 / Table 1: accepted length per round; Section 2: draft calls per round), added by
+// the one thread per sequence that has the sequence's accepted length.  That thread calls stats_begin before its
+// walk: the sequence's depth is read and goes into the round's running maximum while the walk runs, so that the end
+// of the walk waits for nothing.  The sequence that arrives last closes the round: every sequence's depth has gone
+// into the maximum before its arrival (the arrival's operand depends on the value the maximum returned, so the
+// two atomics cannot pass each other), and the two words are zero again when the launch ends.  A batch of one has
+// nothing to agree on.  Every update is an integer atomic without a returned value where none is needed.
+struct StatsPre {
+  int d;
+  unsigned before;
+};
+__device__ __forceinline__ StatsPre stats_begin(const StatsArgs& s, int b, int B) {
+  StatsPre p{0, 0u};
+  if (s.sync == nullptr) return p;
+  if (s.steps != nullptr) p.d = min(max(s.steps[b], 0), 31);
+  if (B > 1) p.before = atomicMax(s.sync + 1, (unsigned)p.d);
+  return p;
+}
+__device__ __forceinline__ void stats_end(const StatsArgs& s, const StatsPre& p, int B, int len) {
+  if (s.sync == nullptr) return;
+  typedef unsigned long long u64;
+  if (s.accept_hist != nullptr) atomicAdd(reinterpret_cast<u64*>(s.accept_hist + min(max(len, 0), 31)), 1ull);
+  if (s.depth_hist != nullptr && s.steps != nullptr) atomicAdd(reinterpret_cast<u64*>(s.depth_hist + p.d), 1ull);
+  unsigned deepest = (unsigned)p.d;
+  if (B > 1) {
+    unsigned one = 1u;
+    asm volatile("" : "+v"(one) : "v"(p.before));
+    if (atomicAdd(s.sync, one) != (unsigned)(B - 1)) return;
+    deepest = atomicExch(s.sync + 1, 0u);
+    atomicExch(s.sync, 0u);
+  }
+  if (s.batch_depth_hist != nullptr && s.steps != nullptr) atomicAdd(reinterpret_cast<u64*>(s.batch_depth_hist + deepest), 1ull);
+  if (s.rounds != nullptr) atomicAdd(reinterpret_cast<u64*>(s.rounds), 1ull);
+}
+
 // Section 1 / Section 3.1 (temperature 0): follow the child whose token equals the target's
 // argmax at the current node until there is none; the argmax there is the bonus token.
 __global__ __launch_bounds__(64) void verify_accept_kernel(VerifyArgs a) {
@@ -26,7 +61,11 @@ __global__ __launch_bounds__(64) void verify_accept_kernel(VerifyArgs a) {
   const int32_t* tgt = a.target_argmax + (size_t)b * T;
   int32_t* path = a.accept_path + (size_t)b * (a.D + 1);
   int cur = 0, len = 0;
-  if (lane == 0) path[0] = 0;
+  StatsPre sp{0, 0u};
+  if (lane == 0) {
+    path[0] = 0;
+    sp = stats_begin(a.stats, b, a.B);
+  }
   for (int it = 0; it < a.D; ++it) {
     const int want = tgt[cur];
     int found = 0x7FFFFFFF;
@@ -43,6 +82,7 @@ __global__ __launch_bounds__(64) void verify_accept_kernel(VerifyArgs a) {
     for (int i = len + 1; i <= a.D; ++i) path[i] = -1;
     a.accept_len[b] = len;
     a.bonus_token[b] = tgt[cur];
+    stats_end(a.stats, sp, a.B, len);
   }
 }
 
@@ -144,6 +184,8 @@ __global__ __launch_bounds__(kVsThreads) void verify_sample_kernel(VerifySampleA
     s_ub[tid] = a.u_bonus[(size_t)b * T + tid];
   }
   const int n = min(a.tree.n_sel[b], a.m) + 1;
+  StatsPre sp{0, 0u};
+  if (tid == 0) sp = stats_begin(a.stats, b, a.B);
   __syncthreads();
   int32_t* path = a.accept_path + (size_t)b * (a.D + 1);
   const int cpb = (V + kVsSub * kVsChunk - 1) / (kVsSub * kVsChunk);      // chunks per block
@@ -315,6 +357,7 @@ __global__ __launch_bounds__(kVsThreads) void verify_sample_kernel(VerifySampleA
     for (int i = len + 1; i <= a.D; ++i) path[i] = -1;
     a.accept_len[b] = len;
     a.bonus_token[b] = bonus;
+    stats_end(a.stats, sp, a.B, len);
   }
 }
 

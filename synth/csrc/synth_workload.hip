@@ -316,10 +316,12 @@ int ddd_synth_post(void* user, const ddd_state* st, const ddd_tree* tree, void* 
   if (rc != DDD_OK) return rc;
   rc = ddd_verify_accept(a->ctx, tree, a->target_argmax, a->accept_len, a->accept_path, a->bonus_token, stream);
   if (rc != DDD_OK) return rc;
-  int64_t* ctr = const_cast<int64_t*>(a->params->round_ctr);   // the round's own counter: the statistics step advances it
-  rc = ddd_synth_round_stats(ctr, st->steps, a->accept_len, a->params->cfg.B, a->depth_hist,
-                             a->accept_hist, a->batch_depth_hist, stream);
-  if (rc != DDD_OK) return rc;
+  if (a->depth_hist != nullptr || a->accept_hist != nullptr || a->batch_depth_hist != nullptr) {
+    int64_t* ctr = const_cast<int64_t*>(a->params->round_ctr);   // the round's own counter: the statistics step advances it
+    rc = ddd_synth_round_stats(ctr, st->steps, a->accept_len, a->params->cfg.B, a->depth_hist,
+                               a->accept_hist, a->batch_depth_hist, stream);
+    if (rc != DDD_OK) return rc;
+  }
   if (a->hash_tokens != nullptr)
     rc = ddd_synth_hash_tokens(a->params->round_ctr, a->hash_tokens, a->params->cfg.B, a->params->cfg.V,
                                a->params->seed, stream);

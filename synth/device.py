@@ -71,9 +71,13 @@ class GpuWorkload:
         pa.accept_len = self.accept_len.data_ptr()
         pa.accept_path = self.accept_path.data_ptr()
         pa.bonus_token = self.bonus.data_ptr()
-        pa.depth_hist = self.depth_hist.data_ptr()
-        pa.accept_hist = self.accept_hist.data_ptr()
-        pa.batch_depth_hist = self.batch_depth_hist.data_ptr()
+        # the histograms and the round counter are kept by the accept walk's own launch (ddd_stats_bind): no
+        # separate statistics launch per round
+        pa.depth_hist = None
+        pa.accept_hist = None
+        pa.batch_depth_hist = None
+        D.ddd_stats_bind(self.ctx, rounds=self.round_ctr, depth_hist=self.depth_hist, accept_hist=self.accept_hist,
+                         batch_depth_hist=self.batch_depth_hist, steps=self.st_t["steps"])
         pa.hash_tokens = None
         self.post_args = pa
         self.captured = False

@@ -90,6 +90,7 @@ int main() {
         DDD_ERR_INVALID_ARG);
   CHECK(ddd_profile_lmhead(nullptr, &word, &word, 1, 1, &f, &f, nullptr) == DDD_ERR_INVALID_ARG);
   CHECK(ddd_trace_enable(nullptr, 1) == DDD_ERR_INVALID_ARG);
+  CHECK(ddd_stats_bind(nullptr, nullptr) == DDD_ERR_INVALID_ARG);
   uint64_t w64 = 0;
   CHECK(ddd_trace_read(nullptr, &w64, 1) == DDD_ERR_INVALID_ARG);
   CHECK(ddd_trace_words() == (size_t)(DDD_DMAX + 1) * DDD_TRACE_CALL_WORDS);

@@ -125,6 +125,7 @@ def test_error_strings_and_null_arguments(D):
     from synth import native
     assert native.load_library().ddd_synth_next_round(None, None) == D.DDD_ERR_INVALID_ARG
     assert lib.ddd_round_run_stats(None, None, None, None, None) == D.DDD_ERR_INVALID_ARG
+    assert lib.ddd_stats_bind(None, None) == D.DDD_ERR_INVALID_ARG
     # the allocation-free entry point validates before it touches a device
     assert lib.ddd_static_scratch_bytes() == 16 * 16 * 256 * 8 + 16 * 256 * 4
     cfg = D.make_config(1, 256, 1000, 4, 6, 16, 0.35)

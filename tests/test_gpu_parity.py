@@ -695,6 +695,46 @@ def test_host_paced_round_matches_enqueued_round(gpu, wname, B):
         g.close()
 
 
+@pytest.mark.parametrize("wname,B", [("tiny", 1), ("tiny", 5), ("tiny", 40), ("7b_b1", 1)])
+def test_round_statistics_kept_by_the_accept_walk(gpu, wname, B):
+    """ddd_stats_bind: the accept walk's own launch counts rounds, draft calls and accepted lengths (Section 3.3 /
+    Table 1 report the mean accepted length).  The totals equal the sums of the per-round outputs, which the other
+    tests compare with the oracle; the round counter the workload generators read is the `rounds` word."""
+    torch, D, SD = gpu
+    wl = synth.WORKLOADS[wname].with_(B=B)
+    print(f"[case] round statistics {wname} B={B}", flush=True)
+    g = SD.GpuWorkload(wl, debug=False)
+    try:
+        g.set_round(3)
+        for h in (g.depth_hist, g.accept_hist, g.batch_depth_hist):
+            h.zero_()
+        want_d, want_a, want_b = np.zeros(32, np.int64), np.zeros(32, np.int64), np.zeros(32, np.int64)
+        for i in range(7):
+            if i % 2 == 0:
+                g.enqueue_round()
+            else:
+                g.run_round()
+            snap = g.snapshot()
+            assert int(g.round_ctr.item()) == 3 + i + 1          # advanced once, by the last sequence to arrive
+            np.add.at(want_d, np.minimum(snap["steps"], 31), 1)
+            np.add.at(want_a, np.minimum(snap["accept_len"], 31), 1)
+            want_b[min(int(snap["steps"].max()), 31)] += 1
+        assert np.array_equal(g.depth_hist.cpu().numpy(), want_d)
+        assert np.array_equal(g.accept_hist.cpu().numpy(), want_a)
+        assert np.array_equal(g.batch_depth_hist.cpu().numpy(), want_b)
+        assert want_d.sum() == 7 * B and len(np.nonzero(want_d)[0]) >= (2 if B > 1 else 1)
+        # unbound: the same rounds leave the arrays and the counter alone
+        D.ddd_stats_bind(g.ctx)
+        g.set_round(3)
+        g.enqueue_round()
+        torch.cuda.synchronize()
+        assert int(g.round_ctr.item()) == 3
+        assert np.array_equal(g.depth_hist.cpu().numpy(), want_d)
+        assert np.array_equal(g.accept_hist.cpu().numpy(), want_a)
+    finally:
+        g.close()
+
+
 def _edge_configs():
     """Seeded small configurations that sit on the edges of the parameter ranges (one beam, one call, one tree
     node, few vocabulary rows, several sequences on every path)."""

@@ -44,8 +44,14 @@ def _run(torch, D, B, V, k, Dm, m, toks, pars, n_sels, logits, T, ua, ub):
         alen = torch.full((B,), -7, dtype=torch.int32, device="cuda")
         apath = torch.full((B, Dm + 1), -7, dtype=torch.int32, device="cuda")
         bonus = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+        # statistics bound without the rounds' depths: accepted lengths and the round count only
+        acc_hist = torch.zeros(32, dtype=torch.int64, device="cuda")
+        n_rounds = torch.zeros(1, dtype=torch.int64, device="cuda")
+        D.ddd_stats_bind(ctx, rounds=n_rounds, accept_hist=acc_hist)
         D.ddd_verify_sample(ctx, tree, lg, T, torch.from_numpy(ua).cuda(), torch.from_numpy(ub).cuda(), alen, apath, bonus)
         torch.cuda.synchronize()
+        assert int(n_rounds.item()) == 1
+        assert np.array_equal(acc_hist.cpu().numpy(), np.bincount(np.minimum(alen.cpu().numpy(), 31), minlength=32))
         return alen.cpu().numpy(), apath.cpu().numpy(), bonus.cpu().numpy()
     finally:
         D.ddd_destroy(ctx)
