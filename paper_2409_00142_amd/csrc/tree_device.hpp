@@ -141,9 +141,207 @@ __device__ __forceinline__ void bitonic_sort_desc(uint64_t* keys, int n2, int ti
   if (n2 < 128) __syncthreads();
 }
 
+// rank[i] = number of keys[0..n) larger than keys[i] (keys distinct, rank zeroed beforehand), by every thread of the block: with fewer keys than threads the comparisons of a key are shared
+// by nthr / n threads.  No barrier inside.
+__device__ __forceinline__ void count_larger_keys(const uint64_t* keys, int n, int* rank, int tid, int nthr) {
+  if (n <= nthr) {                                               // uniform
+    const int P = nthr / n, part = tid / n, i = tid - part * n;
+    if (part < P) {
+      const int chunk = ((n + P - 1) / P + 1) & ~1;              // even, so a pair never straddles two parts
+      const int lo = part * chunk, hi = min(n, lo + chunk);
+      const uint64_t mine = keys[i];
+      int cnt = 0;
+      for (int j = lo; j < hi; j += 2) {
+        const uint64_t x = keys[j], y = (j + 1 < hi) ? keys[j + 1] : 0ull;
+        cnt += (x > mine ? 1 : 0) + (y > mine ? 1 : 0);
+      }
+      if (cnt != 0) atomicAdd(&rank[i], cnt);
+    }
+  } else {
+    for (int i = tid; i < n; i += nthr) {
+      const uint64_t mine = keys[i];
+      int cnt = 0;
+      for (int j = 0; j < n; j += 2) {
+        const uint64_t x = keys[j], y = (j + 1 < n) ? keys[j + 1] : 0ull;
+        cnt += (x > mine ? 1 : 0) + (y > mine ? 1 : 0);
+      }
+      rank[i] = cnt;
+    }
+  }
+}
+
+// Pools of up to kSelMax nodes on a block with at least half as many threads: thread t looks after pool nodes
+// t + 1 and t + 1 + nthr from their scores to their lines of the tree, so nothing is searched for and nothing is
+// fetched twice.  One round trip brings a node's score, parent, token and depth.  Selection: the m-th best key
+// among the first kSub nodes is a lower bound of the tree's keys (summed logprobs fall with depth, so the early
+// nodes hold most of the tree and the bound is tight); the nodes at or above it - the candidates, usually little
+// more than m - are ranked among themselves by counting (keys are distinct: the id is part of them), which costs
+// kSub^2 + C^2 comparisons instead of N^2 or a sort's long chain of dependent stages; up to kDirect nodes all are
+// ranked at once, which saves the three barriers of the bound (7B shape, k = 10, microseconds inside the stopping
+// call for 111 / 211 / 311 / 411 / 911 nodes: 3.6 / 5.7 / 6.3 / 6.7 / 9.5; ranking every node against all others
+// took 3.5 / 5.2 / 7.8 / 15 / 34, the sort 16 at 911).  More than kSelCand
+// candidates: the caller's general path takes over (returns false; nothing has been written to the tree).  The
+// tree index of a selected node is 1 + the number of selected nodes with a smaller id (ballots and popcounts); a
+// parent's tree index is read from the node -> index table (a selected node's parent is selected: its score is no
+// smaller and its id is smaller).
+constexpr int kSelMax = 2048, kSub = 128, kSelCand = 384, kDirect = 256;
+static_assert(kDirect <= kSelCand, "the rank array holds every node of a directly ranked pool");
+static_assert(kSub >= DDD_MMAX, "the subset must hold m keys");
+__device__ __forceinline__ bool tree_select_block(const ddd_state& st, const ddd_tree& tree, int b, int m, int nmax,
+                                                  int tid, int nthr, TreeSmem& sm, int N) {
+  const int m_eff = min(m, N), T = m + 1;
+  // the upper half of the key array holds the working set of the selection
+  int* tidx = reinterpret_cast<int*>(sm.keys + kSelMax + 2);     // [kSelMax + 1]  tree index of a pool node; -1: not in the tree
+  uint64_t* ckey = reinterpret_cast<uint64_t*>(tidx + kSelMax + 2);   // [kSelCand] candidate keys
+  int* cnode = reinterpret_cast<int*>(ckey + kSelCand);          // [kSelCand]     their pool ids
+  int* rank = cnode + kSelCand;                                   // [kSelCand]     larger keys counted
+  int* wtot = rank + kSelCand;                                    // [2][16]        selected nodes per wave and pass
+  int* misc = wtot + 32;                                          // [0] candidates so far
+  uint64_t* bound = reinterpret_cast<uint64_t*>(misc + 2);        // [1] the lower bound
+  static_assert((kSelMax + 2) * 8 + (kSelMax + 2) * 4 + kSelCand * 16 + 34 * 4 + 8 <= (kPoolMax + 2) * 8, "working set");
+  const int32_t* ppar = st.pool_parent + (size_t)b * nmax;
+  const int32_t* pdep = st.pool_depth + (size_t)b * nmax;
+  const int32_t* ptok = st.pool_token + (size_t)b * nmax;
+  const float* psc = st.pool_score + (size_t)b * nmax;
+  const int lane = tid & 63, wave = tid >> 6, nwaves = nthr >> 6;
+  bool node[2];
+  uint64_t my_key[2];
+  int my_pn[2], my_tok[2], my_dep[2], root_tok = -1, root_dep = 0;
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int n = tid + q * nthr;                                 // pool node n + 1
+    node[q] = n < N;
+    my_key[q] = 0ull;
+    my_pn[q] = 0;
+    my_tok[q] = -1;
+    my_dep[q] = 0;
+    if (node[q]) {
+      my_key[q] = rerank_key(psc[n + 1], n + 1);
+      sm.keys[n] = my_key[q];
+      tidx[n + 1] = -1;
+      my_pn[q] = ppar[n + 1];
+      my_tok[q] = ptok[n + 1];
+      my_dep[q] = pdep[n + 1];
+    }
+  }
+  const int S = min(N, kSub);
+  if (tid < kSelCand) rank[tid] = 0;
+  for (int i = tid + nthr; i < kSelCand; i += nthr) rank[i] = 0;
+  if (tid == 0) {
+    tidx[0] = 0;
+    misc[0] = 0;
+    sm.e.sel[0] = 0;
+    sm.e.par[0] = -1;
+    root_tok = ptok[0];
+    root_dep = pdep[0];
+  }
+  __syncthreads();
+  if (N <= kDirect) {                                             // uniform: few enough nodes to rank them all
+    count_larger_keys(sm.keys, N, rank, tid, nthr);
+    __syncthreads();
+    for (int i = tid; i < N; i += nthr)
+      if (rank[i] < m_eff) tidx[i + 1] = -2;                      // in the tree; its index follows
+    __syncthreads();
+  } else {
+    count_larger_keys(sm.keys, S, rank, tid, nthr);
+    __syncthreads();
+    for (int i = tid; i < S; i += nthr)
+      if (rank[i] == min(m_eff, S) - 1) bound[0] = sm.keys[i];      // exactly one key has this rank
+    __syncthreads();
+    const uint64_t lowest = bound[0];
+    __syncthreads();                                                // everybody has the bound and is done with the ranks
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const bool cand = node[q] && my_key[q] >= lowest;
+      const unsigned long long bal = __ballot(cand);
+      int base = 0;
+      if (lane == 0 && bal != 0ull) base = atomicAdd(&misc[0], __popcll(bal));
+      base = __shfl(base, 0, 64);
+      const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
+      if (cand && pos < kSelCand) {
+        ckey[pos] = my_key[q];
+        cnode[pos] = tid + q * nthr + 1;
+      }
+    }
+    if (tid < kSelCand) rank[tid] = 0;
+    for (int i = tid + nthr; i < kSelCand; i += nthr) rank[i] = 0;
+    __syncthreads();
+    const int C = misc[0];
+    if (C > kSelCand) return false;                                 // uniform
+    count_larger_keys(ckey, C, rank, tid, nthr);
+    __syncthreads();
+    for (int c = tid; c < C; c += nthr)
+      if (rank[c] < m_eff) tidx[cnode[c]] = -2;                     // in the tree; its index follows
+    __syncthreads();
+  }
+  bool chosen[2];
+  unsigned long long bal[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    chosen[q] = node[q] && tidx[tid + q * nthr + 1] == -2;
+    bal[q] = __ballot(chosen[q]);
+    if (lane == 0) wtot[q * 16 + wave] = __popcll(bal[q]);
+  }
+  __syncthreads();
+  int ti[2] = {-1, -1};
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    if (chosen[q]) {
+      int t = 1 + __popcll(bal[q] & ((1ull << lane) - 1ull));
+      for (int w = 0; w < wave; ++w) t += wtot[q * 16 + w];
+      if (q == 1)
+        for (int w = 0; w < nwaves; ++w) t += wtot[w];
+      ti[q] = t;
+      sm.e.sel[t] = tid + q * nthr + 1;
+      tidx[tid + q * nthr + 1] = t;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+    if (chosen[q]) sm.e.par[ti[q]] = tidx[my_pn[q]];
+  __syncthreads();
+  for (int i = tid; i < T; i += nthr) {
+#pragma unroll
+    for (int w = 0; w < kMaskWords; ++w) sm.e.bits[i][w] = 0u;
+    if (i <= m_eff) {
+      int c = i;
+      while (c >= 0) {
+        sm.e.bits[i][c >> 5] |= (1u << (c & 31));
+        c = sm.e.par[c];
+      }
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    tree.n_sel[b] = m_eff;
+    tree.tree_token[(size_t)b * T] = root_tok;
+    tree.pos[(size_t)b * T] = root_dep;
+    tree.parent_idx[(size_t)b * T] = -1;
+  }
+  for (int i = tid; i < m; i += nthr) tree.sel_node[(size_t)b * m + i] = (i < m_eff) ? sm.e.sel[1 + i] : -1;
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+    if (chosen[q]) {
+      tree.tree_token[(size_t)b * T + ti[q]] = my_tok[q];
+      tree.pos[(size_t)b * T + ti[q]] = my_dep[q];
+      tree.parent_idx[(size_t)b * T + ti[q]] = sm.e.par[ti[q]];
+    }
+  for (int i = m_eff + 1 + tid; i < T; i += nthr) {     // padding
+    tree.tree_token[(size_t)b * T + i] = -1;
+    tree.pos[(size_t)b * T + i] = 0;
+    tree.parent_idx[(size_t)b * T + i] = -1;
+  }
+  uint8_t* mask = tree.mask + (size_t)b * T * T;
+  for (int e = tid; e < T * T; e += nthr) {
+    const int i = e / T, j = e - i * T;
+    mask[e] = (uint8_t)((sm.e.bits[i][j >> 5] >> (j & 31)) & 1u);
+  }
+  return true;
+}
+
 // Pools of at most DDD_POOL_MAX nodes: the rerank keys sit in LDS (they are distinct: the id is part
 // of the key) and the m_eff largest are kept.
-constexpr int kCountMax = 320;
 // Must be called by every thread of the block.
 // n_nodes: the sequence's pool size (st.n_nodes[b]) if the caller has it at hand, else -1.
 __device__ __forceinline__ void tree_finalize_block(const ddd_state& st, const ddd_tree& tree, int b, int m, int nmax,
@@ -153,9 +351,13 @@ __device__ __forceinline__ void tree_finalize_block(const ddd_state& st, const d
   const int m_eff = min(m, N);
   const float* psc = st.pool_score + (size_t)b * nmax;
 
-  if (N <= kCountMax) {
-    // Small pools: rank by counting (the number of larger keys is a node's position in the rerank
-    // order); cheaper than the sort's chain of dependent stages up to a few hundred nodes.
+  if (N >= 1 && N <= kSelMax && N <= 2 * nthr && nthr <= 1024) {   // uniform
+    if (tree_select_block(st, tree, b, m, nmax, tid, nthr, sm, N)) return;
+    __syncthreads();                                              // the general path reuses the key array
+  }
+  if (N <= 320) {
+    // Small pools on a block much narrower than the pool: rank by counting (the number of larger keys is a node's
+    // position in the rerank order); cheaper than the sort's chain of dependent stages up to a few hundred nodes.
     for (int i = tid; i < N; i += nthr) sm.keys[i] = rerank_key(psc[i + 1], i + 1);
     if (tid == 0) sm.keys[N] = 0ull;   // pad: the counting loop reads keys in pairs
     __syncthreads();
