@@ -191,7 +191,11 @@ def trace_rounds(torch, D, g, wl, n_rounds, launch, side):
                     if (st[:, :6] == 0).any() or (bk[:6] == 0).any():
                         continue
                     t0, t1, t2, t3 = st[:, 0], st[:, 1], st[:, 2], st[:, 5]
-                    add("stream: last tile multiplied -> folded into the row statistics, median", np.median(st[:, 3] - t2))
+                    if (st[:, 6] != 0).all():
+                        add("stream: last tile multiplied by wave 0 -> by every wave (barrier), median", np.median(st[:, 6] - t2))
+                        add("stream: -> folded into the row statistics, median", np.median(st[:, 3] - st[:, 6]))
+                    else:
+                        add("stream: last tile multiplied -> folded into the row statistics, median", np.median(st[:, 3] - t2))
                     add("stream: -> the lanes' lists exchanged through LDS, median", np.median(st[:, 4] - st[:, 3]))
                     add("stream: -> k merge rounds, partials written, median", np.median(st[:, 5] - st[:, 4]))
                     per_slice.append((t3 - t0.min()) / 100.0)

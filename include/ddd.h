@@ -346,8 +346,8 @@ int ddd_profile_lmhead(ddd_ctx* ctx, const void* W_bf16, const void* hid_bf16, i
  * While enabled, every draft call of the context (ddd_draft_step and the round calls) leaves 100 MHz wall-clock
  * stamps in a device buffer the context allocates on enabling: for call number s, at word s * DDD_TRACE_CALL_WORDS,
  * first DDD_STATIC_SLICES * 8 words of the weight stream (per workgroup: entry, first tile multiplied, last tile
- * multiplied, last tile folded into the row statistics, the lanes' lists exchanged, partial results written, two
- * unused; zero on the MFMA path), then 8 words of the bookkeeping launch's workgroup 0
+ * multiplied (first streaming wave), last tile folded into the row statistics, the lanes' lists exchanged, partial
+ * results written, last tile multiplied by every streaming wave, one unused; zero on the MFMA path), then 8 words of the bookkeeping launch's workgroup 0
  * (entry, slice keys arrived, rows merged, beam update and stop test done, final tree done - equal to the previous
  * stamp if none was built -, exit; two unused).  Kernels of a later round overwrite the stamps of an earlier one.
  * ddd_trace_enable waits for the device, then allocates / clears (on != 0) or frees (on == 0) the buffer: do not

@@ -541,6 +541,284 @@ __global__ __launch_bounds__(kSeqThreads) void body_attention_seq_kernel(BodyAtt
   }
 }
 
+// ---- batched rounds, the prompt part on the matrix cores ---------------------------------------------------------
+// One workgroup of four waves per (sequence, head).  The L prompt keys are the same for every row of the sequence, so
+// their scores and their part of the output are two small contractions, 16 rows at a time:
+//   S[key][row] = sum_d K[key][d] q[row][d]      (v_mfma_f32_16x16x32_bf16: A = 16 keys x 32 d, B = 16 rows x 32 d)
+//   O[d][row]   = sum_key V[key][d] p[row][key]  (A = 16 d x 32 keys, B = 16 rows x 32 keys)
+// The fp32 operands (rotated queries, softmax weights) go in as two bf16 halves, x = hi + lo with |x - hi - lo| <=
+// 2^-17 |x| (two MFMAs per tile), so no rounding point is added to the layer's definition.  Both A operands come
+// straight from global memory, 16 bytes per lane: 8 consecutive d of one key for the first contraction (the cache's
+// own layout), 8 consecutive keys of one d for the second, which needs the values with the keys of an element
+// contiguous: pack_prompt_values_kernel writes that copy in the prompt call of every round.  No operand is staged in
+// LDS, which leaves room for three workgroups per CU: each is a chain of dependent steps, and the others' loads run
+// under it.  The rows' own keys and their ancestors' (at most 32 per row, different from row to row) are handled by
+// ordinary arithmetic.  (With one workgroup per (row, head) the launch took 510 us at the 7B shape with 640 rows, with
+// ordinary arithmetic per (sequence, head) 177 us.)
+constexpr int kMfThreads = 256;
+
+static size_t attention_mfma_lds(int Lp, int n_vis) {
+  return (size_t)(kSeqRows * kHeadDim + kSeqRows + kSeqRows * 32 + (size_t)n_vis * kSeqRows) * sizeof(float) +
+         (size_t)(2 * kSeqRows * kHeadDim + 2 * kSeqRows * (Lp + 8)) * sizeof(uint16_t);
+}
+
+__device__ __forceinline__ void split_bf16x8(const float* x, bool on, bf16x8& hi, bf16x8& lo) {
+  u32x4 h, l;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float x0 = on ? x[2 * e] : 0.f, x1 = on ? x[2 * e + 1] : 0.f;
+    const uint32_t h0 = f32_to_bf16_rne(x0), h1 = f32_to_bf16_rne(x1);
+    const uint32_t l0 = f32_to_bf16_rne(x0 - bf16_to_f32((uint16_t)h0)), l1 = f32_to_bf16_rne(x1 - bf16_to_f32((uint16_t)h1));
+    h[e] = h0 | (h1 << 16);
+    l[e] = l0 | (l1 << 16);
+  }
+  hi = __builtin_bit_cast(bf16x8, h);
+  lo = __builtin_bit_cast(bf16x8, l);
+}
+
+__global__ __launch_bounds__(kMfThreads) void body_attention_mfma_kernel(BodyAttnArgs a) {
+  extern __shared__ __align__(16) unsigned char smb[];
+  const int nh = a.H / kHeadDim;
+  const int b = blockIdx.x / nh, h = blockIdx.x % nh, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kk = (a.step == 0) ? 1 : a.k;                 // rows of this sequence
+  const int r0 = (a.step == 0) ? b : b * a.k;
+  if (a.row_active != nullptr && a.row_active[r0] == 0) return;   // uniform: a sequence's rows share their flag
+  const int L = a.L, Lp = a.Lp, n_vis = L + a.step + 1;
+  const int ppitch = Lp + 8;
+  float* qs = reinterpret_cast<float*>(smb);        // [kSeqRows][128] rotated queries; later the prompt's part of the outputs
+  float* rsum = qs + kSeqRows * kHeadDim;           // [kSeqRows] sums of the weights
+  int* anc = reinterpret_cast<int*>(rsum + kSeqRows);            // [kSeqRows][32] row of the ancestor in each earlier call
+  float* sct = reinterpret_cast<float*>(anc + kSeqRows * 32);    // [n_vis][kSeqRows] scores; weights of the keys past the prompt
+  uint16_t* ks = reinterpret_cast<uint16_t*>(sct + (size_t)n_vis * kSeqRows);   // [kSeqRows][128] own keys as stored
+  uint16_t* vs = ks + kSeqRows * kHeadDim;                                      // [kSeqRows][128] own values as stored
+  uint16_t* ph = vs + kSeqRows * kHeadDim;          // [kSeqRows][ppitch] weights of the prompt keys, high halves
+  uint16_t* pl = ph + kSeqRows * ppitch;            // ... low halves
+
+  // ---- the first 256 prompt keys: requested now, multiplied once the queries are rotated ------------------------
+  // lane (row, dq) of the A operand holds 8 consecutive d of key `row` of the tile; tile t belongs to wave t mod 4
+  const int ntile = (L + 15) >> 4;
+  u32x4 kf[4][4];
+  auto load_keys = [&](int t0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int key = min((t0 + wave + 4 * i) * 16 + (lane & 15), L - 1);
+      const uint16_t* kp = a.Kp + ((size_t)(b * L + key) * a.H + h * kHeadDim + (lane >> 4) * 8);
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) kf[i][s4] = *reinterpret_cast<const u32x4*>(kp + s4 * 32);
+    }
+  };
+  load_keys(0);
+  // ---- own rows: rotate, store, ancestors (as in the kernels above) -----------------------------------------------
+  for (int t = tid; t < kk * 64; t += kMfThreads) {
+    const int i = t >> 6, p = t & 63, r = r0 + i;
+    const float inv_freq = exp2f(-(float)(2 * p) / (float)kHeadDim * 13.287712379549449f);   // log2(10000)
+    float sn, cs;
+    sincosf((float)(L + a.step) * inv_freq, &sn, &cs);
+    const float* row = a.qkv + (size_t)r * 3 * a.H + h * kHeadDim;
+    const float q0 = row[p], q1 = row[p + 64];
+    const float k0 = row[a.H + p], k1 = row[a.H + p + 64];
+    const float v0 = row[2 * a.H + p], v1 = row[2 * a.H + p + 64];
+    qs[i * kHeadDim + p] = q0 * cs - q1 * sn;
+    qs[i * kHeadDim + p + 64] = q1 * cs + q0 * sn;
+    const uint16_t kb0 = f32_to_bf16_rne(k0 * cs - k1 * sn), kb1 = f32_to_bf16_rne(k1 * cs + k0 * sn);
+    const uint16_t vb0 = f32_to_bf16_rne(v0), vb1 = f32_to_bf16_rne(v1);
+    const size_t slot = ((size_t)a.step * a.hist_rows + r) * a.H + h * kHeadDim;
+    a.k_hist[slot + p] = kb0;
+    a.k_hist[slot + p + 64] = kb1;
+    a.v_hist[slot + p] = vb0;
+    a.v_hist[slot + p + 64] = vb1;
+    ks[i * kHeadDim + p] = kb0;
+    ks[i * kHeadDim + p + 64] = kb1;
+    vs[i * kHeadDim + p] = vb0;
+    vs[i * kHeadDim + p + 64] = vb1;
+  }
+  for (int t = tid; t < kk * 32; t += kMfThreads) {   // walk the parent slots back from row i to call number c
+    const int i = t >> 5, c = t & 31;
+    if (c >= a.step) continue;
+    int cur = r0 + i;
+    for (int s = a.step; s > c; --s) {
+      const int pslot = (s == a.step) ? a.beam_parent_slot[cur] : a.par_hist[s * a.hist_rows + cur];
+      cur = (s - 1 == 0) ? b : b * a.k + pslot;
+    }
+    anc[i * 32 + c] = cur;
+  }
+  if (h == 0 && a.step >= 1 && tid < kk) a.par_hist[a.step * a.hist_rows + r0 + tid] = a.beam_parent_slot[r0 + tid];
+  for (int e = tid; e < kSeqRows * ppitch / 2; e += kMfThreads) {   // rows and keys that do not exist weigh nothing
+    reinterpret_cast<uint32_t*>(ph)[e] = 0u;
+    reinterpret_cast<uint32_t*>(pl)[e] = 0u;
+  }
+  __syncthreads();
+
+  // ---- scores of the prompt keys ------------------------------------------------------------------------------------
+  const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
+  const int row = lane & 15, q4 = lane >> 4;  // operand coordinates of the lane (B: row of the sequence; A: key or d)
+  {
+    bf16x8 qh[4], ql[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) split_bf16x8(qs + row * kHeadDim + s4 * 32 + q4 * 8, row < kk, qh[s4], ql[s4]);
+    for (int t0 = 0; t0 < ntile; t0 += 16) {
+      if (t0 > 0) load_keys(t0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = t0 + wave + 4 * i;
+        if (t >= ntile) continue;                                    // wave-uniform
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+          const bf16x8 kfr = __builtin_bit_cast(bf16x8, kf[i][s4]);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr, qh[s4], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr, ql[s4], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {                                // accumulator e: key 4 * (lane >> 4) + e, row lane & 15
+          const int key = t * 16 + q4 * 4 + e;
+          if (key < L) sct[key * kSeqRows + row] = acc[e] * scale;
+        }
+      }
+    }
+  }
+  // ---- the prompt's values for this wave's two d tiles (first 256 keys): on their way from here on ----------------
+  // lane (d, kq) of the A operand holds 8 consecutive keys of element d
+  const int nstep = Lp >> 5;
+  u32x4 vf[2][8];
+  auto load_values = [&](int st0) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const uint16_t* vp = a.Vt + ((size_t)b * a.H + h * kHeadDim + (wave * 2 + j) * 16 + row) * Lp + q4 * 8;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) vf[j][u] = *reinterpret_cast<const u32x4*>(vp + min(st0 + u, nstep - 1) * 32);
+    }
+  };
+  load_values(0);
+  // ---- the rows' ancestors and themselves: four threads per (row, key) pair, 32 elements each ---------------------
+  for (int e4 = tid; e4 < kk * (a.step + 1) * 4; e4 += kMfThreads) {
+    const int e = e4 >> 2, qd = e4 & 3;
+    const int i = e / (a.step + 1), c = e - i * (a.step + 1);
+    const uint16_t* kp = (c == a.step) ? ks + i * kHeadDim + qd * 32
+                                       : a.k_hist + (((size_t)c * a.hist_rows + anc[i * 32 + c]) * a.H + h * kHeadDim + qd * 32);
+    u32x4 u[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) u[x] = *reinterpret_cast<const u32x4*>(kp + x * 8);
+    const float* q = qs + i * kHeadDim + qd * 32;
+    float dot = 0.f;
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        dot += q[x * 8 + 2 * y] * __uint_as_float(u[x][y] << 16);
+        dot += q[x * 8 + 2 * y + 1] * __uint_as_float(u[x][y] & 0xFFFF0000u);
+      }
+    dot += dpp_move_f32<0xB1>(dot);       // the four quarters of the key: lanes ^1, then ^2 (fixed order)
+    dot += dpp_move_f32<0x4E>(dot);
+    if (qd == 0) sct[(L + c) * kSeqRows + i] = dot * scale;
+  }
+  __syncthreads();
+  // ---- softmax weights: wave w takes rows w, w + 4, ...; the prompt's weights as two bf16 halves ------------------
+  for (int i = wave; i < kk; i += kMfThreads / 64) {
+    float mx = -INFINITY;
+    for (int j = lane; j < n_vis; j += 64) mx = fmaxf(mx, sct[j * kSeqRows + i]);
+    mx = wave_max_f32(mx);
+    float sum = 0.f;
+    for (int j = lane; j < n_vis; j += 64) {
+      const float p = __expf(sct[j * kSeqRows + i] - mx);
+      sum += p;
+      if (j < L) {
+        const uint16_t hi = f32_to_bf16_rne(p);
+        ph[i * ppitch + j] = hi;
+        pl[i * ppitch + j] = f32_to_bf16_rne(p - bf16_to_f32(hi));
+      } else {
+        sct[j * kSeqRows + i] = p;
+      }
+    }
+    sum = wave_sum_f32(sum);
+    if (lane == 0) rsum[i] = sum;
+  }
+  __syncthreads();
+  // ---- the prompt's part of the outputs: wave w takes d tiles 2w and 2w + 1 --------------------------------------
+  {
+    f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    for (int st0 = 0; st0 < nstep; st0 += 8) {
+      if (st0 > 0) load_values(st0);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int st = st0 + u;
+        if (st >= nstep) continue;                                   // uniform
+        // B operand: weights of row `row`, keys 32 st + 8 q4 .. + 7
+        const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ph + row * ppitch + st * 32 + q4 * 8));
+        const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pl + row * ppitch + st * 32 + q4 * 8));
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const bf16x8 af = __builtin_bit_cast(bf16x8, vf[j][u]);
+          acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bh, acc[j], 0, 0, 0);
+          acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bl, acc[j], 0, 0, 0);
+        }
+      }
+    }
+    // the queries are no longer needed: their place takes the outputs (accumulator e: d 4 * (lane >> 4) + e of the tile)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) qs[row * kHeadDim + (wave * 2 + j) * 16 + q4 * 4 + e] = acc[j][e];
+  }
+  __syncthreads();
+  // ---- ancestors and the row itself, normalisation: the values of four ancestors in flight ------------------------
+  {
+    const int d = tid & (kHeadDim - 1);
+    for (int i = tid >> 7; i < kk; i += kMfThreads / kHeadDim) {
+      float o = qs[i * kHeadDim + d];
+      const uint16_t* vh = a.v_hist + (size_t)h * kHeadDim + d;
+      int c = 0;
+      for (; c + 3 < a.step; c += 4) {
+        uint16_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = vh[((size_t)(c + u) * a.hist_rows + anc[i * 32 + c + u]) * a.H];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o += sct[(L + c + u) * kSeqRows + i] * bf16_to_f32(v[u]);
+      }
+      for (; c < a.step; ++c) o += sct[(L + c) * kSeqRows + i] * bf16_to_f32(vh[((size_t)c * a.hist_rows + anc[i * 32 + c]) * a.H]);
+      o += sct[(n_vis - 1) * kSeqRows + i] * bf16_to_f32(vs[i * kHeadDim + d]);
+      a.o[(size_t)(r0 + i) * a.H + h * kHeadDim + d] = f32_to_bf16_rne(o / rsum[i]);
+    }
+  }
+}
+
+// Vt[b][e][key] = Vp[b][key][e]: one workgroup per (sequence, block of 128 elements, block of 128 keys); a thread
+// writes 64 keys of one element, a whole cache line.
+constexpr int kPackKeys = 128;
+__global__ __launch_bounds__(256) void pack_prompt_values_kernel(const uint16_t* __restrict__ Vp, uint16_t* __restrict__ Vt,
+                                                                 int H, int L, int Lp) {
+  __shared__ uint16_t tile[kPackKeys][kHeadDim + 8];
+  const int nhb = H / kHeadDim;
+  const int b = blockIdx.x / nhb, hb = blockIdx.x % nhb, k0 = blockIdx.y * kPackKeys, tid = threadIdx.x;
+  for (int c = tid; c < kPackKeys * 16; c += 256) {         // 16-byte pieces, whole rows of the cache
+    const int kin = c >> 4, pc = c & 15, key = k0 + kin;
+    u32x4 u = {0u, 0u, 0u, 0u};
+    if (key < L) u = *reinterpret_cast<const u32x4*>(Vp + ((size_t)(b * L + key) * H + hb * kHeadDim + pc * 8));
+    *reinterpret_cast<u32x4*>(&tile[kin][pc * 8]) = u;
+  }
+  __syncthreads();
+  const int d = tid & (kHeadDim - 1), kh = tid >> 7;          // keys k0 + 64 kh .. + 63 of element d
+  uint16_t* dst = Vt + ((size_t)b * H + hb * kHeadDim + d) * Lp + k0 + kh * 64;
+#pragma unroll
+  for (int g = 0; g < 8; ++g) {
+    if (k0 + kh * 64 + g * 8 >= Lp) break;                    // Lp is a multiple of 32
+    u32x4 o;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const uint32_t lo = tile[kh * 64 + g * 8 + 2 * x][d], hi = tile[kh * 64 + g * 8 + 2 * x + 1][d];
+      o[x] = lo | (hi << 16);
+    }
+    *reinterpret_cast<u32x4*>(dst + g * 8) = o;
+  }
+}
+
+hipError_t launch_pack_prompt_values(const uint16_t* Vp, uint16_t* Vt, int B, int H, int L, int Lp, hipStream_t stream) {
+  hipLaunchKernelGGL(pack_prompt_values_kernel, dim3(B * (H / kHeadDim), (Lp + kPackKeys - 1) / kPackKeys), dim3(256), 0,
+                     stream, Vp, Vt, H, L, Lp);
+  return hipGetLastError();
+}
+
 static size_t attention_seq_lds(int n_vis) {
   return (size_t)(3 * kSeqRows * kHeadDim + 8 * kSeqRows * kHeadDim + kSeqRows + kSeqRows * 32 + (size_t)n_vis * kSeqRows) *
          sizeof(float);
@@ -548,7 +826,21 @@ static size_t attention_seq_lds(int n_vis) {
 
 hipError_t launch_body_attention(const BodyAttnArgs& a, hipStream_t stream) {
   const int n_vis = a.L + a.step + 1;
-  // batched rounds: one workgroup per (sequence, head) when the sequence's rows and weights fit its LDS
+  // batched rounds with a prompt: one workgroup per (sequence, head), the prompt part on the matrix cores
+  if (a.R > kBodyRows && a.k <= kSeqRows && a.Vt != nullptr && attention_mfma_lds(a.Lp, n_vis) <= 150 * 1024) {
+    static bool prepared_mf = false;
+    if (!prepared_mf) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&body_attention_mfma_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+      if (e != hipSuccess) return e;
+      prepared_mf = true;
+    }
+    const int n_seq = (a.step == 0) ? a.R : a.R / a.k;
+    hipLaunchKernelGGL(body_attention_mfma_kernel, dim3(n_seq * (a.H / kHeadDim)), dim3(kMfThreads),
+                       attention_mfma_lds(a.Lp, n_vis), stream, a);
+    return hipGetLastError();
+  }
+  // ... without one (or with one too long for the LDS): the same by ordinary arithmetic
   if (a.R > kBodyRows && a.k <= kSeqRows && attention_seq_lds(n_vis) <= 150 * 1024) {
     static bool prepared = false;
     if (!prepared) {

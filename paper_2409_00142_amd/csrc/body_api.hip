@@ -29,6 +29,8 @@ struct ddd_body {
   uint16_t* x0;      // bf16 [rows][2H]  FC input rows, assembled (null if rows <= kBodyRows)
   int32_t* row_list; // [rows] ids of the active rows of the current call
   int32_t* n_act;    // [1]
+  uint16_t* vt;      // bf16 [B][H][Lp] the prompt's values, keys contiguous (null if rows <= kBodyRows or L < 32);
+  int Lp;            //   rewritten by the prompt call of every round
 };
 
 namespace {
@@ -186,6 +188,8 @@ int ddd_body_create(const ddd_body_config* cfg, ddd_body** out) {
   if (e == hipSuccess && b->rows > kBodyRows) {
     e = hipMalloc(&b->x0, R * 2 * H * sizeof(uint16_t));
     if (e == hipSuccess) e = prepare_lmhead_gemm();
+    b->Lp = (cfg->L + 31) & ~31;
+    if (e == hipSuccess && cfg->L >= 32) e = hipMalloc(&b->vt, (size_t)cfg->B * H * b->Lp * sizeof(uint16_t));
   }
   if (e != hipSuccess) {
     ddd_body_destroy(b);
@@ -206,6 +210,7 @@ int ddd_body_destroy(ddd_body* b) {
   (void)hipFree(b->v_hist);
   (void)hipFree(b->par_hist);
   (void)hipFree(b->x0);
+  (void)hipFree(b->vt);
   (void)hipFree(b->row_list);
   (void)hipFree(b->n_act);
   delete b;
@@ -278,6 +283,10 @@ int ddd_body_step(void* user, int32_t step, const ddd_state* st, void* hid_out, 
   t.step = step;
   t.R = R;
   t.hist_rows = (int)hist_rows;
+  t.Vt = b->vt;
+  t.Lp = b->Lp;
+  if (step == 0 && b->vt != nullptr)   // the round's prompt, laid out for the batched attention's second contraction
+    BODY_HIP(launch_pack_prompt_values(t.Vp, b->vt, b->cfg.B, H, b->cfg.L, b->Lp, s));
   RmsNormArgs n2 = n1;
   n2.g = b->w.g2;
 

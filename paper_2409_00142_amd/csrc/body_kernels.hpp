@@ -68,8 +68,12 @@ struct BodyAttnArgs {
   uint16_t* o;                // bf16 [R][H]
   int H, L, k, step, R;
   int hist_rows;              // rows per call in the histories (B*k)
+  const uint16_t* Vt;         // null, or bf16 [B][H][Lp]: the prompt's values with the keys of one element contiguous
+  int Lp;                     // L rounded up to a multiple of 32 (the keys past L are zero)
 };
 hipError_t launch_body_attention(const BodyAttnArgs& a, hipStream_t stream);
+// Vt[b][e][key] = Vp[b][key][e] for key < L, 0 up to Lp (the A operand of the batched attention's second contraction).
+hipError_t launch_pack_prompt_values(const uint16_t* Vp, uint16_t* Vt, int B, int H, int L, int Lp, hipStream_t stream);
 
 // Input rows of the FC for calls that go through the MFMA GEMM: x0[r] = [E[token of r], feature of r's parent],
 // assembled once (the GEMM gathers whole rows of one matrix).

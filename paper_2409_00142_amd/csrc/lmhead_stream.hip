@@ -137,6 +137,7 @@ __global__ __launch_bounds__(768) void lmhead_stream_kernel(StreamArgs a) {
 
     for (int t = 0; t < nt; ++t) {
       __syncthreads();
+      if (trace != nullptr && t == nt - 1 && lane == 0) trace[6] = (uint64_t)wall_clock64();
       f32x4 s = {0.f, 0.f, 0.f, 0.f};
       for (int w = 0; w < NW; ++w)   // fixed order: equal W rows give bit-equal logits
         s += *reinterpret_cast<const f32x4*>(red + ((t & 1) * NW + w) * 256 + lane * 4);

@@ -158,7 +158,13 @@ def test_body_steps_with_scripted_beams(gpu, B, k):
                                    ("b5_k6_gemm_rows", 5, 6, 512, 1024, 2000, 17, 4),
                                    # the same with a stop threshold: the sequences stop after different calls, the later
                                    # calls run the layer on the rows that are left
-                                   ("b7_k6_gemm_ragged_stops", 7, 6, 512, 1024, 2000, 17, 5, 0.03)],
+                                   ("b7_k6_gemm_ragged_stops", 7, 6, 512, 1024, 2000, 17, 5, 0.03),
+                                   # prompts of 32 positions and more: the batched attention takes the prompt part to
+                                   # the matrix cores (a ragged last tile of keys; more than 256 keys: two passes;
+                                   # sequences that stop)
+                                   ("b5_k6_prompt_mfma_ragged", 5, 6, 512, 1024, 2000, 70, 4),
+                                   ("b3_k10_prompt_mfma_two_passes", 3, 10, 256, 384, 1000, 272, 3),
+                                   ("b7_k6_prompt_mfma_stops", 7, 6, 512, 1024, 2000, 40, 5, 0.03)],
                          ids=lambda s: s[0])
 def test_round_with_body_matches_oracle(gpu, shape):
     """Whole rounds with the layer as the draft body: eager calls (rows inspected after every body call), then the
