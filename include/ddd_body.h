@@ -70,7 +70,11 @@ typedef struct ddd_body ddd_body;
 int ddd_body_create(const ddd_body_config* cfg, ddd_body** out);
 int ddd_body_destroy(ddd_body* body);
 
-/* Weights and prompt context used by the following calls (pointers are copied, not the data). */
+/* Weights and prompt context used by the following calls (pointers are copied, not the data).  The prompt's keys
+ * and values are read by every call of a round and must not change while a round is in flight; with more than 16
+ * rows per call and a prompt of 32 positions or more, the prompt call (step 0) of every round also writes a copy of
+ * the values laid out for the matrix cores (B * H * ceil(L / 32) * 32 bf16, allocated by ddd_body_create), which the
+ * later calls of that round read. */
 int ddd_body_bind(ddd_body* body, const ddd_body_weights* w, const ddd_body_prompt* p);
 
 /* The body as a ddd_draft_body_fn: user = ddd_body*.  Enqueues the layer for the rows of draft
