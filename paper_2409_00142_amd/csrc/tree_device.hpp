@@ -176,15 +176,17 @@ __device__ __forceinline__ void count_larger_keys(const uint64_t* keys, int n, i
 // among the first kSub nodes is a lower bound of the tree's keys (summed logprobs fall with depth, so the early
 // nodes hold most of the tree and the bound is tight); the nodes at or above it - the candidates, usually little
 // more than m - are ranked among themselves by counting (keys are distinct: the id is part of them), which costs
-// kSub^2 + C^2 comparisons instead of N^2 or a sort's long chain of dependent stages; up to kDirect nodes all are
+// kSub^2 + C^2 comparisons instead of N^2 or a sort's long chain of dependent stages (if more than kSelCand nodes
+// pass the bound, the m-th best of kRefine of them is a tighter one: twice at most); up to kDirect nodes all are
 // ranked at once, which saves the three barriers of the bound (7B shape, k = 10, microseconds inside the stopping
 // call for 111 / 211 / 311 / 411 / 911 nodes: 3.6 / 5.7 / 6.3 / 6.7 / 9.5; ranking every node against all others
-// took 3.5 / 5.2 / 7.8 / 15 / 34, the sort 16 at 911).  More than kSelCand
-// candidates: the caller's general path takes over (returns false; nothing has been written to the tree).  The
+// took 3.5 / 5.2 / 7.8 / 15 / 34, the sort 16 at 911).  Still more than kSelCand candidates after two tightenings:
+// the caller's general path takes over (returns false; nothing has been written to the tree).  The
 // tree index of a selected node is 1 + the number of selected nodes with a smaller id (ballots and popcounts); a
 // parent's tree index is read from the node -> index table (a selected node's parent is selected: its score is no
 // smaller and its id is smaller).
-constexpr int kSelMax = 2048, kSub = 128, kSelCand = 384, kDirect = 256;
+constexpr int kSelMax = 2048, kSub = 128, kSelCand = 384, kDirect = 256, kRefine = 256;
+static_assert(kRefine >= DDD_MMAX && kRefine <= kSelCand, "the refining sample holds m keys and lies in the candidate list");
 static_assert(kDirect <= kSelCand, "the rank array holds every node of a directly ranked pool");
 static_assert(kSub >= DDD_MMAX, "the subset must hold m keys");
 __device__ __forceinline__ bool tree_select_block(const ddd_state& st, const ddd_tree& tree, int b, int m, int nmax,
@@ -243,31 +245,41 @@ __device__ __forceinline__ bool tree_select_block(const ddd_state& st, const ddd
       if (rank[i] < m_eff) tidx[i + 1] = -2;                      // in the tree; its index follows
     __syncthreads();
   } else {
-    count_larger_keys(sm.keys, S, rank, tid, nthr);
-    __syncthreads();
-    for (int i = tid; i < S; i += nthr)
-      if (rank[i] == min(m_eff, S) - 1) bound[0] = sm.keys[i];      // exactly one key has this rank
-    __syncthreads();
-    const uint64_t lowest = bound[0];
-    __syncthreads();                                                // everybody has the bound and is done with the ranks
+    // the bound: first from the early nodes, then - while more than kSelCand nodes pass it (a confident sequence: its
+    // deep nodes score as well as the early ones) - from the first kRefine candidates, which lie above the old bound
+    const uint64_t* sample = sm.keys;
+    int n_sample = S, C = 0;
+    for (int attempt = 0;; ++attempt) {
+      count_larger_keys(sample, n_sample, rank, tid, nthr);
+      __syncthreads();
+      for (int i = tid; i < n_sample; i += nthr)
+        if (rank[i] == min(m_eff, n_sample) - 1) bound[0] = sample[i];   // exactly one key has this rank
+      if (tid == 0) misc[0] = 0;
+      __syncthreads();
+      const uint64_t lowest = bound[0];
+      __syncthreads();                                              // everybody has the bound and is done with the ranks and the sample
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const bool cand = node[q] && my_key[q] >= lowest;
-      const unsigned long long bal = __ballot(cand);
-      int base = 0;
-      if (lane == 0 && bal != 0ull) base = atomicAdd(&misc[0], __popcll(bal));
-      base = __shfl(base, 0, 64);
-      const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
-      if (cand && pos < kSelCand) {
-        ckey[pos] = my_key[q];
-        cnode[pos] = tid + q * nthr + 1;
+      for (int q = 0; q < 2; ++q) {
+        const bool cand = node[q] && my_key[q] >= lowest;
+        const unsigned long long bal = __ballot(cand);
+        int base = 0;
+        if (lane == 0 && bal != 0ull) base = atomicAdd(&misc[0], __popcll(bal));
+        base = __shfl(base, 0, 64);
+        const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
+        if (cand && pos < kSelCand) {
+          ckey[pos] = my_key[q];
+          cnode[pos] = tid + q * nthr + 1;
+        }
       }
+      if (tid < kSelCand) rank[tid] = 0;
+      for (int i = tid + nthr; i < kSelCand; i += nthr) rank[i] = 0;
+      __syncthreads();
+      C = misc[0];
+      if (C <= kSelCand) break;                                     // uniform
+      if (attempt == 2) return false;                               // uniform: the general path
+      sample = ckey;
+      n_sample = kRefine;
     }
-    if (tid < kSelCand) rank[tid] = 0;
-    for (int i = tid + nthr; i < kSelCand; i += nthr) rank[i] = 0;
-    __syncthreads();
-    const int C = misc[0];
-    if (C > kSelCand) return false;                                 // uniform
     count_larger_keys(ckey, C, rank, tid, nthr);
     __syncthreads();
     for (int c = tid; c < C; c += nthr)
