@@ -345,6 +345,66 @@ def test_bookkeeping_calls_teacher_forced(gpu, wname, rnd, thr):
         D.ddd_destroy(ctx)
 
 
+def _crafted_logprobs(kind, k, Dm, seed):
+    """Per call: row top-k tokens and logprobs (descending per row) that steer the shape of the pool's scores."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for s in range(Dm):
+        rows = 1 if s == 0 else k
+        tok = np.stack([rng.permutation(50_000)[:k].astype(np.int32) for _ in range(rows)])
+        if kind == "flat":              # every score equal: the order is the ids' alone
+            lp = np.zeros((rows, k), np.float32)
+        elif kind == "confident_chain":  # one good child of the root, the rest bad: the early nodes are mostly bad ones
+            lp = -np.sort(rng.exponential(1e-3, (rows, k))).astype(np.float32)   # and every later node scores well
+            if s == 0:
+                lp[0, 1:] = -10.0 - np.arange(k - 1, dtype=np.float32)
+        elif kind == "ties_in_blocks":   # a handful of distinct scores, many nodes on each
+            lp = -np.sort(rng.integers(0, 3, (rows, k))).astype(np.float32) * np.float32(0.5)
+        else:                            # "steep": scores fall fast with depth, the tree is the early nodes
+            lp = -np.sort(rng.exponential(2.0, (rows, k))).astype(np.float32)
+        out.append((tok, lp))
+    return out
+
+
+@pytest.mark.parametrize("kind", ["flat", "confident_chain", "ties_in_blocks", "steep"])
+@pytest.mark.parametrize("k,Dm,m", [(10, 10, 60), (10, 10, 128), (10, 5, 7), (16, 8, 80), (3, 12, 128), (10, 3, 60)])
+def test_tree_finalize_on_crafted_pools(gpu, kind, k, Dm, m):
+    """Final tree (Section 1: the m best nodes by summed logprob, ties to the lower id) on pools whose scores are
+    shaped to reach every branch of the selection: few nodes, many nodes passing the first bound, large groups of
+    equal scores, two pool nodes per thread.  Pools are built on both sides from the same row top-k lists."""
+    torch, D, SD = gpu
+    print(f"[case] crafted pool {kind} k={k} D={Dm} m={m}", flush=True)
+    recs = _crafted_logprobs(kind, k, Dm, seed=k * 100 + Dm)
+    pool = O.Pool(k=k, D=Dm)
+    beam = O.beam_first(pool, 5, recs[0][0][0], recs[0][1][0])
+    for s in range(1, Dm):
+        beam = O.beam_expand(pool, beam, s, recs[s][0], recs[s][1])
+    want = O.tree_finalize(pool, m)
+    cfg = D.make_config(1, 256, 50_000, k, Dm, m, 0.0, 0)
+    ctx = D.ddd_create(cfg)
+    try:
+        st, st_t = D.alloc_state(cfg)
+        tree, tree_t = D.alloc_tree(cfg)
+        D.ddd_round_reset(ctx, st, torch.tensor([5], dtype=torch.int32, device="cuda"))
+        for s, (tok, lp) in enumerate(recs):
+            D.ddd_beam_select(ctx, s, _upload_i32(torch, tok), _upload_f32(torch, lp), st)
+            D.ddd_depth_continue(ctx, s + 1, st)
+        D.ddd_tree_finalize(ctx, st, tree)
+        torch.cuda.synchronize()
+        n = pool.n_nodes
+        assert int(st_t["n_nodes"].cpu()[0]) == n
+        assert np.array_equal(st_t["pool_score"].cpu().numpy()[0, :n], pool.score[:n])
+        assert np.array_equal(st_t["pool_parent"].cpu().numpy()[0, :n], pool.parent[:n])
+        assert int(tree_t["n_sel"].cpu()[0]) == want.n_sel
+        assert np.array_equal(tree_t["sel_node"].cpu().numpy()[0], want.sel_node)
+        assert np.array_equal(tree_t["tree_token"].cpu().numpy()[0], want.tree_token)
+        assert np.array_equal(tree_t["pos"].cpu().numpy()[0], want.pos)
+        assert np.array_equal(tree_t["parent_idx"].cpu().numpy()[0], want.parent_idx)
+        assert np.array_equal(tree_t["mask"].cpu().numpy()[0], want.mask)
+    finally:
+        D.ddd_destroy(ctx)
+
+
 # ------------------------------------------------------------------------------------------------
 # the on-device stand-in draft body reproduces the numpy generator bit for bit
 # ------------------------------------------------------------------------------------------------
