@@ -9,7 +9,11 @@
 //                          Input rows are gathered in place (embedding row of the token, feature row of
 //                          the parent).
 //   rmsnorm_kernel         bf16(x / sqrt(mean x^2 + eps) * g)
-//   body_attention_kernel  RoPE, bf16 key / value store, softmax over prompt + ancestors + self
+//   body_attention_kernel  RoPE, bf16 key / value store, softmax over prompt + ancestors + self: one workgroup per
+//                          (row, head); batched rounds: one per (sequence, head), by ordinary arithmetic
+//                          (body_attention_seq_kernel) or with the prompt part on the matrix cores
+//                          (body_attention_mfma_kernel, pack_prompt_values_kernel)
+//   pack_x0_kernel         the FC's input rows assembled for the MFMA path of calls with more than 16 rows
 //   The SiLU gate and the final bf16 rounding of the hidden rows ride in the epilogues of the
 //   linears that produce their inputs.
 // Rows of stopped sequences are skipped; a launch whose rows are all inactive exits at once.

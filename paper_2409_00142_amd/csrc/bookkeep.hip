@@ -225,8 +225,19 @@ __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
     block_sort_desc(s_cand, n2, tid, 256);
     for (int j = tid; j < a.k; j += 256) a.part_key[(size_t)row * a.k + j] = s_cand[j];
     if (tid == 0) a.part_sum[row] = lse;
+  } else if (cnt <= 256) {                                     // uniform: the usual case, a few more than k candidates
+    // ---- exact top-k among the candidates: a candidate's rank is the number of larger keys (keys are distinct) ---
+    if (tid < cnt) {
+      const uint64_t mine = s_cand[tid];
+      int rank = 0;
+      for (int j = 0; j < cnt; ++j) rank += (s_cand[j] > mine) ? 1 : 0;
+      if (rank < a.k) a.part_key[(size_t)row * a.k + rank] = mine;
+    } else if (tid < a.k) {
+      a.part_key[(size_t)row * a.k + tid] = 0ull;              // fewer candidates than beams (V < k cannot happen; kept total)
+    }
+    if (tid == 0) a.part_sum[row] = lse;
   } else if (cnt <= kCandMax) {                                // uniform
-    // ---- exact top-k among the candidates: wave 0, k rounds of wave max over its strided share ---
+    // ---- many candidates (ties at the threshold): wave 0, k rounds of wave max over its strided share ---
     if (wave == 0) {
       uint64_t mine[2] = {0ull, 0ull};                         // ranks lane and lane + 64
       for (int round = 0; round < a.k; ++round) {
