@@ -46,7 +46,7 @@ hipError_t launch_merge(const MergeArgs& a, hipStream_t stream) {
 // T is a lower bound of the row's k-th largest logit (k distinct elements are >= T), and only the
 // groups whose max reaches T - k of them, or a few more - can hold an element >= T: those groups'
 // logits are read (64 values each), the candidates >= T collected, and the exact top-k by (logit
-// desc, token asc) taken among them.  Massive ties (e.g. constant logits) overflow the lists: with
+// desc, token asc) taken among them (a candidate's rank is the number of larger keys).  Massive ties (e.g. constant logits) overflow the lists: with
 // too many candidate groups the whole row is scanned instead, and with too many candidates an
 // exact but slow path takes over: k passes over the row, each finding the largest key below the
 // previous winner.
