@@ -6,6 +6,7 @@ namespace ddd {
 
 // ---- standalone merge: one wave per row ------------------------------------------------------
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+  __shared__ uint64_t s_mrg[4][kMergeWords];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + wave;
   if (row >= a.n_rows) return;                                 // wave-uniform
@@ -26,7 +27,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
     RowHeads heads;
     const uint64_t* pk = a.part_key + (size_t)row * a.nslice * a.k;
     merge_load_heads(pk, a.part_sum + (size_t)row * a.nslice, a.nslice, a.k, lane, heads);
-    merge_row_dispatch(pk, heads, a.nslice, a.k, lane, key, lse);
+    merge_row_dispatch(pk, heads, a.nslice, a.k, lane, key, lse, s_mrg[wave]);
   }
   if (lane < a.k) {
     a.topk_token[(size_t)row * a.k + lane] = key_token(key);

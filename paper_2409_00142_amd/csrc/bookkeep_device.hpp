@@ -109,9 +109,74 @@ __device__ __forceinline__ void merge_row(const uint64_t* __restrict__ pk, RowHe
   }
 }
 
+// The same result without the k dependent rounds, for the usual row (all 64 lanes active; scratch: kMergeWords
+// 64-bit words of LDS that belong to the calling wave).  A lower bound of the row's k-th best logit comes first: the
+// 16 quads of lanes each hold 16 slices, the k-th largest of the 16 quad maxima is reached by k distinct keys (k <= 16).
+// Every key at or above the bound is a candidate - the best fronts and a few runners-up, 20 to 30 keys -, the
+// candidates are written to LDS, one per lane, and a candidate's rank is the number of larger candidates (keys are
+// distinct).  The k rounds above are a chain of cross-lane reductions and scalar round trips (0.37 us each with ten
+// waves on four SIMDs); the counting loops are independent iterations.  A slice whose third key is a candidate
+// may hold more of them, and more than 64 candidates do not fit: such rows (about one in a hundred) take the rounds.
+constexpr int kMergeWords = 64 + kKM;
+template <int HPL>
+__device__ __forceinline__ void merge_row_count(const uint64_t* __restrict__ pk, RowHeads& h, int nslice, int k, int lane,
+                                                uint64_t& my_key, float& lse, uint64_t* scratch) {
+  uint64_t loc = 0;
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) loc = umax64(loc, h.q0[i]);
+  const uint32_t lm = (uint32_t)(loc >> 32);
+  // quad maxima (every lane of a quad holds its quad's), then how many of the 16 are larger than this one
+  uint32_t qm = umax32(lm, dpp_move_u32<0xB1>(lm));
+  qm = umax32(qm, dpp_move_u32<0x4E>(qm));
+  int larger = 0;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) larger += ((uint32_t)__builtin_amdgcn_readlane((int)qm, 4 * q) > qm) ? 1 : 0;
+  // the smallest of the quad maxima that fewer than k others exceed = the k-th largest (ties included)
+  const uint32_t bound = ~wave_max_u32(~(larger < k ? qm : 0xFFFFFFFFu));
+  bool more = false;
+  int base = 0;
+  uint64_t* cand = scratch;          // [64]
+  uint64_t* out = scratch + 64;      // [kKM]
+  if (lane < kKM) out[lane] = 0ull;
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) {
+      const uint64_t key = (r == 0) ? h.q0[i] : (r == 1) ? h.q1[i] : h.q2[i];
+      const bool in = key != 0ull && (uint32_t)(key >> 32) >= bound;
+      const unsigned long long bal = __ballot(in);
+      if (bal == 0ull) continue;                                   // uniform
+      const int pos = base + __popcll(bal & ((1ull << lane) - 1ull));
+      if (in && pos < 64) cand[pos] = key;
+      base += __popcll(bal);
+      if (r == 2 && in && k > 3) more = true;
+    }
+  if (__ballot(more) != 0ull || base > 64) {                       // uniform
+    merge_row<HPL>(pk, h, nslice, k, lane, my_key, lse);
+    return;
+  }
+  // lse as in the rounds' version
+  const float M = unord32(wave_max_u32(lm));
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < HPL; ++i)
+    if (h.q0[i] != 0ull) acc += h.psum[i] * __expf(key_value(h.q0[i]) - M);
+  lse = M + __logf(wave_sum_f32(acc));
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const int C = base;
+  const uint64_t mine = (lane < C) ? cand[lane] : 0ull;
+  int rank = 0;
+  for (int j = 0; j < C; ++j) rank += (cand[j] > mine) ? 1 : 0;
+  if (lane < C && rank < k) out[rank] = mine;
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  my_key = (lane < k) ? out[lane] : 0ull;
+}
+
 __device__ __forceinline__ void merge_row_dispatch(const uint64_t* pk, RowHeads& h, int nslice, int k, int lane,
-                                                   uint64_t& my_key, float& lse) {
-  merge_row<kHPL>(pk, h, nslice, k, lane, my_key, lse);
+                                                   uint64_t& my_key, float& lse, uint64_t* scratch) {
+  merge_row_count<kHPL>(pk, h, nslice, k, lane, my_key, lse, scratch);
 }
 
 // ---- beam update by one wave (all 64 lanes active) -------------------------------------------
@@ -222,6 +287,7 @@ struct StepSmem {
   uint64_t cand[kKM * kKM];   // beam keys of the k*k candidates (beam update by the whole block)
   int rank[kKM * kKM];        // number of candidates with a larger key
   float newlps[kKM];          // logprobsum of the new beam
+  uint64_t mrg[kKM][kMergeWords];   // per wave: candidates of the row merge and its result
   int stopped;
 };
 
@@ -269,7 +335,7 @@ __device__ __forceinline__ bool step_bookkeep_block(const StepArgs& a, int b, in
   // from the rows' results in LDS.
   const bool by_block = g.step >= 1 && nwaves >= rows;
   if (wave < rows) {
-    if (!dense) merge_row_dispatch(pk, heads, a.nslice, g.k, lane, key, lse);
+    if (!dense) merge_row_dispatch(pk, heads, a.nslice, g.k, lane, key, lse, sm.mrg[wave]);
     if (!by_block) step_publish_row(a, sm, wave, row, lane, key, lse);
   }
   if (trace != nullptr) trace[2] = (uint64_t)wall_clock64();
@@ -344,7 +410,7 @@ __device__ __forceinline__ bool step_bookkeep_block(const StepArgs& a, int b, in
     } else {
       RowHeads heads2;
       merge_load_heads(pk2, a.part_sum + row2 * a.nslice, a.nslice, g.k, lane, heads2);
-      merge_row_dispatch(pk2, heads2, a.nslice, g.k, lane, key2, lse2);
+      merge_row_dispatch(pk2, heads2, a.nslice, g.k, lane, key2, lse2, sm.mrg[wave]);
     }
     step_publish_row(a, sm, rw, row2, lane, key2, lse2);
   }
