@@ -112,6 +112,7 @@ __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
   __shared__ float s_T;
   __shared__ int s_cnt, s_ng;
   __shared__ int s_glist[kGrpListMax];
+  __shared__ uint32_t s_bound[4];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (a.row_active != nullptr && !a.row_active[row]) return;   // uniform
   const int ngrp_valid = (a.V + 63) >> 6;
@@ -142,12 +143,52 @@ __global__ __launch_bounds__(256) void row_topk_kernel(RowTopkArgs a) {
     __syncthreads();
     block_sort_desc(s_cand, n2, tid, 256);
     if (tid == 0) s_T = (a.k <= ngrp_valid) ? unord32((uint32_t)s_cand[a.k - 1]) : -INFINITY;
-  } else if (wave == 0) {
-    // up to 2048 groups (V <= 131072): up to 32 per lane, kept as ordered keys, k rounds of wave max
-    const uint32_t T = (ngrp_valid <= 512)    ? kth_largest_group_max<8>(gmax, ngrp_valid, a.k, lane)
-                       : (ngrp_valid <= 1024) ? kth_largest_group_max<16>(gmax, ngrp_valid, a.k, lane)
-                                              : kth_largest_group_max<32>(gmax, ngrp_valid, a.k, lane);
-    if (lane == 0) s_T = (T == 0u) ? -INFINITY : unord32(T);
+  } else {
+    // Up to 2048 groups (V <= 131072), up to 8 per thread, as ordered keys.  A lower bound first: a quad of lanes
+    // holds 4 to 32 groups, and the k-th largest of a wave's 16 quad maxima is reached by k distinct groups (k <= 16);
+    // the best of the four waves' bounds is taken.  The group maxima at or above it - a few dozen - are ranked by
+    // counting, and the one of rank k - 1 is T.  (k rounds of a wave maximum on one wave took three times as long.)
+    uint32_t tm = 0u;
+    for (int g = tid; g < ngrp_valid; g += 256) tm = umax32(tm, ord32(gmax[g]));
+    uint32_t qm = umax32(tm, dpp_move_u32<0xB1>(tm));
+    qm = umax32(qm, dpp_move_u32<0x4E>(qm));
+    int larger = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) larger += ((uint32_t)__builtin_amdgcn_readlane((int)qm, 4 * q) > qm) ? 1 : 0;
+    const uint32_t bound_w = ~wave_max_u32(~(larger < a.k ? qm : 0xFFFFFFFFu));
+    if (lane == 0) s_bound[wave] = bound_w;
+    __syncthreads();
+    const uint32_t bound = umax32(umax32(s_bound[0], s_bound[1]), umax32(s_bound[2], s_bound[3]));
+    for (int g = tid; g < ngrp_valid; g += 256) {
+      const uint32_t v = ord32(gmax[g]);
+      if (v >= bound) {
+        const int p = atomicAdd(&s_ng, 1);
+        if (p < kCandMax) s_cand[p] = ((uint64_t)v << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)g);   // distinct
+      }
+    }
+    __syncthreads();
+    const int ncg = s_ng;
+    __syncthreads();                                             // everybody has the count: the counter is used again below
+    if (ncg <= 256) {                                            // uniform
+      if (tid < ncg) {
+        const uint64_t mine = s_cand[tid];
+        int rank = 0;
+        for (int j = 0; j < ncg; ++j) rank += (s_cand[j] > mine) ? 1 : 0;
+        if (rank == a.k - 1) s_T = unord32((uint32_t)(mine >> 32));
+      }
+      if (tid == 0) {
+        if (ncg < a.k) s_T = -INFINITY;                          // fewer than k groups
+        s_ng = 0;
+      }
+    } else if (wave == 0) {                                      // many equal maxima: the rounds
+      const uint32_t T = (ngrp_valid <= 512)    ? kth_largest_group_max<8>(gmax, ngrp_valid, a.k, lane)
+                         : (ngrp_valid <= 1024) ? kth_largest_group_max<16>(gmax, ngrp_valid, a.k, lane)
+                                                : kth_largest_group_max<32>(gmax, ngrp_valid, a.k, lane);
+      if (lane == 0) {
+        s_T = (T == 0u) ? -INFINITY : unord32(T);
+        s_ng = 0;
+      }
+    }
   }
   __syncthreads();
   const float lse = M + __logf(s_red[4] + s_red[5] + s_red[6] + s_red[7]);
