@@ -20,6 +20,15 @@ constexpr int kGlobalChunk = 8;                    // loads in flight per thread
 constexpr int kFlatBits = 14;                      // k*k <= 16384 flat indices
 constexpr uint32_t kFlatMask = (1u << kFlatBits) - 1u;
 constexpr uint32_t kTokMaskW = (1u << (32 - kFlatBits)) - 1u;   // tokens below 2^18
+// final tree of a large pool: sample, candidates and their ranks (tree_finalize_wide_block)
+constexpr int kWSub = 512, kWCand = 1024;
+constexpr int kWideWorkBytes = kWSub * 8 + kWCand * 8 + kWCand * 4;
+static_assert(kWSub >= DDD_MMAX && kWSub <= kWCand, "the sample holds m keys and lies in the candidate list");
+// LDS in front of WideSmem in the step kernel: the k*k candidate keys of a call, later the work area of the final tree
+__host__ __device__ inline size_t wide_front_bytes(int k) {
+  const size_t keys = ((size_t)k * k * 8 + 15) & ~(size_t)15;
+  return keys > (size_t)kWideWorkBytes ? keys : (size_t)kWideWorkBytes;
+}
 
 __device__ __forceinline__ uint64_t wide_beam_key(float score, int token, int flat) {
   const uint32_t lo = ((kTokMaskW - (uint32_t)token) << kFlatBits) | (kFlatMask - (uint32_t)flat);
@@ -196,23 +205,73 @@ __device__ __forceinline__ void sort_sel_desc_wave(WideSmem& sm, int lane) {
   }
 }
 
-// Final tree for a pool of any size: radix select of the m best rerank keys, then the common part.
+// Final tree for a pool of any size.  The m best rerank keys are found as for narrow beams (tree_device.hpp): the
+// m-th best key of the first kWSub nodes is a lower bound of the tree's keys (summed logprobs fall with depth), one
+// sweep over the pool collects the keys at or above it, and the candidates are ranked by counting; a sweep over
+// 50 000 scores takes about 20 us on the one CU that runs it, and the radix select needs five or six of them.  While
+// more than kWCand keys pass the bound, the m-th best of kWSub of them tightens it (twice at most); after that the
+// radix select takes over.  work: kWideWorkBytes of LDS.
 __device__ __forceinline__ void tree_finalize_wide_block(const ddd_state& st, const ddd_tree& tree, int b, int m, int nmax,
-                                                         int tid, int nthr, WideSmem& sm) {
+                                                         int tid, int nthr, WideSmem& sm, unsigned char* work) {
   const int N = st.n_nodes[b] - 1;
   const int m_eff = min(m, N);
   const float* psc = st.pool_score + (size_t)b * nmax;
   auto key_of = [&](int i) { return rerank_key(psc[i + 1], i + 1); };
-  uint64_t kth = 0ull;                       // every key is at least 1
-  if (m_eff < N) kth = block_select_kth<kGlobalChunk>(N, m_eff - 1, key_of, sm, tid);
-  if (tid == 0) sm.cnt = 0;
-  __syncthreads();
-  sweep_keys<kGlobalChunk>(N, tid, key_of, [&](uint64_t key, bool in) {
-    if (in && key >= kth) {
-      const int p = atomicAdd(&sm.cnt, 1);
-      if (p < kTreeMax) sm.te.pick[p] = (int)(0xFFFFFFFFu - (uint32_t)key);   // exactly m_eff: keys are distinct
+  uint64_t* sample = reinterpret_cast<uint64_t*>(work);            // [kWSub]
+  uint64_t* cand = sample + kWSub;                                   // [kWCand]
+  int* rank = reinterpret_cast<int*>(cand + kWCand);                // [kWCand]
+  bool ranked = false;
+  if (m_eff < N && nthr == kWideThreads) {                           // uniform
+    int n_sample = min(N, kWSub);
+    for (int i = tid; i < n_sample; i += nthr) sample[i] = key_of(i);
+    for (int attempt = 0; attempt < 3; ++attempt) {
+      for (int i = tid; i < kWCand; i += nthr) rank[i] = 0;
+      if (tid == 0) sm.cnt = 0;
+      __syncthreads();
+      count_larger_keys(sample, n_sample, rank, tid, nthr);
+      __syncthreads();
+      for (int i = tid; i < n_sample; i += nthr)
+        if (rank[i] == min(m_eff, n_sample) - 1) {                   // exactly one key has this rank
+          sm.found_lo = (uint32_t)sample[i];
+          sm.found_hi = (uint32_t)(sample[i] >> 32);
+        }
+      __syncthreads();
+      const uint64_t bound = ((uint64_t)sm.found_hi << 32) | sm.found_lo;
+      sweep_keys<kGlobalChunk>(N, tid, key_of, [&](uint64_t key, bool in) {
+        if (in && key >= bound) {
+          const int p = atomicAdd(&sm.cnt, 1);
+          if (p < kWCand) cand[p] = key;
+        }
+      });
+      __syncthreads();
+      const int C = sm.cnt;
+      if (C <= kWCand) {                                             // uniform
+        for (int i = tid; i < kWCand; i += nthr) rank[i] = 0;
+        __syncthreads();
+        count_larger_keys(cand, C, rank, tid, nthr);
+        __syncthreads();
+        for (int c = tid; c < C; c += nthr)
+          if (rank[c] < m_eff) sm.te.pick[rank[c]] = (int)(0xFFFFFFFFu - (uint32_t)cand[c]);
+        ranked = true;
+        break;
+      }
+      for (int i = tid; i < kWSub; i += nthr) sample[i] = cand[i];  // the first kWSub candidates: all above the old bound
+      n_sample = kWSub;
+      __syncthreads();
     }
-  });
+  }
+  if (!ranked) {
+    uint64_t kth = 0ull;                       // every key is at least 1
+    if (m_eff < N) kth = block_select_kth<kGlobalChunk>(N, m_eff - 1, key_of, sm, tid);
+    if (tid == 0) sm.cnt = 0;
+    __syncthreads();
+    sweep_keys<kGlobalChunk>(N, tid, key_of, [&](uint64_t key, bool in) {
+      if (in && key >= kth) {
+        const int p = atomicAdd(&sm.cnt, 1);
+        if (p < kTreeMax) sm.te.pick[p] = (int)(0xFFFFFFFFu - (uint32_t)key);   // exactly m_eff: keys are distinct
+      }
+    });
+  }
   __syncthreads();
   tree_emit_block(st, tree, b, m, m_eff, nmax, tid, nthr, sm.te);
 }
@@ -224,7 +283,7 @@ __device__ __forceinline__ bool step_wide_block(const WideStepArgs& a, unsigned 
   const int b = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
   const int k = g.k, step = g.step;
   uint64_t* keys = reinterpret_cast<uint64_t*>(wsm_raw);                       // [k*k]
-  WideSmem& sm = *reinterpret_cast<WideSmem*>(wsm_raw + (((size_t)k * k * 8 + 15) & ~(size_t)15));
+  WideSmem& sm = *reinterpret_cast<WideSmem*>(wsm_raw + wide_front_bytes(k));
   if (!g.st.active[b]) return false;         // uniform over the workgroup
 
   float* lps = g.st.logprobsum + (size_t)b * k;
@@ -359,7 +418,8 @@ __device__ __forceinline__ bool step_wide_block(const WideStepArgs& a, unsigned 
   }
   __syncthreads();   // also orders the pool writes before the reads below
   const bool stopped = sm.stopped != 0;
-  if (a.tree.mask != nullptr && stopped) tree_finalize_wide_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm);
+  if (a.tree.mask != nullptr && stopped)   // the candidate keys of the beam update are no longer needed: their LDS is the work area
+    tree_finalize_wide_block(g.st, a.tree, b, a.m, g.nmax, tid, nthr, sm, wsm_raw);
   return !stopped;
 }
 
@@ -381,10 +441,11 @@ __global__ __launch_bounds__(kWideThreads) void step_wide_kernel(WideStepArgs a)
 
 __global__ __launch_bounds__(kWideThreads) void tree_finalize_wide_kernel(FinalizeArgs a) {
   __shared__ WideSmem sm;
-  tree_finalize_wide_block(a.st, a.tree, blockIdx.x, a.m, a.nmax, threadIdx.x, blockDim.x, sm);
+  __shared__ __align__(16) unsigned char work[kWideWorkBytes];
+  tree_finalize_wide_block(a.st, a.tree, blockIdx.x, a.m, a.nmax, threadIdx.x, blockDim.x, sm, work);
 }
 
-static size_t wide_lds_bytes(int k) { return (((size_t)k * k * 8 + 15) & ~(size_t)15) + sizeof(WideSmem); }
+static size_t wide_lds_bytes(int k) { return wide_front_bytes(k) + sizeof(WideSmem); }
 
 hipError_t prepare_wide() {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&step_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
