@@ -98,6 +98,44 @@ def test_lmhead_topk_against_oracle(gpu, case):
         assert np.max(np.abs(g_lp[r].astype(np.float64) - o_lp)) <= LOGPROB_TOL
 
 
+def test_lmhead_topk_winners_in_one_slice(gpu):
+    """Every row's k best tokens sit in one tile of the weight stream (one slice holds the whole answer), so the row
+    merge cannot rest on the three keys per slice it keeps in registers and takes its general path; a second set of
+    rows has its winners spread as usual."""
+    torch, D, SD = gpu
+    B, k, H, V, R = 1, 10, 1024, 8000, 10
+    print(f"[case] lmhead_topk winners in one slice k={k} H={H} V={V} R={R}", flush=True)
+    rng = np.random.default_rng(77)
+    W = (rng.standard_normal((V, H)) * 0.03).astype(np.float32)
+    u = rng.choice([-1.0, 1.0], H).astype(np.float32)
+    for j in range(k):                                   # rows 100 .. 109: one tile of 15 or 16 rows at this shape
+        W[100 + j] = u * np.float32(0.05 * (1.0 - 0.02 * j))
+    W_bits = synth.f32_to_bf16_bits(W)
+    hid = (rng.standard_normal((R, H)) * 0.5).astype(np.float32)
+    hid[: R // 2] += u[None, :] * (0.5 + 0.1 * np.arange(R // 2, dtype=np.float32))[:, None]   # rows 0-4: concentrated winners
+    hid_bits = synth.f32_to_bf16_bits(hid)
+    cfg = D.make_config(B, H, V, k, 4, 8, 0.3)
+    ctx = D.ddd_create(cfg)
+    try:
+        tok = torch.full((R, k), -7, dtype=torch.int32, device="cuda")
+        lp = torch.zeros(R, k, dtype=torch.float32, device="cuda")
+        lse = torch.zeros(R, dtype=torch.float32, device="cuda")
+        dbg = torch.full((R, V), float("nan"), dtype=torch.float32, device="cuda")
+        D.ddd_lmhead_topk(ctx, SD.upload_bits(W_bits), SD.upload_bits(hid_bits), R, None, tok, lp, lse, dbg)
+        torch.cuda.synchronize()
+        g_logits, g_tok, g_lse = dbg.cpu().numpy(), tok.cpu().numpy(), lse.cpu().numpy()
+    finally:
+        D.ddd_destroy(ctx)
+    o_logits = O.lmhead_logits(W_bits, hid_bits)
+    assert np.max(np.abs(g_logits.astype(np.float64) - o_logits.astype(np.float64))) <= LOGIT_TOL
+    for r in range(R):
+        want = O.row_topk(g_logits[r], k)
+        assert np.array_equal(g_tok[r], want), (r, g_tok[r], want)
+        assert abs(float(g_lse[r]) - O.logsumexp_row(g_logits[r])) <= LOGPROB_TOL
+    assert all(sorted(g_tok[r]) == list(range(100, 110)) for r in range(R // 2))      # the case is what it claims to be
+    assert any(sorted(g_tok[r]) != list(range(100, 110)) for r in range(R // 2, R))
+
+
 PACK_CASES = [
     # name,  B, k,  H,    V,    R
     ("rows24_ragged_V", 3, 8, 512, 2003, 24),           # one 256-row block short of full, narrow column tile
