@@ -191,13 +191,13 @@ def test_lmhead_topk_with_packed_weights_is_bit_identical(gpu, case):
     assert np.max(np.abs(packed[3].cpu().numpy().astype(np.float64) - o_logits.astype(np.float64))) <= LOGIT_TOL
 
 
-@pytest.mark.parametrize("R", [3, 20])
-def test_lmhead_topk_all_logits_equal(gpu, R):
+@pytest.mark.parametrize("R,V", [(3, 5000), (20, 5000), (20, 20000)])   # 20000: more than 256 groups tie at the threshold
+def test_lmhead_topk_all_logits_equal(gpu, R, V):
     """Degenerate rows: a zero hidden state makes every logit 0, so the top-k is tokens 0..k-1 (lower id wins)
     and lse = log V; on the GEMM path this is the case where every element ties with the threshold."""
     torch, D, SD = gpu
-    B, k, H, V = 4, 8, 256, 5000
-    print(f"[case] lmhead_topk constant logits R={R}", flush=True)
+    B, k, H = 4, 8, 256
+    print(f"[case] lmhead_topk constant logits R={R} V={V}", flush=True)
     rng = np.random.default_rng(21)
     W_bits = synth.make_lm_head(V, H, 0.05, seed=4)
     hid_bits = _rand_hid_bits(rng, R, H, 4.0)
